@@ -1,0 +1,120 @@
+"""CPU ORACLE (test infrastructure, not the product) -- untiled decoder-layer math in float64.
+
+This file defines the result that the tiled, memory-capped GPU execution must reproduce.  The
+paper does not define the layer math itself: its workloads are LLaMA prefill passes (Experiments,
+item 1, and the Introduction's attention example), so the definitions here are the standard
+pre-norm decoder layer with RMSNorm, rotary position embedding, causal softmax attention and a
+SwiGLU feed-forward block, with the constants of the workload list (eps 1e-6, rotary base 10000).
+
+Everything is plain NumPy in float64, written for reading, with no blocking or fusion.  Only
+tests, the smoke check and the benchmark's CPU-baseline leg may import this package; the
+product path never does.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    """y[r, :] = x[r, :] / sqrt(mean_c x[r, c]^2 + eps) * g."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(g, dtype=np.float64)
+
+
+def rope(x: np.ndarray, positions: np.ndarray, base: float) -> np.ndarray:
+    """Rotary embedding on one head, x [rows, hd], interleaved pairs.
+
+    Pair i = (x[:, 2i], x[:, 2i+1]) is rotated counter-clockwise by the angle
+    positions[r] * base**(-2i/hd).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    hd = x.shape[-1]
+    i = np.arange(hd // 2, dtype=np.float64)
+    theta = base ** (-2.0 * i / hd)
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * theta[None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    xe, xo = x[:, 0::2], x[:, 1::2]
+    y = np.empty_like(x)
+    y[:, 0::2] = xe * c - xo * s
+    y[:, 1::2] = xe * s + xo * c
+    return y
+
+
+def causal_attention_head(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+    """softmax_rows(q k^T / sqrt(hd), entries with column > row excluded) v for one head."""
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    n, hd = q.shape
+    s = (q @ k.T) / np.sqrt(hd)
+    r = np.arange(n)
+    s = np.where(r[None, :] > r[:, None], -np.inf, s)
+    s = s - np.max(s, axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / np.sum(p, axis=-1, keepdims=True)
+    return p @ v
+
+
+def silu(z: np.ndarray) -> np.ndarray:
+    z = np.asarray(z, dtype=np.float64)
+    return z / (1.0 + np.exp(-z))
+
+
+def decoder_layer(x, w, layer: int, n_heads: int, head_dim: int, eps: float, base: float,
+                  return_kv: bool = False):
+    """One pre-norm decoder layer on a single sequence x [seq, d]; w maps names to float64 arrays."""
+    x = np.asarray(x, dtype=np.float64)
+    seq = x.shape[0]
+    a = rmsnorm(x, w[f"g1.{layer}"], eps)
+    q, k, v = a @ w[f"wq.{layer}"], a @ w[f"wk.{layer}"], a @ w[f"wv.{layer}"]
+    pos = np.arange(seq)
+    o = np.empty_like(q)
+    for h in range(n_heads):
+        sl = slice(h * head_dim, (h + 1) * head_dim)
+        q[:, sl] = rope(q[:, sl], pos, base)
+        k[:, sl] = rope(k[:, sl], pos, base)
+        o[:, sl] = causal_attention_head(q[:, sl], k[:, sl], v[:, sl])
+    h1 = x + o @ w[f"wo.{layer}"]
+    b = rmsnorm(h1, w[f"g2.{layer}"], eps)
+    y = h1 + (silu(b @ w[f"w1.{layer}"]) * (b @ w[f"w3.{layer}"])) @ w[f"w2.{layer}"]
+    if return_kv:
+        return y, k, v
+    return y
+
+
+def forward(cfg, inputs_f64, n_tokens_prefix=None):
+    """All layers, all sequences of the batch.  inputs_f64: name -> float64 array (full tensors).
+
+    n_tokens_prefix: evaluate only the first that many tokens of each sequence (a causal
+    prefill's rows [0, r) equal the model run on the first r tokens).
+    """
+    out = []
+    for b in range(cfg.batch):
+        x = inputs_f64["x"][b * cfg.seq:(b + 1) * cfg.seq]
+        if n_tokens_prefix is not None:
+            x = x[:n_tokens_prefix]
+        for l in range(cfg.layers):
+            x = decoder_layer(x, inputs_f64, l, cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
+        out.append(x)
+    return np.concatenate(out, axis=0)
+
+
+def widen(cfg, inputs):
+    """Storage-dtype host buffers -> exact float64 copies."""
+    out = {}
+    for k, a in inputs.items():
+        if a.dtype == np.uint16:
+            out[k] = (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+        else:
+            out[k] = a.astype(np.float64)
+    return out
+
+
+def rel_err(a: np.ndarray, b: np.ndarray) -> float:
+    """max_i |a_i - b_i| / max(|b_i|, rms(b)): the error measure the parity thresholds refer to."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    if b.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(b * b)))
+    den = np.maximum(np.abs(b), rms if rms > 0 else 1.0)
+    return float(np.max(np.abs(a - b) / den))

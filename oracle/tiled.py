@@ -1,0 +1,340 @@
+"""CPU ORACLE (test infrastructure, not the product) -- tiled taskgraph of the decoder and its
+interpreter.
+
+A taskgraph is a dataflow DAG: a vertex without inputs holds an input tensor, every other
+vertex is one kernel call with one output tensor, and an edge means "consumes the output of"
+(Section 4, first paragraph).  The paper leaves the production of the taskgraph to an outside
+framework (Section 4, second paragraph) and prints no vertex catalogue, so the catalogue below
+is this build's: each kind is a pure function of its inputs with a fixed summation order, which
+is what makes every dependency-respecting execution order give the same output (Introduction,
+fourth paragraph).
+
+This module has its own tiler (it does not read the library's) and evaluates any graph given
+in the plain format below -- including one exported by the library, so the library's tiler can
+be checked on the CPU.  float64 arithmetic inside a vertex; every vertex output is rounded to
+the vertex's storage type ("f32" or "bf16"), which reproduces the rounding points of the tiled
+execution.  Only tests, the smoke check and the benchmark's CPU-baseline leg import this.
+
+Vertex kinds (inputs -> output):
+  input         ()                                   -> the tile itself
+  gemm          A_0..A_{nk-1}, B_0..B_{nk-1}         -> sum_k A_k @ B_k, k ascending
+  rms_stat      X_0..X_{n-1} (tiles of one row block)-> [rows,1] 1/sqrt(mean over all columns of x^2 + eps)
+  rms_apply     X, stat, gain[1,c]                   -> x * stat * gain
+  rope          X                                    -> rotary embedding; params pos0, col0, head_dim, base
+  attn_block    Q tiles, K tiles, V tiles            -> packed [rows, gw + 2*hpg]: O (unnormalised), m, l
+  attn_combine  partial_0..partial_j                 -> normalised attention output tile
+  silu_mul      gate, up                             -> gate/(1+exp(-gate)) * up
+  add           a, b                                 -> a + b
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# ---------------------------------------------------------------------------------------------
+# storage rounding
+# ---------------------------------------------------------------------------------------------
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding of float64 values to bfloat16, returned as float64."""
+    f = np.ascontiguousarray(x, dtype=np.float32)  # double -> single first, as a store would
+    b = f.view(np.uint32)
+    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
+
+
+def round_store(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return round_bf16(x)
+    return np.asarray(x, dtype=np.float32).astype(np.float64)
+
+
+# ---------------------------------------------------------------------------------------------
+# graph container
+# ---------------------------------------------------------------------------------------------
+
+@dataclass
+class TaskGraph:
+    kind: List[str] = field(default_factory=list)
+    params: List[dict] = field(default_factory=list)
+    inputs: List[List[int]] = field(default_factory=list)
+    shape: List[Tuple[int, int]] = field(default_factory=list)
+    dtype: List[str] = field(default_factory=list)
+    outputs: List[int] = field(default_factory=list)
+    # vid -> (tensor name, row0, row1, col0, col1) for input tiles and for marked outputs
+    binding: Dict[int, Tuple[str, int, int, int, int]] = field(default_factory=dict)
+
+    def add(self, kind, inputs, shape, dtype, **params) -> int:
+        self.kind.append(kind)
+        self.inputs.append(list(inputs))
+        self.shape.append((int(shape[0]), int(shape[1])))
+        self.dtype.append(dtype)
+        self.params.append(params)
+        return len(self.kind) - 1
+
+    def __len__(self):
+        return len(self.kind)
+
+
+# ---------------------------------------------------------------------------------------------
+# vertex semantics
+# ---------------------------------------------------------------------------------------------
+
+def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
+    if kind == "gemm":
+        nk = p["nk"]
+        acc = None
+        for k in range(nk):
+            t = ins[k] @ ins[nk + k]
+            acc = t if acc is None else acc + t
+        return acc
+    if kind == "rms_stat":
+        ss = sum(np.sum(x * x, axis=1, keepdims=True) for x in ins)
+        return 1.0 / np.sqrt(ss / p["d"] + p["eps"])
+    if kind == "rms_apply":
+        x, stat, g = ins
+        return x * stat * g.reshape(1, -1)
+    if kind == "rope":
+        (x,) = ins
+        hd, base = p["head_dim"], p["base"]
+        rows, cols = x.shape
+        pos = p["pos0"] + np.arange(rows, dtype=np.float64)
+        c = p["col0"] + np.arange(0, cols, 2)  # column of the even member of each pair, in its head
+        theta = base ** (-(c % hd).astype(np.float64) / hd)  # (c % hd) = 2i
+        ang = pos[:, None] * theta[None, :]
+        cs, sn = np.cos(ang), np.sin(ang)
+        y = np.empty_like(x)
+        y[:, 0::2] = x[:, 0::2] * cs - x[:, 1::2] * sn
+        y[:, 1::2] = x[:, 0::2] * sn + x[:, 1::2] * cs
+        return y
+    if kind == "attn_block":
+        nq, nkv, nc, hd = p["n_q_tiles"], p["n_kv_tiles"], p["n_col_tiles"], p["head_dim"]
+        def gather(off, nr):
+            return np.concatenate([np.concatenate(ins[off + r * nc: off + (r + 1) * nc], axis=1)
+                                   for r in range(nr)], axis=0)
+        q = gather(0, nq)
+        k = gather(nq * nc, nkv)
+        v = gather(nq * nc + nkv * nc, nkv)
+        gw = q.shape[1]
+        hpg = gw // hd
+        rows = q.shape[0]
+        out = np.zeros((rows, gw + 2 * hpg))
+        qpos = p["q_pos0"] + np.arange(rows)
+        kpos = p["k_pos0"] + np.arange(k.shape[0])
+        for h in range(hpg):
+            sl = slice(h * hd, (h + 1) * hd)
+            s = (q[:, sl] @ k[:, sl].T) * p["scale"]
+            if p["causal"]:
+                s = np.where(kpos[None, :] > qpos[:, None], -np.inf, s)
+            m = np.max(s, axis=1)
+            msafe = np.where(np.isfinite(m), m, 0.0)
+            pr = np.exp(s - msafe[:, None])
+            out[:, sl] = pr @ v[:, sl]
+            out[:, gw + h] = m
+            out[:, gw + hpg + h] = np.sum(pr, axis=1)
+        return out
+    if kind == "attn_combine":
+        hd, hpg = p["head_dim"], p["hpg"]
+        gw = hd * hpg
+        r0, c0, rows, cols = p["row0"], p["col0"], p["rows"], p["cols"]
+        m = np.stack([x[r0:r0 + rows, gw:gw + hpg] for x in ins])  # [j, rows, hpg]
+        l = np.stack([x[r0:r0 + rows, gw + hpg:gw + 2 * hpg] for x in ins])
+        mstar = np.max(m, axis=0)
+        w = np.exp(m - mstar[None])  # exp(-inf) = 0 for empty partials
+        lstar = np.sum(l * w, axis=0)
+        out = np.zeros((rows, cols))
+        head_of_col = (c0 + np.arange(cols)) // hd
+        for j, x in enumerate(ins):
+            out += x[r0:r0 + rows, c0:c0 + cols] * w[j][:, head_of_col]
+        return out / lstar[:, head_of_col]
+    if kind == "silu_mul":
+        g, u = ins
+        return g / (1.0 + np.exp(-g)) * u
+    if kind == "add":
+        return ins[0] + ins[1]
+    raise ValueError(f"unknown vertex kind {kind}")
+
+
+def evaluate(tg: TaskGraph, input_values: Dict[int, np.ndarray],
+             order: Optional[Sequence[int]] = None, keep_all: bool = False) -> Dict[int, np.ndarray]:
+    """Run the graph in `order` (default: vertex numbering, which must be topological).
+
+    input_values: vid -> float64 tile for every input vertex.  Returns vid -> float64 value for
+    the marked outputs (or for every vertex with keep_all).  Every value is rounded to its
+    vertex's storage type, except attention partials and RMS statistics, which are "f32".
+    """
+    n = len(tg)
+    order = range(n) if order is None else order
+    remaining = [0] * n
+    for v in range(n):
+        for u in tg.inputs[v]:
+            remaining[u] += 1
+    keep = set(tg.outputs)
+    val: Dict[int, np.ndarray] = {}
+    done = [False] * n
+    for v in order:
+        if tg.kind[v] == "input":
+            r = np.asarray(input_values[v], dtype=np.float64).reshape(tg.shape[v])
+        else:
+            for u in tg.inputs[v]:
+                if not done[u]:
+                    raise ValueError(f"order is not topological at vertex {v}")
+            r = _eval_vertex(tg.kind[v], tg.params[v], [val[u] for u in tg.inputs[v]])
+            assert r.shape == tg.shape[v], (tg.kind[v], r.shape, tg.shape[v])
+        val[v] = round_store(r, tg.dtype[v])
+        done[v] = True
+        if not keep_all:
+            for u in tg.inputs[v]:
+                remaining[u] -= 1
+                if remaining[u] == 0 and u not in keep:
+                    del val[u]
+    return val if keep_all else {v: val[v] for v in tg.outputs}
+
+
+# ---------------------------------------------------------------------------------------------
+# the oracle's own tiler
+# ---------------------------------------------------------------------------------------------
+
+def _splits(n: int, t: int) -> List[Tuple[int, int]]:
+    return [(s, min(s + t, n)) for s in range(0, n, t)]
+
+
+def build_llama_taskgraph(cfg) -> TaskGraph:
+    """Tile the decoder of `cfg` (a workloads.LlamaConfig) into a taskgraph.
+
+    Tensors are cut into tile x tile pieces (ragged at the right and bottom edges); row blocks
+    never straddle sequences.  Attention runs per (sequence, head group, q block, kv block <= q
+    block) with one partial per pair and one combine per output tile; blocks above the diagonal
+    are never created.  A head group is the set of heads covering max(tile, head_dim) columns.
+    """
+    tg = TaskGraph()
+    dt, t, d, f, hd = cfg.dtype, cfg.tile, cfg.d_model, cfg.ffn, cfg.head_dim
+    assert (t % hd == 0 or hd % t == 0) and cfg.attn_block % t == 0
+    dcols, fcols = _splits(d, t), _splits(f, t)
+    gw = max(t, hd)
+    hpg = gw // hd
+    ctg = gw // t  # column tiles per head group
+
+    def input_tiles(name, rows, cols, r_off=0):
+        """Grid of input vertices for the matrix `name`, cut by `rows` x `cols` ranges."""
+        grid = []
+        for (r0, r1) in rows:
+            line = []
+            for (c0, c1) in cols:
+                v = tg.add("input", [], (r1 - r0, c1 - c0), dt)
+                tg.binding[v] = (name, r_off + r0, r_off + r1, c0, c1)
+                line.append(v)
+            grid.append(line)
+        return grid
+
+    def gain_tiles(name, cols):
+        out = []
+        for (c0, c1) in cols:
+            v = tg.add("input", [], (1, c1 - c0), dt)
+            tg.binding[v] = (name, 0, 1, c0, c1)
+            out.append(v)
+        return out
+
+    def gemm(a_grid, b_grid, out_cols):
+        """a_grid [row tiles][k tiles], b_grid [k tiles][col tiles]."""
+        res = []
+        for arow in a_grid:
+            line = []
+            m = tg.shape[arow[0]][0]
+            for j, (c0, c1) in enumerate(out_cols):
+                ins = list(arow) + [b_grid[k][j] for k in range(len(arow))]
+                line.append(tg.add("gemm", ins, (m, c1 - c0), dt, nk=len(arow)))
+            res.append(line)
+        return res
+
+    def rmsnorm(x_grid, gains, cols):
+        res = []
+        for xrow in x_grid:
+            m = tg.shape[xrow[0]][0]
+            st = tg.add("rms_stat", xrow, (m, 1), "f32", eps=cfg.eps, d=d)
+            res.append([tg.add("rms_apply", [xv, st, gains[j]], tg.shape[xv], dt)
+                        for j, xv in enumerate(xrow)])
+        return res
+
+    def ewise(kind, a_grid, b_grid):
+        return [[tg.add(kind, [a, b], tg.shape[a], dt) for a, b in zip(ar, br)]
+                for ar, br in zip(a_grid, b_grid)]
+
+    rows = _splits(cfg.seq, t)
+    blocks = _splits(cfg.seq, cfg.attn_block)
+    tiles_of_block = [[i for i, (r0, _) in enumerate(rows) if b0 <= r0 < b1] for (b0, b1) in blocks]
+    xs = [input_tiles("x", rows, dcols, r_off=b * cfg.seq) for b in range(cfg.batch)]
+
+    def roped(grid):
+        return [[tg.add("rope", [xv], tg.shape[xv], dt, pos0=rows[i][0], col0=dcols[j][0] % hd,
+                        head_dim=hd, base=cfg.rope_base)
+                 for j, xv in enumerate(line)] for i, line in enumerate(grid)]
+
+    def attention(q, k, v):
+        """Blocked causal attention of one sequence; returns the grid of output tiles."""
+        o = [[None] * len(dcols) for _ in rows]
+        for g in range(d // gw):
+            cts = list(range(g * ctg, (g + 1) * ctg))
+            for bi, (q0, q1) in enumerate(blocks):
+                parts = []
+                for bj in range(bi + 1):
+                    k0 = blocks[bj][0]
+                    qi, kj = tiles_of_block[bi], tiles_of_block[bj]
+                    ins = ([q[r][c] for r in qi for c in cts] + [k[r][c] for r in kj for c in cts]
+                           + [v[r][c] for r in kj for c in cts])
+                    parts.append(tg.add("attn_block", ins, (q1 - q0, gw + 2 * hpg), "f32",
+                                        n_q_tiles=len(qi), n_kv_tiles=len(kj), n_col_tiles=ctg,
+                                        head_dim=hd, q_pos0=q0, k_pos0=k0, causal=(bj == bi),
+                                        scale=1.0 / np.sqrt(hd)))
+                for r in tiles_of_block[bi]:
+                    for ci, c in enumerate(cts):
+                        m, n_ = rows[r][1] - rows[r][0], dcols[c][1] - dcols[c][0]
+                        o[r][c] = tg.add("attn_combine", parts, (m, n_), dt, row0=rows[r][0] - q0,
+                                         col0=ci * t, rows=m, cols=n_, head_dim=hd, hpg=hpg)
+        return o
+
+    for l in range(cfg.layers):
+        w = {k: input_tiles(f"{k}.{l}", dcols, dcols) for k in ("wq", "wk", "wv", "wo")}
+        w["w1"] = input_tiles(f"w1.{l}", dcols, fcols)
+        w["w3"] = input_tiles(f"w3.{l}", dcols, fcols)
+        w["w2"] = input_tiles(f"w2.{l}", fcols, dcols)
+        g1, g2 = gain_tiles(f"g1.{l}", dcols), gain_tiles(f"g2.{l}", dcols)
+        for b in range(cfg.batch):
+            x = xs[b]
+            a = rmsnorm(x, g1, dcols)
+            q, k, v = gemm(a, w["wq"], dcols), gemm(a, w["wk"], dcols), gemm(a, w["wv"], dcols)
+            o = attention(roped(q), roped(k), v)
+            h1 = ewise("add", x, gemm(o, w["wo"], dcols))
+            bn = rmsnorm(h1, g2, dcols)
+            act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
+            xs[b] = ewise("add", h1, gemm(act, w["w2"], dcols))
+    for b in range(cfg.batch):
+        for i, line in enumerate(xs[b]):
+            for j, vtx in enumerate(line):
+                tg.outputs.append(vtx)
+                tg.binding[vtx] = ("y", b * cfg.seq + rows[i][0], b * cfg.seq + rows[i][1],
+                                   dcols[j][0], dcols[j][1])
+    return tg
+
+
+def cut_inputs(tg: TaskGraph, full_f64: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
+    """Slice the full input tensors into the tiles the graph's input vertices name."""
+    out = {}
+    for v, (name, r0, r1, c0, c1) in tg.binding.items():
+        if tg.kind[v] != "input":
+            continue
+        a = full_f64[name]
+        a = a.reshape(1, -1) if a.ndim == 1 else a
+        out[v] = a[r0:r1, c0:c1]
+    return out
+
+
+def assemble_outputs(tg: TaskGraph, values: Dict[int, np.ndarray], tokens: int, d: int) -> np.ndarray:
+    y = np.full((tokens, d), np.nan)
+    for v in tg.outputs:
+        _, r0, r1, c0, c1 = tg.binding[v]
+        y[r0:r1, c0:c1] = values[v]
+    return y

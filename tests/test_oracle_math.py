@@ -1,0 +1,174 @@
+"""Pins for the oracle's untiled layer math (CPU only): closed forms, invariants, and special
+cases that reduce to a library routine.  Each would fail for a plausible mistake (dropped scale,
+wrong mask direction, wrong rotation sign or pairing, missing eps, transposed weight)."""
+import numpy as np
+import pytest
+from scipy.special import expit, softmax
+
+from oracle import llama_ref as R
+from workloads import config, make_llama_inputs
+
+
+def test_rmsnorm_closed_forms():
+    # (3, 4): mean square 12.5
+    y = R.rmsnorm(np.array([[3.0, 4.0]]), np.array([1.0, 2.0]), 1e-6)
+    np.testing.assert_allclose(y, [[3 / np.sqrt(12.5 + 1e-6), 8 / np.sqrt(12.5 + 1e-6)]], rtol=1e-15)
+    # unit-RMS rows and unit gain: identity up to eps
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((5, 64))
+    x /= np.sqrt(np.mean(x * x, axis=1, keepdims=True))
+    np.testing.assert_allclose(R.rmsnorm(x, np.ones(64), 1e-6), x, rtol=1e-6)
+    # eps matters for a zero row (no division by zero) and scale invariance holds otherwise
+    assert np.all(R.rmsnorm(np.zeros((1, 8)), np.ones(8), 1e-6) == 0)
+    np.testing.assert_allclose(R.rmsnorm(1e3 * x, np.ones(64), 1e-6), R.rmsnorm(x, np.ones(64), 1e-6), rtol=1e-6)
+
+
+def test_rope_closed_forms():
+    hd = 8
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((6, hd))
+    pos = np.arange(6) + 3
+    y = R.rope(x, pos, 10000.0)
+    # position 0 is the identity
+    np.testing.assert_array_equal(R.rope(x, np.zeros(6), 10000.0), x)
+    # pair 0 has frequency 1: (1, 0) at position 1 goes to (cos 1, sin 1)
+    e = np.zeros((1, hd)); e[0, 0] = 1.0
+    r = R.rope(e, np.array([1]), 10000.0)
+    np.testing.assert_allclose(r[0, :2], [np.cos(1.0), np.sin(1.0)], rtol=1e-15)
+    # the last pair has frequency base**(-(hd-2)/hd)
+    e = np.zeros((1, hd)); e[0, hd - 2] = 1.0
+    r = R.rope(e, np.array([5]), 10000.0)
+    th = 5 * 10000.0 ** (-(hd - 2) / hd)
+    np.testing.assert_allclose(r[0, hd - 2:], [np.cos(th), np.sin(th)], rtol=1e-14)
+    # the same thing as multiplication of complex numbers x_{2i} + i x_{2i+1} by exp(i pos theta_i)
+    z = (x[:, 0::2] + 1j * x[:, 1::2]) * np.exp(1j * pos[:, None] * 10000.0 ** (-np.arange(0, hd, 2) / hd)[None, :])
+    np.testing.assert_allclose(y[:, 0::2], z.real, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(y[:, 1::2], z.imag, rtol=1e-13, atol=1e-14)
+    # pair norms are preserved and q.k depends only on the position difference
+    np.testing.assert_allclose(y[:, 0::2] ** 2 + y[:, 1::2] ** 2, x[:, 0::2] ** 2 + x[:, 1::2] ** 2, rtol=1e-13)
+    k = rng.standard_normal((6, hd))
+    d1 = R.rope(x, pos, 1e4) @ R.rope(k, pos, 1e4).T
+    d2 = R.rope(x, pos + 11, 1e4) @ R.rope(k, pos + 11, 1e4).T
+    np.testing.assert_allclose(d1, d2, rtol=1e-10, atol=1e-12)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(2)
+    n, hd = 7, 4
+    v = rng.standard_normal((n, hd))
+    # zero queries: every allowed key weighs the same, so row r is the mean of v[0..r]
+    o = R.causal_attention_head(np.zeros((n, hd)), rng.standard_normal((n, hd)), v)
+    np.testing.assert_allclose(o, np.cumsum(v, axis=0) / np.arange(1, n + 1)[:, None], rtol=1e-13)
+    # row 0 sees only key 0
+    q, k = rng.standard_normal((n, hd)), rng.standard_normal((n, hd))
+    o = R.causal_attention_head(q, k, v)
+    np.testing.assert_allclose(o[0], v[0], rtol=1e-14)
+    # the scale: with hd = 4, q.k1/2 = ln 3 and q.k2/2 = 0 give weights (3/4, 1/4) on row 1
+    q2 = np.zeros((2, 4)); q2[1, 0] = 2.0
+    k2 = np.zeros((2, 4)); k2[0, 0] = np.log(3.0)
+    v2 = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0]])
+    o2 = R.causal_attention_head(q2, k2, v2)
+    np.testing.assert_allclose(o2[1, :2], [0.75, 0.25], rtol=1e-14)
+    # the mask direction: a huge score on a *later* key must be ignored, on an earlier key it wins
+    kk = np.eye(n, hd * 2)[:, :hd] * 0
+    kk = rng.standard_normal((n, hd)); kk /= np.linalg.norm(kk, axis=1, keepdims=True)
+    qq = np.zeros((n, hd)); qq[2] = 1e4 * kk[5]; qq[6] = 1e4 * kk[1]
+    oo = R.causal_attention_head(qq, kk, v)
+    assert not np.allclose(oo[2], v[5], atol=1e-3)
+    sc = (qq[6] @ kk.T) / 2
+    np.testing.assert_allclose(oo[6], softmax(sc) @ v, rtol=1e-12)
+    # against the library softmax on explicitly masked scores
+    s = q @ k.T / np.sqrt(hd)
+    s[np.triu_indices(n, 1)] = -np.inf
+    np.testing.assert_allclose(o, softmax(s, axis=1) @ v, rtol=1e-12)
+
+
+def test_silu_closed_forms():
+    z = np.linspace(-20, 20, 401)
+    np.testing.assert_allclose(R.silu(z), z * expit(z), rtol=1e-13, atol=1e-300)
+    np.testing.assert_allclose(R.silu(z) - R.silu(-z), z, rtol=1e-12, atol=1e-13)
+    assert R.silu(np.array([0.0]))[0] == 0.0
+    np.testing.assert_allclose(R.silu(np.array([np.log(3.0)])), [np.log(3.0) * 0.75], rtol=1e-14)
+
+
+def _small_layer(seed=0, seq=12, d=16, heads=2, f=24):
+    rng = np.random.default_rng(seed)
+    w = {f"{k}.0": rng.standard_normal((d, d)) * 0.3 for k in ("wq", "wk", "wv", "wo")}
+    w["w1.0"] = rng.standard_normal((d, f)) * 0.3
+    w["w3.0"] = rng.standard_normal((d, f)) * 0.3
+    w["w2.0"] = rng.standard_normal((f, d)) * 0.3
+    w["g1.0"] = 1 + 0.1 * rng.standard_normal(d)
+    w["g2.0"] = 1 + 0.1 * rng.standard_normal(d)
+    x = rng.standard_normal((seq, d))
+    return x, w, heads, d // heads
+
+
+def test_layer_special_cases():
+    x, w, heads, hd = _small_layer()
+    # zero output projections leave only the residual path
+    w0 = dict(w); w0["wo.0"] = np.zeros_like(w["wo.0"]); w0["w2.0"] = np.zeros_like(w["w2.0"])
+    np.testing.assert_array_equal(R.decoder_layer(x, w0, 0, heads, hd, 1e-6, 1e4), x)
+    # zero feed-forward output: y = x + attention, and with wq = wk = 0 attention is a running
+    # mean of v = rmsnorm(x) wv, which pins weight orientation (x @ W) and the order of the steps
+    w1 = dict(w); w1["w2.0"] = np.zeros_like(w["w2.0"]); w1["wq.0"] = np.zeros_like(w["wq.0"])
+    a = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + 1e-6) * w["g1.0"]
+    vv = a @ w["wv.0"]
+    run_mean = np.cumsum(vv, axis=0) / np.arange(1, x.shape[0] + 1)[:, None]
+    np.testing.assert_allclose(R.decoder_layer(x, w1, 0, heads, hd, 1e-6, 1e4), x + run_mean @ w["wo.0"], rtol=1e-12)
+    # zero attention output: y = x + (silu(b w1) * (b w3)) w2 with b = rmsnorm(x; g2)
+    w2 = dict(w); w2["wo.0"] = np.zeros_like(w["wo.0"])
+    b = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + 1e-6) * w["g2.0"]
+    g = b @ w["w1.0"]
+    np.testing.assert_allclose(R.decoder_layer(x, w2, 0, heads, hd, 1e-6, 1e4),
+                               x + ((g * expit(g)) * (b @ w["w3.0"])) @ w["w2.0"], rtol=1e-12)
+
+
+def test_causality_and_prefix_property():
+    x, w, heads, hd = _small_layer(3)
+    y = R.decoder_layer(x, w, 0, heads, hd, 1e-6, 1e4)
+    x2 = x.copy(); x2[8:] += 1.0
+    y2 = R.decoder_layer(x2, w, 0, heads, hd, 1e-6, 1e4)
+    np.testing.assert_array_equal(y[:8], y2[:8])
+    assert not np.allclose(y[8:], y2[8:])
+    np.testing.assert_allclose(R.decoder_layer(x[:5], w, 0, heads, hd, 1e-6, 1e4), y[:5], rtol=1e-12)
+
+
+def test_heads_are_independent_column_groups():
+    # permuting whole heads of wq, wk, wv (columns) and wo (rows) together leaves y unchanged
+    x, w, heads, hd = _small_layer(4)
+    y = R.decoder_layer(x, w, 0, heads, hd, 1e-6, 1e4)
+    perm = np.concatenate([np.arange(hd, 2 * hd), np.arange(0, hd)])
+    wp = dict(w)
+    for k in ("wq", "wk", "wv"):
+        wp[f"{k}.0"] = w[f"{k}.0"][:, perm]
+    wp["wo.0"] = w["wo.0"][perm, :]
+    np.testing.assert_allclose(R.decoder_layer(x, wp, 0, heads, hd, 1e-6, 1e4), y, rtol=1e-11)
+
+
+def test_batch_elements_are_independent():
+    cfg = config("batch2_f32")
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    y = R.forward(cfg, w)
+    one = cfg.with_(batch=1)
+    w1 = dict(w); w1["x"] = w["x"][cfg.seq:]
+    np.testing.assert_array_equal(R.forward(one, w1), y[cfg.seq:])
+
+
+def test_error_measure():
+    b = np.array([1.0, -2.0, 0.0, 1e-9])
+    a = b + np.array([0.0, 0.02, 0.001, 0.0])
+    rms = np.sqrt(np.mean(b * b))
+    assert R.rel_err(a, b) == pytest.approx(max(0.02 / 2.0, 0.001 / rms))
+    assert R.rel_err(b, b) == 0.0
+
+
+def test_input_generator_is_counter_based_and_normal():
+    from workloads import normal, to_bf16_bits, bf16_bits_to_f32
+    a = normal(3, 17, 1000)
+    np.testing.assert_array_equal(normal(3, 17, 300, start=200), a[200:500])
+    assert not np.array_equal(normal(4, 17, 1000), a)
+    big = normal(0, 1, 200000)
+    assert abs(big.mean()) < 0.01 and abs(big.std() - 1) < 0.01
+    # bf16 rounding: nearest, ties to even
+    f = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7], dtype=np.float32)
+    np.testing.assert_array_equal(bf16_bits_to_f32(to_bf16_bits(f)), [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7])
