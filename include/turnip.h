@@ -1,0 +1,330 @@
+/*
+ * turnip.h -- C ABI of the single-GPU memgraph runtime (gfx950 / MI355X).
+ *
+ * The calls follow the paper's statement of the problem:
+ *   taskgraph in (Section 4, first paragraph: a dataflow DAG whose input vertices hold tensors
+ *   and whose other vertices are kernel calls)
+ *     -> BuildMemgraph (Section 6, Algorithms 1 and 2: fixed GPU location per vertex output,
+ *        memory dependencies, inserted offload/reload vertices, for a given serial order V
+ *        and a given amount of GPU memory)
+ *     -> execution by an event loop that launches any vertex whose dependencies have completed
+ *        and for which a stream is free, with no allocation calls while it runs (Section 5 and
+ *        Appendix A).
+ *
+ * Conventions
+ *   - Every function returns a tn_status (0 = TN_OK, negative = error) unless stated.  No
+ *     exception and no abort crosses this boundary.  tn_last_error() returns a thread-local,
+ *     NUL-terminated description of the most recent error on the calling thread.
+ *   - "host" pointers are CPU memory, "device" pointers are GPU memory of the current HIP
+ *     device.  The library never frees or reallocates caller memory.
+ *   - Objects returned through an out-parameter belong to the caller and are released with the
+ *     matching *_destroy.  A memgraph owns a copy of everything it needs from the taskgraph, so
+ *     the taskgraph may be destroyed after tn_compile.  A memgraph must outlive its executors.
+ *   - All tensors are dense row-major 2-D tiles [rows, cols] of fp32 or bf16 elements, each
+ *     stored contiguously (leading dimension = cols).
+ */
+#ifndef TURNIP_H
+#define TURNIP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tn_status;
+typedef int32_t tn_vid; /* taskgraph vertex id, dense from 0 in insertion order */
+
+enum {
+  TN_OK = 0,
+  TN_ERR_INVALID = -1,         /* bad argument, bad handle, call out of sequence */
+  TN_ERR_NOT_TOPOLOGICAL = -2, /* the given serial order violates a dataflow edge */
+  TN_ERR_CYCLE = -3,           /* the graph has a cycle */
+  TN_ERR_CAP_TOO_SMALL = -4,   /* some vertex's inputs and output cannot be co-resident */
+  TN_ERR_ARENA = -5,           /* pinned host arena exhausted */
+  TN_ERR_HIP = -6,             /* a HIP call failed; the executor is poisoned afterwards */
+  TN_ERR_SHAPE = -7            /* operand shapes or types do not fit the vertex kind */
+};
+
+const char* tn_last_error(void);
+
+typedef struct tn_taskgraph tn_taskgraph;
+typedef struct tn_memgraph tn_memgraph;
+typedef struct tn_executor tn_executor;
+
+enum { TN_F32 = 0, TN_BF16 = 1 };    /* element type of a tensor */
+enum { TN_HOST = 0, TN_DEVICE = 1 }; /* where an input tensor lies when execution starts */
+
+/* Vertex kinds of a taskgraph.  Each is a pure function of its operands with a fixed summation
+ * order, so that every dependency-respecting execution order produces the same bits
+ * (Introduction, fourth paragraph: the output is correct no matter the execution order). */
+enum {
+  TN_OP_INPUT = 0,        /* ()                       -> the tensor itself                        */
+  TN_OP_GEMM = 1,         /* A_0..A_{nk-1}, B_0..B_{nk-1} -> sum_k A_k B_k, k ascending, fp32 acc  */
+  TN_OP_RMS_STAT = 2,     /* X_0..X_{n-1} (one row block) -> fp32 [rows,1]: rsqrt(sum x^2 / d + eps) */
+  TN_OP_RMS_APPLY = 3,    /* X, stat[rows,1] fp32, gain[1,cols] -> x * stat * gain                 */
+  TN_OP_ROPE = 4,         /* X -> rotary embedding of interleaved pairs (2i, 2i+1)                 */
+  TN_OP_ATTN_BLOCK = 5,   /* Q tiles, K tiles, V tiles -> fp32 partial [rows, gw + 2*hpg]          */
+  TN_OP_ATTN_COMBINE = 6, /* partial_0..partial_j -> normalised attention output tile              */
+  TN_OP_SILU_MUL = 7,     /* gate, up -> gate / (1 + exp(-gate)) * up                              */
+  TN_OP_ADD = 8           /* a, b -> a + b                                                          */
+};
+
+typedef struct {
+  int32_t dtype; /* TN_F32 or TN_BF16 */
+  int32_t rows;
+  int32_t cols;
+} tn_tensor_desc;
+
+/* Parameters of a vertex; fields a kind does not use are ignored.
+ *   GEMM         nk, trans_b            number of k tiles; operands are A_0..A_{nk-1} then B_0..B_{nk-1};
+ *                                       A_k is [rows, K_k]; B_k is [K_k, cols], or, with trans_b != 0,
+ *                                       stored transposed as [cols, K_k] (the usual [out, in] layout
+ *                                       of linear-layer weights, which the MFMA kernel reads directly)
+ *   RMS_STAT     d, eps                 d = total number of columns of the row block
+ *   ROPE         pos0, col0, head_dim, rope_base
+ *                                       row r has position pos0 + r; column c belongs to pair
+ *                                       ((col0 + c) mod head_dim) / 2; pair i turns by
+ *                                       position * rope_base^(-2i/head_dim)
+ *   ATTN_BLOCK   n_q_tiles, n_kv_tiles, n_col_tiles, head_dim, q_pos0, k_pos0, causal, scale
+ *                                       operands: Q tiles row-major over (row tile, column tile),
+ *                                       then K tiles, then V tiles.  gw = total columns = hpg *
+ *                                       head_dim.  Output row: gw unnormalised sums of
+ *                                       exp(s - m) v, then hpg row maxima m, then hpg sums l.
+ *                                       causal != 0 excludes keys with k_pos0 + c > q_pos0 + r.
+ *   ATTN_COMBINE row0, col0, head_dim, hpg
+ *                                       output tile = rows [row0, row0 + rows) and columns
+ *                                       [col0, col0 + cols) of the merged, normalised block. */
+typedef struct {
+  int32_t nk;
+  int32_t d;
+  float eps;
+  int32_t pos0;
+  int32_t col0;
+  int32_t head_dim;
+  float rope_base;
+  int32_t n_q_tiles;
+  int32_t n_kv_tiles;
+  int32_t n_col_tiles;
+  int32_t q_pos0;
+  int32_t k_pos0;
+  int32_t causal;
+  float scale;
+  int32_t row0;
+  int32_t hpg;
+  int32_t trans_b;
+} tn_op_params;
+
+/* ------------------------------------------------------------------------------------------ */
+/* Taskgraph (host only)                                                                       */
+/* ------------------------------------------------------------------------------------------ */
+
+tn_status tn_taskgraph_create(tn_taskgraph** out);
+void tn_taskgraph_destroy(tn_taskgraph* tg);
+
+/* Adds an input vertex (Section 4: a vertex without inputs is associated with an input tensor).
+ * residency TN_DEVICE: the tensor is in GPU memory at its compiled location before execution
+ * starts, as in the paper's examples; TN_HOST: it is copied from the caller's host buffer by a
+ * load vertex when the memgraph says so. */
+tn_status tn_taskgraph_add_input(tn_taskgraph* tg, const tn_tensor_desc* desc, int32_t residency,
+                                 tn_vid* out);
+
+/* Adds a kernel-call vertex reading the outputs of `inputs` (operand order matters).  Operand
+ * shapes and types are validated against the kind: TN_ERR_SHAPE on mismatch. */
+tn_status tn_taskgraph_add_op(tn_taskgraph* tg, int32_t kind, const tn_op_params* params,
+                              const tn_vid* inputs, int32_t n_inputs, const tn_tensor_desc* out_desc,
+                              tn_vid* out);
+
+/* Marks a vertex whose tensor the caller wants back.  Output index = order of marking. */
+tn_status tn_taskgraph_mark_output(tn_taskgraph* tg, tn_vid v);
+
+typedef struct {
+  int32_t kind;
+  int32_t residency; /* inputs only */
+  int32_t n_inputs;
+  int32_t output_index; /* -1 if not a marked output */
+  tn_tensor_desc desc;
+  tn_op_params params;
+} tn_tg_vertex;
+
+int64_t tn_taskgraph_num_vertices(const tn_taskgraph* tg);
+int64_t tn_taskgraph_num_outputs(const tn_taskgraph* tg);
+tn_status tn_taskgraph_vertex(const tn_taskgraph* tg, tn_vid v, tn_tg_vertex* out);
+/* Copies up to cap operand ids of v into out; returns the operand count (or a negative status). */
+int32_t tn_taskgraph_inputs(const tn_taskgraph* tg, tn_vid v, tn_vid* out, int32_t cap);
+
+/* A tiled LLaMA-style decoder forward pass as a taskgraph (the paper's workload, Section 8;
+ * the decomposition into tiles is this library's, since the paper leaves taskgraph production
+ * to an outside framework, Section 4 second paragraph). */
+typedef struct {
+  int32_t layers, d_model, n_heads, head_dim, ffn, seq, batch;
+  int32_t dtype;      /* storage type of activations and weights */
+  int32_t tile;       /* edge of a GEMM / elementwise tile */
+  int32_t attn_block; /* edge of an attention block, a multiple of tile */
+  float eps;
+  float rope_base;
+  int32_t weights_residency; /* TN_HOST (streamed) or TN_DEVICE (pre-placed) */
+  int32_t x_residency;
+  int32_t kv_outputs; /* != 0: post-rotary K and V tiles of every layer are marked outputs too */
+  int32_t weights_transposed; /* != 0: weight tiles are stored [out, in] and GEMMs use trans_b */
+} tn_llama_config;
+
+/* Which vertex is which piece of which tensor of the decoder. */
+enum {
+  TN_T_X = 0, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2,
+  TN_T_Y, TN_T_K, TN_T_V
+};
+typedef struct {
+  tn_vid vid;
+  int32_t tensor; /* TN_T_* */
+  int32_t layer;  /* -1 for x and y */
+  int32_t row0, row1, col0, col1; /* the slice [row0,row1) x [col0,col1) of the full tensor */
+  int32_t transposed; /* != 0: the vertex holds the slice transposed, [col1-col0, row1-row0] */
+} tn_llama_binding;
+
+tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out);
+int64_t tn_taskgraph_num_bindings(const tn_taskgraph* tg);
+tn_status tn_taskgraph_binding(const tn_taskgraph* tg, int64_t i, tn_llama_binding* out);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Compile: BuildMemgraph (host only)                                                          */
+/* ------------------------------------------------------------------------------------------ */
+
+typedef struct {
+  /* Run-ahead of the allocation horizon past the execution horizon (Section 6, third
+   * paragraph), in bytes of not-yet-produced outputs; UINT64_MAX = greedy as in Algorithm 1,
+   * 0 = allocate a vertex only when it is about to run. */
+  uint64_t max_lookahead_bytes;
+  /* != 0: an evicted input whose host copy is still valid is dropped instead of copied back
+   * (no bytes move); its reload is a fresh load from the caller's buffer. */
+  int32_t drop_clean_inputs;
+  /* != 0: add dependencies that force kernels to run in the order V and transfers to run in
+   * the order V (the partially deterministic variant of Section 8, item 3). */
+  int32_t fix_order;
+  /* != 0: leave out memory dependencies that duplicate a data dependency (Section 4 calls them
+   * superfluous). */
+  int32_t prune_superfluous;
+  uint32_t alignment; /* location granularity in bytes, power of two; 0 = 256 */
+} tn_compile_opts;
+
+/* Compiles tg for gpu_cap_bytes of GPU memory.  order: a permutation of all vertex ids that
+ * respects every edge, or NULL for insertion order with each TN_HOST input moved to just before
+ * its first consumer.  TN_DEVICE inputs are placed first, in id order, whatever `order` says.
+ * Errors: TN_ERR_NOT_TOPOLOGICAL, TN_ERR_CAP_TOO_SMALL (message names the vertex). */
+tn_status tn_compile(const tn_taskgraph* tg, const tn_vid* order, uint64_t gpu_cap_bytes,
+                     const tn_compile_opts* opts, tn_memgraph** out);
+void tn_memgraph_destroy(tn_memgraph* mg);
+
+/* Memgraph vertex kinds.  Vertices 0..n_task-1 are the taskgraph's, with the same ids. */
+enum {
+  TN_MG_INPUT = 0, /* TN_DEVICE input, in place before execution                     */
+  TN_MG_LOAD = 1,  /* host -> GPU copy of a TN_HOST input (first load, or after a drop) */
+  TN_MG_OP = 2,    /* kernel call                                                      */
+  TN_MG_OFFLOAD = 3,
+  TN_MG_RELOAD = 4,
+  TN_MG_DROP = 5,  /* eviction without a copy                                          */
+  TN_MG_STORE = 6  /* GPU -> host copy of a marked output into the caller's buffer     */
+};
+enum { TN_EDGE_DATA = 0, TN_EDGE_MEM = 1, TN_EDGE_ORDER = 2 /* only with fix_order */ };
+
+typedef struct {
+  int32_t kind;       /* TN_MG_* */
+  int32_t op_kind;    /* TN_OP_* for TN_MG_OP */
+  tn_vid src;         /* taskgraph vertex whose tensor this vertex produces or moves */
+  int64_t offset;     /* byte offset of its output in [0, cap), or -1 if it writes no GPU memory */
+  uint64_t bytes;     /* size of the tensor */
+  int32_t n_operands; /* memgraph vertices whose output it reads */
+  int64_t order_pos;  /* position in the extended serial order (Section 7) */
+} tn_mg_vertex;
+
+typedef struct {
+  int64_t from, to;
+  int32_t kind; /* TN_EDGE_* */
+} tn_mg_edge;
+
+typedef struct {
+  uint64_t cap;              /* as given */
+  uint64_t high_water;       /* highest byte offset + size ever assigned */
+  uint64_t peak_live_bytes;  /* peak of allocated bytes during the simulated serial run */
+  uint64_t host_arena_bytes; /* sum of all offload sizes (aligned): a safe arena size */
+  int64_t n_task, n_vertices, n_edges, n_mem_edges;
+  int64_t n_offload, n_reload, n_drop, n_load, n_store;
+  uint64_t offload_bytes, reload_bytes, load_bytes, store_bytes;
+  int64_t n_revoked;     /* run-ahead allocations that had to be undone */
+  int64_t n_compactions; /* times memory had to be emptied to defeat fragmentation */
+} tn_mg_stats;
+
+int64_t tn_memgraph_num_vertices(const tn_memgraph* mg);
+tn_status tn_memgraph_vertex(const tn_memgraph* mg, int64_t i, tn_mg_vertex* out);
+int32_t tn_memgraph_operands(const tn_memgraph* mg, int64_t i, int64_t* out, int32_t cap);
+int64_t tn_memgraph_num_edges(const tn_memgraph* mg);
+tn_status tn_memgraph_edge(const tn_memgraph* mg, int64_t i, tn_mg_edge* out);
+tn_status tn_memgraph_stats(const tn_memgraph* mg, tn_mg_stats* out);
+/* Writes vertices, edges, locations and the extended order as JSON. */
+tn_status tn_memgraph_dump_json(const tn_memgraph* mg, const char* path);
+/* CPU dry run of `order` (n = number of memgraph vertices; NULL = the extended serial order):
+ * checks that the order respects every edge, that no vertex writes over a tensor that still
+ * has readers, and that every read finds the tensor it expects.  No arithmetic is done. */
+tn_status tn_memgraph_simulate(const tn_memgraph* mg, const int64_t* order, int64_t n);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Execute (GPU)                                                                               */
+/* ------------------------------------------------------------------------------------------ */
+
+enum { TN_POLICY_FIFO = 0, TN_POLICY_LIFO = 1, TN_POLICY_RANDOM = 2, TN_POLICY_BY_ORDER = 3 };
+
+typedef struct {
+  int32_t policy;        /* which ready vertex the loop takes first */
+  uint64_t order_seed;   /* TN_POLICY_RANDOM */
+  uint64_t delay_seed;   /* transfers: completion is held back by a pseudo-random time ... */
+  uint32_t max_delay_us; /* ... in [0, max_delay_us]; 0 = no injected delay */
+  int32_t max_batch;     /* most same-kind ready vertices put into one kernel launch; 0 = default */
+  int32_t profile;       /* != 0: time every launch with HIP events (fills the *_ms fields) */
+} tn_exec_opts;
+
+typedef struct {
+  double wall_ms;                /* host clock around the whole run */
+  uint64_t h2d_bytes, d2h_bytes; /* all transfers, per direction */
+  int64_t n_vertices, n_launches, n_kernel_launches;
+  int64_t n_offload, n_reload;
+  uint64_t arena_high_water;
+  /* per kernel family (profile != 0): summed device time, launches, algorithmic work */
+  double gemm_ms, attn_ms, ewise_ms, h2d_ms, d2h_ms;
+  int64_t gemm_launches, attn_launches, ewise_launches;
+  double gemm_flops, attn_flops;
+  double ewise_bytes;
+  double kernel_busy_ms; /* union of kernel intervals over all compute streams */
+  double idle_frac;      /* 1 - kernel_busy_ms / span of device activity */
+} tn_exec_report;
+
+/* device_base: device memory of at least the memgraph's cap bytes, 256-byte aligned; borrowed
+ * for the executor's lifetime.  pinned_arena: pinned host memory for offloaded tensors, or NULL
+ * to let the library allocate arena_bytes itself (arena_bytes 0 = the memgraph's safe bound).
+ * Streams are hipStream_t values created by the caller at default priority; n_compute >= 1.
+ * Creation allocates the descriptor tables the kernels read; nothing is allocated later. */
+tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t device_bytes,
+                             void* pinned_arena, uint64_t arena_bytes, void* const* compute_streams,
+                             int32_t n_compute, void* h2d_stream, void* d2h_stream,
+                             tn_executor** out);
+void tn_executor_destroy(tn_executor* ex);
+
+/* Copies every TN_DEVICE input from host_inputs[vid] to its compiled location and waits.  Must
+ * precede each tn_execute of a graph that has such inputs (their locations are reused once they
+ * are dead).  host_inputs has one entry per taskgraph vertex; entries of non-inputs are ignored. */
+tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inputs);
+
+/* Runs the memgraph to completion (Section 5; Appendix A).  host_inputs as above, read by load
+ * vertices (pinned memory recommended); host_outputs[i] receives marked output i.  Synchronous:
+ * returns after every vertex has completed.  Makes no hipMalloc/hipFree/hipHostMalloc call.
+ * opts NULL = FIFO, no delays; report may be NULL.  Calls on one executor must not overlap. */
+tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                     const tn_exec_opts* opts, tn_exec_report* report);
+
+/* Launch order of the last run: copies up to cap memgraph vertex ids in the order the loop
+ * launched them; returns the count. */
+int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TURNIP_H */

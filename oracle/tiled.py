@@ -17,7 +17,7 @@ execution.  Only tests, the smoke check and the benchmark's CPU-baseline leg imp
 
 Vertex kinds (inputs -> output):
   input         ()                                   -> the tile itself
-  gemm          A_0..A_{nk-1}, B_0..B_{nk-1}         -> sum_k A_k @ B_k, k ascending
+  gemm          A_0..A_{nk-1}, B_0..B_{nk-1}         -> sum_k A_k @ B_k, k ascending (B_k held transposed if trans_b)
   rms_stat      X_0..X_{n-1} (tiles of one row block)-> [rows,1] 1/sqrt(mean over all columns of x^2 + eps)
   rms_apply     X, stat, gain[1,c]                   -> x * stat * gain
   rope          X                                    -> rotary embedding; params pos0, col0, head_dim, base
@@ -64,8 +64,8 @@ class TaskGraph:
     shape: List[Tuple[int, int]] = field(default_factory=list)
     dtype: List[str] = field(default_factory=list)
     outputs: List[int] = field(default_factory=list)
-    # vid -> (tensor name, row0, row1, col0, col1) for input tiles and for marked outputs
-    binding: Dict[int, Tuple[str, int, int, int, int]] = field(default_factory=dict)
+    # vid -> (tensor name, row0, row1, col0, col1[, transposed]) for input tiles and marked outputs
+    binding: Dict[int, tuple] = field(default_factory=dict)
 
     def add(self, kind, inputs, shape, dtype, **params) -> int:
         self.kind.append(kind)
@@ -88,7 +88,7 @@ def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
         nk = p["nk"]
         acc = None
         for k in range(nk):
-            t = ins[k] @ ins[nk + k]
+            t = ins[k] @ (ins[nk + k].T if p.get("trans_b") else ins[nk + k])
             acc = t if acc is None else acc + t
         return acc
     if kind == "rms_stat":
@@ -323,18 +323,19 @@ def build_llama_taskgraph(cfg) -> TaskGraph:
 def cut_inputs(tg: TaskGraph, full_f64: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
     """Slice the full input tensors into the tiles the graph's input vertices name."""
     out = {}
-    for v, (name, r0, r1, c0, c1) in tg.binding.items():
+    for v, bnd in tg.binding.items():
         if tg.kind[v] != "input":
             continue
+        name, r0, r1, c0, c1 = bnd[:5]
         a = full_f64[name]
         a = a.reshape(1, -1) if a.ndim == 1 else a
-        out[v] = a[r0:r1, c0:c1]
+        out[v] = a[r0:r1, c0:c1].T if len(bnd) > 5 and bnd[5] else a[r0:r1, c0:c1]
     return out
 
 
 def assemble_outputs(tg: TaskGraph, values: Dict[int, np.ndarray], tokens: int, d: int) -> np.ndarray:
     y = np.full((tokens, d), np.nan)
     for v in tg.outputs:
-        _, r0, r1, c0, c1 = tg.binding[v]
+        _, r0, r1, c0, c1 = tg.binding[v][:5]
         y[r0:r1, c0:c1] = values[v]
     return y

@@ -1,0 +1,672 @@
+// Event-driven execution of a memgraph on one GPU.
+//
+// Section 5 and Appendix A: a central loop launches any vertex whose memgraph dependencies have
+// completed and for which a resource (a stream) is free, learns of completions, frees the
+// resources and looks for more work; it never calls an allocator, because every tensor's GPU
+// location was fixed by the compile.  Offloads take a slot of a pinned host arena, reloads give
+// it back.
+//
+// Differences from the paper's engine, chosen for this hardware: completions are observed by
+// polling one HIP event per stream from the loop thread (no callback thread); a stream carries
+// one *group* at a time, where a group is up to `max_batch` ready vertices of the same kernel
+// family served by a single grouped launch (a 512x512 tile cannot fill 256 compute units on its
+// own, and a launch costs more than such a tile's run time); the operand tables the kernels read
+// are built once at creation, since locations never change.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <map>
+
+#include "graph.h"
+#include "kernels.h"
+
+namespace tn {
+namespace {
+
+using Clock = std::chrono::steady_clock;
+
+struct VInfo {
+  int8_t cls = -1;  // LaunchClass, or -1 for non-kernel vertices
+  int8_t dtype = 0;
+  int16_t head_dim = 0;
+  int32_t desc = -1;
+  int32_t nblocks = 0;
+  double flops = 0, bytes = 0;
+};
+
+struct Slot {  // one stream and the group it carries
+  hipStream_t stream = nullptr;
+  hipEvent_t done = nullptr;
+  bool busy = false, event_seen = false;
+  int family = 0;  // 0 gemm, 1 attention, 2 elementwise, 3 h2d, 4 d2h
+  Clock::time_point release;
+  std::vector<int64_t> verts;
+  int prof = -1;  // index of the (start, stop) event pair when profiling
+  double flops = 0, bytes = 0;
+};
+
+struct ArenaBlock {
+  uint64_t size;
+  bool used;
+};
+
+inline uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+}  // namespace
+}  // namespace tn
+
+using namespace tn;
+
+struct tn_executor {
+  const MemGraph* mg = nullptr;
+  char* dbase = nullptr;
+  uint64_t dbytes = 0;
+  char* arena = nullptr;
+  uint64_t arena_bytes = 0;
+  bool own_arena = false, poisoned = false;
+  int n_compute = 0;
+  std::vector<Slot> slots;  // compute streams, then h2d, then d2h
+  // device tables
+  OpDesc* d_descs = nullptr;
+  void** d_ptrs = nullptr;
+  int32_t* d_aux = nullptr;
+  double* d_theta = nullptr;
+  DeviceTables tables{};
+  std::vector<VInfo> info;
+  // dependency structure (CSR of successors)
+  std::vector<int64_t> succ_start, succ, indeg;
+  // per run
+  std::vector<int64_t> remaining, last_order, arena_off;
+  std::map<uint64_t, ArenaBlock> arena_map;
+  std::vector<hipEvent_t> prof_events;
+  std::vector<int> prof_family;
+};
+
+namespace {
+
+#define TN_HIP(call)                                                                     \
+  do {                                                                                   \
+    hipError_t e_ = (call);                                                              \
+    if (e_ != hipSuccess) return fail(TN_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+tn_status build_tables(tn_executor& ex) {
+  const MemGraph& mg = *ex.mg;
+  const int64_t nv = (int64_t)mg.v.size();
+  std::vector<OpDesc> descs;
+  std::vector<void*> ptrs;
+  std::vector<int32_t> aux;
+  std::vector<double> theta;
+  std::map<std::pair<int32_t, uint32_t>, int32_t> theta_at;
+  ex.info.assign(nv, VInfo{});
+  auto addr = [&](int64_t m, uint64_t need, void** out) -> tn_status {
+    const MVertex& o = mg.v[m];
+    if (o.offset < 0 || (uint64_t)o.offset + need > ex.dbytes || need > o.bytes)
+      return fail(TN_ERR_INVALID, "operand vertex %lld lies outside the device buffer", (long long)m);
+    *out = ex.dbase + o.offset;
+    return TN_OK;
+  };
+  for (int64_t m = 0; m < nv; ++m) {
+    const MVertex& x = mg.v[m];
+    if (x.offset >= 0 && (uint64_t)x.offset + x.bytes > ex.dbytes)
+      return fail(TN_ERR_INVALID, "vertex %lld lies outside the device buffer", (long long)m);
+    if (x.kind != TN_MG_OP) continue;
+    OpDesc d{};
+    d.out = ex.dbase + x.offset;
+    d.ptr0 = (uint32_t)ptrs.size();
+    d.aux0 = (uint32_t)aux.size();
+    d.rows = x.desc.rows;
+    d.cols = x.desc.cols;
+    d.n_in = (int32_t)x.operands.size();
+    d.p = x.p;
+    d.trans_b = x.p.trans_b;
+    const MVertex& first = mg.v[x.operands[0]];
+    d.dtype = first.desc.dtype;
+    for (int64_t o : x.operands) {
+      void* p = nullptr;
+      tn_status s = addr(o, tensor_bytes(mg.v[o].desc), &p);
+      if (s != TN_OK) return s;
+      ptrs.push_back(p);
+    }
+    VInfo& vi = ex.info[m];
+    vi.dtype = (int8_t)d.dtype;
+    auto odesc = [&](int i) -> const tn_tensor_desc& { return mg.v[x.operands[i]].desc; };
+    switch (x.op_kind) {
+      case TN_OP_GEMM: {
+        bool mfma = d.dtype == TN_BF16 && d.trans_b;
+        double K = 0;
+        for (int k = 0; k < x.p.nk; ++k) {
+          aux.push_back(odesc(k).cols);
+          K += odesc(k).cols;
+          if (odesc(k).cols % 8) mfma = false;
+        }
+        vi.cls = mfma ? LC_GEMM_BF16_NT : LC_GEMM_F32;
+        vi.flops = 2.0 * d.rows * d.cols * K;
+        break;
+      }
+      case TN_OP_RMS_STAT:
+        for (int i = 0; i < d.n_in; ++i) aux.push_back(odesc(i).cols);
+        vi.cls = LC_RMS_STAT;
+        vi.bytes = (double)d.rows * x.p.d * elem_bytes(d.dtype) + d.rows * 4.0;
+        break;
+      case TN_OP_RMS_APPLY:
+        vi.cls = LC_RMS_APPLY;
+        vi.bytes = 2.0 * x.bytes + d.rows * 4.0 + d.cols * (double)elem_bytes(d.dtype);
+        break;
+      case TN_OP_ROPE: {
+        vi.cls = LC_ROPE;
+        vi.bytes = 2.0 * x.bytes;
+        uint32_t bits;
+        memcpy(&bits, &x.p.rope_base, 4);
+        auto key = std::make_pair(x.p.head_dim, bits);
+        auto it = theta_at.find(key);
+        if (it == theta_at.end()) {
+          it = theta_at.emplace(key, (int32_t)theta.size()).first;
+          for (int i = 0; i < x.p.head_dim / 2; ++i)
+            theta.push_back(std::pow((double)x.p.rope_base, -2.0 * i / x.p.head_dim));
+        }
+        d.aux0 = (uint32_t)it->second;
+        break;
+      }
+      case TN_OP_ATTN_BLOCK: {
+        const int nq = x.p.n_q_tiles, nkv = x.p.n_kv_tiles, nc = x.p.n_col_tiles, hd = x.p.head_dim;
+        const int tq = odesc(0).rows, tk = odesc(nq * nc).rows, tc = odesc(0).cols;
+        int q_rows = 0, kv_rows = 0;
+        // the kernels address tiles as a uniform grid: equal tiles except a shorter last row tile
+        for (int r = 0; r < nq; ++r) {
+          q_rows += odesc(r * nc).rows;
+          if ((r + 1 < nq && odesc(r * nc).rows != tq) || odesc(r * nc).rows > tq)
+            return fail(TN_ERR_SHAPE, "attn_block %lld: Q row tiles are not uniform", (long long)m);
+        }
+        for (int r = 0; r < nkv; ++r) {
+          kv_rows += odesc(nq * nc + r * nc).rows;
+          if ((r + 1 < nkv && odesc(nq * nc + r * nc).rows != tk) || odesc(nq * nc + r * nc).rows > tk)
+            return fail(TN_ERR_SHAPE, "attn_block %lld: K/V row tiles are not uniform", (long long)m);
+        }
+        for (int c = 0; c < nc; ++c)
+          if (odesc(c).cols != tc) return fail(TN_ERR_SHAPE, "attn_block %lld: column tiles are not uniform", (long long)m);
+        if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_block %lld: head_dim must be 64 or 128", (long long)m);
+        aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
+        vi.cls = (d.dtype == TN_BF16 && tc % 8 == 0) ? LC_ATTN_BF16 : LC_ATTN_F32;
+        vi.head_dim = (int16_t)hd;
+        vi.flops = 4.0 * q_rows * kv_rows * (double)(nc * tc);
+        break;
+      }
+      case TN_OP_ATTN_COMBINE:
+        vi.cls = LC_ATTN_COMBINE;
+        d.dtype = x.desc.dtype;
+        vi.dtype = (int8_t)d.dtype;
+        vi.bytes = x.bytes + d.n_in * ((double)d.rows * d.cols * 4.0);
+        break;
+      case TN_OP_SILU_MUL:
+      case TN_OP_ADD:
+        vi.cls = x.op_kind == TN_OP_ADD ? LC_ADD : LC_SILU_MUL;
+        vi.bytes = 3.0 * x.bytes;
+        break;
+      default: return fail(TN_ERR_INVALID, "vertex %lld has an unknown kind", (long long)m);
+    }
+    d.nblocks = blocks_for(vi.cls, d, aux.data());
+    vi.nblocks = d.nblocks;
+    vi.desc = (int32_t)descs.size();
+    descs.push_back(d);
+  }
+  auto upload = [&](const void* src, size_t bytes, void** dst) -> tn_status {
+    if (bytes == 0) bytes = 16;
+    TN_HIP(hipMalloc(dst, bytes));
+    if (src) TN_HIP(hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice));
+    return TN_OK;
+  };
+  tn_status s;
+  if ((s = upload(descs.empty() ? nullptr : descs.data(), descs.size() * sizeof(OpDesc), (void**)&ex.d_descs)) != TN_OK) return s;
+  if ((s = upload(ptrs.empty() ? nullptr : ptrs.data(), ptrs.size() * sizeof(void*), (void**)&ex.d_ptrs)) != TN_OK) return s;
+  if ((s = upload(aux.empty() ? nullptr : aux.data(), aux.size() * 4, (void**)&ex.d_aux)) != TN_OK) return s;
+  if ((s = upload(theta.empty() ? nullptr : theta.data(), theta.size() * 8, (void**)&ex.d_theta)) != TN_OK) return s;
+  ex.tables = {ex.d_descs, ex.d_ptrs, ex.d_aux, ex.d_theta};
+  return TN_OK;
+}
+
+// first-fit host arena with coalescing; offsets are 256-byte aligned
+bool arena_alloc(tn_executor& ex, uint64_t size, uint64_t* off) {
+  size = (size + 255) / 256 * 256;
+  for (auto it = ex.arena_map.begin(); it != ex.arena_map.end(); ++it) {
+    if (it->second.used || it->second.size < size) continue;
+    const uint64_t o = it->first, rest = it->second.size - size;
+    it->second = {size, true};
+    if (rest) ex.arena_map[o + size] = {rest, false};
+    *off = o;
+    return true;
+  }
+  return false;
+}
+
+void arena_free(tn_executor& ex, uint64_t off) {
+  auto it = ex.arena_map.find(off);
+  it->second.used = false;
+  auto nx = std::next(it);
+  if (nx != ex.arena_map.end() && !nx->second.used) {
+    it->second.size += nx->second.size;
+    ex.arena_map.erase(nx);
+  }
+  if (it != ex.arena_map.begin()) {
+    auto pv = std::prev(it);
+    if (!pv->second.used) {
+      pv->second.size += it->second.size;
+      ex.arena_map.erase(it);
+    }
+  }
+}
+
+int family_of(int cls) {
+  switch (cls) {
+    case LC_GEMM_F32:
+    case LC_GEMM_BF16_NT: return 0;
+    case LC_ATTN_F32:
+    case LC_ATTN_BF16: return 1;
+    default: return 2;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t device_bytes, void* pinned_arena,
+                             uint64_t arena_bytes, void* const* compute_streams, int32_t n_compute,
+                             void* h2d_stream, void* d2h_stream, tn_executor** out) {
+  if (!mg || !device_base || !compute_streams || n_compute < 1 || n_compute > 64 || !out)
+    return fail(TN_ERR_INVALID, "NULL argument or bad stream count");
+  if ((uintptr_t)device_base % 256) return fail(TN_ERR_INVALID, "device_base must be 256-byte aligned");
+  if (device_bytes < mg->stats.high_water)
+    return fail(TN_ERR_INVALID, "device buffer of %llu bytes is smaller than the memgraph's high-water mark %llu",
+                (unsigned long long)device_bytes, (unsigned long long)mg->stats.high_water);
+  auto* ex = new (std::nothrow) tn_executor();
+  if (!ex) return fail(TN_ERR_INVALID, "out of host memory");
+  ex->mg = mg;
+  ex->dbase = (char*)device_base;
+  ex->dbytes = device_bytes;
+  ex->n_compute = n_compute;
+  ex->slots.resize(n_compute + 2);
+  for (int i = 0; i < n_compute; ++i) ex->slots[i].stream = (hipStream_t)compute_streams[i];
+  ex->slots[n_compute].stream = (hipStream_t)h2d_stream;
+  ex->slots[n_compute + 1].stream = (hipStream_t)d2h_stream;
+  auto bail = [&](tn_status s) {
+    tn_executor_destroy(ex);
+    return s;
+  };
+  for (auto& sl : ex->slots) {
+    hipError_t e = hipEventCreateWithFlags(&sl.done, hipEventDisableTiming);
+    if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)));
+  }
+  if (arena_bytes == 0) arena_bytes = mg->stats.host_arena_bytes;
+  ex->arena_bytes = arena_bytes / 256 * 256;
+  if (pinned_arena) {
+    ex->arena = (char*)pinned_arena;
+  } else if (ex->arena_bytes) {
+    hipError_t e = hipHostMalloc((void**)&ex->arena, ex->arena_bytes, hipHostMallocDefault);
+    if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipHostMalloc(%llu): %s", (unsigned long long)ex->arena_bytes, hipGetErrorString(e)));
+    ex->own_arena = true;
+  }
+  // dependency structure
+  const int64_t nv = (int64_t)mg->v.size();
+  ex->indeg.assign(nv, 0);
+  ex->succ_start.assign(nv + 1, 0);
+  for (const auto& e : mg->edges) {
+    ++ex->succ_start[e.from + 1];
+    ++ex->indeg[e.to];
+  }
+  for (int64_t i = 0; i < nv; ++i) ex->succ_start[i + 1] += ex->succ_start[i];
+  ex->succ.resize(mg->edges.size());
+  {
+    std::vector<int64_t> at(ex->succ_start.begin(), ex->succ_start.end() - 1);
+    for (const auto& e : mg->edges) ex->succ[at[e.from]++] = e.to;
+  }
+  ex->arena_off.assign(nv, -1);
+  tn_status s = build_tables(*ex);
+  if (s != TN_OK) return bail(s);
+  *out = ex;
+  return TN_OK;
+}
+
+void tn_executor_destroy(tn_executor* ex) {
+  if (!ex) return;
+  for (auto& sl : ex->slots)
+    if (sl.done) (void)hipEventDestroy(sl.done);
+  for (auto e : ex->prof_events) (void)hipEventDestroy(e);
+  if (ex->d_descs) (void)hipFree(ex->d_descs);
+  if (ex->d_ptrs) (void)hipFree(ex->d_ptrs);
+  if (ex->d_aux) (void)hipFree(ex->d_aux);
+  if (ex->d_theta) (void)hipFree(ex->d_theta);
+  if (ex->own_arena && ex->arena) (void)hipHostFree(ex->arena);
+  delete ex;
+}
+
+tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inputs) {
+  if (!ex || !host_inputs) return fail(TN_ERR_INVALID, "NULL argument");
+  if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
+  const MemGraph& mg = *ex->mg;
+  hipStream_t s = ex->slots[ex->n_compute].stream;
+  for (int64_t m = 0; m < mg.n_task; ++m) {
+    const MVertex& x = mg.v[m];
+    if (x.kind != TN_MG_INPUT) continue;
+    if (!host_inputs[m]) return fail(TN_ERR_INVALID, "no host buffer for device-resident input %lld", (long long)m);
+    TN_HIP(hipMemcpyAsync(ex->dbase + x.offset, host_inputs[m], x.bytes, hipMemcpyHostToDevice, s));
+  }
+  TN_HIP(hipStreamSynchronize(s));
+  return TN_OK;
+}
+
+tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                     const tn_exec_opts* opts_in, tn_exec_report* report) {
+  if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
+  if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
+  const MemGraph& mg = *ex->mg;
+  const int64_t nv = (int64_t)mg.v.size();
+  tn_exec_opts opt{};
+  if (opts_in) opt = *opts_in;
+  const int max_batch = opt.max_batch > 0 ? std::min<int>(opt.max_batch, kMaxBatch) : 64;
+  // every buffer the run will touch must be there before anything is launched
+  for (int64_t m = 0; m < nv; ++m) {
+    const MVertex& x = mg.v[m];
+    if (x.kind == TN_MG_LOAD && (!host_inputs || !host_inputs[x.src]))
+      return fail(TN_ERR_INVALID, "no host buffer for input %d", (int)x.src);
+    if (x.kind == TN_MG_STORE && (!host_outputs || !host_outputs[x.output_index]))
+      return fail(TN_ERR_INVALID, "no host buffer for output %d", x.output_index);
+  }
+  ex->remaining = ex->indeg;
+  ex->last_order.clear();
+  ex->last_order.reserve(nv);
+  ex->arena_map.clear();
+  if (ex->arena_bytes) ex->arena_map[0] = {ex->arena_bytes, false};
+  std::fill(ex->arena_off.begin(), ex->arena_off.end(), -1);
+  for (auto& sl : ex->slots) {
+    sl.busy = false;
+    sl.verts.clear();
+  }
+  tn_exec_report rep{};
+  std::vector<int64_t> ready_k, ready_h2d, ready_d2h, work;
+  int64_t completed = 0;
+  uint64_t rng = mix64(opt.order_seed ^ 0x7475726E6970ull);
+  uint64_t arena_used = 0;
+  size_t prof_used = 0;
+  hipEvent_t prof_base = nullptr;
+  tn_status status = TN_OK;
+
+  auto prof_event = [&](hipEvent_t* e) -> bool {
+    if (prof_used == ex->prof_events.size()) {
+      hipEvent_t ne;
+      if (hipEventCreate(&ne) != hipSuccess) return false;
+      ex->prof_events.push_back(ne);
+    }
+    *e = ex->prof_events[prof_used++];
+    return true;
+  };
+
+  // a vertex whose dependencies are all complete joins a ready list; vertices with no work
+  // (inputs already in place, drops) complete on the spot
+  auto complete = [&](int64_t first) {
+    work.push_back(first);
+    while (!work.empty()) {
+      const int64_t m = work.back();
+      work.pop_back();
+      ++completed;
+      for (int64_t i = ex->succ_start[m]; i < ex->succ_start[m + 1]; ++i) {
+        const int64_t w = ex->succ[i];
+        if (--ex->remaining[w] != 0) continue;
+        switch (mg.v[w].kind) {
+          case TN_MG_INPUT:
+          case TN_MG_DROP: ex->last_order.push_back(w); work.push_back(w); break;
+          case TN_MG_OP: ready_k.push_back(w); break;
+          case TN_MG_LOAD:
+          case TN_MG_RELOAD: ready_h2d.push_back(w); break;
+          default: ready_d2h.push_back(w); break;
+        }
+      }
+    }
+  };
+  for (int64_t m = 0; m < nv; ++m) {
+    if (ex->indeg[m] != 0) continue;
+    switch (mg.v[m].kind) {
+      case TN_MG_INPUT:
+      case TN_MG_DROP: ex->last_order.push_back(m); complete(m); break;
+      case TN_MG_OP: ready_k.push_back(m); break;
+      case TN_MG_LOAD:
+      case TN_MG_RELOAD: ready_h2d.push_back(m); break;
+      default: ready_d2h.push_back(m); break;
+    }
+  }
+
+  auto pick = [&](const std::vector<int64_t>& r) -> size_t {
+    switch (opt.policy) {
+      case TN_POLICY_LIFO: return r.size() - 1;
+      case TN_POLICY_RANDOM: rng = mix64(rng); return (size_t)(rng % r.size());
+      case TN_POLICY_BY_ORDER: {
+        size_t best = 0;
+        for (size_t i = 1; i < r.size(); ++i)
+          if (mg.v[r[i]].order_pos < mg.v[r[best]].order_pos) best = i;
+        return best;
+      }
+      default: return 0;
+    }
+  };
+
+  auto hip_fail = [&](const char* what, hipError_t e) {
+    ex->poisoned = true;
+    status = fail(TN_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  };
+
+  if (opt.profile) {
+    if (!prof_event(&prof_base) || hipEventRecord(prof_base, ex->slots[0].stream) != hipSuccess)
+      return fail(TN_ERR_HIP, "cannot record the profiling base event");
+    ex->prof_family.clear();
+  }
+  const auto t_start = Clock::now();
+  Batch batch;
+  std::vector<int64_t> same;
+
+  while (completed < nv && status == TN_OK) {
+    bool progressed = false;
+    // ---- launch transfers: one per direction at a time -----------------------------------
+    for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
+      Slot& sl = ex->slots[ex->n_compute + dir];
+      auto& r = dir == 0 ? ready_h2d : ready_d2h;
+      if (sl.busy || r.empty()) continue;
+      const size_t i = pick(r);
+      const int64_t m = r[i];
+      const MVertex& x = mg.v[m];
+      hipError_t e = hipSuccess;
+      if (x.kind == TN_MG_LOAD) {
+        e = hipMemcpyAsync(ex->dbase + x.offset, host_inputs[x.src], x.bytes, hipMemcpyHostToDevice, sl.stream);
+      } else if (x.kind == TN_MG_RELOAD) {
+        const int64_t off = ex->arena_off[x.operands[0]];
+        e = hipMemcpyAsync(ex->dbase + x.offset, ex->arena + off, x.bytes, hipMemcpyHostToDevice, sl.stream);
+      } else if (x.kind == TN_MG_STORE) {
+        e = hipMemcpyAsync(host_outputs[x.output_index], ex->dbase + mg.v[x.operands[0]].offset, x.bytes,
+                           hipMemcpyDeviceToHost, sl.stream);
+      } else {  // offload
+        uint64_t off;
+        if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
+          status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
+                        (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
+          break;
+        }
+        ex->arena_off[m] = (int64_t)off;
+        arena_used += (x.bytes + 255) / 256 * 256;
+        rep.arena_high_water = std::max(rep.arena_high_water, arena_used);
+        e = hipMemcpyAsync(ex->arena + off, ex->dbase + mg.v[x.operands[0]].offset, x.bytes, hipMemcpyDeviceToHost, sl.stream);
+        ++rep.n_offload;
+      }
+      if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
+      if (e != hipSuccess) { hip_fail("transfer", e); break; }
+      r.erase(r.begin() + i);
+      sl.busy = true;
+      sl.event_seen = false;
+      sl.family = 3 + dir;
+      sl.verts.assign(1, m);
+      sl.bytes = (double)x.bytes;
+      (dir == 0 ? rep.h2d_bytes : rep.d2h_bytes) += x.bytes;
+      rep.n_reload += x.kind == TN_MG_RELOAD;
+      ex->last_order.push_back(m);
+      ++rep.n_launches;
+      progressed = true;
+    }
+    // ---- launch kernels: one group per free compute stream --------------------------------
+    for (int si = 0; si < ex->n_compute && status == TN_OK && !ready_k.empty(); ++si) {
+      Slot& sl = ex->slots[si];
+      if (sl.busy) continue;
+      const size_t i0 = pick(ready_k);
+      const VInfo lead = ex->info[ready_k[i0]];
+      same.clear();
+      same.push_back(ready_k[i0]);
+      // the rest of the group: ready vertices of the same family, in the policy's order
+      if (max_batch > 1) {
+        std::vector<size_t> idx;
+        for (size_t i = 0; i < ready_k.size(); ++i) {
+          const VInfo& v = ex->info[ready_k[i]];
+          if (i != i0 && v.cls == lead.cls && v.dtype == lead.dtype && v.head_dim == lead.head_dim) idx.push_back(i);
+        }
+        if (opt.policy == TN_POLICY_LIFO) std::reverse(idx.begin(), idx.end());
+        else if (opt.policy == TN_POLICY_RANDOM)
+          for (size_t k = idx.size(); k > 1; --k) { rng = mix64(rng); std::swap(idx[k - 1], idx[rng % k]); }
+        else if (opt.policy == TN_POLICY_BY_ORDER)
+          std::sort(idx.begin(), idx.end(), [&](size_t a, size_t b) { return mg.v[ready_k[a]].order_pos < mg.v[ready_k[b]].order_pos; });
+        for (size_t k = 0; k < idx.size() && (int)same.size() < max_batch; ++k) same.push_back(ready_k[idx[k]]);
+      }
+      batch.n = (int32_t)same.size();
+      int32_t max_blocks = 0;
+      sl.flops = sl.bytes = 0;
+      for (int k = 0; k < batch.n; ++k) {
+        const VInfo& v = ex->info[same[k]];
+        batch.idx[k] = v.desc;
+        max_blocks = std::max(max_blocks, v.nblocks);
+        sl.flops += v.flops;
+        sl.bytes += v.bytes;
+      }
+      hipError_t e = hipSuccess;
+      sl.prof = -1;
+      if (opt.profile) {
+        hipEvent_t a, b;
+        if (prof_event(&a) && prof_event(&b)) {
+          sl.prof = (int)prof_used - 2;
+          e = hipEventRecord(a, sl.stream);
+        }
+      }
+      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, ex->tables, batch, max_blocks, sl.stream);
+      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof + 1], sl.stream);
+      if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
+      if (e != hipSuccess) { hip_fail("kernel launch", e); break; }
+      // remove the group from the ready list
+      {
+        std::vector<char> taken;  // small: mark by sorting the group
+        std::sort(same.begin(), same.end());
+        size_t w = 0;
+        for (size_t i = 0; i < ready_k.size(); ++i)
+          if (!std::binary_search(same.begin(), same.end(), ready_k[i])) ready_k[w++] = ready_k[i];
+        ready_k.resize(w);
+      }
+      sl.busy = true;
+      sl.event_seen = false;
+      sl.family = family_of(lead.cls);
+      sl.verts = same;
+      for (int64_t m : same) ex->last_order.push_back(m);
+      ++rep.n_launches;
+      ++rep.n_kernel_launches;
+      if (sl.family == 0) { ++rep.gemm_launches; rep.gemm_flops += sl.flops; }
+      else if (sl.family == 1) { ++rep.attn_launches; rep.attn_flops += sl.flops; }
+      else { ++rep.ewise_launches; rep.ewise_bytes += sl.bytes; }
+      if (sl.prof >= 0) ex->prof_family.push_back(sl.family), ex->prof_family.push_back(sl.prof);
+      progressed = true;
+    }
+    if (status != TN_OK) break;
+    // ---- completions -----------------------------------------------------------------------
+    for (auto& sl : ex->slots) {
+      if (!sl.busy) continue;
+      if (!sl.event_seen) {
+        hipError_t e = hipEventQuery(sl.done);
+        if (e == hipErrorNotReady) continue;
+        if (e != hipSuccess) { hip_fail("hipEventQuery", e); break; }
+        sl.event_seen = true;
+        sl.release = Clock::now();
+        if (sl.family >= 3 && opt.max_delay_us) {
+          // injected transfer delay: the completion is reported late; the copy itself ran normally
+          const uint64_t us = mix64(opt.delay_seed ^ (uint64_t)sl.verts[0] * 0x9E3779B1ull) % (opt.max_delay_us + 1ull);
+          sl.release += std::chrono::microseconds(us);
+        }
+      }
+      if (Clock::now() < sl.release) continue;
+      sl.busy = false;
+      for (int64_t m : sl.verts) {
+        const MVertex& x = mg.v[m];
+        if (x.kind == TN_MG_RELOAD) {
+          const int64_t o = x.operands[0];
+          arena_free(*ex, (uint64_t)ex->arena_off[o]);
+          arena_used -= (mg.v[o].bytes + 255) / 256 * 256;
+          ex->arena_off[o] = -1;
+        }
+        complete(m);
+      }
+      progressed = true;
+    }
+    if (!progressed) {
+      bool any_busy = false;
+      for (auto& sl : ex->slots) any_busy |= sl.busy;
+      if (!any_busy && ready_k.empty() && ready_h2d.empty() && ready_d2h.empty() && completed < nv) {
+        status = fail(TN_ERR_CYCLE, "no vertex is ready and none is running: %lld of %lld completed",
+                      (long long)completed, (long long)nv);
+        break;
+      }
+    }
+  }
+  // drain whatever is still in flight (error paths): every stream the run used is idle on return
+  for (auto& sl : ex->slots)
+    if (sl.busy) {
+      (void)hipStreamSynchronize(sl.stream);
+      sl.busy = false;
+    }
+  rep.wall_ms = std::chrono::duration<double, std::milli>(Clock::now() - t_start).count();
+  rep.n_vertices = completed;
+  if (status == TN_OK && opt.profile) {
+    // device time per family and the union of kernel intervals
+    std::vector<std::pair<float, float>> iv;
+    for (size_t k = 0; k + 1 < ex->prof_family.size(); k += 2) {
+      const int fam = ex->prof_family[k], p = ex->prof_family[k + 1];
+      float t0 = 0, t1 = 0;
+      if (hipEventElapsedTime(&t0, prof_base, ex->prof_events[p]) != hipSuccess ||
+          hipEventElapsedTime(&t1, prof_base, ex->prof_events[p + 1]) != hipSuccess)
+        continue;
+      (fam == 0 ? rep.gemm_ms : fam == 1 ? rep.attn_ms : rep.ewise_ms) += t1 - t0;
+      iv.emplace_back(t0, t1);
+    }
+    std::sort(iv.begin(), iv.end());
+    float lo = 0, hi = -1, first = 0, last = 0;
+    for (size_t k = 0; k < iv.size(); ++k) {
+      if (k == 0) { first = iv[0].first; lo = iv[0].first; hi = iv[0].second; }
+      else if (iv[k].first <= hi) hi = std::max(hi, iv[k].second);
+      else { rep.kernel_busy_ms += hi - lo; lo = iv[k].first; hi = iv[k].second; }
+      last = std::max(last, iv[k].second);
+    }
+    if (!iv.empty()) {
+      rep.kernel_busy_ms += hi - lo;
+      const double span = std::max<double>(last - first, 1e-9);
+      rep.idle_frac = 1.0 - rep.kernel_busy_ms / span;
+    }
+  }
+  if (report) *report = rep;
+  return status;
+}
+
+int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap) {
+  if (!ex) return TN_ERR_INVALID;
+  const int64_t n = (int64_t)ex->last_order.size();
+  for (int64_t i = 0; i < n && i < cap; ++i) out[i] = ex->last_order[i];
+  return n;
+}
+
+}  // extern "C"

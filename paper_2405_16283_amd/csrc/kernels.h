@@ -1,0 +1,67 @@
+// Interface between the executor (host) and the gfx950 task kernels.
+//
+// Every kernel is *grouped*: one launch serves a batch of ready memgraph vertices of the same
+// launch class.  Because a memgraph fixes the GPU location of every tensor before execution
+// (Section 5, first paragraph), the per-vertex operand tables can be built once, at executor
+// creation, and stay in device memory; a launch only names the vertices it covers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "turnip.h"
+
+namespace tn {
+
+// One kernel-call vertex, as the kernels see it.
+struct OpDesc {
+  void* out;        // device address of the output tensor
+  uint32_t ptr0;    // index of the first operand address in the pointer table
+  uint32_t aux0;    // index of the first auxiliary integer (meaning depends on the kind)
+  int32_t rows, cols;  // output shape
+  int32_t n_in;
+  int32_t nblocks;  // workgroups this vertex needs in its launch class
+  int32_t dtype;    // storage type of its non-statistics operands (TN_F32 / TN_BF16)
+  int32_t trans_b;  // gemm: B tiles are stored [cols, K]
+  tn_op_params p;
+};
+
+// Launch classes: vertices of one class can share a launch.
+enum LaunchClass {
+  LC_GEMM_F32 = 0,   // generic fp32-accumulate GEMM on the vector ALUs, any layout, fp32 or bf16 storage
+  LC_GEMM_BF16_NT,   // MFMA bf16 GEMM, B tiles stored [cols, K]
+  LC_RMS_STAT,
+  LC_RMS_APPLY,
+  LC_ROPE,
+  LC_ATTN_F32,       // attention block on the vector ALUs (fp32 storage, or shapes the MFMA kernel does not take)
+  LC_ATTN_BF16,      // MFMA attention block
+  LC_ATTN_COMBINE,
+  LC_SILU_MUL,
+  LC_ADD,
+  LC_COUNT
+};
+
+constexpr int kMaxBatch = 240;  // vertices per launch (the list travels in the kernel arguments)
+
+struct Batch {
+  int32_t n;
+  int32_t idx[kMaxBatch];  // indices into the descriptor table
+};
+
+struct DeviceTables {
+  const OpDesc* descs;
+  void* const* ptrs;
+  const int32_t* aux;
+  const double* rope_theta;  // base^(-2i/head_dim), i < head_dim/2, for the graph's rotary vertices
+};
+
+// Workgroups a vertex needs in the given class (host side, used to fill OpDesc::nblocks).
+int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux);
+
+// Enqueues one grouped launch on `stream`.  All vertices of the batch share the class, the storage
+// type and (for attention) the head size.  max_blocks = largest nblocks in the batch.
+hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t, const Batch& b,
+                        int32_t max_blocks, hipStream_t stream);
+
+}  // namespace tn

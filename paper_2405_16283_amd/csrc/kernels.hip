@@ -1,0 +1,569 @@
+// gfx950 task kernels of the memgraph runtime: tile GEMMs, blocked attention with online
+// softmax, attention combine, RMSNorm (statistic + apply), rotary embedding, SiLU*mul, add.
+//
+// The paper runs such vertices through a vendor tensor library plus a few hand-written kernels
+// (Appendix A); here every vertex kind has its own kernel, written for 64-wide wavefronts and
+// the MFMA units.  All kernels are grouped (see kernels.h) and deterministic: fixed summation
+// order, no atomics, so any dispatch order gives the same bits.
+#include "kernels.h"
+
+namespace tn {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef unsigned short bf16_t;  // storage of a bf16 value
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {  // round to nearest, ties to even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ld(const T* p);
+template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t* p) { return bf2f(*p); }
+template <typename T> __device__ __forceinline__ void st(T* p, float v);
+template <> __device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p = f2bf(v); }
+
+// ---------------------------------------------------------------------------------------------
+// elementwise: add, silu*mul
+// ---------------------------------------------------------------------------------------------
+template <typename T, bool SILU>
+__global__ void __launch_bounds__(256) ewise2_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* x = (const T*)t.ptrs[d.ptr0];
+  const T* y = (const T*)t.ptrs[d.ptr0 + 1];
+  T* o = (T*)d.out;
+  const int n = d.rows * d.cols;
+  const int i0 = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i0 >= n) return;
+  float a[8], c[8];
+  if (i0 + 8 <= n) {
+    if constexpr (sizeof(T) == 2) {
+      uint4 va = *(const uint4*)(x + i0), vb = *(const uint4*)(y + i0);
+      const bf16_t* pa = (const bf16_t*)&va;
+      const bf16_t* pb = (const bf16_t*)&vb;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { a[k] = bf2f(pa[k]); c[k] = bf2f(pb[k]); }
+    } else {
+      float4 a0 = *(const float4*)(x + i0), a1 = *(const float4*)(x + i0 + 4);
+      float4 c0 = *(const float4*)(y + i0), c1 = *(const float4*)(y + i0 + 4);
+      a[0] = a0.x; a[1] = a0.y; a[2] = a0.z; a[3] = a0.w; a[4] = a1.x; a[5] = a1.y; a[6] = a1.z; a[7] = a1.w;
+      c[0] = c0.x; c[1] = c0.y; c[2] = c0.z; c[3] = c0.w; c[4] = c1.x; c[5] = c1.y; c[6] = c1.z; c[7] = c1.w;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a[k] = SILU ? a[k] / (1.f + __expf(-a[k])) * c[k] : a[k] + c[k];
+    if constexpr (sizeof(T) == 2) {
+      uint4 vo;
+      bf16_t* po = (bf16_t*)&vo;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) po[k] = f2bf(a[k]);
+      *(uint4*)(o + i0) = vo;
+    } else {
+      *(float4*)(o + i0) = make_float4(a[0], a[1], a[2], a[3]);
+      *(float4*)(o + i0 + 4) = make_float4(a[4], a[5], a[6], a[7]);
+    }
+  } else {
+    for (int i = i0; i < n; ++i) {
+      float u = ld(x + i), v = ld(y + i);
+      st(o + i, SILU ? u / (1.f + __expf(-u)) * v : u + v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm statistic: one wavefront per row, over all column tiles of the row block
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) rms_stat_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= d.rows) return;
+  float ss = 0.f;
+  for (int j = 0; j < d.n_in; ++j) {
+    const int cols = t.aux[d.aux0 + j];
+    const T* x = (const T*)t.ptrs[d.ptr0 + j] + (size_t)row * cols;
+    for (int c = lane * 8; c < cols; c += 512) {
+      if (c + 8 <= cols && (cols & 7) == 0) {
+        if constexpr (sizeof(T) == 2) {
+          uint4 v = *(const uint4*)(x + c);
+          const bf16_t* p = (const bf16_t*)&v;
+#pragma unroll
+          for (int k = 0; k < 8; ++k) { float f = bf2f(p[k]); ss += f * f; }
+        } else {
+          float4 v0 = *(const float4*)(x + c), v1 = *(const float4*)(x + c + 4);
+          ss += v0.x * v0.x; ss += v0.y * v0.y; ss += v0.z * v0.z; ss += v0.w * v0.w;
+          ss += v1.x * v1.x; ss += v1.y * v1.y; ss += v1.z * v1.z; ss += v1.w * v1.w;
+        }
+      } else {
+        for (int k = c; k < min(c + 8, cols); ++k) { float f = ld(x + k); ss += f * f; }
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if (lane == 0) ((float*)d.out)[row] = 1.0f / sqrtf(ss / (float)d.p.d + d.p.eps);
+}
+
+// RMSNorm apply: out = x * stat[row] * gain[col]
+template <typename T>
+__global__ void __launch_bounds__(256) rms_apply_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* x = (const T*)t.ptrs[d.ptr0];
+  const float* stat = (const float*)t.ptrs[d.ptr0 + 1];
+  const T* g = (const T*)t.ptrs[d.ptr0 + 2];
+  T* o = (T*)d.out;
+  const int segs = (d.cols + 7) / 8;
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= d.rows * segs) return;
+  const int row = id / segs, c0 = (id % segs) * 8;
+  const float s = stat[row];
+  for (int c = c0; c < min(c0 + 8, d.cols); ++c)
+    st(o + (size_t)row * d.cols + c, ld(x + (size_t)row * d.cols + c) * s * ld(g + c));
+}
+
+// Rotary embedding on interleaved pairs; the angle is formed and reduced in double so that long
+// sequences lose no accuracy, then the single-precision sincos is taken of the reduced angle
+template <typename T>
+__global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* x = (const T*)t.ptrs[d.ptr0];
+  T* o = (T*)d.out;
+  const int pairs = d.cols / 2;
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= d.rows * pairs) return;
+  const int row = id / pairs, pc = id % pairs;
+  const int i = ((d.p.col0 + 2 * pc) % d.p.head_dim) / 2;
+  double ang = (double)(d.p.pos0 + row) * t.rope_theta[d.aux0 + i];
+  ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+  float sn, cs;
+  sincosf((float)ang, &sn, &cs);
+  const size_t e = (size_t)row * d.cols + 2 * pc;
+  const float xe = ld(x + e), xo = ld(x + e + 1);
+  st(o + e, xe * cs - xo * sn);
+  st(o + e + 1, xe * sn + xo * cs);
+}
+
+// Attention combine: merge the partials of one query block (j ascending) and normalise
+template <typename T>
+__global__ void __launch_bounds__(256) attn_combine_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= d.rows * d.cols) return;
+  const int row = id / d.cols, c = id % d.cols;
+  const int hd = d.p.head_dim, hpg = d.p.hpg, gw = hd * hpg, ldp = gw + 2 * hpg;
+  const int col = d.p.col0 + c, h = col / hd;
+  const size_t r = (size_t)(d.p.row0 + row) * ldp;
+  float mstar = -INFINITY;
+  for (int j = 0; j < d.n_in; ++j) mstar = fmaxf(mstar, ((const float*)t.ptrs[d.ptr0 + j])[r + gw + h]);
+  float num = 0.f, den = 0.f;
+  for (int j = 0; j < d.n_in; ++j) {
+    const float* p = (const float*)t.ptrs[d.ptr0 + j];
+    const float w = __expf(p[r + gw + h] - mstar);
+    num += p[r + col] * w;
+    den += p[r + gw + hpg + h] * w;
+  }
+  st((T*)d.out + (size_t)row * d.cols + c, num / den);
+}
+
+// ---------------------------------------------------------------------------------------------
+// generic GEMM on the vector ALUs (fp32 accumulate): 64x64 output tile per workgroup
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  __shared__ float As[16][68];
+  __shared__ float Bs[16][68];
+  const int M = d.rows, N = d.cols, nk = d.p.nk;
+  const int tn_ = (N + 63) / 64;
+  const int m0 = (blockIdx.x / tn_) * 64, n0 = (blockIdx.x % tn_) * 64;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {};
+  for (int kt = 0; kt < nk; ++kt) {
+    const T* A = (const T*)t.ptrs[d.ptr0 + kt];
+    const T* B = (const T*)t.ptrs[d.ptr0 + nk + kt];
+    const int K = t.aux[d.aux0 + kt];
+    for (int k0 = 0; k0 < K; k0 += 16) {
+      {
+        const int r = threadIdx.x / 4, kk = (threadIdx.x % 4) * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int gr = m0 + r, gk = k0 + kk + i;
+          As[kk + i][r] = (gr < M && gk < K) ? ld(A + (size_t)gr * K + gk) : 0.f;
+        }
+        if (d.trans_b) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int gc = n0 + r, gk = k0 + kk + i;
+            Bs[kk + i][r] = (gc < N && gk < K) ? ld(B + (size_t)gc * K + gk) : 0.f;
+          }
+        } else {
+          const int kr = threadIdx.x / 16, cc = (threadIdx.x % 16) * 4;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int gc = n0 + cc + i, gk = k0 + kr;
+            Bs[kr][cc + i] = (gc < N && gk < K) ? ld(B + (size_t)gk * N + gc) : 0.f;
+          }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        float a[4], bb[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; bb[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], bb[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+  T* Cp = (T*)d.out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = m0 + ty * 4 + i, c = n0 + tx * 4 + j;
+      if (r < M && c < N) st(Cp + (size_t)r * N + c, acc[i][j]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA bf16 GEMM, C[M,N] = sum_k A_k[M,K_k] * B_k[N,K_k]^T, fp32 accumulate, bf16 store.
+// 128x128 output tile per workgroup of 4 wavefronts (2x2, 64x64 each = 2x2 MFMA 32x32 tiles),
+// K step 64 staged through LDS.  Rows are padded by 8 elements so that the 16-byte fragment
+// reads of the 32 lanes of a half-wave fall on different banks.
+// ---------------------------------------------------------------------------------------------
+constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_LD = GB_K + 8;
+
+__global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  __shared__ __attribute__((aligned(16))) bf16_t As[GB_M * GB_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[GB_N * GB_LD];
+  const int M = d.rows, N = d.cols, nk = d.p.nk;
+  const int tn_ = (N + GB_N - 1) / GB_N;
+  const int m0 = (blockIdx.x / tn_) * GB_M, n0 = (blockIdx.x % tn_) * GB_N;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w >> 1, wn = w & 1;
+  const int l32 = lane & 31, g = lane >> 5;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16_t* A = (const bf16_t*)t.ptrs[d.ptr0 + kt];
+    const bf16_t* B = (const bf16_t*)t.ptrs[d.ptr0 + nk + kt];
+    const int K = t.aux[d.aux0 + kt];
+    for (int k0 = 0; k0 < K; k0 += GB_K) {
+      // 128 rows x 8 segments of 16 bytes per operand; 4 segments per thread and operand
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int s = threadIdx.x + 256 * i, r = s >> 3, ks = (s & 7) * 8;
+        uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
+        if (m0 + r < M && k0 + ks < K) va = *(const uint4*)(A + (size_t)(m0 + r) * K + k0 + ks);
+        if (n0 + r < N && k0 + ks < K) vb = *(const uint4*)(B + (size_t)(n0 + r) * K + k0 + ks);
+        *(uint4*)(As + r * GB_LD + ks) = va;
+        *(uint4*)(Bs + r * GB_LD + ks) = vb;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < GB_K / 16; ++s) {
+        bf16x8 a[2], bb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          a[i] = *(const bf16x8*)(As + (wm * 64 + i * 32 + l32) * GB_LD + s * 16 + g * 8);
+          bb[i] = *(const bf16x8*)(Bs + (wn * 64 + i * 32 + l32) * GB_LD + s * 16 + g * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+      }
+      __syncthreads();
+    }
+  }
+  bf16_t* Cp = (bf16_t*)d.out;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+        const int col = n0 + wn * 64 + j * 32 + l32;
+        if (row < M && col < N) Cp[(size_t)row * N + col] = f2bf(acc[i][j][r]);
+      }
+}
+
+// ---------------------------------------------------------------------------------------------
+// attention block on the vector ALUs: one thread per (query row, head), online softmax over
+// the key rows in ascending order.  Serves fp32 graphs and shapes the MFMA kernel does not take.
+// aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ const T* tile_elem(void* const* tiles, int nc, int t_rows, int t_cols, int row, int col) {
+  const int rt = row / t_rows, ct = col / t_cols;
+  return (const T*)tiles[rt * nc + ct] + (size_t)(row - rt * t_rows) * t_cols + (col - ct * t_cols);
+}
+
+template <typename T, int HD>
+__global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int* ax = t.aux + d.aux0;
+  const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
+  const int nc = d.p.n_col_tiles, gw = nc * tc;
+  const int hpg = gw / HD;
+  const int qblocks = (q_rows + 63) / 64;
+  const int h = blockIdx.x / qblocks, row = (blockIdx.x % qblocks) * 64 + threadIdx.x;
+  if (row >= q_rows) return;
+  void* const* Qt = t.ptrs + d.ptr0;
+  void* const* Kt = Qt + d.p.n_q_tiles * nc;
+  void* const* Vt = Kt + d.p.n_kv_tiles * nc;
+  float q[HD], o[HD];
+#pragma unroll
+  for (int c = 0; c < HD; ++c) {
+    q[c] = ld(tile_elem<T>(Qt, nc, tq, tc, row, h * HD + c)) * d.p.scale;
+    o[c] = 0.f;
+  }
+  float m = -INFINITY, l = 0.f;
+  const int qpos = d.p.q_pos0 + row;
+  for (int j = 0; j < kv_rows; ++j) {
+    if (d.p.causal && d.p.k_pos0 + j > qpos) break;
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < HD; ++c) s = fmaf(q[c], ld(tile_elem<T>(Kt, nc, tk, tc, j, h * HD + c)), s);
+    const float mn = fmaxf(m, s);
+    const float alpha = __expf(m - mn), p = __expf(s - mn);
+    l = l * alpha + p;
+#pragma unroll
+    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + p * ld(tile_elem<T>(Vt, nc, tk, tc, j, h * HD + c));
+    m = mn;
+  }
+  float* out = (float*)d.out + (size_t)row * d.cols;
+#pragma unroll
+  for (int c = 0; c < HD; ++c) out[h * HD + c] = o[c];
+  out[gw + h] = m;
+  out[gw + hpg + h] = l;
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA attention block (bf16 storage).  One workgroup = one head x 128 query rows; each of its 4
+// wavefronts owns 32 query rows.  Per chunk of 32 key rows the wavefront forms the *transposed*
+// score tile S^T = K Q^T, so that a lane owns one query (its column) and the softmax statistics
+// are per-lane scalars; the probabilities then are already laid out as the B operand of
+// O^T += V^T P^T.  K is staged row-major in LDS, V transposed.
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256) attn_bf16_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  constexpr int KLD = HD + 8, VLD = 32 + 8;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[32 * KLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[HD * VLD];
+  const int* ax = t.aux + d.aux0;
+  const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
+  const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD;
+  const int qblocks = (q_rows + 127) / 128;
+  const int h = blockIdx.x / qblocks, qb = blockIdx.x % qblocks;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
+  void* const* Qp = t.ptrs + d.ptr0;
+  void* const* Kp = Qp + d.p.n_q_tiles * nc;
+  void* const* Vp = Kp + d.p.n_kv_tiles * nc;
+  const int qrow = qb * 128 + w * 32 + l32;  // this lane's query row inside the block
+  const bool qvalid = qrow < q_rows;
+
+  bf16x8 qf[HD / 16];
+#pragma unroll
+  for (int s = 0; s < HD / 16; ++s) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (qvalid) v = *(const uint4*)tile_elem<bf16_t>(Qp, nc, tq, tc, qrow, h * HD + s * 16 + g * 8);
+    qf[s] = *(bf16x8*)&v;
+  }
+  f32x16 ot[HD / 32];
+#pragma unroll
+  for (int i = 0; i < HD / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ot[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const int qpos = d.p.q_pos0 + qrow;
+  // key chunks entirely above the diagonal of this workgroup's rows contribute nothing
+  int kv_end = kv_rows;
+  if (d.p.causal) kv_end = min(kv_rows, d.p.q_pos0 + qb * 128 + 128 - d.p.k_pos0);
+
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 32) {
+    __syncthreads();
+    // stage K (row-major) and V (transposed): 32 rows x HD/8 segments of 16 bytes each
+    for (int s = threadIdx.x; s < 32 * (HD / 8); s += 256) {
+      const int r = s / (HD / 8), c = (s % (HD / 8)) * 8;
+      uint4 vk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (kv0 + r < kv_rows) {
+        vk = *(const uint4*)tile_elem<bf16_t>(Kp, nc, tk, tc, kv0 + r, h * HD + c);
+        vv = *(const uint4*)tile_elem<bf16_t>(Vp, nc, tk, tc, kv0 + r, h * HD + c);
+      }
+      *(uint4*)(Ks + r * KLD + c) = vk;
+      const bf16_t* pv = (const bf16_t*)&vv;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) Vt[(c + k) * VLD + r] = pv[k];
+    }
+    __syncthreads();
+    f32x16 sT;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sT[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < HD / 16; ++s) {
+      bf16x8 a = *(const bf16x8*)(Ks + l32 * KLD + s * 16 + g * 8);
+      sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sT, 0, 0, 0);
+    }
+    // sT[r] is the score of key (8*(r/4) + 4*g + r%4) against this lane's query
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kv = kv0 + 8 * (r / 4) + 4 * g + (r % 4);
+      const bool ok = kv < kv_rows && !(d.p.causal && d.p.k_pos0 + kv > qpos);
+      sT[r] = ok ? sT[r] * d.p.scale : -INFINITY;
+      mx = fmaxf(mx, sT[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    bf16x8 p0, p1;
+    if (mn == -INFINITY) {  // nothing visible yet for this query
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { p0[k] = (__bf16)0.f; p1[k] = (__bf16)0.f; }
+    } else {
+      const float alpha = __expf(m - mn);
+      float ls = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __expf(sT[r] - mn);
+        ls += p;
+        if (r < 8) p0[r] = (__bf16)p; else p1[r - 8] = (__bf16)p;
+      }
+      l = l * alpha + ls;
+#pragma unroll
+      for (int i = 0; i < HD / 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+      m = mn;
+    }
+    // O^T[d, q] += sum_kv V[kv, d] P[q, kv]; the kv order inside each MFMA follows sT's layout
+#pragma unroll
+    for (int i = 0; i < HD / 32; ++i) {
+      const bf16_t* vrow = Vt + (i * 32 + l32) * VLD;
+      bf16x8 a0, a1;
+      *(uint2*)&a0 = *(const uint2*)(vrow + 4 * g);
+      *((uint2*)&a0 + 1) = *(const uint2*)(vrow + 8 + 4 * g);
+      *(uint2*)&a1 = *(const uint2*)(vrow + 16 + 4 * g);
+      *((uint2*)&a1 + 1) = *(const uint2*)(vrow + 24 + 4 * g);
+      ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0, ot[i], 0, 0, 0);
+      ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1, ot[i], 0, 0, 0);
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (!qvalid) return;
+  float* out = (float*)d.out + (size_t)qrow * d.cols;
+#pragma unroll
+  for (int i = 0; i < HD / 32; ++i)
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      *(float4*)(out + h * HD + i * 32 + 8 * a + 4 * g) =
+          make_float4(ot[i][4 * a], ot[i][4 * a + 1], ot[i][4 * a + 2], ot[i][4 * a + 3]);
+  if (g == 0) {
+    out[gw + h] = m;
+    out[gw + hpg + h] = l;
+  }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static inline int32_t cdiv(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
+
+int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
+  switch (cls) {
+    case LC_GEMM_F32: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
+    case LC_GEMM_BF16_NT: return cdiv(d.rows, GB_M) * cdiv(d.cols, GB_N);
+    case LC_RMS_STAT: return cdiv(d.rows, 4);
+    case LC_RMS_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
+    case LC_ROPE: return cdiv((int64_t)d.rows * (d.cols / 2), 256);
+    case LC_ATTN_F32: {
+      const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
+      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + 3], 64);
+    }
+    case LC_ATTN_BF16: {
+      const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
+      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + 3], 128);
+    }
+    case LC_ATTN_COMBINE: return cdiv((int64_t)d.rows * d.cols, 256);
+    case LC_SILU_MUL:
+    case LC_ADD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
+    default: return 0;
+  }
+}
+
+hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t, const Batch& b,
+                        int32_t max_blocks, hipStream_t s) {
+  if (b.n <= 0 || max_blocks <= 0) return hipSuccess;
+  const dim3 grid((unsigned)max_blocks, (unsigned)b.n), wg(256);
+  const bool bf = dtype == TN_BF16;
+#define TN_LAUNCH_T(kernel)                                                     \
+  do {                                                                          \
+    if (bf) hipLaunchKernelGGL(kernel<bf16_t>, grid, wg, 0, s, t, b);           \
+    else hipLaunchKernelGGL(kernel<float>, grid, wg, 0, s, t, b);               \
+  } while (0)
+  switch (cls) {
+    case LC_GEMM_F32: TN_LAUNCH_T(gemm_generic_kernel); break;
+    case LC_GEMM_BF16_NT: hipLaunchKernelGGL(gemm_bf16_nt_kernel, grid, wg, 0, s, t, b); break;
+    case LC_RMS_STAT: TN_LAUNCH_T(rms_stat_kernel); break;
+    case LC_RMS_APPLY: TN_LAUNCH_T(rms_apply_kernel); break;
+    case LC_ROPE: TN_LAUNCH_T(rope_kernel); break;
+    case LC_ATTN_COMBINE: TN_LAUNCH_T(attn_combine_kernel); break;
+    case LC_SILU_MUL:
+      if (bf) hipLaunchKernelGGL((ewise2_kernel<bf16_t, true>), grid, wg, 0, s, t, b);
+      else hipLaunchKernelGGL((ewise2_kernel<float, true>), grid, wg, 0, s, t, b);
+      break;
+    case LC_ADD:
+      if (bf) hipLaunchKernelGGL((ewise2_kernel<bf16_t, false>), grid, wg, 0, s, t, b);
+      else hipLaunchKernelGGL((ewise2_kernel<float, false>), grid, wg, 0, s, t, b);
+      break;
+    case LC_ATTN_F32:
+      if (head_dim == 64) {
+        if (bf) hipLaunchKernelGGL((attn_generic_kernel<bf16_t, 64>), grid, dim3(64), 0, s, t, b);
+        else hipLaunchKernelGGL((attn_generic_kernel<float, 64>), grid, dim3(64), 0, s, t, b);
+      } else if (head_dim == 128) {
+        if (bf) hipLaunchKernelGGL((attn_generic_kernel<bf16_t, 128>), grid, dim3(64), 0, s, t, b);
+        else hipLaunchKernelGGL((attn_generic_kernel<float, 128>), grid, dim3(64), 0, s, t, b);
+      } else {
+        return hipErrorInvalidValue;
+      }
+      break;
+    case LC_ATTN_BF16:
+      if (head_dim == 64) hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, wg, 0, s, t, b);
+      else if (head_dim == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, wg, 0, s, t, b);
+      else return hipErrorInvalidValue;
+      break;
+    default: return hipErrorInvalidValue;
+  }
+#undef TN_LAUNCH_T
+  return hipGetLastError();
+}
+
+}  // namespace tn

@@ -1,0 +1,468 @@
+// Taskgraph container, operand validation, and the tiler that turns a LLaMA-style decoder
+// forward pass into a taskgraph.
+//
+// Section 4, first paragraph: a taskgraph is a dataflow DAG; a vertex without inputs carries an
+// input tensor, any other vertex is a kernel call.  The paper leaves the production of the
+// taskgraph to an outside framework (Section 4, second paragraph), so the decomposition below is
+// this library's own.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "graph.h"
+
+namespace tn {
+
+static thread_local char g_err[1024] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+tn_status fail(tn_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static bool same(const tn_tensor_desc& a, const tn_tensor_desc& b) {
+  return a.dtype == b.dtype && a.rows == b.rows && a.cols == b.cols;
+}
+
+tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, const tn_vid* in,
+                      int32_t n_in, const tn_tensor_desc& out) {
+  auto D = [&](int i) -> const tn_tensor_desc& { return g.v[in[i]].desc; };
+  if (out.rows <= 0 || out.cols <= 0 || (out.dtype != TN_F32 && out.dtype != TN_BF16))
+    return fail(TN_ERR_SHAPE, "output tensor must be non-empty fp32 or bf16");
+  switch (kind) {
+    case TN_OP_GEMM: {
+      if (p.nk < 1 || n_in != 2 * p.nk) return fail(TN_ERR_SHAPE, "gemm: needs 2*nk operands");
+      for (int k = 0; k < p.nk; ++k) {
+        const auto &a = D(k), &b = D(p.nk + k);
+        const int32_t bk = p.trans_b ? b.cols : b.rows, bn = p.trans_b ? b.rows : b.cols;
+        if (a.rows != out.rows || bn != out.cols || a.cols != bk || a.dtype != out.dtype ||
+            b.dtype != out.dtype)
+          return fail(TN_ERR_SHAPE, "gemm: k tile %d has A [%d,%d] B [%d,%d] for C [%d,%d]", k,
+                      a.rows, a.cols, b.rows, b.cols, out.rows, out.cols);
+      }
+      return TN_OK;
+    }
+    case TN_OP_RMS_STAT: {
+      if (n_in < 1 || out.dtype != TN_F32 || out.cols != 1)
+        return fail(TN_ERR_SHAPE, "rms_stat: output must be fp32 [rows,1]");
+      int64_t cols = 0;
+      for (int i = 0; i < n_in; ++i) {
+        if (D(i).rows != out.rows || D(i).dtype != D(0).dtype)
+          return fail(TN_ERR_SHAPE, "rms_stat: operand %d does not match the row block", i);
+        cols += D(i).cols;
+      }
+      if (cols != p.d) return fail(TN_ERR_SHAPE, "rms_stat: operands cover %lld columns, d = %d",
+                                   (long long)cols, p.d);
+      return TN_OK;
+    }
+    case TN_OP_RMS_APPLY: {
+      if (n_in != 3) return fail(TN_ERR_SHAPE, "rms_apply: needs x, stat, gain");
+      if (!same(D(0), out) || D(1).dtype != TN_F32 || D(1).rows != out.rows || D(1).cols != 1 ||
+          D(2).rows != 1 || D(2).cols != out.cols || D(2).dtype != out.dtype)
+        return fail(TN_ERR_SHAPE, "rms_apply: operand shapes do not fit");
+      return TN_OK;
+    }
+    case TN_OP_ROPE: {
+      if (n_in != 1 || !same(D(0), out)) return fail(TN_ERR_SHAPE, "rope: one operand of the output's shape");
+      if ((out.cols & 1) || (p.col0 & 1) || p.head_dim < 2 || (p.head_dim & 1) || p.col0 < 0 ||
+          p.pos0 < 0 || !(p.rope_base > 0))
+        return fail(TN_ERR_SHAPE, "rope: pairs must not straddle tiles (even cols, col0, head_dim)");
+      return TN_OK;
+    }
+    case TN_OP_ATTN_BLOCK: {
+      int nq = p.n_q_tiles, nkv = p.n_kv_tiles, nc = p.n_col_tiles;
+      if (nq < 1 || nkv < 1 || nc < 1 || n_in != (nq + 2 * nkv) * nc || p.head_dim < 1)
+        return fail(TN_ERR_SHAPE, "attn_block: needs (n_q_tiles + 2 n_kv_tiles) * n_col_tiles operands");
+      int64_t gw = 0, qrows = 0;
+      for (int c = 0; c < nc; ++c) gw += D(c).cols;
+      if (gw % p.head_dim) return fail(TN_ERR_SHAPE, "attn_block: columns are not whole heads");
+      int32_t dt = D(0).dtype;
+      for (int r = 0; r < nq; ++r) {
+        qrows += D(r * nc).rows;
+        for (int c = 0; c < nc; ++c)
+          if (D(r * nc + c).rows != D(r * nc).rows || D(r * nc + c).cols != D(c).cols ||
+              D(r * nc + c).dtype != dt)
+            return fail(TN_ERR_SHAPE, "attn_block: Q tile (%d,%d) does not fit the grid", r, c);
+      }
+      for (int r = 0; r < nkv; ++r)
+        for (int c = 0; c < nc; ++c) {
+          const auto &k = D(nq * nc + r * nc + c), &v = D((nq + nkv) * nc + r * nc + c);
+          if (k.cols != D(c).cols || !same(k, v) || k.rows != D(nq * nc + r * nc).rows || k.dtype != dt)
+            return fail(TN_ERR_SHAPE, "attn_block: K/V tile (%d,%d) does not fit the grid", r, c);
+        }
+      int64_t hpg = gw / p.head_dim;
+      if (out.dtype != TN_F32 || out.rows != qrows || out.cols != gw + 2 * hpg)
+        return fail(TN_ERR_SHAPE, "attn_block: output must be fp32 [%lld,%lld]", (long long)qrows,
+                    (long long)(gw + 2 * hpg));
+      return TN_OK;
+    }
+    case TN_OP_ATTN_COMBINE: {
+      if (n_in < 1 || p.hpg < 1 || p.head_dim < 1) return fail(TN_ERR_SHAPE, "attn_combine: needs partials");
+      int64_t gw = (int64_t)p.hpg * p.head_dim;
+      for (int i = 0; i < n_in; ++i)
+        if (D(i).dtype != TN_F32 || D(i).cols != gw + 2 * p.hpg || D(i).rows != D(0).rows)
+          return fail(TN_ERR_SHAPE, "attn_combine: operand %d is not a partial of this group", i);
+      if (p.row0 < 0 || p.col0 < 0 || p.row0 + out.rows > D(0).rows || p.col0 + out.cols > gw)
+        return fail(TN_ERR_SHAPE, "attn_combine: output window leaves the block");
+      return TN_OK;
+    }
+    case TN_OP_SILU_MUL:
+    case TN_OP_ADD:
+      if (n_in != 2 || !same(D(0), out) || !same(D(1), out))
+        return fail(TN_ERR_SHAPE, "elementwise: two operands of the output's shape and type");
+      return TN_OK;
+    default:
+      return fail(TN_ERR_INVALID, "unknown vertex kind %d", kind);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LLaMA tiler
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+
+struct Range { int32_t a, b; int32_t len() const { return b - a; } };
+
+std::vector<Range> cut(int32_t n, int32_t t) {
+  std::vector<Range> r;
+  for (int32_t s = 0; s < n; s += t) r.push_back({s, std::min(s + t, n)});
+  return r;
+}
+
+using Grid = std::vector<std::vector<tn_vid>>;  // [row tile][column tile]
+
+struct Tiler {
+  const tn_llama_config& c;
+  TaskGraph& g;
+  std::vector<Range> dcols, fcols, rows;
+
+  Tiler(const tn_llama_config& cfg, TaskGraph& tg) : c(cfg), g(tg) {
+    dcols = cut(c.d_model, c.tile);
+    fcols = cut(c.ffn, c.tile);
+    rows = cut(c.seq, c.tile);
+  }
+
+  tn_vid input(int32_t rws, int32_t cls, int32_t residency, int32_t tensor, int32_t layer, Range rr,
+               Range cr) {
+    Vertex v;
+    v.kind = TN_OP_INPUT;
+    v.residency = residency;
+    v.desc = {c.dtype, rws, cls};
+    g.v.push_back(v);
+    tn_vid id = (tn_vid)g.v.size() - 1;
+    g.bindings.push_back({id, tensor, layer, rr.a, rr.b, cr.a, cr.b, 0});
+    return id;
+  }
+
+  tn_vid op(int32_t kind, const tn_op_params& p, std::vector<tn_vid> in, tn_tensor_desc d) {
+    Vertex v;
+    v.kind = kind;
+    v.p = p;
+    v.desc = d;
+    v.in = std::move(in);
+    g.v.push_back(std::move(v));
+    return (tn_vid)g.v.size() - 1;
+  }
+
+  Grid weight(int32_t tensor, int32_t layer, const std::vector<Range>& rr, const std::vector<Range>& cc) {
+    Grid w(rr.size(), std::vector<tn_vid>(cc.size()));
+    for (size_t i = 0; i < rr.size(); ++i)
+      for (size_t j = 0; j < cc.size(); ++j) {
+        if (c.weights_transposed) {
+          w[i][j] = input(cc[j].len(), rr[i].len(), c.weights_residency, tensor, layer, rr[i], cc[j]);
+          g.bindings.back().transposed = 1;
+        } else {
+          w[i][j] = input(rr[i].len(), cc[j].len(), c.weights_residency, tensor, layer, rr[i], cc[j]);
+        }
+      }
+    return w;
+  }
+
+  std::vector<tn_vid> gain(int32_t tensor, int32_t layer) {
+    std::vector<tn_vid> gns;
+    for (auto& cr : dcols) gns.push_back(input(1, cr.len(), c.weights_residency, tensor, layer, {0, 1}, cr));
+    return gns;
+  }
+
+  // one output tile of X(row tile) * W, full K inside the vertex
+  tn_vid gemm(const std::vector<tn_vid>& xrow, const Grid& w, size_t j, int32_t m, int32_t n) {
+    tn_op_params p{};
+    p.nk = (int32_t)xrow.size();
+    p.trans_b = c.weights_transposed ? 1 : 0;
+    std::vector<tn_vid> in(xrow);
+    for (size_t k = 0; k < xrow.size(); ++k) in.push_back(w[k][j]);
+    return op(TN_OP_GEMM, p, std::move(in), {c.dtype, m, n});
+  }
+
+  std::vector<tn_vid> rmsnorm(const std::vector<tn_vid>& xrow, const std::vector<tn_vid>& gns, int32_t m) {
+    tn_op_params p{};
+    p.d = c.d_model;
+    p.eps = c.eps;
+    tn_vid st = op(TN_OP_RMS_STAT, p, xrow, {TN_F32, m, 1});
+    std::vector<tn_vid> out;
+    for (size_t j = 0; j < xrow.size(); ++j)
+      out.push_back(op(TN_OP_RMS_APPLY, tn_op_params{}, {xrow[j], st, gns[j]}, {c.dtype, m, dcols[j].len()}));
+    return out;
+  }
+
+  tn_vid rope(tn_vid x, int32_t pos0, int32_t col_start, int32_t m, int32_t n) {
+    tn_op_params p{};
+    p.pos0 = pos0;
+    p.col0 = col_start % c.head_dim;
+    p.head_dim = c.head_dim;
+    p.rope_base = c.rope_base;
+    return op(TN_OP_ROPE, p, {x}, {c.dtype, m, n});
+  }
+};
+
+}  // namespace
+}  // namespace tn
+
+using namespace tn;
+
+extern "C" {
+
+const char* tn_last_error(void) { return g_err; }
+
+tn_status tn_taskgraph_create(tn_taskgraph** out) {
+  if (!out) return fail(TN_ERR_INVALID, "out is NULL");
+  *out = new (std::nothrow) tn_taskgraph();
+  return *out ? TN_OK : fail(TN_ERR_INVALID, "out of host memory");
+}
+
+void tn_taskgraph_destroy(tn_taskgraph* tg) { delete tg; }
+
+tn_status tn_taskgraph_add_input(tn_taskgraph* tg, const tn_tensor_desc* desc, int32_t residency, tn_vid* out) {
+  if (!tg || !desc || !out) return fail(TN_ERR_INVALID, "NULL argument");
+  if (desc->rows <= 0 || desc->cols <= 0 || (desc->dtype != TN_F32 && desc->dtype != TN_BF16))
+    return fail(TN_ERR_SHAPE, "input tensor must be non-empty fp32 or bf16");
+  if (residency != TN_HOST && residency != TN_DEVICE) return fail(TN_ERR_INVALID, "bad residency");
+  Vertex v;
+  v.kind = TN_OP_INPUT;
+  v.residency = residency;
+  v.desc = *desc;
+  tg->v.push_back(v);
+  *out = (tn_vid)tg->v.size() - 1;
+  return TN_OK;
+}
+
+tn_status tn_taskgraph_add_op(tn_taskgraph* tg, int32_t kind, const tn_op_params* params, const tn_vid* inputs,
+                              int32_t n_inputs, const tn_tensor_desc* out_desc, tn_vid* out) {
+  if (!tg || !params || !out_desc || !out || (n_inputs > 0 && !inputs) || n_inputs < 1)
+    return fail(TN_ERR_INVALID, "NULL argument or no operands");
+  if (kind == TN_OP_INPUT) return fail(TN_ERR_INVALID, "use tn_taskgraph_add_input for inputs");
+  for (int i = 0; i < n_inputs; ++i)
+    if (inputs[i] < 0 || inputs[i] >= (tn_vid)tg->v.size())
+      return fail(TN_ERR_INVALID, "operand %d names vertex %d, which does not exist yet", i, inputs[i]);
+  tn_status s = validate_op(*tg, kind, *params, inputs, n_inputs, *out_desc);
+  if (s != TN_OK) return s;
+  Vertex v;
+  v.kind = kind;
+  v.p = *params;
+  v.desc = *out_desc;
+  v.in.assign(inputs, inputs + n_inputs);
+  tg->v.push_back(std::move(v));
+  *out = (tn_vid)tg->v.size() - 1;
+  return TN_OK;
+}
+
+tn_status tn_taskgraph_mark_output(tn_taskgraph* tg, tn_vid v) {
+  if (!tg || v < 0 || v >= (tn_vid)tg->v.size()) return fail(TN_ERR_INVALID, "no such vertex");
+  if (tg->v[v].output_index >= 0) return fail(TN_ERR_INVALID, "vertex %d is already an output", v);
+  tg->v[v].output_index = (int32_t)tg->outputs.size();
+  tg->outputs.push_back(v);
+  return TN_OK;
+}
+
+int64_t tn_taskgraph_num_vertices(const tn_taskgraph* tg) { return tg ? (int64_t)tg->v.size() : TN_ERR_INVALID; }
+int64_t tn_taskgraph_num_outputs(const tn_taskgraph* tg) { return tg ? (int64_t)tg->outputs.size() : TN_ERR_INVALID; }
+
+tn_status tn_taskgraph_vertex(const tn_taskgraph* tg, tn_vid v, tn_tg_vertex* out) {
+  if (!tg || !out || v < 0 || v >= (tn_vid)tg->v.size()) return fail(TN_ERR_INVALID, "no such vertex");
+  const Vertex& x = tg->v[v];
+  out->kind = x.kind;
+  out->residency = x.residency;
+  out->n_inputs = (int32_t)x.in.size();
+  out->output_index = x.output_index;
+  out->desc = x.desc;
+  out->params = x.p;
+  return TN_OK;
+}
+
+int32_t tn_taskgraph_inputs(const tn_taskgraph* tg, tn_vid v, tn_vid* out, int32_t cap) {
+  if (!tg || v < 0 || v >= (tn_vid)tg->v.size()) return fail(TN_ERR_INVALID, "no such vertex");
+  const auto& in = tg->v[v].in;
+  for (int32_t i = 0; i < cap && i < (int32_t)in.size(); ++i) out[i] = in[i];
+  return (int32_t)in.size();
+}
+
+int64_t tn_taskgraph_num_bindings(const tn_taskgraph* tg) { return tg ? (int64_t)tg->bindings.size() : TN_ERR_INVALID; }
+
+tn_status tn_taskgraph_binding(const tn_taskgraph* tg, int64_t i, tn_llama_binding* out) {
+  if (!tg || !out || i < 0 || i >= (int64_t)tg->bindings.size()) return fail(TN_ERR_INVALID, "no such binding");
+  *out = tg->bindings[i];
+  return TN_OK;
+}
+
+// The decoder is emitted stripe by stripe: a stripe is one attention block of rows of one
+// sequence.  Causal attention of a stripe needs K and V of the stripes before it only, so the
+// serial order "layer, sequence, stripe" keeps the live set small: per-stripe activations die
+// at the end of the stripe and only K/V of earlier stripes stay.
+tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
+  if (!cfg || !out) return fail(TN_ERR_INVALID, "NULL argument");
+  const tn_llama_config& c = *cfg;
+  if (c.layers < 1 || c.d_model < 1 || c.n_heads < 1 || c.head_dim < 2 || c.ffn < 1 || c.seq < 1 ||
+      c.batch < 1 || c.tile < 2 || c.attn_block < c.tile)
+    return fail(TN_ERR_INVALID, "non-positive model dimension");
+  if (c.n_heads * c.head_dim != c.d_model) return fail(TN_ERR_SHAPE, "n_heads * head_dim != d_model");
+  if (c.attn_block % c.tile) return fail(TN_ERR_SHAPE, "attn_block must be a multiple of tile");
+  if ((c.tile % c.head_dim) && (c.head_dim % c.tile))
+    return fail(TN_ERR_SHAPE, "tile and head_dim must divide one another");
+  if ((c.tile & 1) || (c.head_dim & 1)) return fail(TN_ERR_SHAPE, "tile and head_dim must be even");
+  const int32_t gw = std::max(c.tile, c.head_dim);  // columns of a head group
+  if (c.d_model % gw) return fail(TN_ERR_SHAPE, "d_model must be a multiple of max(tile, head_dim)");
+  if (c.dtype != TN_F32 && c.dtype != TN_BF16) return fail(TN_ERR_INVALID, "bad dtype");
+
+  auto* tg = new (std::nothrow) tn_taskgraph();
+  if (!tg) return fail(TN_ERR_INVALID, "out of host memory");
+  Tiler t(c, *tg);
+  const int32_t hpg = gw / c.head_dim, ctg = gw / c.tile, n_groups = c.d_model / gw;
+  const auto stripes = cut(c.seq, c.attn_block);
+  const size_t nd = t.dcols.size(), nf = t.fcols.size();
+
+  // residual stream, one grid per sequence
+  std::vector<Grid> x(c.batch);
+  for (int b = 0; b < c.batch; ++b) {
+    x[b].assign(t.rows.size(), std::vector<tn_vid>(nd));
+    for (size_t i = 0; i < t.rows.size(); ++i)
+      for (size_t j = 0; j < nd; ++j) {
+        Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
+        x[b][i][j] = t.input(t.rows[i].len(), t.dcols[j].len(), c.x_residency, TN_T_X, -1, rr, t.dcols[j]);
+      }
+  }
+
+  for (int l = 0; l < c.layers; ++l) {
+    Grid wq = t.weight(TN_T_WQ, l, t.dcols, t.dcols), wk = t.weight(TN_T_WK, l, t.dcols, t.dcols);
+    Grid wv = t.weight(TN_T_WV, l, t.dcols, t.dcols), wo = t.weight(TN_T_WO, l, t.dcols, t.dcols);
+    Grid w1 = t.weight(TN_T_W1, l, t.dcols, t.fcols), w3 = t.weight(TN_T_W3, l, t.dcols, t.fcols);
+    Grid w2 = t.weight(TN_T_W2, l, t.fcols, t.dcols);
+    auto g1 = t.gain(TN_T_G1, l), g2 = t.gain(TN_T_G2, l);
+
+    for (int b = 0; b < c.batch; ++b) {
+      Grid kk(t.rows.size()), vv(t.rows.size());  // K, V of the stripes done so far
+      for (size_t s = 0; s < stripes.size(); ++s) {
+        std::vector<size_t> rt;  // row tiles of this stripe
+        for (size_t i = 0; i < t.rows.size(); ++i)
+          if (t.rows[i].a >= stripes[s].a && t.rows[i].a < stripes[s].b) rt.push_back(i);
+        Grid q(t.rows.size());
+        for (size_t i : rt) {
+          const int32_t m = t.rows[i].len();
+          auto a = t.rmsnorm(x[b][i], g1, m);
+          for (size_t j = 0; j < nd; ++j) {
+            const int32_t n = t.dcols[j].len();
+            q[i].push_back(t.rope(t.gemm(a, wq, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
+            kk[i].push_back(t.rope(t.gemm(a, wk, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
+            vv[i].push_back(t.gemm(a, wv, j, m, n));
+            if (c.kv_outputs) {
+              Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
+              for (int which = 0; which < 2; ++which) {
+                tn_vid id = which ? vv[i][j] : kk[i][j];
+                tg->v[id].output_index = (int32_t)tg->outputs.size();
+                tg->outputs.push_back(id);
+                tg->bindings.push_back({id, which ? TN_T_V : TN_T_K, l, rr.a, rr.b, t.dcols[j].a, t.dcols[j].b, 0});
+              }
+            }
+          }
+        }
+        // attention of this stripe against stripes 0..s, one partial per pair, per head group
+        Grid o(t.rows.size(), std::vector<tn_vid>(nd, -1));
+        for (int32_t gi = 0; gi < n_groups; ++gi) {
+          std::vector<tn_vid> parts;
+          for (size_t s2 = 0; s2 <= s; ++s2) {
+            std::vector<size_t> kt;
+            for (size_t i = 0; i < t.rows.size(); ++i)
+              if (t.rows[i].a >= stripes[s2].a && t.rows[i].a < stripes[s2].b) kt.push_back(i);
+            std::vector<tn_vid> in;
+            for (size_t i : rt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[i][gi * ctg + cc]);
+            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kk[i][gi * ctg + cc]);
+            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(vv[i][gi * ctg + cc]);
+            tn_op_params p{};
+            p.n_q_tiles = (int32_t)rt.size();
+            p.n_kv_tiles = (int32_t)kt.size();
+            p.n_col_tiles = ctg;
+            p.head_dim = c.head_dim;
+            p.q_pos0 = stripes[s].a;
+            p.k_pos0 = stripes[s2].a;
+            p.causal = (s2 == s);
+            p.scale = 1.0f / std::sqrt((float)c.head_dim);
+            parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, stripes[s].len(), gw + 2 * hpg}));
+          }
+          for (size_t i : rt)
+            for (int32_t cc = 0; cc < ctg; ++cc) {
+              tn_op_params p{};
+              p.row0 = t.rows[i].a - stripes[s].a;
+              p.col0 = cc * c.tile;
+              p.head_dim = c.head_dim;
+              p.hpg = hpg;
+              o[i][gi * ctg + cc] = t.op(TN_OP_ATTN_COMBINE, p, parts,
+                                        {c.dtype, t.rows[i].len(), t.dcols[gi * ctg + cc].len()});
+            }
+        }
+        // output projection, residual, feed-forward, residual -- row tile by row tile
+        for (size_t i : rt) {
+          const int32_t m = t.rows[i].len();
+          std::vector<tn_vid> h(nd);
+          for (size_t j = 0; j < nd; ++j) {
+            const int32_t n = t.dcols[j].len();
+            h[j] = t.op(TN_OP_ADD, tn_op_params{}, {x[b][i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
+          }
+          auto bn = t.rmsnorm(h, g2, m);
+          std::vector<tn_vid> act(nf);
+          for (size_t j = 0; j < nf; ++j) {
+            const int32_t n = t.fcols[j].len();
+            tn_vid gate = t.gemm(bn, w1, j, m, n), up = t.gemm(bn, w3, j, m, n);
+            act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {gate, up}, {c.dtype, m, n});
+          }
+          for (size_t j = 0; j < nd; ++j) {
+            const int32_t n = t.dcols[j].len();
+            x[b][i][j] = t.op(TN_OP_ADD, tn_op_params{}, {h[j], t.gemm(act, w2, j, m, n)}, {c.dtype, m, n});
+          }
+        }
+      }
+    }
+  }
+  for (int b = 0; b < c.batch; ++b)
+    for (size_t i = 0; i < t.rows.size(); ++i)
+      for (size_t j = 0; j < nd; ++j) {
+        tn_vid id = x[b][i][j];
+        tg->v[id].output_index = (int32_t)tg->outputs.size();
+        tg->outputs.push_back(id);
+        tg->bindings.push_back({id, TN_T_Y, -1, b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b,
+                                t.dcols[j].a, t.dcols[j].b, 0});
+      }
+  // every vertex the tiler emitted must satisfy the same rules a caller's would
+  for (size_t v = 0; v < tg->v.size(); ++v) {
+    const Vertex& x_ = tg->v[v];
+    if (x_.kind == TN_OP_INPUT) continue;
+    tn_status s = validate_op(*tg, x_.kind, x_.p, x_.in.data(), (int32_t)x_.in.size(), x_.desc);
+    if (s != TN_OK) {
+      delete tg;
+      return s;
+    }
+  }
+  *out = tg;
+  return TN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+"""Array marshalling around the C ABI: config structs, cutting full tensors into the per-vertex
+host tiles the library reads, exporting graphs as plain lists, and the torch plumbing (device
+buffer, streams, pinned memory) for a run.  No step of the method is computed here."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding as B
+
+_TENSOR_NAMES = {B.TN_T_X: "x", B.TN_T_WQ: "wq", B.TN_T_WK: "wk", B.TN_T_WV: "wv", B.TN_T_WO: "wo",
+                 B.TN_T_W1: "w1", B.TN_T_W3: "w3", B.TN_T_W2: "w2", B.TN_T_G1: "g1", B.TN_T_G2: "g2",
+                 B.TN_T_Y: "y", B.TN_T_K: "k", B.TN_T_V: "v"}
+OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms_stat",
+            B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
+            B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add"}
+MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op", B.TN_MG_OFFLOAD: "offload",
+                 B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store"}
+EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}
+
+
+def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True) -> B.tn_llama_config:
+    """workloads.LlamaConfig -> tn_llama_config."""
+    return B.tn_llama_config(
+        layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
+        seq=cfg.seq, batch=cfg.batch, dtype=B.TN_F32 if cfg.dtype == "f32" else B.TN_BF16, tile=cfg.tile,
+        attn_block=cfg.attn_block, eps=cfg.eps, rope_base=cfg.rope_base,
+        weights_residency=B.TN_DEVICE if cfg.weights_resident else B.TN_HOST,
+        x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
+        weights_transposed=int(weights_transposed))
+
+
+def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
+    """[(vid, tensor name such as "wq.3" / "x" / "y", row0, row1, col0, col1, transposed)]."""
+    out = []
+    for i in range(B.tn_taskgraph_num_bindings(tg)):
+        b = B.tn_taskgraph_binding(tg, i)
+        name = _TENSOR_NAMES[b.tensor] + (f".{b.layer}" if b.layer >= 0 else "")
+        out.append((b.vid, name, b.row0, b.row1, b.col0, b.col1, b.transposed))
+    return out
+
+
+def export_taskgraph(tg) -> dict:
+    """The taskgraph as plain lists: kind names, parameter dicts, operand lists, shapes, dtypes."""
+    n = B.tn_taskgraph_num_vertices(tg)
+    kind, params, inputs, shape, dtype, resid = [], [], [], [], [], []
+    outputs: Dict[int, int] = {}
+    for v in range(n):
+        x = B.tn_taskgraph_vertex(tg, v)
+        kind.append(OP_NAMES[x.kind])
+        params.append({f: getattr(x.params, f) for f, _ in B.tn_op_params._fields_})
+        inputs.append(B.tn_taskgraph_inputs(tg, v) if x.n_inputs else [])
+        shape.append((x.desc.rows, x.desc.cols))
+        dtype.append("f32" if x.desc.dtype == B.TN_F32 else "bf16")
+        resid.append(x.residency)
+        if x.output_index >= 0:
+            outputs[x.output_index] = v
+    return dict(kind=kind, params=params, inputs=inputs, shape=shape, dtype=dtype, residency=resid,
+                outputs=[outputs[i] for i in range(len(outputs))], bindings=bindings(tg))
+
+
+def export_memgraph(mg) -> dict:
+    """The memgraph as plain lists (for checkers that share no code with the library)."""
+    n = B.tn_memgraph_num_vertices(mg)
+    kind, src, loc, operands, order_pos = [], [], [], [], []
+    for i in range(n):
+        x = B.tn_memgraph_vertex(mg, i)
+        kind.append(MG_KIND_NAMES[x.kind])
+        src.append(x.src)
+        writes = x.kind in (B.TN_MG_INPUT, B.TN_MG_LOAD, B.TN_MG_OP, B.TN_MG_RELOAD)
+        loc.append((x.offset, x.bytes) if writes and x.offset >= 0 else None)
+        operands.append(B.tn_memgraph_operands(mg, i, x.n_operands) if x.n_operands else [])
+        order_pos.append(x.order_pos)
+    edges = []
+    for i in range(B.tn_memgraph_num_edges(mg)):
+        e = B.tn_memgraph_edge(mg, i)
+        edges.append((e.from_, e.to, EDGE_NAMES[e.kind]))
+    order = [0] * n
+    for v, p in enumerate(order_pos):
+        order[p] = v
+    st = B.tn_memgraph_stats(mg)
+    return dict(n_task=st.n_task, cap=st.cap, kind=kind, src=src, loc=loc, operands=operands, edges=edges,
+                order=order, stats={f: getattr(st, f) for f, _ in B.tn_mg_stats._fields_})
+
+
+def cut_host_tiles(tg, full: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
+    """vid -> contiguous tile (storage dtype) for every input vertex, cut from the full tensors."""
+    out = {}
+    for vid, name, r0, r1, c0, c1, tr in bindings(tg):
+        if name.split(".")[0] in ("y", "k", "v"):
+            continue
+        a = full[name]
+        a = a.reshape(1, -1) if a.ndim == 1 else a
+        out[vid] = np.ascontiguousarray(a[r0:r1, c0:c1].T if tr else a[r0:r1, c0:c1])
+    return out
+
+
+def uncapped_peak(tg) -> int:
+    """Peak bytes of the serial run with unlimited memory and no run-ahead allocation."""
+    opts = B.tn_compile_opts(max_lookahead_bytes=0, drop_clean_inputs=1)
+    mg = B.tn_compile(tg, None, 1 << 62, opts)
+    try:
+        return int(B.tn_memgraph_stats(mg).peak_live_bytes)
+    finally:
+        B.tn_memgraph_destroy(mg)
+
+
+def cap_for(cfg, tg) -> int:
+    """The workload's GPU-memory cap in bytes."""
+    if cfg.cap_bytes:
+        return int(cfg.cap_bytes)
+    return (int(cfg.cap_frac * uncapped_peak(tg)) + 255) // 256 * 256
