@@ -481,9 +481,15 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(DeviceTables t, Batch b)
 #pragma unroll
   for (int i = 0; i < HD / 32; ++i)
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-      *(float4*)(out + h * HD + i * 32 + 8 * a + 4 * g) =
-          make_float4(ot[i][4 * a], ot[i][4 * a + 1], ot[i][4 * a + 2], ot[i][4 * a + 3]);
+    for (int a = 0; a < 4; ++a) {
+      float* o4 = out + h * HD + i * 32 + 8 * a + 4 * g;
+      if ((d.cols & 3) == 0) {  // rows of the partial are 16-byte aligned
+        *(float4*)o4 = make_float4(ot[i][4 * a], ot[i][4 * a + 1], ot[i][4 * a + 2], ot[i][4 * a + 3]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o4[k] = ot[i][4 * a + k];
+      }
+    }
   if (g == 0) {
     out[gw + h] = m;
     out[gw + hpg + h] = l;

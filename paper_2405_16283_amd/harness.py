@@ -111,3 +111,97 @@ def cap_for(cfg, tg) -> int:
     if cfg.cap_bytes:
         return int(cfg.cap_bytes)
     return (int(cfg.cap_frac * uncapped_peak(tg)) + 255) // 256 * 256
+
+
+class GpuSession:
+    """Torch plumbing for running one compiled workload on cuda:0: device buffer of `cap` bytes,
+    streams, pinned host tiles for inputs and outputs, and the executor.  Arithmetic-free."""
+
+    def __init__(self, cfg, full_inputs: Dict[str, np.ndarray], cap: Optional[int] = None,
+                 compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
+                 kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
+                 weights_transposed: bool = True, arena_bytes: int = 0):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
+        self.torch = torch
+        self.cfg = cfg
+        self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed))
+        self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
+        self.mg = B.tn_compile(self.tg, order, self.cap, compile_opts)
+        self.stats = B.tn_memgraph_stats(self.mg)
+        self.n_task = B.tn_taskgraph_num_vertices(self.tg)
+        self.elem = np.float32 if cfg.dtype == "f32" else np.uint16
+        # inputs: one pinned slab, tiles back to back (256-byte aligned)
+        tiles = cut_host_tiles(self.tg, full_inputs)
+        offs, total = {}, 0
+        for v, a in tiles.items():
+            offs[v] = total
+            total += (a.nbytes + 255) // 256 * 256
+        self.in_slab = torch.empty(max(total, 256), dtype=torch.uint8).pin_memory()
+        slab_np = self.in_slab.numpy()
+        self.in_ptrs = [0] * self.n_task
+        for v, a in tiles.items():
+            slab_np[offs[v]:offs[v] + a.nbytes] = a.view(np.uint8).reshape(-1)
+            self.in_ptrs[v] = self.in_slab.data_ptr() + offs[v]
+        # outputs: one pinned slab
+        e = export_taskgraph(self.tg)
+        self.out_vids = e["outputs"]
+        self.out_shapes = [e["shape"][v] for v in self.out_vids]
+        self.out_bind = {b[0]: b for b in e["bindings"] if b[1].split(".")[0] in ("y", "k", "v")}
+        es = np.dtype(self.elem).itemsize
+        self.out_offs, total = [], 0
+        for (r, c) in self.out_shapes:
+            self.out_offs.append(total)
+            total += (r * c * es + 255) // 256 * 256
+        self.out_slab = torch.empty(max(total, 256), dtype=torch.uint8).pin_memory()
+        self.out_ptrs = [self.out_slab.data_ptr() + o for o in self.out_offs]
+        # device memory and streams
+        self.dev = torch.empty(self.cap, dtype=torch.uint8, device="cuda:0")
+        self.streams = [torch.cuda.Stream(device="cuda:0") for _ in range(n_compute + 2)]
+        torch.cuda.synchronize()
+        handles = [s.cuda_stream for s in self.streams]
+        self.ex = B.tn_executor_create(self.mg, self.dev.data_ptr(), self.cap, 0, arena_bytes,
+                                       handles[:n_compute], handles[n_compute], handles[n_compute + 1])
+
+    def place_inputs(self):
+        B.tn_executor_place_inputs(self.ex, self.in_ptrs)
+
+    def execute(self, opts: Optional[B.tn_exec_opts] = None) -> B.tn_exec_report:
+        return B.tn_execute(self.ex, self.in_ptrs, self.out_ptrs, opts)
+
+    def run(self, opts: Optional[B.tn_exec_opts] = None, poison: bool = True):
+        """place inputs, execute, and return ({"y": array, ["k.l", "v.l": arrays]}, report)."""
+        if poison:
+            self.out_slab.fill_(0xFF)
+        self.place_inputs()
+        rep = self.execute(opts)
+        return self.outputs(), rep
+
+    def outputs(self) -> Dict[str, np.ndarray]:
+        cfg = self.cfg
+        out: Dict[str, np.ndarray] = {}
+        slab = self.out_slab.numpy()
+        es = np.dtype(self.elem).itemsize
+        for i, v in enumerate(self.out_vids):
+            _, name, r0, r1, c0, c1, _ = self.out_bind[v]
+            if name not in out:
+                out[name] = np.zeros((cfg.tokens, cfg.d_model), dtype=self.elem)
+            r, c = self.out_shapes[i]
+            out[name][r0:r1, c0:c1] = slab[self.out_offs[i]:self.out_offs[i] + r * c * es].view(self.elem).reshape(r, c)
+        return out
+
+    def last_order(self) -> List[int]:
+        return B.tn_executor_last_order(self.ex, B.tn_memgraph_num_vertices(self.mg))
+
+    def close(self):
+        if getattr(self, "ex", None):
+            self.torch.cuda.synchronize()
+            B.tn_executor_destroy(self.ex)
+            self.ex = None
+        if getattr(self, "mg", None):
+            B.tn_memgraph_destroy(self.mg)
+            self.mg = None
+        if getattr(self, "tg", None):
+            B.tn_taskgraph_destroy(self.tg)
+            self.tg = None

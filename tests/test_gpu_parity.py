@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs; across dispatch orders and injected transfer delays; on the offload path."""
+import numpy as np
+import pytest
+
+from oracle import llama_ref as R
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import bf16_bits_to_f32, config, make_llama_inputs
+
+from util import oracle_taskgraph
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}  # max relative error allowed against the oracle, per storage type
+
+
+def _as_f64(cfg, a):
+    return (bf16_bits_to_f32(a) if cfg.dtype == "bf16" else a).astype(np.float64)
+
+
+def _oracle(cfg, full, tg_handle=None):
+    """Tiled oracle (same rounding points as the taskgraph) and untiled float64 reference."""
+    w = R.widen(cfg, full)
+    own = T.build_llama_taskgraph(cfg)
+    y_tiled = T.assemble_outputs(own, T.evaluate(own, T.cut_inputs(own, w)), cfg.tokens, cfg.d_model)
+    return y_tiled, R.forward(cfg, w)
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_f32", "batch2_f32", "ragged_bf16"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_forward_matches_oracle_under_the_cap(name, seed):
+    cfg = config(name)
+    full = make_llama_inputs(cfg, seed)
+    y_tiled, y_ref = _oracle(cfg, full)
+    print(f"[case] {name} seed {seed}", flush=True)
+    s = H.GpuSession(cfg, full)
+    try:
+        assert s.stats.n_offload > 0, "cap must force offload"
+        out, rep = s.run()
+        y = _as_f64(cfg, out["y"])
+        assert np.isfinite(y).all()
+        err = R.rel_err(y, y_tiled)
+        print(f"  rel err vs tiled oracle {err:.3e}, vs untiled {R.rel_err(y, y_ref):.3e}; "
+              f"{rep.n_offload} offloads, {rep.n_reload} reloads, {rep.n_launches} launches", flush=True)
+        assert err < TOL[cfg.dtype]
+        assert rep.n_offload == s.stats.n_offload and rep.n_reload == s.stats.n_reload
+        assert rep.n_vertices == s.stats.n_vertices
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_twenty_dispatch_orders_and_transfer_delays_give_identical_bits(name):
+    """Any dependency-respecting order must produce the same output (Introduction); the vertex
+    kernels have a fixed summation order, so 'same' means bit for bit."""
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 0)
+    y_tiled, _ = _oracle(cfg, full)
+    s = H.GpuSession(cfg, full)
+    try:
+        ref, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1))
+        assert R.rel_err(_as_f64(cfg, ref["y"]), y_tiled) < TOL[cfg.dtype]
+        orders = set()
+        for seed in range(20):
+            delay = (0, 50, 500)[seed % 3]
+            batch = (1, 4, 0)[(seed // 3) % 3]
+            print(f"[case] {name} order_seed {seed} delay {delay} batch {batch}", flush=True)
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, delay_seed=100 + seed,
+                                            max_delay_us=delay, max_batch=batch))
+            np.testing.assert_array_equal(out["y"], ref["y"])
+            orders.add(tuple(s.last_order()))
+        assert len(orders) >= 15, "the seeds must really perturb the dispatch order"
+        for policy in (B.TN_POLICY_FIFO, B.TN_POLICY_LIFO):
+            out, _ = s.run(B.tn_exec_opts(policy=policy))
+            np.testing.assert_array_equal(out["y"], ref["y"])
+    finally:
+        s.close()
+
+
+def test_launch_order_respects_every_dependency():
+    cfg = config("c1")
+    s = H.GpuSession(cfg, make_llama_inputs(cfg, 0))
+    try:
+        s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=5, max_batch=3))
+        order = s.last_order()
+        e = H.export_memgraph(s.mg)
+        assert sorted(order) == list(range(len(e["kind"])))
+        # the launch order is a valid order for the library's own dry run, too
+        B.tn_memgraph_simulate(s.mg, order)
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("opts", [
+    dict(max_lookahead_bytes=0, drop_clean_inputs=1),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=0),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, fix_order=1),
+])
+def test_compile_variants_on_the_gpu(opts):
+    cfg = config("ragged_f32")
+    full = make_llama_inputs(cfg, 3)
+    y_tiled, _ = _oracle(cfg, full)
+    s = H.GpuSession(cfg, full, compile_opts=B.tn_compile_opts(**opts))
+    try:
+        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=1))
+        assert R.rel_err(out["y"].astype(np.float64), y_tiled) < TOL["f32"]
+    finally:
+        s.close()
+
+
+def test_device_resident_inputs_and_untransposed_weights():
+    cfg = config("batch2_f32").with_(weights_resident=True, x_resident=True)
+    full = make_llama_inputs(cfg, 0)
+    y_tiled, _ = _oracle(cfg, full)
+    for tr in (True, False):
+        s = H.GpuSession(cfg, full, cap=760_000, weights_transposed=tr)
+        try:
+            assert s.stats.n_offload > 0 and s.stats.n_load == 0
+            for _ in range(2):  # inputs are re-placed before every run
+                out, rep = s.run()
+                assert R.rel_err(out["y"].astype(np.float64), y_tiled) < TOL["f32"]
+        finally:
+            s.close()
+
+
+def test_kv_outputs_match_the_oracle():
+    cfg = config("c1")
+    full = make_llama_inputs(cfg, 0)
+    w = R.widen(cfg, full)
+    s = H.GpuSession(cfg, full, kv_outputs=True)
+    try:
+        out, _ = s.run()
+        x = w["x"]
+        for l in range(cfg.layers):
+            y, k, v = R.decoder_layer(x, w, l, cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base, return_kv=True)
+            assert R.rel_err(out[f"k.{l}"].astype(np.float64), k) < TOL["f32"]
+            assert R.rel_err(out[f"v.{l}"].astype(np.float64), v) < TOL["f32"]
+            x = y
+    finally:
+        s.close()
+
+
+def test_exhausted_host_arena_is_an_error_not_a_hang():
+    cfg = config("c1")
+    s = H.GpuSession(cfg, make_llama_inputs(cfg, 0), arena_bytes=4096)
+    try:
+        s.place_inputs()
+        with pytest.raises(B.TurnipError) as e:
+            s.execute()
+        assert e.value.status == B.TN_ERR_ARENA
+    finally:
+        s.close()
+
+
+def test_generic_taskgraph_through_the_abi():
+    """A hand-built graph (not the LLaMA tiler): C = A B^T + A B^T, one output, fp32."""
+    import torch
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal((40, 24)).astype(np.float32)
+    b = rng.standard_normal((56, 24)).astype(np.float32)
+    tg = B.tn_taskgraph_create()
+    va = B.tn_taskgraph_add_input(tg, B.TN_F32, 40, 24, B.TN_HOST)
+    vb = B.tn_taskgraph_add_input(tg, B.TN_F32, 56, 24, B.TN_HOST)
+    g = B.tn_taskgraph_add_op(tg, B.TN_OP_GEMM, B.tn_op_params(nk=1, trans_b=1), [va, vb], B.TN_F32, 40, 56)
+    s = B.tn_taskgraph_add_op(tg, B.TN_OP_ADD, B.tn_op_params(), [g, g], B.TN_F32, 40, 56)
+    B.tn_taskgraph_mark_output(tg, s)
+    mg = B.tn_compile(tg, None, 1 << 20, None)
+    dev = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    ta, tb = torch.from_numpy(a).pin_memory(), torch.from_numpy(b).pin_memory()
+    out = torch.zeros(40, 56).pin_memory()
+    ex = B.tn_executor_create(mg, dev.data_ptr(), 1 << 20, 0, 0, [streams[0].cuda_stream],
+                              streams[1].cuda_stream, streams[2].cuda_stream)
+    try:
+        B.tn_execute(ex, [ta.data_ptr(), tb.data_ptr(), 0, 0], [out.data_ptr()])
+        ref = 2.0 * (a.astype(np.float64) @ b.astype(np.float64).T)
+        assert R.rel_err(out.numpy().astype(np.float64), ref) < 1e-5
+    finally:
+        B.tn_executor_destroy(ex)
+        B.tn_memgraph_destroy(mg)
+        B.tn_taskgraph_destroy(tg)
