@@ -141,14 +141,15 @@ tn_status build_tables(tn_executor& ex) {
     auto odesc = [&](int i) -> const tn_tensor_desc& { return mg.v[x.operands[i]].desc; };
     switch (x.op_kind) {
       case TN_OP_GEMM: {
-        bool mfma = d.dtype == TN_BF16 && d.trans_b;
+        bool mfma = d.dtype == TN_BF16 && d.trans_b, k32 = true;
         double K = 0;
         for (int k = 0; k < x.p.nk; ++k) {
           aux.push_back(odesc(k).cols);
           K += odesc(k).cols;
           if (odesc(k).cols % 8) mfma = false;
+          if (odesc(k).cols % 32) k32 = false;
         }
-        vi.cls = mfma ? LC_GEMM_BF16_NT : LC_GEMM_F32;
+        vi.cls = !mfma ? LC_GEMM_F32 : (k32 && d.rows >= 256 && d.cols >= 256) ? LC_GEMM_BF16_NT256 : LC_GEMM_BF16_NT;
         vi.flops = 2.0 * d.rows * d.cols * K;
         break;
       }
@@ -267,7 +268,8 @@ void arena_free(tn_executor& ex, uint64_t off) {
 int family_of(int cls) {
   switch (cls) {
     case LC_GEMM_F32:
-    case LC_GEMM_BF16_NT: return 0;
+    case LC_GEMM_BF16_NT:
+    case LC_GEMM_BF16_NT256: return 0;
     case LC_ATTN_F32:
     case LC_ATTN_BF16: return 1;
     default: return 2;

@@ -30,7 +30,8 @@ struct OpDesc {
 // Launch classes: vertices of one class can share a launch.
 enum LaunchClass {
   LC_GEMM_F32 = 0,   // generic fp32-accumulate GEMM on the vector ALUs, any layout, fp32 or bf16 storage
-  LC_GEMM_BF16_NT,   // MFMA bf16 GEMM, B tiles stored [cols, K]
+  LC_GEMM_BF16_NT,   // MFMA bf16 GEMM, B tiles stored [cols, K], 128x128 tile per workgroup
+  LC_GEMM_BF16_NT256,  // the same for output tiles of at least 256x256: 256x256 per workgroup
   LC_RMS_STAT,
   LC_RMS_APPLY,
   LC_ROPE,

@@ -312,6 +312,164 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch
 }
 
 // ---------------------------------------------------------------------------------------------
+// MFMA bf16 GEMM for large tiles: 256x256 output tile per workgroup, 4 wavefronts in 2x2, each
+// 128x128 = 4x4 MFMA 32x32x16 tiles (256 accumulator registers per lane).
+//
+// K advances in steps of 32 through a ring of four LDS stages that the global-to-LDS loads of
+// gfx950 fill directly (no staging registers, no LDS store instructions).  The loads of step
+// s+3 are issued while step s computes, so a load has three steps of MFMA work to land; one
+// barrier per step both publishes stage s and frees the stage that step s-1 read.
+//
+// A direct load writes the 64 lanes' 16-byte chunks back to back, so the LDS image of a stage is
+// unpadded: 256 rows x 4 chunks per operand.  Bank conflicts are avoided by choosing *which*
+// chunk each lane fetches: logical chunk c of row r lives at position c ^ ((r >> 2) & 3).
+// ---------------------------------------------------------------------------------------------
+constexpr int G2_M = 256, G2_N = 256, G2_K = 32, G2_STAGES = 4;
+constexpr int G2_OPER_BYTES = G2_M * G2_K * 2;               // one operand of one stage: 16 KiB
+constexpr int G2_STAGE_BYTES = 2 * G2_OPER_BYTES;            // A then B
+constexpr int G2_LDS_BYTES = G2_STAGES * G2_STAGE_BYTES;     // 128 KiB
+
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane.  Issued as
+// inline assembly so that the compiler does not track it: the kernel keeps several such loads
+// in flight across barriers and waits for them with explicit vmcnt values.
+__device__ __forceinline__ void load_lds16(const void* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_addr) : "memory");
+}
+// Reads of the (read-only, wavefront-uniform) operand tables through the scalar unit, so that
+// they are counted by lgkmcnt and never force a wait on the vector loads in flight.
+__device__ __forceinline__ const void* sload_ptr(const void* const* addr) {
+  const void* v;
+  asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ int sload_int(const int* addr) {
+  int v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(addr) : "memory");
+  return v;
+}
+
+__global__ void __launch_bounds__(256, 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int M = d.rows, N = d.cols, nk = d.p.nk;
+  const void* const* ptrA = t.ptrs + d.ptr0;  // A_0.., then nk entries later B_0..
+  const int* ksz = t.aux + d.aux0;
+  bf16_t* const Cp = (bf16_t*)d.out;
+  const int tn_ = (N + G2_N - 1) / G2_N;
+  const int m0 = (blockIdx.x / tn_) * G2_M, n0 = (blockIdx.x % tn_) * G2_N;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w >> 1, wn = w & 1;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // loader: wave-instruction i of wavefront w fills chunks [w*256 + i*64, +64) of an operand;
+  // this lane's chunk is row w*64 + i*16 + lane/4, logical chunk (lane & 3) ^ ((lane >> 4) & 3).
+  // Rows past the edge of a ragged tile are clamped (their products are never stored).
+  const int lrow = w * 64 + (lane >> 2);
+  const int lcol = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+  int rowA[4], rowB[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    rowA[i] = min(m0 + lrow + i * 16, M - 1);
+    rowB[i] = min(n0 + lrow + i * 16, N - 1);
+  }
+  int nsteps = 0;
+  for (int k = 0; k < nk; ++k) nsteps += ksz[k] / G2_K;
+  int kt = 0, k0 = 0, K = sload_int(ksz);
+  const bf16_t* A = (const bf16_t*)sload_ptr(ptrA);
+  const bf16_t* B = (const bf16_t*)sload_ptr(ptrA + nk);
+
+  const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
+  auto issue = [&](int stage) {  // loads of the K step (kt, k0) into `stage`, then advance
+    const uint32_t dstA = __builtin_amdgcn_readfirstlane(lds0 + stage * G2_STAGE_BYTES + w * 4096);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      load_lds16(A + (size_t)rowA[i] * K + k0 + lcol, dstA + i * 1024);
+      load_lds16(B + (size_t)rowB[i] * K + k0 + lcol, dstA + G2_OPER_BYTES + i * 1024);
+    }
+    k0 += G2_K;
+    if (k0 >= K && kt + 1 < nk) {
+      ++kt;
+      k0 = 0;
+      K = sload_int(ksz + kt);
+      A = (const bf16_t*)sload_ptr(ptrA + kt);
+      B = (const bf16_t*)sload_ptr(ptrA + nk + kt);
+    }
+  };
+
+  // fragment addresses inside a stage: row-major chunks, swizzled as above
+  const int sw = (l32 >> 2) & 3;
+  const int fragA = ((wm * 128 + l32) * 4) * 16, fragB = G2_OPER_BYTES + ((wn * 128 + l32) * 4) * 16;
+  const int c0 = ((0 + g) ^ sw) * 16, c1 = ((2 + g) ^ sw) * 16;
+
+  for (int s = 0; s < G2_STAGES - 1 && s < nsteps; ++s) issue(s);
+  // The second half of a step's MFMAs is deferred to the next iteration, where it covers the
+  // latency of that iteration's first fragment reads.
+  bf16x8 a1[4], b1[4];
+  for (int s = 0; s < nsteps; ++s) {
+    // stage s must have landed: at most the loads of the next two steps may still be in flight
+    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16)
+    else if (s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+    __syncthreads();
+    if (s + G2_STAGES - 1 < nsteps) issue((s + G2_STAGES - 1) % G2_STAGES);
+    const char* st_ = lds + (s % G2_STAGES) * G2_STAGE_BYTES;
+    bf16x8 a0[4], b0[4], an[4], bn[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a0[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c0);
+      b0[i] = *(const bf16x8*)(st_ + fragB + i * 2048 + c0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      an[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c1);
+      bn[i] = *(const bf16x8*)(st_ + fragB + i * 2048 + c1);
+    }
+    if (s > 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a1[i] = an[i];
+      b1[i] = bn[i];
+    }
+  }
+  if (nsteps > 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+        const int col = n0 + wn * 128 + j * 32 + l32;
+        if (row < M && col < N) Cp[(size_t)row * N + col] = f2bf(acc[i][j][r]);
+      }
+}
+
+// ---------------------------------------------------------------------------------------------
 // attention block on the vector ALUs: one thread per (query row, head), online softmax over
 // the key rows in ascending order.  Serves fp32 graphs and shapes the MFMA kernel does not take.
 // aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
@@ -507,6 +665,7 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
   switch (cls) {
     case LC_GEMM_F32: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
     case LC_GEMM_BF16_NT: return cdiv(d.rows, GB_M) * cdiv(d.cols, GB_N);
+    case LC_GEMM_BF16_NT256: return cdiv(d.rows, G2_M) * cdiv(d.cols, G2_N);
     case LC_RMS_STAT: return cdiv(d.rows, 4);
     case LC_RMS_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ROPE: return cdiv((int64_t)d.rows * (d.cols / 2), 256);
@@ -538,6 +697,13 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
   switch (cls) {
     case LC_GEMM_F32: TN_LAUNCH_T(gemm_generic_kernel); break;
     case LC_GEMM_BF16_NT: hipLaunchKernelGGL(gemm_bf16_nt_kernel, grid, wg, 0, s, t, b); break;
+    case LC_GEMM_BF16_NT256: {
+      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+      if (attr != hipSuccess) return attr;
+      hipLaunchKernelGGL(gemm_bf16_nt256_kernel, grid, wg, G2_LDS_BYTES, s, t, b);
+      break;
+    }
     case LC_RMS_STAT: TN_LAUNCH_T(rms_stat_kernel); break;
     case LC_RMS_APPLY: TN_LAUNCH_T(rms_apply_kernel); break;
     case LC_ROPE: TN_LAUNCH_T(rope_kernel); break;
