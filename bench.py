@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--streams", type=int, default=4)
     ap.add_argument("--max-batch", type=int, default=0)
+    ap.add_argument("--max-transfers", type=int, default=0)
+    ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order"])
     ap.add_argument("--cpu-tokens", type=int, default=512, help="tokens of the CPU-oracle sample; 0 = skip")
     ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
     args = ap.parse_args()
@@ -91,11 +93,14 @@ def main():
     t0 = time.perf_counter()
     s = H.GpuSession(cfg, full, n_compute=args.streams)
     t_compile = time.perf_counter() - t0
-    opts = B.tn_exec_opts(policy=B.TN_POLICY_FIFO, max_batch=args.max_batch, profile=1)
+    policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
+              "by_order": B.TN_POLICY_BY_ORDER}[args.policy]
+    opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
-    plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=B.TN_POLICY_FIFO, max_batch=args.max_batch))
+    plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
+                                                                max_transfers=args.max_transfers))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs()["y"]
     st = s.stats
@@ -119,7 +124,7 @@ def main():
                                f"{cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, batch {cfg.batch}, "
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
-                   "compute_streams": args.streams, "memgraph_vertices": int(st.n_vertices),
+                   "compute_streams": args.streams, "ready_policy": args.policy, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

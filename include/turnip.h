@@ -280,6 +280,7 @@ typedef struct {
   uint32_t max_delay_us; /* ... in [0, max_delay_us]; 0 = no injected delay */
   int32_t max_batch;     /* most same-kind ready vertices put into one kernel launch; 0 = default */
   int32_t profile;       /* != 0: time every launch with HIP events (fills the *_ms fields) */
+  int32_t max_transfers; /* most ready copies of one direction queued back to back; 0 = default */
 } tn_exec_opts;
 
 typedef struct {

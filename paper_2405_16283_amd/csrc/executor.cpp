@@ -374,6 +374,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   tn_exec_opts opt{};
   if (opts_in) opt = *opts_in;
   const int max_batch = opt.max_batch > 0 ? std::min<int>(opt.max_batch, kMaxBatch) : 64;
+  const int max_xfer = opt.max_transfers > 0 ? opt.max_transfers : 8;
   // every buffer the run will touch must be there before anything is launched
   for (int64_t m = 0; m < nv; ++m) {
     const MVertex& x = mg.v[m];
@@ -475,47 +476,57 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
 
   while (completed < nv && status == TN_OK) {
     bool progressed = false;
-    // ---- launch transfers: one per direction at a time -----------------------------------
+    // ---- launch transfers: per direction one group of copies at a time, queued back to back
     for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
       Slot& sl = ex->slots[ex->n_compute + dir];
       auto& r = dir == 0 ? ready_h2d : ready_d2h;
       if (sl.busy || r.empty()) continue;
-      const size_t i = pick(r);
-      const int64_t m = r[i];
-      const MVertex& x = mg.v[m];
+      sl.verts.clear();
+      sl.bytes = 0;
       hipError_t e = hipSuccess;
-      if (x.kind == TN_MG_LOAD) {
-        e = hipMemcpyAsync(ex->dbase + x.offset, host_inputs[x.src], x.bytes, hipMemcpyHostToDevice, sl.stream);
-      } else if (x.kind == TN_MG_RELOAD) {
-        const int64_t off = ex->arena_off[x.operands[0]];
-        e = hipMemcpyAsync(ex->dbase + x.offset, ex->arena + off, x.bytes, hipMemcpyHostToDevice, sl.stream);
-      } else if (x.kind == TN_MG_STORE) {
-        e = hipMemcpyAsync(host_outputs[x.output_index], ex->dbase + mg.v[x.operands[0]].offset, x.bytes,
-                           hipMemcpyDeviceToHost, sl.stream);
-      } else {  // offload
-        uint64_t off;
-        if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
-          status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
-                        (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
-          break;
+      while (!r.empty() && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
+        const size_t i = pick(r);
+        const int64_t m = r[i];
+        const MVertex& x = mg.v[m];
+        if (x.kind == TN_MG_LOAD) {
+          e = hipMemcpyAsync(ex->dbase + x.offset, host_inputs[x.src], x.bytes, hipMemcpyHostToDevice, sl.stream);
+        } else if (x.kind == TN_MG_RELOAD) {
+          const int64_t off = ex->arena_off[x.operands[0]];
+          e = hipMemcpyAsync(ex->dbase + x.offset, ex->arena + off, x.bytes, hipMemcpyHostToDevice, sl.stream);
+        } else if (x.kind == TN_MG_STORE) {
+          e = hipMemcpyAsync(host_outputs[x.output_index], ex->dbase + mg.v[x.operands[0]].offset, x.bytes,
+                             hipMemcpyDeviceToHost, sl.stream);
+        } else {  // offload
+          uint64_t off;
+          if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
+            if (!sl.verts.empty()) break;  // let the copies already queued (and later reloads) free slots
+            bool reload_pending = ex->slots[ex->n_compute].busy || !ready_h2d.empty();
+            if (reload_pending) break;
+            status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
+                          (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
+            break;
+          }
+          ex->arena_off[m] = (int64_t)off;
+          arena_used += (x.bytes + 255) / 256 * 256;
+          rep.arena_high_water = std::max(rep.arena_high_water, arena_used);
+          e = hipMemcpyAsync(ex->arena + off, ex->dbase + mg.v[x.operands[0]].offset, x.bytes, hipMemcpyDeviceToHost, sl.stream);
+          ++rep.n_offload;
         }
-        ex->arena_off[m] = (int64_t)off;
-        arena_used += (x.bytes + 255) / 256 * 256;
-        rep.arena_high_water = std::max(rep.arena_high_water, arena_used);
-        e = hipMemcpyAsync(ex->arena + off, ex->dbase + mg.v[x.operands[0]].offset, x.bytes, hipMemcpyDeviceToHost, sl.stream);
-        ++rep.n_offload;
+        if (e != hipSuccess) break;
+        r.erase(r.begin() + i);
+        sl.verts.push_back(m);
+        sl.bytes += (double)x.bytes;
+        (dir == 0 ? rep.h2d_bytes : rep.d2h_bytes) += x.bytes;
+        rep.n_reload += x.kind == TN_MG_RELOAD;
+        ex->last_order.push_back(m);
       }
+      if (status != TN_OK) break;
+      if (sl.verts.empty() && e == hipSuccess) continue;
       if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }
-      r.erase(r.begin() + i);
       sl.busy = true;
       sl.event_seen = false;
       sl.family = 3 + dir;
-      sl.verts.assign(1, m);
-      sl.bytes = (double)x.bytes;
-      (dir == 0 ? rep.h2d_bytes : rep.d2h_bytes) += x.bytes;
-      rep.n_reload += x.kind == TN_MG_RELOAD;
-      ex->last_order.push_back(m);
       ++rep.n_launches;
       progressed = true;
     }
