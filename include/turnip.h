@@ -80,7 +80,9 @@ typedef struct {
  *   GEMM         nk, trans_b            number of k tiles; operands are A_0..A_{nk-1} then B_0..B_{nk-1};
  *                                       A_k is [rows, K_k]; B_k is [K_k, cols], or, with trans_b != 0,
  *                                       stored transposed as [cols, K_k] (the usual [out, in] layout
- *                                       of linear-layer weights, which the MFMA kernel reads directly)
+ *                                       of linear-layer weights, which the MFMA kernel reads directly).
+ *                                       trans_c != 0: the output tensor holds the product transposed,
+ *                                       [cols, rows] of the logical [rows, cols] result
  *   RMS_STAT     d, eps                 d = total number of columns of the row block
  *   ROPE         pos0, col0, head_dim, rope_base
  *                                       row r has position pos0 + r; column c belongs to pair
@@ -92,6 +94,8 @@ typedef struct {
  *                                       head_dim.  Output row: gw unnormalised sums of
  *                                       exp(s - m) v, then hpg row maxima m, then hpg sums l.
  *                                       causal != 0 excludes keys with k_pos0 + c > q_pos0 + r.
+ *                                       v_trans != 0: the V operands are tiles of V^T, each
+ *                                       [columns of the tile, key rows of the tile]
  *   ATTN_COMBINE row0, col0, head_dim, hpg
  *                                       output tile = rows [row0, row0 + rows) and columns
  *                                       [col0, col0 + cols) of the merged, normalised block. */
@@ -113,6 +117,8 @@ typedef struct {
   int32_t row0;
   int32_t hpg;
   int32_t trans_b;
+  int32_t trans_c;
+  int32_t v_trans;
 } tn_op_params;
 
 /* ------------------------------------------------------------------------------------------ */
@@ -167,6 +173,7 @@ typedef struct {
   int32_t x_residency;
   int32_t kv_outputs; /* != 0: post-rotary K and V tiles of every layer are marked outputs too */
   int32_t weights_transposed; /* != 0: weight tiles are stored [out, in] and GEMMs use trans_b */
+  int32_t v_transposed;       /* != 0: the V projection stores V^T tiles (trans_c) and attention reads them (v_trans) */
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

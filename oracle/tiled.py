@@ -17,11 +17,13 @@ execution.  Only tests, the smoke check and the benchmark's CPU-baseline leg imp
 
 Vertex kinds (inputs -> output):
   input         ()                                   -> the tile itself
-  gemm          A_0..A_{nk-1}, B_0..B_{nk-1}         -> sum_k A_k @ B_k, k ascending (B_k held transposed if trans_b)
+  gemm          A_0..A_{nk-1}, B_0..B_{nk-1}         -> sum_k A_k @ B_k, k ascending (B_k held transposed if trans_b;
+                                                        result stored transposed if trans_c)
   rms_stat      X_0..X_{n-1} (tiles of one row block)-> [rows,1] 1/sqrt(mean over all columns of x^2 + eps)
   rms_apply     X, stat, gain[1,c]                   -> x * stat * gain
   rope          X                                    -> rotary embedding; params pos0, col0, head_dim, base
   attn_block    Q tiles, K tiles, V tiles            -> packed [rows, gw + 2*hpg]: O (unnormalised), m, l
+                                                        (V tiles hold V^T if v_trans)
   attn_combine  partial_0..partial_j                 -> normalised attention output tile
   silu_mul      gate, up                             -> gate/(1+exp(-gate)) * up
   add           a, b                                 -> a + b
@@ -90,7 +92,7 @@ def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
         for k in range(nk):
             t = ins[k] @ (ins[nk + k].T if p.get("trans_b") else ins[nk + k])
             acc = t if acc is None else acc + t
-        return acc
+        return acc.T if p.get("trans_c") else acc
     if kind == "rms_stat":
         ss = sum(np.sum(x * x, axis=1, keepdims=True) for x in ins)
         return 1.0 / np.sqrt(ss / p["d"] + p["eps"])
@@ -112,12 +114,13 @@ def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
         return y
     if kind == "attn_block":
         nq, nkv, nc, hd = p["n_q_tiles"], p["n_kv_tiles"], p["n_col_tiles"], p["head_dim"]
-        def gather(off, nr):
-            return np.concatenate([np.concatenate(ins[off + r * nc: off + (r + 1) * nc], axis=1)
-                                   for r in range(nr)], axis=0)
+        def gather(off, nr, transposed=False):
+            tiles = [[ins[off + r * nc + c].T if transposed else ins[off + r * nc + c] for c in range(nc)]
+                     for r in range(nr)]
+            return np.concatenate([np.concatenate(row, axis=1) for row in tiles], axis=0)
         q = gather(0, nq)
         k = gather(nq * nc, nkv)
-        v = gather(nq * nc + nkv * nc, nkv)
+        v = gather(nq * nc + nkv * nc, nkv, bool(p.get("v_trans")))
         gw = q.shape[1]
         hpg = gw // hd
         rows = q.shape[0]

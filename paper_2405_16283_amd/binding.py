@@ -42,7 +42,8 @@ class tn_op_params(C.Structure):
                 ("col0", C.c_int32), ("head_dim", C.c_int32), ("rope_base", C.c_float),
                 ("n_q_tiles", C.c_int32), ("n_kv_tiles", C.c_int32), ("n_col_tiles", C.c_int32),
                 ("q_pos0", C.c_int32), ("k_pos0", C.c_int32), ("causal", C.c_int32),
-                ("scale", C.c_float), ("row0", C.c_int32), ("hpg", C.c_int32), ("trans_b", C.c_int32)]
+                ("scale", C.c_float), ("row0", C.c_int32), ("hpg", C.c_int32), ("trans_b", C.c_int32),
+                ("trans_c", C.c_int32), ("v_trans", C.c_int32)]
 
 
 class tn_tg_vertex(C.Structure):
@@ -54,7 +55,8 @@ class tn_llama_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("layers", "d_model", "n_heads", "head_dim", "ffn", "seq", "batch",
                                           "dtype", "tile", "attn_block")] + \
                [("eps", C.c_float), ("rope_base", C.c_float), ("weights_residency", C.c_int32),
-                ("x_residency", C.c_int32), ("kv_outputs", C.c_int32), ("weights_transposed", C.c_int32)]
+                ("x_residency", C.c_int32), ("kv_outputs", C.c_int32), ("weights_transposed", C.c_int32),
+                ("v_transposed", C.c_int32)]
 
 
 class tn_llama_binding(C.Structure):

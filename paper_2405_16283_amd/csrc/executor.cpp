@@ -141,6 +141,7 @@ tn_status build_tables(tn_executor& ex) {
     auto odesc = [&](int i) -> const tn_tensor_desc& { return mg.v[x.operands[i]].desc; };
     switch (x.op_kind) {
       case TN_OP_GEMM: {
+        if (x.p.trans_c) std::swap(d.rows, d.cols);  // the kernels work on the logical [rows, cols] product
         bool mfma = d.dtype == TN_BF16 && d.trans_b, k32 = true;
         double K = 0;
         for (int k = 0; k < x.p.nk; ++k) {
@@ -196,7 +197,10 @@ tn_status build_tables(tn_executor& ex) {
           if (odesc(c).cols != tc) return fail(TN_ERR_SHAPE, "attn_block %lld: column tiles are not uniform", (long long)m);
         if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_block %lld: head_dim must be 64 or 128", (long long)m);
         aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
-        vi.cls = (d.dtype == TN_BF16 && tc % 8 == 0) ? LC_ATTN_BF16 : LC_ATTN_F32;
+        // the MFMA kernel wants V^T tiles, whole heads inside one column tile, 64-key chunks inside
+        // one row tile, and 16-byte chunks that do not straddle anything
+        vi.cls = (d.dtype == TN_BF16 && x.p.v_trans && tc % hd == 0 && tk % 64 == 0 && kv_rows % 8 == 0)
+                     ? LC_ATTN_BF16 : LC_ATTN_F32;
         vi.head_dim = (int16_t)hd;
         vi.flops = 4.0 * q_rows * kv_rows * (double)(nc * tc);
         break;

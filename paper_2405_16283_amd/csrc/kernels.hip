@@ -236,7 +236,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int r = m0 + ty * 4 + i, c = n0 + tx * 4 + j;
-      if (r < M && c < N) st(Cp + (size_t)r * N + c, acc[i][j]);
+      if (r < M && c < N) st(d.p.trans_c ? Cp + (size_t)c * M + r : Cp + (size_t)r * N + c, acc[i][j]);
     }
 }
 
@@ -246,6 +246,43 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch
 // K step 64 staged through LDS.  Rows are padded by 8 elements so that the 16-byte fragment
 // reads of the 32 lanes of a half-wave fall on different banks.
 // ---------------------------------------------------------------------------------------------
+// Writes a wavefront's TI x TJ grid of 32x32 accumulator tiles as bf16.  In an accumulator tile a
+// lane holds column l32 and the rows 8*(r/4) + 4*g + r%4: four consecutive rows per group of four
+// registers, which makes the transposed store (C^T, rows contiguous) an 8-byte store per group.
+template <int TI, int TJ>
+__device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[TI][TJ], bf16_t* Cp, int M, int N, int row0, int col0,
+                                              int l32, int g, bool trans_c) {
+  const bool wide = trans_c && (M & 3) == 0;
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      const int col = col0 + j * 32 + l32;
+      const f32x16 c = acc[i][j];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int row = row0 + i * 32 + 8 * a + 4 * g;
+        const bf16_t h0 = f2bf(c[4 * a]), h1 = f2bf(c[4 * a + 1]), h2 = f2bf(c[4 * a + 2]), h3 = f2bf(c[4 * a + 3]);
+        if (wide) {
+          if (col < N && row < M) {
+            uint2 v;
+            v.x = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            v.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
+            *(uint2*)(Cp + (size_t)col * M + row) = v;
+          }
+        } else if (col < N) {
+          const size_t sr = trans_c ? 1 : (size_t)N, sc = trans_c ? (size_t)M : 1;
+          bf16_t* p = Cp + (size_t)row * sr + (size_t)col * sc;
+          if (row < M) p[0] = h0;
+          if (row + 1 < M) p[sr] = h1;
+          if (row + 2 < M) p[2 * sr] = h2;
+          if (row + 3 < M) p[3 * sr] = h3;
+        }
+      }
+    }
+  }
+}
+
 constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_LD = GB_K + 8;
 
 __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch b) {
@@ -298,17 +335,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch
       __syncthreads();
     }
   }
-  bf16_t* Cp = (bf16_t*)d.out;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-        const int col = n0 + wn * 64 + j * 32 + l32;
-        if (row < M && col < N) Cp[(size_t)row * N + col] = f2bf(acc[i][j][r]);
-      }
+  store_c_tiles<2, 2>(acc, (bf16_t*)d.out, M, N, m0 + wm * 64, n0 + wn * 64, l32, g, d.p.trans_c != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -457,16 +484,7 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt256_kernel(DeviceTables t,
       for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
   }
 
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-        const int col = n0 + wn * 128 + j * 32 + l32;
-        if (row < M && col < N) Cp[(size_t)row * N + col] = f2bf(acc[i][j][r]);
-      }
+  store_c_tiles<4, 4>(acc, Cp, M, N, m0 + wm * 128, n0 + wn * 128, l32, g, d.p.trans_c != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -478,6 +496,16 @@ template <typename T>
 __device__ __forceinline__ const T* tile_elem(void* const* tiles, int nc, int t_rows, int t_cols, int row, int col) {
   const int rt = row / t_rows, ct = col / t_cols;
   return (const T*)tiles[rt * nc + ct] + (size_t)(row - rt * t_rows) * t_cols + (col - ct * t_cols);
+}
+
+// The same for a grid of transposed tiles: tile (rt, ct) holds [its columns, its rows]; the last
+// row tile may be shorter, which changes its pitch.
+template <typename T>
+__device__ __forceinline__ const T* tile_elem_t(void* const* tiles, int nc, int t_rows, int t_cols, int total_rows,
+                                                int row, int col) {
+  const int rt = row / t_rows, ct = col / t_cols;
+  const int pitch = min(t_rows, total_rows - rt * t_rows);
+  return (const T*)tiles[rt * nc + ct] + (size_t)(col - ct * t_cols) * pitch + (row - rt * t_rows);
 }
 
 template <typename T, int HD>
@@ -511,7 +539,11 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch 
     const float alpha = __expf(m - mn), p = __expf(s - mn);
     l = l * alpha + p;
 #pragma unroll
-    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + p * ld(tile_elem<T>(Vt, nc, tk, tc, j, h * HD + c));
+    for (int c = 0; c < HD; ++c) {
+      const float v = d.p.v_trans ? ld(tile_elem_t<T>(Vt, nc, tk, tc, kv_rows, j, h * HD + c))
+                                  : ld(tile_elem<T>(Vt, nc, tk, tc, j, h * HD + c));
+      o[c] = o[c] * alpha + p * v;
+    }
     m = mn;
   }
   float* out = (float*)d.out + (size_t)row * d.cols;
@@ -522,19 +554,26 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch 
 }
 
 // ---------------------------------------------------------------------------------------------
-// MFMA attention block (bf16 storage).  One workgroup = one head x 128 query rows; each of its 4
-// wavefronts owns 32 query rows.  Per chunk of 32 key rows the wavefront forms the *transposed*
-// score tile S^T = K Q^T, so that a lane owns one query (its column) and the softmax statistics
-// are per-lane scalars; the probabilities then are already laid out as the B operand of
-// O^T += V^T P^T.  K is staged row-major in LDS, V transposed.
+// MFMA attention block (bf16 storage, V given as V^T tiles).  One workgroup = one head x 128 query
+// rows; each of its 4 wavefronts owns 32 query rows; two workgroups share a compute unit.
+//
+// Per 32 keys a wavefront forms the *transposed* score tile S^T = K Q^T, so that a lane owns one
+// query (its column) and the softmax statistics are per-lane scalars.  The rows of S^T are fed
+// with the keys in a permuted order, pi(i) = 16*(a>>1) + 8*g + 4*(a&1) + b for i = 8a + 4g + b,
+// chosen so that the 8 probabilities a lane holds per 16-key slab belong to 8 consecutive keys:
+// P^T is then already the B operand of O^T += V^T P^T, and the A operand is a plain 16-byte read
+// of a V^T row.  K and V^T chunks of 64 keys are double-buffered in LDS and filled by direct
+// global-to-LDS loads; conflicts are avoided by swizzling which chunk each lane fetches.
 // ---------------------------------------------------------------------------------------------
 template <int HD>
-__global__ void __launch_bounds__(256) attn_bf16_kernel(DeviceTables t, Batch b) {
+__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.idx[blockIdx.y]];
   if ((int)blockIdx.x >= d.nblocks) return;
-  constexpr int KLD = HD + 8, VLD = 32 + 8;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[32 * KLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[HD * VLD];
+  constexpr int KC = 64;                   // keys per iteration
+  constexpr int CPR = HD / 8;              // 16-byte chunks per K row
+  constexpr int KBYTES = KC * HD * 2, BUF = 2 * KBYTES;  // K chunk, then V^T chunk [HD][KC]
+  constexpr int NLD = KC * CPR / 256;      // wave-instructions per thread and operand
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int* ax = t.aux + d.aux0;
   const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
   const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD;
@@ -544,14 +583,18 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(DeviceTables t, Batch b)
   void* const* Qp = t.ptrs + d.ptr0;
   void* const* Kp = Qp + d.p.n_q_tiles * nc;
   void* const* Vp = Kp + d.p.n_kv_tiles * nc;
-  const int qrow = qb * 128 + w * 32 + l32;  // this lane's query row inside the block
+  const int qrow = qb * 128 + w * 32 + l32;
   const bool qvalid = qrow < q_rows;
+  const float scale = d.p.scale;
+  const int causal = d.p.causal, k_pos0 = d.p.k_pos0;
+  const int qpos = d.p.q_pos0 + qrow;
+  float* const outp = (float*)d.out;
+  const int ldo = d.cols;
 
   bf16x8 qf[HD / 16];
 #pragma unroll
   for (int s = 0; s < HD / 16; ++s) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (qvalid) v = *(const uint4*)tile_elem<bf16_t>(Qp, nc, tq, tc, qrow, h * HD + s * 16 + g * 8);
+    uint4 v = *(const uint4*)tile_elem<bf16_t>(Qp, nc, tq, tc, min(qrow, q_rows - 1), h * HD + s * 16 + g * 8);
     qf[s] = *(bf16x8*)&v;
   }
   f32x16 ot[HD / 32];
@@ -560,88 +603,140 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(DeviceTables t, Batch b)
 #pragma unroll
     for (int r = 0; r < 16; ++r) ot[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;
-  const int qpos = d.p.q_pos0 + qrow;
-  // key chunks entirely above the diagonal of this workgroup's rows contribute nothing
-  int kv_end = kv_rows;
-  if (d.p.causal) kv_end = min(kv_rows, d.p.q_pos0 + qb * 128 + 128 - d.p.k_pos0);
+  int kv_end = kv_rows;  // keys above the diagonal of this workgroup's rows contribute nothing
+  if (causal) kv_end = min(kv_rows, d.p.q_pos0 + qb * 128 + 128 - k_pos0);
+  const int niter = (kv_end + KC - 1) / KC;
 
-  for (int kv0 = 0; kv0 < kv_end; kv0 += 32) {
-    __syncthreads();
-    // stage K (row-major) and V (transposed): 32 rows x HD/8 segments of 16 bytes each
-    for (int s = threadIdx.x; s < 32 * (HD / 8); s += 256) {
-      const int r = s / (HD / 8), c = (s % (HD / 8)) * 8;
-      uint4 vk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (kv0 + r < kv_rows) {
-        vk = *(const uint4*)tile_elem<bf16_t>(Kp, nc, tk, tc, kv0 + r, h * HD + c);
-        vv = *(const uint4*)tile_elem<bf16_t>(Vp, nc, tk, tc, kv0 + r, h * HD + c);
+  // loader: operand chunk p = i*256 + tid.  K: row p / CPR, stored chunk p % CPR holds logical
+  // chunk (p % CPR) ^ swizzle(row).  V^T: row (= head column) p / 8, stored chunk p % 8.
+  // A head's columns lie inside one column tile and a chunk of 64 keys inside one row tile (the
+  // executor checks both), so the tile pointers are wavefront-uniform and change rarely.
+  const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
+  const int ct = (h * HD) / tc, cin0 = (h * HD) % tc;
+  int kr_[NLD], kcol_[NLD], vrow_[NLD], vkv_[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int p = i * 256 + threadIdx.x;
+    const int kr = p / CPR;
+    kr_[i] = kr;
+    kcol_[i] = cin0 + (((p % CPR) ^ (CPR == 16 ? (kr & 15) : ((kr >> 1) & 7))) * 8);
+    const int vr = p / 8;
+    vrow_[i] = cin0 + vr;
+    vkv_[i] = ((p % 8) ^ ((vr >> 1) & 7)) * 8;
+  }
+  int rt = -1;                 // row tile the current chunk lies in
+  const bf16_t* Kt = nullptr;  // its K tile and V^T tile
+  const bf16_t* Vt = nullptr;
+  int trows = 0;               // rows of that tile
+  auto issue = [&](int it, int buf) {
+    const int kv0 = it * KC;
+    const int nrt = kv0 / tk;
+    if (nrt != rt) {
+      rt = nrt;
+      Kt = (const bf16_t*)sload_ptr((const void* const*)(Kp + rt * nc + ct));
+      Vt = (const bf16_t*)sload_ptr((const void* const*)(Vp + rt * nc + ct));
+      trows = min(tk, kv_rows - rt * tk);
+    }
+    const int kin = kv0 - rt * tk;
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + buf * BUF + w * 1024);
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int krow = min(kin + kr_[i], trows - 1);  // rows past the end: any valid row, masked later
+      load_lds16(Kt + (size_t)krow * tc + kcol_[i], dst + i * 4096);
+      int kv = kin + vkv_[i];
+      if (kv >= trows) kv = 0;  // multiplied by zero probabilities; any valid data will do
+      load_lds16(Vt + (size_t)vrow_[i] * trows + kv, dst + KBYTES + i * 4096);
+    }
+  };
+
+  constexpr float LOG2E = 1.44269504088896340736f;
+  const float scale2 = scale * LOG2E;  // scores are kept in units of log2: exp(x) = exp2(x * log2 e)
+  // first query row of this wavefront: a chunk whose last key is not after it needs no mask
+  const int qpos_w0 = d.p.q_pos0 + qb * 128 + w * 32;
+  const int a_ = l32 >> 3, b_ = l32 & 3, g_ = (l32 >> 2) & 1;
+  const int kperm = 16 * (a_ >> 1) + 8 * g_ + 4 * (a_ & 1) + b_;
+
+  if (niter > 0) issue(0, 0);
+  for (int it = 0; it < niter; ++it) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this iteration's chunk has landed
+    __syncthreads();                     // ... for everybody, and the other buffer is free
+    if (it + 1 < niter) issue(it + 1, (it + 1) & 1);
+    const char* kb = lds + (it & 1) * BUF;
+    const char* vb = kb + KBYTES;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      // S^T: row i of the MFMA tile is key pi(i)
+      const int krow = sub * 32 + kperm;
+      const int ksw = CPR == 16 ? (krow & 15) : ((krow >> 1) & 7);
+      f32x16 sT;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sT[r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < HD / 16; ++s) {
+        bf16x8 a = *(const bf16x8*)(kb + (krow * CPR + ((2 * s + g) ^ ksw)) * 16);
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sT, 0, 0, 0);
       }
-      *(uint4*)(Ks + r * KLD + c) = vk;
-      const bf16_t* pv = (const bf16_t*)&vv;
+      // register r = 4a + b of this lane is the score of key 16*(a>>1) + 8g + 4*(a&1) + b
+      const int kvs = it * KC + sub * 32;
+      const bool need_mask = kvs + 32 > kv_rows || (causal && k_pos0 + kvs + 31 > qpos_w0);
+      float mx = -INFINITY;
+      if (need_mask) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) Vt[(c + k) * VLD + r] = pv[k];
-    }
-    __syncthreads();
-    f32x16 sT;
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kvs + 16 * (r >> 3) + 8 * g + (r & 7);
+          const bool ok = kv < kv_rows && !(causal && k_pos0 + kv > qpos);
+          sT[r] = ok ? sT[r] * scale2 : -INFINITY;
+          mx = fmaxf(mx, sT[r]);
+        }
+      } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sT[r] = 0.f;
+        for (int r = 0; r < 16; ++r) {
+          sT[r] *= scale2;
+          mx = fmaxf(mx, sT[r]);
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m, mx);
+      if (__any(mn > m)) {  // some query of the wavefront has a new maximum: rescale what is summed so far
+        const float alpha = mn == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - mn);
+        l *= alpha;
 #pragma unroll
-    for (int s = 0; s < HD / 16; ++s) {
-      bf16x8 a = *(const bf16x8*)(Ks + l32 * KLD + s * 16 + g * 8);
-      sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sT, 0, 0, 0);
-    }
-    // sT[r] is the score of key (8*(r/4) + 4*g + r%4) against this lane's query
-    float mx = -INFINITY;
+        for (int i = 0; i < HD / 32; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int kv = kv0 + 8 * (r / 4) + 4 * g + (r % 4);
-      const bool ok = kv < kv_rows && !(d.p.causal && d.p.k_pos0 + kv > qpos);
-      sT[r] = ok ? sT[r] * d.p.scale : -INFINITY;
-      mx = fmaxf(mx, sT[r]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);
-    bf16x8 p0, p1;
-    if (mn == -INFINITY) {  // nothing visible yet for this query
-#pragma unroll
-      for (int k = 0; k < 8; ++k) { p0[k] = (__bf16)0.f; p1[k] = (__bf16)0.f; }
-    } else {
-      const float alpha = __expf(m - mn);
+          for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+        m = mn;
+      }
+      const float msub = m == -INFINITY ? 0.f : m;  // nothing visible yet: every probability is exp2(-inf) = 0
+      bf16x8 p0, p1;
       float ls = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __expf(sT[r] - mn);
-        ls += p;
-        if (r < 8) p0[r] = (__bf16)p; else p1[r - 8] = (__bf16)p;
+        const float pr = __builtin_amdgcn_exp2f(sT[r] - msub);
+        ls += pr;
+        if (r < 8) p0[r] = (__bf16)pr; else p1[r - 8] = (__bf16)pr;
       }
-      l = l * alpha + ls;
+      l += ls;
+      // O^T[d, q] += sum over the slab's 16 keys of V^T[d, key] P^T[key, q]
 #pragma unroll
-      for (int i = 0; i < HD / 32; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
-      m = mn;
-    }
-    // O^T[d, q] += sum_kv V[kv, d] P[q, kv]; the kv order inside each MFMA follows sT's layout
-#pragma unroll
-    for (int i = 0; i < HD / 32; ++i) {
-      const bf16_t* vrow = Vt + (i * 32 + l32) * VLD;
-      bf16x8 a0, a1;
-      *(uint2*)&a0 = *(const uint2*)(vrow + 4 * g);
-      *((uint2*)&a0 + 1) = *(const uint2*)(vrow + 8 + 4 * g);
-      *(uint2*)&a1 = *(const uint2*)(vrow + 16 + 4 * g);
-      *((uint2*)&a1 + 1) = *(const uint2*)(vrow + 24 + 4 * g);
-      ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0, ot[i], 0, 0, 0);
-      ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1, ot[i], 0, 0, 0);
+      for (int i = 0; i < HD / 32; ++i) {
+        const int dr = i * 32 + l32, vsw = (dr >> 1) & 7;
+        bf16x8 a0 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + g) ^ vsw)) * 16);
+        bf16x8 a1 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + 2 + g) ^ vsw)) * 16);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1, ot[i], 0, 0, 0);
+      }
     }
   }
+  m *= 0.69314718055994530942f;  // back to natural-log units for the combine step
   l += __shfl_xor(l, 32, 64);
   if (!qvalid) return;
-  float* out = (float*)d.out + (size_t)qrow * d.cols;
+  float* out = outp + (size_t)qrow * ldo;
 #pragma unroll
   for (int i = 0; i < HD / 32; ++i)
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       float* o4 = out + h * HD + i * 32 + 8 * a + 4 * g;
-      if ((d.cols & 3) == 0) {  // rows of the partial are 16-byte aligned
+      if ((ldo & 3) == 0) {  // rows of the partial are 16-byte aligned
         *(float4*)o4 = make_float4(ot[i][4 * a], ot[i][4 * a + 1], ot[i][4 * a + 2], ot[i][4 * a + 3]);
       } else {
 #pragma unroll
@@ -728,9 +823,16 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
       }
       break;
     case LC_ATTN_BF16:
-      if (head_dim == 64) hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, wg, 0, s, t, b);
-      else if (head_dim == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, wg, 0, s, t, b);
-      else return hipErrorInvalidValue;
+      if (head_dim == 64) {
+        hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, wg, 4 * 64 * 64 * 2, s, t, b);
+      } else if (head_dim == 128) {
+        static const hipError_t attr = hipFuncSetAttribute((const void*)attn_bf16_kernel<128>,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 64 * 128 * 2);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, wg, 4 * 64 * 128 * 2, s, t, b);
+      } else {
+        return hipErrorInvalidValue;
+      }
       break;
     default: return hipErrorInvalidValue;
   }

@@ -42,13 +42,15 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
   switch (kind) {
     case TN_OP_GEMM: {
       if (p.nk < 1 || n_in != 2 * p.nk) return fail(TN_ERR_SHAPE, "gemm: needs 2*nk operands");
+      tn_tensor_desc lo = out;  // logical [rows, cols] of the product
+      if (p.trans_c) std::swap(lo.rows, lo.cols);
       for (int k = 0; k < p.nk; ++k) {
         const auto &a = D(k), &b = D(p.nk + k);
         const int32_t bk = p.trans_b ? b.cols : b.rows, bn = p.trans_b ? b.rows : b.cols;
-        if (a.rows != out.rows || bn != out.cols || a.cols != bk || a.dtype != out.dtype ||
+        if (a.rows != lo.rows || bn != lo.cols || a.cols != bk || a.dtype != out.dtype ||
             b.dtype != out.dtype)
           return fail(TN_ERR_SHAPE, "gemm: k tile %d has A [%d,%d] B [%d,%d] for C [%d,%d]", k,
-                      a.rows, a.cols, b.rows, b.cols, out.rows, out.cols);
+                      a.rows, a.cols, b.rows, b.cols, lo.rows, lo.cols);
       }
       return TN_OK;
     }
@@ -96,7 +98,9 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
       }
       for (int r = 0; r < nkv; ++r)
         for (int c = 0; c < nc; ++c) {
-          const auto &k = D(nq * nc + r * nc + c), &v = D((nq + nkv) * nc + r * nc + c);
+          const auto& k = D(nq * nc + r * nc + c);
+          tn_tensor_desc v = D((nq + nkv) * nc + r * nc + c);
+          if (p.v_trans) std::swap(v.rows, v.cols);
           if (k.cols != D(c).cols || !same(k, v) || k.rows != D(nq * nc + r * nc).rows || k.dtype != dt)
             return fail(TN_ERR_SHAPE, "attn_block: K/V tile (%d,%d) does not fit the grid", r, c);
         }
@@ -196,13 +200,15 @@ struct Tiler {
   }
 
   // one output tile of X(row tile) * W, full K inside the vertex
-  tn_vid gemm(const std::vector<tn_vid>& xrow, const Grid& w, size_t j, int32_t m, int32_t n) {
+  tn_vid gemm(const std::vector<tn_vid>& xrow, const Grid& w, size_t j, int32_t m, int32_t n,
+              bool trans_c = false) {
     tn_op_params p{};
     p.nk = (int32_t)xrow.size();
     p.trans_b = c.weights_transposed ? 1 : 0;
+    p.trans_c = trans_c ? 1 : 0;
     std::vector<tn_vid> in(xrow);
     for (size_t k = 0; k < xrow.size(); ++k) in.push_back(w[k][j]);
-    return op(TN_OP_GEMM, p, std::move(in), {c.dtype, m, n});
+    return op(TN_OP_GEMM, p, std::move(in), trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
   }
 
   std::vector<tn_vid> rmsnorm(const std::vector<tn_vid>& xrow, const std::vector<tn_vid>& gns, int32_t m) {
@@ -373,14 +379,15 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
             const int32_t n = t.dcols[j].len();
             q[i].push_back(t.rope(t.gemm(a, wq, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
             kk[i].push_back(t.rope(t.gemm(a, wk, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
-            vv[i].push_back(t.gemm(a, wv, j, m, n));
+            vv[i].push_back(t.gemm(a, wv, j, m, n, c.v_transposed != 0));
             if (c.kv_outputs) {
               Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
               for (int which = 0; which < 2; ++which) {
                 tn_vid id = which ? vv[i][j] : kk[i][j];
                 tg->v[id].output_index = (int32_t)tg->outputs.size();
                 tg->outputs.push_back(id);
-                tg->bindings.push_back({id, which ? TN_T_V : TN_T_K, l, rr.a, rr.b, t.dcols[j].a, t.dcols[j].b, 0});
+                tg->bindings.push_back({id, which ? TN_T_V : TN_T_K, l, rr.a, rr.b, t.dcols[j].a, t.dcols[j].b,
+                                        (which && c.v_transposed) ? 1 : 0});
               }
             }
           }
@@ -405,6 +412,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
             p.q_pos0 = stripes[s].a;
             p.k_pos0 = stripes[s2].a;
             p.causal = (s2 == s);
+            p.v_trans = c.v_transposed ? 1 : 0;
             p.scale = 1.0f / std::sqrt((float)c.head_dim);
             parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, stripes[s].len(), gw + 2 * hpg}));
           }

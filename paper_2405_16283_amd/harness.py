@@ -20,7 +20,8 @@ MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op",
 EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}
 
 
-def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True) -> B.tn_llama_config:
+def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
+                        v_transposed: bool = True) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -28,7 +29,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         attn_block=cfg.attn_block, eps=cfg.eps, rope_base=cfg.rope_base,
         weights_residency=B.TN_DEVICE if cfg.weights_resident else B.TN_HOST,
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
-        weights_transposed=int(weights_transposed))
+        weights_transposed=int(weights_transposed), v_transposed=int(v_transposed))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -120,13 +121,13 @@ class GpuSession:
     def __init__(self, cfg, full_inputs: Dict[str, np.ndarray], cap: Optional[int] = None,
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
-                 weights_transposed: bool = True, arena_bytes: int = 0):
+                 weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
         self.torch = torch
         self.cfg = cfg
-        self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed))
+        self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         self.mg = B.tn_compile(self.tg, order, self.cap, compile_opts)
         self.stats = B.tn_memgraph_stats(self.mg)
@@ -184,11 +185,12 @@ class GpuSession:
         slab = self.out_slab.numpy()
         es = np.dtype(self.elem).itemsize
         for i, v in enumerate(self.out_vids):
-            _, name, r0, r1, c0, c1, _ = self.out_bind[v]
+            _, name, r0, r1, c0, c1, tr = self.out_bind[v]
             if name not in out:
                 out[name] = np.zeros((cfg.tokens, cfg.d_model), dtype=self.elem)
             r, c = self.out_shapes[i]
-            out[name][r0:r1, c0:c1] = slab[self.out_offs[i]:self.out_offs[i] + r * c * es].view(self.elem).reshape(r, c)
+            tile = slab[self.out_offs[i]:self.out_offs[i] + r * c * es].view(self.elem).reshape(r, c)
+            out[name][r0:r1, c0:c1] = tile.T if tr else tile
         return out
 
     def last_order(self) -> List[int]:
