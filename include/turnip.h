@@ -279,6 +279,11 @@ tn_status tn_memgraph_simulate(const tn_memgraph* mg, const int64_t* order, int6
 /* ------------------------------------------------------------------------------------------ */
 
 enum { TN_POLICY_FIFO = 0, TN_POLICY_LIFO = 1, TN_POLICY_RANDOM = 2, TN_POLICY_BY_ORDER = 3 };
+/* How transfers are carried out.  MEMCPY: one hipMemcpyAsync per tensor on the copy streams.
+ * KERNEL: one grouped copy kernel per group of ready transfers, on the same streams; needs every
+ * host buffer to be pinned memory the GPU can address (hipHostMalloc), else TN_ERR_INVALID.
+ * AUTO: KERNEL when all host buffers of the call qualify, otherwise MEMCPY. */
+enum { TN_COPY_AUTO = 0, TN_COPY_MEMCPY = 1, TN_COPY_KERNEL = 2 };
 
 typedef struct {
   int32_t policy;        /* which ready vertex the loop takes first */
@@ -287,7 +292,8 @@ typedef struct {
   uint32_t max_delay_us; /* ... in [0, max_delay_us]; 0 = no injected delay */
   int32_t max_batch;     /* most same-kind ready vertices put into one kernel launch; 0 = default */
   int32_t profile;       /* != 0: time every launch with HIP events (fills the *_ms fields) */
-  int32_t max_transfers; /* most ready copies of one direction queued back to back; 0 = default */
+  int32_t max_transfers; /* most ready copies of one direction put into one group; 0 = default */
+  int32_t copy_engine;   /* TN_COPY_AUTO, TN_COPY_MEMCPY or TN_COPY_KERNEL */
 } tn_exec_opts;
 
 typedef struct {

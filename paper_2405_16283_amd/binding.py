@@ -23,6 +23,7 @@ TN_HOST, TN_DEVICE = 0, 1
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE) = range(7)
 TN_EDGE_DATA, TN_EDGE_MEM, TN_EDGE_ORDER = 0, 1, 2
 TN_POLICY_FIFO, TN_POLICY_LIFO, TN_POLICY_RANDOM, TN_POLICY_BY_ORDER = 0, 1, 2, 3
+TN_COPY_AUTO, TN_COPY_MEMCPY, TN_COPY_KERNEL = 0, 1, 2
 UINT64_MAX = (1 << 64) - 1
 
 
@@ -90,7 +91,7 @@ class tn_mg_stats(C.Structure):
 class tn_exec_opts(C.Structure):
     _fields_ = [("policy", C.c_int32), ("order_seed", C.c_uint64), ("delay_seed", C.c_uint64),
                 ("max_delay_us", C.c_uint32), ("max_batch", C.c_int32), ("profile", C.c_int32),
-                ("max_transfers", C.c_int32)]
+                ("max_transfers", C.c_int32), ("copy_engine", C.c_int32)]
 
 
 class tn_exec_report(C.Structure):

@@ -88,6 +88,9 @@ struct tn_executor {
   std::map<uint64_t, ArenaBlock> arena_map;
   std::vector<hipEvent_t> prof_events;
   std::vector<int> prof_family;
+  // host buffers already found to be GPU-addressable pinned memory (start, end)
+  std::vector<std::pair<const char*, const char*>> pinned_ranges;
+  bool arena_device_visible = false;
 };
 
 namespace {
@@ -269,6 +272,34 @@ void arena_free(tn_executor& ex, uint64_t off) {
   }
 }
 
+// True if [p, p+bytes) is pinned host memory that kernels can address.  Ranges found once are
+// remembered, so that a repeated call with the same buffers costs a few comparisons.
+bool device_visible_host(tn_executor& ex, const void* p, uint64_t bytes) {
+  const char* a = (const char*)p;
+  for (auto& r : ex.pinned_ranges)
+    if (a >= r.first && a + bytes <= r.second) return true;
+  hipPointerAttribute_t at{};
+  if (hipPointerGetAttributes(&at, p) != hipSuccess) {
+    (void)hipGetLastError();  // pageable memory is reported as an error: not ours to keep
+    return false;
+  }
+  if (at.type != hipMemoryTypeHost || !at.devicePointer) return false;
+  void* base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange((hipDeviceptr_t*)&base, &size, (hipDeviceptr_t)at.devicePointer) == hipSuccess && base && size) {
+    // identity-mapped pinned allocation: remember the whole of it
+    if (at.devicePointer == p && (const char*)base <= a && a + bytes <= (const char*)base + size) {
+      ex.pinned_ranges.emplace_back((const char*)base, (const char*)base + size);
+      return true;
+    }
+  } else {
+    (void)hipGetLastError();
+  }
+  if (at.devicePointer != p) return false;
+  ex.pinned_ranges.emplace_back(a, a + bytes);
+  return true;
+}
+
 int family_of(int cls) {
   switch (cls) {
     case LC_GEMM_F32:
@@ -320,6 +351,7 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
     if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipHostMalloc(%llu): %s", (unsigned long long)ex->arena_bytes, hipGetErrorString(e)));
     ex->own_arena = true;
   }
+  if (ex->arena && ex->arena_bytes) ex->arena_device_visible = device_visible_host(*ex, ex->arena, ex->arena_bytes);
   // dependency structure
   const int64_t nv = (int64_t)mg->v.size();
   ex->indeg.assign(nv, 0);
@@ -378,7 +410,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   tn_exec_opts opt{};
   if (opts_in) opt = *opts_in;
   const int max_batch = opt.max_batch > 0 ? std::min<int>(opt.max_batch, kMaxBatch) : 64;
-  const int max_xfer = opt.max_transfers > 0 ? opt.max_transfers : 8;
+  const int max_xfer = std::min(opt.max_transfers > 0 ? opt.max_transfers : 32, kMaxCopies);
   // every buffer the run will touch must be there before anything is launched
   for (int64_t m = 0; m < nv; ++m) {
     const MVertex& x = mg.v[m];
@@ -386,6 +418,18 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       return fail(TN_ERR_INVALID, "no host buffer for input %d", (int)x.src);
     if (x.kind == TN_MG_STORE && (!host_outputs || !host_outputs[x.output_index]))
       return fail(TN_ERR_INVALID, "no host buffer for output %d", x.output_index);
+  }
+  bool use_copy_kernel = opt.copy_engine != TN_COPY_MEMCPY;
+  if (use_copy_kernel) {
+    bool ok = ex->arena_device_visible || mg.stats.n_offload == 0;
+    for (int64_t m = 0; m < nv && ok; ++m) {
+      const MVertex& x = mg.v[m];
+      if (x.kind == TN_MG_LOAD) ok = device_visible_host(*ex, host_inputs[x.src], x.bytes);
+      else if (x.kind == TN_MG_STORE) ok = device_visible_host(*ex, host_outputs[x.output_index], x.bytes);
+    }
+    if (!ok && opt.copy_engine == TN_COPY_KERNEL)
+      return fail(TN_ERR_INVALID, "copy_engine KERNEL needs every host buffer to be GPU-addressable pinned memory");
+    use_copy_kernel = ok;
   }
   ex->remaining = ex->indeg;
   ex->last_order.clear();
@@ -476,36 +520,40 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   }
   const auto t_start = Clock::now();
   Batch batch;
+  CopyBatch copies;
   std::vector<int64_t> same;
 
   while (completed < nv && status == TN_OK) {
     bool progressed = false;
-    // ---- launch transfers: per direction one group of copies at a time, queued back to back
+    // ---- launch transfers: per direction one group of copies at a time
     for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
       Slot& sl = ex->slots[ex->n_compute + dir];
       auto& r = dir == 0 ? ready_h2d : ready_d2h;
       if (sl.busy || r.empty()) continue;
       sl.verts.clear();
       sl.bytes = 0;
+      copies.n = 0;
       hipError_t e = hipSuccess;
       while (!r.empty() && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
         const size_t i = pick(r);
         const int64_t m = r[i];
         const MVertex& x = mg.v[m];
+        const void* src;
+        void* dst;
         if (x.kind == TN_MG_LOAD) {
-          e = hipMemcpyAsync(ex->dbase + x.offset, host_inputs[x.src], x.bytes, hipMemcpyHostToDevice, sl.stream);
+          src = host_inputs[x.src];
+          dst = ex->dbase + x.offset;
         } else if (x.kind == TN_MG_RELOAD) {
-          const int64_t off = ex->arena_off[x.operands[0]];
-          e = hipMemcpyAsync(ex->dbase + x.offset, ex->arena + off, x.bytes, hipMemcpyHostToDevice, sl.stream);
+          src = ex->arena + ex->arena_off[x.operands[0]];
+          dst = ex->dbase + x.offset;
         } else if (x.kind == TN_MG_STORE) {
-          e = hipMemcpyAsync(host_outputs[x.output_index], ex->dbase + mg.v[x.operands[0]].offset, x.bytes,
-                             hipMemcpyDeviceToHost, sl.stream);
+          src = ex->dbase + mg.v[x.operands[0]].offset;
+          dst = host_outputs[x.output_index];
         } else {  // offload
           uint64_t off;
           if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
             if (!sl.verts.empty()) break;  // let the copies already queued (and later reloads) free slots
-            bool reload_pending = ex->slots[ex->n_compute].busy || !ready_h2d.empty();
-            if (reload_pending) break;
+            if (ex->slots[ex->n_compute].busy || !ready_h2d.empty()) break;
             status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
                           (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
             break;
@@ -513,10 +561,16 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           ex->arena_off[m] = (int64_t)off;
           arena_used += (x.bytes + 255) / 256 * 256;
           rep.arena_high_water = std::max(rep.arena_high_water, arena_used);
-          e = hipMemcpyAsync(ex->arena + off, ex->dbase + mg.v[x.operands[0]].offset, x.bytes, hipMemcpyDeviceToHost, sl.stream);
+          src = ex->dbase + mg.v[x.operands[0]].offset;
+          dst = ex->arena + off;
           ++rep.n_offload;
         }
-        if (e != hipSuccess) break;
+        if (use_copy_kernel) {
+          copies.it[copies.n++] = {src, dst, (uint32_t)x.bytes, (uint32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes)};
+        } else {
+          e = hipMemcpyAsync(dst, src, x.bytes, dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
+          if (e != hipSuccess) break;
+        }
         r.erase(r.begin() + i);
         sl.verts.push_back(m);
         sl.bytes += (double)x.bytes;
@@ -526,11 +580,27 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       }
       if (status != TN_OK) break;
       if (sl.verts.empty() && e == hipSuccess) continue;
+      sl.prof = -1;
+      if (e == hipSuccess && opt.profile) {
+        hipEvent_t a, b2;
+        if (prof_event(&a) && prof_event(&b2)) {
+          sl.prof = (int)prof_used - 2;
+          // the start stamp goes after whatever the stream still carries; a group's copies are
+          // queued behind it
+        }
+      }
+      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof], sl.stream);
+      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, sl.stream);
+      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof + 1], sl.stream);
       if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }
       sl.busy = true;
       sl.event_seen = false;
       sl.family = 3 + dir;
+      if (sl.prof >= 0) {
+        ex->prof_family.push_back(sl.family);
+        ex->prof_family.push_back(sl.prof);
+      }
       ++rep.n_launches;
       progressed = true;
     }
@@ -658,6 +728,10 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       if (hipEventElapsedTime(&t0, prof_base, ex->prof_events[p]) != hipSuccess ||
           hipEventElapsedTime(&t1, prof_base, ex->prof_events[p + 1]) != hipSuccess)
         continue;
+      if (fam >= 3) {  // transfers: time per direction, not part of the kernel-busy union
+        (fam == 3 ? rep.h2d_ms : rep.d2h_ms) += t1 - t0;
+        continue;
+      }
       (fam == 0 ? rep.gemm_ms : fam == 1 ? rep.attn_ms : rep.ewise_ms) += t1 - t0;
       iv.emplace_back(t0, t1);
     }

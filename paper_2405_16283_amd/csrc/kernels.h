@@ -57,6 +57,25 @@ struct DeviceTables {
   const double* rope_theta;  // base^(-2i/head_dim), i < head_dim/2, for the graph's rotary vertices
 };
 
+// A group of tensor copies between GPU memory and pinned (device-visible) host memory, moved by
+// one kernel launch: offloads, reloads, loads and stores of the memgraph.  The copy routine of
+// the runtime spends a launch and a gap per tensor, which at tile sizes of a few hundred KiB
+// leaves half of the host link idle.
+constexpr int kMaxCopies = 128;
+constexpr uint32_t kCopyBlockBytes = 32768;  // bytes one workgroup moves
+struct CopyItem {
+  const void* src;
+  void* dst;
+  uint32_t bytes;
+  uint32_t nblocks;
+};
+struct CopyBatch {
+  int32_t n;
+  int32_t pad;
+  CopyItem it[kMaxCopies];
+};
+hipError_t launch_copies(const CopyBatch& b, hipStream_t stream);
+
 // Workgroups a vertex needs in the given class (host side, used to fill OpDesc::nblocks).
 int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux);
 

@@ -749,6 +749,33 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// grouped tensor copy (see kernels.h): a workgroup moves 32 KiB with eight 16-byte loads in
+// flight per lane, which is what it takes to keep the host link busy in the reload direction
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) copy_kernel(CopyBatch b) {
+  const CopyItem it = b.it[blockIdx.y];
+  if (blockIdx.x >= it.nblocks) return;
+  const uint32_t off = blockIdx.x * kCopyBlockBytes;
+  const uint32_t len = min(kCopyBlockBytes, it.bytes - off);
+  const char* src = (const char*)it.src + off;
+  char* dst = (char*)it.dst + off;
+  const uint32_t vec = len / 16;  // whole 16-byte pieces (tensor locations are 256-byte aligned)
+  uint4 v[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const uint32_t i = threadIdx.x + 256 * k;
+    if (i < vec) v[k] = ((const uint4*)src)[i];
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const uint32_t i = threadIdx.x + 256 * k;
+    if (i < vec) ((uint4*)dst)[i] = v[k];
+  }
+  const uint32_t tail = vec * 16 + threadIdx.x;
+  if (tail < len) dst[tail] = src[tail];
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -777,6 +804,15 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     case LC_ADD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
     default: return 0;
   }
+}
+
+hipError_t launch_copies(const CopyBatch& b, hipStream_t s) {
+  if (b.n <= 0) return hipSuccess;
+  uint32_t max_blocks = 0;
+  for (int i = 0; i < b.n; ++i) max_blocks = b.it[i].nblocks > max_blocks ? b.it[i].nblocks : max_blocks;
+  if (max_blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_kernel, dim3(max_blocks, (unsigned)b.n), dim3(256), 0, s, b);
+  return hipGetLastError();
 }
 
 hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t, const Batch& b,

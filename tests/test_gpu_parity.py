@@ -142,6 +142,45 @@ def test_kv_outputs_match_the_oracle():
         s.close()
 
 
+@pytest.mark.parametrize("engine", [B.TN_COPY_MEMCPY, B.TN_COPY_KERNEL])
+def test_both_copy_engines_give_identical_bits(engine):
+    cfg = config("ragged_bf16")
+    s = H.GpuSession(cfg, make_llama_inputs(cfg, 0))
+    try:
+        ref, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER))
+        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=3, copy_engine=engine, max_transfers=5))
+        np.testing.assert_array_equal(out["y"], ref["y"])
+        assert rep.n_offload == s.stats.n_offload > 0
+    finally:
+        s.close()
+
+
+def test_pageable_host_buffers_fall_back_to_memcpy_and_kernel_engine_refuses_them():
+    import torch
+    rng = np.random.default_rng(1)
+    a = rng.standard_normal((64, 32)).astype(np.float32)  # plain, pageable memory
+    tg = B.tn_taskgraph_create()
+    va = B.tn_taskgraph_add_input(tg, B.TN_F32, 64, 32, B.TN_HOST)
+    s = B.tn_taskgraph_add_op(tg, B.TN_OP_ADD, B.tn_op_params(), [va, va], B.TN_F32, 64, 32)
+    B.tn_taskgraph_mark_output(tg, s)
+    mg = B.tn_compile(tg, None, 1 << 20, None)
+    dev = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    out = np.zeros((64, 32), dtype=np.float32)
+    ex = B.tn_executor_create(mg, dev.data_ptr(), 1 << 20, 0, 0, [streams[0].cuda_stream],
+                              streams[1].cuda_stream, streams[2].cuda_stream)
+    try:
+        B.tn_execute(ex, [a.ctypes.data, 0], [out.ctypes.data])
+        np.testing.assert_array_equal(out, 2 * a)
+        with pytest.raises(B.TurnipError) as e:
+            B.tn_execute(ex, [a.ctypes.data, 0], [out.ctypes.data], B.tn_exec_opts(copy_engine=B.TN_COPY_KERNEL))
+        assert e.value.status == B.TN_ERR_INVALID
+    finally:
+        B.tn_executor_destroy(ex)
+        B.tn_memgraph_destroy(mg)
+        B.tn_taskgraph_destroy(tg)
+
+
 def test_exhausted_host_arena_is_an_error_not_a_hang():
     cfg = config("c1")
     s = H.GpuSession(cfg, make_llama_inputs(cfg, 0), arena_bytes=4096)
