@@ -53,8 +53,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--streams", type=int, default=4)
-    ap.add_argument("--max-batch", type=int, default=0)
+    ap.add_argument("--max-batch", type=int, default=240)
     ap.add_argument("--max-transfers", type=int, default=0)
+    ap.add_argument("--max-gemm-inflight", type=int, default=2)
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order"])
     ap.add_argument("--cpu-tokens", type=int, default=512, help="tokens of the CPU-oracle sample; 0 = skip")
     ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
@@ -95,12 +96,14 @@ def main():
     t_compile = time.perf_counter() - t0
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER}[args.policy]
-    opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers)
+    opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
+                          max_gemm_inflight=args.max_gemm_inflight)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
     plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
-                                                                max_transfers=args.max_transfers))
+                                                                max_transfers=args.max_transfers,
+                                                                max_gemm_inflight=args.max_gemm_inflight))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs()["y"]
     st = s.stats
@@ -115,6 +118,14 @@ def main():
     rep0 = reps[-1][1]
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     total_flops = rep0.gemm_flops + rep0.attn_flops
+    # HBM bytes per GEMM launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE
+    # and WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel calibration)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"{cfg.name}_gemm_traffic.txt")
+    if os.path.exists(tpath):
+        kv = dict(l.split() for l in open(tpath) if l.strip() and not l.startswith("#"))
+        traffic = 1024.0 * (float(kv["fetch_kib_per_launch"]) / float(kv["fetch_scale"])
+                            + float(kv["write_kib_per_launch"]) / float(kv["write_scale"]))
     line = {
         "metric": "tokens/s under GPU-RAM cap", "value": cfg.tokens / (ms * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -124,11 +135,12 @@ def main():
                                f"{cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, batch {cfg.batch}, "
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
-                   "compute_streams": args.streams, "ready_policy": args.policy, "memgraph_vertices": int(st.n_vertices),
+                   "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
+                   "max_gemm_inflight": args.max_gemm_inflight, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": traffic,
                      "avg_launch_ms": gemm_ms / max(1, gemm_launches),
                      "flops_per_launch": gemm_flops / max(1, gemm_launches)},
         "extra": {

@@ -294,6 +294,7 @@ typedef struct {
   int32_t profile;       /* != 0: time every launch with HIP events (fills the *_ms fields) */
   int32_t max_transfers; /* most ready copies of one direction put into one group; 0 = default */
   int32_t copy_engine;   /* TN_COPY_AUTO, TN_COPY_MEMCPY or TN_COPY_KERNEL */
+  int32_t max_gemm_inflight; /* most GEMM groups running at once; 0 = as many as there are streams */
 } tn_exec_opts;
 
 typedef struct {

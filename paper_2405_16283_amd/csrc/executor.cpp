@@ -442,7 +442,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     sl.verts.clear();
   }
   tn_exec_report rep{};
-  std::vector<int64_t> ready_k, ready_h2d, ready_d2h, work;
+  std::vector<int64_t> ready_k, ready_h2d, ready_d2h, work, cand;
   int64_t completed = 0;
   uint64_t rng = mix64(opt.order_seed ^ 0x7475726E6970ull);
   uint64_t arena_used = 0;
@@ -608,7 +608,25 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     for (int si = 0; si < ex->n_compute && status == TN_OK && !ready_k.empty(); ++si) {
       Slot& sl = ex->slots[si];
       if (sl.busy) continue;
-      const size_t i0 = pick(ready_k);
+      size_t i0;
+      if (opt.max_gemm_inflight > 0) {
+        // GEMM groups that overlap only share the compute units; holding the next one back until
+        // a running one ends lets it gather more ready tiles and fill the chip on its own
+        int inflight = 0;
+        for (int k = 0; k < ex->n_compute; ++k) inflight += ex->slots[k].busy && ex->slots[k].family == 0;
+        if (inflight >= opt.max_gemm_inflight) {
+          cand.clear();
+          for (size_t i = 0; i < ready_k.size(); ++i)
+            if (family_of(ex->info[ready_k[i]].cls) != 0) cand.push_back(ready_k[i]);
+          if (cand.empty()) break;
+          const int64_t chosen = cand[pick(cand)];
+          i0 = std::find(ready_k.begin(), ready_k.end(), chosen) - ready_k.begin();
+        } else {
+          i0 = pick(ready_k);
+        }
+      } else {
+        i0 = pick(ready_k);
+      }
       const VInfo lead = ex->info[ready_k[i0]];
       same.clear();
       same.push_back(ready_k[i0]);

@@ -351,6 +351,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch
 // unpadded: 256 rows x 4 chunks per operand.  Bank conflicts are avoided by choosing *which*
 // chunk each lane fetches: logical chunk c of row r lives at position c ^ ((r >> 2) & 3).
 // ---------------------------------------------------------------------------------------------
+#ifndef TN_GEMM_WAVES
+#define TN_GEMM_WAVES 8
+#endif
 constexpr int G2_M = 256, G2_N = 256, G2_K = 32, G2_STAGES = 4;
 constexpr int G2_OPER_BYTES = G2_M * G2_K * 2;               // one operand of one stage: 16 KiB
 constexpr int G2_STAGE_BYTES = 2 * G2_OPER_BYTES;            // A then B
@@ -363,6 +366,11 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // in flight across barriers and waits for them with explicit vmcnt values.
 __device__ __forceinline__ void load_lds16(const void* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_addr) : "memory");
+}
+// The same with a wavefront-uniform base address and a 32-bit per-lane byte offset, which leaves
+// the per-step address arithmetic to the scalar unit.
+__device__ __forceinline__ void load_lds16_so(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
 }
 // Reads of the (read-only, wavefront-uniform) operand tables through the scalar unit, so that
 // they are counted by lgkmcnt and never force a wait on the vector loads in flight.
@@ -377,114 +385,151 @@ __device__ __forceinline__ int sload_int(const int* addr) {
   return v;
 }
 
-__global__ void __launch_bounds__(256, 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
-  if ((int)blockIdx.x >= d.nblocks) return;
+// Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
+// This turns the launch position into a position in which each XCD gets a contiguous run of
+// (vertex, tile) pairs, so that the workgroups sharing an L2 work on neighbouring tiles -- the
+// tiles of one vertex and of vertices with the same A row block -- instead of every XCD
+// streaming every operand.
+__device__ __forceinline__ void xcd_remap(int& bx, int& by) {
+  const int gx = gridDim.x, total = gx * gridDim.y;
+  const int n = blockIdx.x + gx * blockIdx.y;
+  const int xcd = n & 7, slot = n >> 3;
+  const int q = total >> 3, r = total & 7;
+  const int v = xcd * q + min(xcd, r) + slot;
+  by = v / gx;
+  bx = v - by * gx;
+}
+
+// NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two
+// per SIMD, so that one wavefront's MFMAs fill the time the other spends issuing its loads).
+template <int NW>
+__global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
+  constexpr int TJ = 16 / NW;             // 32-column MFMA tiles per wavefront (TI = 4 row tiles)
+  constexpr int NLD = 16 / NW;            // load instructions per thread, operand and step
+  constexpr int WNS = NW / 2;             // wavefronts along N
+  int bx, by;
+  xcd_remap(bx, by);
+  const OpDesc& d = t.descs[b.idx[by]];
+  if (bx >= d.nblocks) return;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int M = d.rows, N = d.cols, nk = d.p.nk;
   const void* const* ptrA = t.ptrs + d.ptr0;  // A_0.., then nk entries later B_0..
   const int* ksz = t.aux + d.aux0;
   bf16_t* const Cp = (bf16_t*)d.out;
   const int tn_ = (N + G2_N - 1) / G2_N;
-  const int m0 = (blockIdx.x / tn_) * G2_M, n0 = (blockIdx.x % tn_) * G2_N;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w >> 1, wn = w & 1;
+  const int m0 = (bx / tn_) * G2_M, n0 = (bx % tn_) * G2_N;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w / WNS, wn = w % WNS;
   const int l32 = lane & 31, g = lane >> 5;
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][TJ];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // loader: wave-instruction i of wavefront w fills chunks [w*256 + i*64, +64) of an operand;
-  // this lane's chunk is row w*64 + i*16 + lane/4, logical chunk (lane & 3) ^ ((lane >> 4) & 3).
-  // Rows past the edge of a ragged tile are clamped (their products are never stored).
-  const int lrow = w * 64 + (lane >> 2);
+  // loader: load instruction i of wavefront w fills chunks [(i*NW + w)*64, +64) of an operand;
+  // this lane's chunk is row (i*NW + w)*16 + lane/4, logical chunk (lane & 3) ^ ((lane >> 4) & 3).
+  // Rows past the edge of a ragged tile are clamped (their products are never stored).  A lane's
+  // byte offset inside an operand tile changes only with the tile's K; the position along K is
+  // added to the (scalar) tile address.
+  const int lrow = w * 16 + (lane >> 2);
   const int lcol = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
-  int rowA[4], rowB[4];
+  int rowA[NLD], rowB[NLD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    rowA[i] = min(m0 + lrow + i * 16, M - 1);
-    rowB[i] = min(n0 + lrow + i * 16, N - 1);
+  for (int i = 0; i < NLD; ++i) {
+    rowA[i] = min(m0 + lrow + i * 16 * NW, M - 1);
+    rowB[i] = min(n0 + lrow + i * 16 * NW, N - 1);
   }
   int nsteps = 0;
   for (int k = 0; k < nk; ++k) nsteps += ksz[k] / G2_K;
   int kt = 0, k0 = 0, K = sload_int(ksz);
   const bf16_t* A = (const bf16_t*)sload_ptr(ptrA);
   const bf16_t* B = (const bf16_t*)sload_ptr(ptrA + nk);
-
-  const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
-  auto issue = [&](int stage) {  // loads of the K step (kt, k0) into `stage`, then advance
-    const uint32_t dstA = __builtin_amdgcn_readfirstlane(lds0 + stage * G2_STAGE_BYTES + w * 4096);
+  uint32_t offA[NLD], offB[NLD];
+  auto set_offsets = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      load_lds16(A + (size_t)rowA[i] * K + k0 + lcol, dstA + i * 1024);
-      load_lds16(B + (size_t)rowB[i] * K + k0 + lcol, dstA + G2_OPER_BYTES + i * 1024);
+    for (int i = 0; i < NLD; ++i) {
+      offA[i] = (uint32_t)(rowA[i] * K + lcol) * 2u;
+      offB[i] = (uint32_t)(rowB[i] * K + lcol) * 2u;
+    }
+  };
+  set_offsets();
+  const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
+  const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + w * 1024);
+  auto issue = [&](int stage) {  // loads of the K step (kt, k0) into `stage`, then advance
+    const uint32_t dstA = ldsw + stage * G2_STAGE_BYTES;
+    const bf16_t* a = A + k0;
+    const bf16_t* bq = B + k0;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      load_lds16_so(a, offA[i], dstA + i * 1024 * NW);
+      load_lds16_so(bq, offB[i], dstA + G2_OPER_BYTES + i * 1024 * NW);
     }
     k0 += G2_K;
     if (k0 >= K && kt + 1 < nk) {
       ++kt;
       k0 = 0;
-      K = sload_int(ksz + kt);
+      const int Kn = sload_int(ksz + kt);
       A = (const bf16_t*)sload_ptr(ptrA + kt);
       B = (const bf16_t*)sload_ptr(ptrA + nk + kt);
+      if (Kn != K) {
+        K = Kn;
+        set_offsets();
+      }
     }
   };
 
   // fragment addresses inside a stage: row-major chunks, swizzled as above
   const int sw = (l32 >> 2) & 3;
-  const int fragA = ((wm * 128 + l32) * 4) * 16, fragB = G2_OPER_BYTES + ((wn * 128 + l32) * 4) * 16;
+  const int fragA = ((wm * 128 + l32) * 4) * 16, fragB = G2_OPER_BYTES + ((wn * 32 * TJ + l32) * 4) * 16;
   const int c0 = ((0 + g) ^ sw) * 16, c1 = ((2 + g) ^ sw) * 16;
 
   for (int s = 0; s < G2_STAGES - 1 && s < nsteps; ++s) issue(s);
-  // The second half of a step's MFMAs is deferred to the next iteration, where it covers the
-  // latency of that iteration's first fragment reads.
-  bf16x8 a1[4], b1[4];
+  // The second half of a step's MFMAs is deferred to the next iteration, where it runs while
+  // that iteration's fragment reads are in flight and its loads are being issued.
+  bf16x8 a1[4], b1[TJ];
   for (int s = 0; s < nsteps; ++s) {
     // stage s must have landed: at most the loads of the next two steps may still be in flight
-    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16)
-    else if (s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(NW == 4 ? 0x4F70 : 0x0F78);       // vmcnt(16 | 8)
+    else if (s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(NW == 4 ? 0x0F78 : 0x0F74);  // vmcnt(8 | 4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                                         // vmcnt(0)
     __syncthreads();
-    if (s + G2_STAGES - 1 < nsteps) issue((s + G2_STAGES - 1) % G2_STAGES);
     const char* st_ = lds + (s % G2_STAGES) * G2_STAGE_BYTES;
-    bf16x8 a0[4], b0[4], an[4], bn[4];
+    bf16x8 a0[4], b0[TJ], an[4], bn[TJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a0[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c0);
-      b0[i] = *(const bf16x8*)(st_ + fragB + i * 2048 + c0);
-    }
+    for (int i = 0; i < 4; ++i) a0[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      an[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c1);
-      bn[i] = *(const bf16x8*)(st_ + fragB + i * 2048 + c1);
-    }
+    for (int j = 0; j < TJ; ++j) b0[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + c0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) an[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c1);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) bn[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + c1);
     if (s > 0) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
     }
+    if (s + G2_STAGES - 1 < nsteps) issue((s + G2_STAGES - 1) % G2_STAGES);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a1[i] = an[i];
-      b1[i] = bn[i];
-    }
+    for (int i = 0; i < 4; ++i) a1[i] = an[i];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) b1[j] = bn[j];
   }
   if (nsteps > 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
   }
 
-  store_c_tiles<4, 4>(acc, Cp, M, N, m0 + wm * 128, n0 + wn * 128, l32, g, d.p.trans_c != 0);
+  store_c_tiles<4, TJ>(acc, Cp, M, N, m0 + wm * 128, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -829,10 +874,10 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
     case LC_GEMM_F32: TN_LAUNCH_T(gemm_generic_kernel); break;
     case LC_GEMM_BF16_NT: hipLaunchKernelGGL(gemm_bf16_nt_kernel, grid, wg, 0, s, t, b); break;
     case LC_GEMM_BF16_NT256: {
-      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel,
+      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel<TN_GEMM_WAVES>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
       if (attr != hipSuccess) return attr;
-      hipLaunchKernelGGL(gemm_bf16_nt256_kernel, grid, wg, G2_LDS_BYTES, s, t, b);
+      hipLaunchKernelGGL(gemm_bf16_nt256_kernel<TN_GEMM_WAVES>, grid, dim3(64 * TN_GEMM_WAVES), G2_LDS_BYTES, s, t, b);
       break;
     }
     case LC_RMS_STAT: TN_LAUNCH_T(rms_stat_kernel); break;
