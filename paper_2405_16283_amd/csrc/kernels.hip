@@ -752,13 +752,18 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
         m = mn;
       }
       const float msub = m == -INFINITY ? 0.f : m;  // nothing visible yet: every probability is exp2(-inf) = 0
-      bf16x8 p0, p1;
+      // Probabilities enter the MFMA as bf16.  A single bf16 would carry 8 bits of each weight;
+      // the remainder p - bf16(p) is fed through a second MFMA, so that the product sees 16 bits
+      // and the block's result does not depend on where the running maximum stood.
+      bf16x8 p0, p1, q0, q1;
       float ls = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float pr = __builtin_amdgcn_exp2f(sT[r] - msub);
         ls += pr;
-        if (r < 8) p0[r] = (__bf16)pr; else p1[r - 8] = (__bf16)pr;
+        const __bf16 hi = (__bf16)pr;
+        const __bf16 lo = (__bf16)(pr - (float)hi);
+        if (r < 8) { p0[r] = hi; q0[r] = lo; } else { p1[r - 8] = hi; q1[r - 8] = lo; }
       }
       l += ls;
       // O^T[d, q] += sum over the slab's 16 keys of V^T[d, key] P^T[key, q]
@@ -767,6 +772,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
         const int dr = i * 32 + l32, vsw = (dr >> 1) & 7;
         bf16x8 a0 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + g) ^ vsw)) * 16);
         bf16x8 a1 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + 2 + g) ^ vsw)) * 16);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, q0, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, q1, ot[i], 0, 0, 0);
         ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0, ot[i], 0, 0, 0);
         ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1, ot[i], 0, 0, 0);
       }

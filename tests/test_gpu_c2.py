@@ -1,0 +1,65 @@
+"""GPU parity at the benchmark's full size (one LLaMA-7B-shaped layer, seq 4096, bf16) and in the
+launch configuration bench.py times: whole output against the tiled CPU oracle, identical bits
+across dispatch orders, and the offload path at 40 % of the uncapped peak."""
+import numpy as np
+import pytest
+
+from oracle import llama_ref as R
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import bf16_bits_to_f32, config, make_llama_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c2():
+    cfg = config("c2")
+    full = make_llama_inputs(cfg, 0)
+    w = R.widen(cfg, full)
+    tg = T.build_llama_taskgraph(cfg)
+    y = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
+    return cfg, full, y
+
+
+def bench_opts(**kw):
+    return B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=240, max_gemm_inflight=2, **kw)
+
+
+def test_c2_bench_configuration_matches_the_oracle_everywhere(c2):
+    cfg, full, y_oracle = c2
+    print("[case] c2 full size, bench configuration", flush=True)
+    s = H.GpuSession(cfg, full)
+    try:
+        out, rep = s.run(bench_opts())
+        y = bf16_bits_to_f32(out["y"]).astype(np.float64)
+        err = R.rel_err(y, y_oracle)
+        print(f"  rel err vs tiled oracle over all {y.size} outputs: {err:.3e}", flush=True)
+        assert np.isfinite(y).all() and err < 2e-2
+        assert rep.n_vertices == s.stats.n_vertices
+        # other dispatch orders, group sizes and copy engines: same bits
+        for seed, (batch, engine) in enumerate([(64, B.TN_COPY_KERNEL), (7, B.TN_COPY_MEMCPY), (240, B.TN_COPY_AUTO)]):
+            print(f"[case] c2 random order seed {seed} batch {batch}", flush=True)
+            o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, max_batch=batch, copy_engine=engine,
+                                         delay_seed=seed, max_delay_us=100))
+            np.testing.assert_array_equal(o2["y"], out["y"])
+    finally:
+        s.close()
+
+
+def test_c2_streamed_under_forty_percent_cap_gives_the_same_bits(c2):
+    cfg, full, y_oracle = c2
+    capped = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
+    print("[case] c2 streamed, cap = 40 % of the uncapped peak", flush=True)
+    s = H.GpuSession(capped, full)
+    try:
+        assert s.stats.n_offload > 0 and s.stats.n_load > 0
+        out, rep = s.run(bench_opts())
+        y = bf16_bits_to_f32(out["y"]).astype(np.float64)
+        assert R.rel_err(y, y_oracle) < 2e-2
+        assert rep.n_offload == s.stats.n_offload and rep.arena_high_water > 0
+        o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=11, max_batch=32, max_delay_us=200))
+        np.testing.assert_array_equal(o2["y"], out["y"])
+    finally:
+        s.close()
