@@ -53,9 +53,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--streams", type=int, default=4)
-    ap.add_argument("--max-batch", type=int, default=240)
+    ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
     ap.add_argument("--max-gemm-inflight", type=int, default=2)
+    ap.add_argument("--queue-depth", type=int, default=3)
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order"])
     ap.add_argument("--cpu-tokens", type=int, default=512, help="tokens of the CPU-oracle sample; 0 = skip")
     ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
@@ -97,13 +98,13 @@ def main():
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER}[args.policy]
     opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
-                          max_gemm_inflight=args.max_gemm_inflight)
+                          max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
     plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
                                                                 max_transfers=args.max_transfers,
-                                                                max_gemm_inflight=args.max_gemm_inflight))
+                                                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs()["y"]
     st = s.stats
@@ -136,7 +137,7 @@ def main():
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

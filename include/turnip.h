@@ -295,6 +295,10 @@ typedef struct {
   int32_t max_transfers; /* most ready copies of one direction put into one group; 0 = default */
   int32_t copy_engine;   /* TN_COPY_AUTO, TN_COPY_MEMCPY or TN_COPY_KERNEL */
   int32_t max_gemm_inflight; /* most GEMM groups running at once; 0 = as many as there are streams */
+  int32_t queue_depth;   /* kernel groups in flight per compute stream (1..8; 0 = 1).  1: a kernel is
+                            launched when its dependencies have completed.  >1: it may be enqueued once the
+                            kernels it depends on are enqueued, ordered on the device by stream events;
+                            dependencies on transfers are always awaited on the host. */
 } tn_exec_opts;
 
 typedef struct {

@@ -18,6 +18,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstring>
+#include <deque>
 #include <map>
 
 #include "graph.h"
@@ -27,6 +28,7 @@ namespace tn {
 namespace {
 
 using Clock = std::chrono::steady_clock;
+constexpr int kMaxQueueDepth = 8;  // groups in flight per compute stream, at most
 
 struct VInfo {
   int8_t cls = -1;  // LaunchClass, or -1 for non-kernel vertices
@@ -46,6 +48,12 @@ struct Slot {  // one stream and the group it carries
   std::vector<int64_t> verts;
   int prof = -1;  // index of the (start, stop) event pair when profiling
   double flops = 0, bytes = 0;
+};
+
+struct Group {  // one grouped kernel launch in flight on a compute stream
+  std::vector<int64_t> verts;
+  hipEvent_t done = nullptr;
+  int family = 0, prof = -1;
 };
 
 struct ArenaBlock {
@@ -74,6 +82,9 @@ struct tn_executor {
   bool own_arena = false, poisoned = false;
   int n_compute = 0;
   std::vector<Slot> slots;  // compute streams, then h2d, then d2h
+  std::vector<std::vector<hipEvent_t>> cevents;  // per compute stream: ring of completion events
+  std::vector<std::deque<Group>> cqueue;         // per compute stream: groups in flight, oldest first
+  std::vector<int64_t> pred_start, pred;         // CSR of predecessors
   // device tables
   OpDesc* d_descs = nullptr;
   void** d_ptrs = nullptr;
@@ -366,6 +377,23 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
     std::vector<int64_t> at(ex->succ_start.begin(), ex->succ_start.end() - 1);
     for (const auto& e : mg->edges) ex->succ[at[e.from]++] = e.to;
   }
+  ex->pred_start.assign(nv + 1, 0);
+  for (const auto& e : mg->edges) ++ex->pred_start[e.to + 1];
+  for (int64_t i = 0; i < nv; ++i) ex->pred_start[i + 1] += ex->pred_start[i];
+  ex->pred.resize(mg->edges.size());
+  {
+    std::vector<int64_t> at(ex->pred_start.begin(), ex->pred_start.end() - 1);
+    for (const auto& e : mg->edges) ex->pred[at[e.to]++] = e.from;
+  }
+  ex->cevents.resize(n_compute);
+  ex->cqueue.resize(n_compute);
+  for (int i = 0; i < n_compute; ++i)
+    for (int k = 0; k < kMaxQueueDepth; ++k) {
+      hipEvent_t ev;
+      hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)));
+      ex->cevents[i].push_back(ev);
+    }
   ex->arena_off.assign(nv, -1);
   tn_status s = build_tables(*ex);
   if (s != TN_OK) return bail(s);
@@ -378,6 +406,8 @@ void tn_executor_destroy(tn_executor* ex) {
   for (auto& sl : ex->slots)
     if (sl.done) (void)hipEventDestroy(sl.done);
   for (auto e : ex->prof_events) (void)hipEventDestroy(e);
+  for (auto& ring : ex->cevents)
+    for (auto e : ring) (void)hipEventDestroy(e);
   if (ex->d_descs) (void)hipFree(ex->d_descs);
   if (ex->d_ptrs) (void)hipFree(ex->d_ptrs);
   if (ex->d_aux) (void)hipFree(ex->d_aux);
@@ -411,6 +441,13 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   if (opts_in) opt = *opts_in;
   const int max_batch = opt.max_batch > 0 ? std::min<int>(opt.max_batch, kMaxBatch) : 64;
   const int max_xfer = std::min(opt.max_transfers > 0 ? opt.max_transfers : 32, kMaxCopies);
+  // queue_depth 1 is the paper's rule: a vertex is launched once its dependencies have completed.
+  // With a deeper queue a kernel may be enqueued as soon as the kernels it depends on are
+  // enqueued: the stream waits for their events on the device, so the order of execution still
+  // respects every dependency while the host no longer sits between two dependent kernels.
+  // Anything that depends on a transfer still waits for the host to see that transfer complete.
+  const int depth = std::max(1, std::min<int>(opt.queue_depth > 0 ? opt.queue_depth : 1, kMaxQueueDepth));
+  const bool ahead = depth > 1;
   // every buffer the run will touch must be there before anything is launched
   for (int64_t m = 0; m < nv; ++m) {
     const MVertex& x = mg.v[m];
@@ -432,6 +469,11 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     use_copy_kernel = ok;
   }
   ex->remaining = ex->indeg;
+  std::vector<int64_t> rem_enq(ex->indeg);           // dependencies not yet enqueued (kernels) or completed
+  std::vector<hipEvent_t> ev_of(nv, nullptr);        // event of the group a kernel vertex was enqueued in
+  std::vector<int8_t> stream_of(nv, -1), state(nv, 0);  // state: 0 waiting, 1 enqueued, 2 complete
+  std::vector<int> ring_next(ex->n_compute, 0);
+  for (auto& q : ex->cqueue) q.clear();
   ex->last_order.clear();
   ex->last_order.reserve(nv);
   ex->arena_map.clear();
@@ -468,13 +510,24 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       const int64_t m = work.back();
       work.pop_back();
       ++completed;
+      const bool was_enqueued_kernel = ahead && mg.v[m].kind == TN_MG_OP;  // its successors were told at enqueue time
+      state[m] = 2;
       for (int64_t i = ex->succ_start[m]; i < ex->succ_start[m + 1]; ++i) {
         const int64_t w = ex->succ[i];
-        if (--ex->remaining[w] != 0) continue;
-        switch (mg.v[w].kind) {
+        const bool all_done = --ex->remaining[w] == 0;
+        const int32_t k = mg.v[w].kind;
+        if (k == TN_MG_OP) {
+          if (ahead) {
+            if (!was_enqueued_kernel && --rem_enq[w] == 0) ready_k.push_back(w);
+          } else if (all_done) {
+            ready_k.push_back(w);
+          }
+          continue;
+        }
+        if (!all_done) continue;
+        switch (k) {
           case TN_MG_INPUT:
           case TN_MG_DROP: ex->last_order.push_back(w); work.push_back(w); break;
-          case TN_MG_OP: ready_k.push_back(w); break;
           case TN_MG_LOAD:
           case TN_MG_RELOAD: ready_h2d.push_back(w); break;
           default: ready_d2h.push_back(w); break;
@@ -522,6 +575,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   Batch batch;
   CopyBatch copies;
   std::vector<int64_t> same;
+  std::vector<hipEvent_t> waited;
 
   while (completed < nv && status == TN_OK) {
     bool progressed = false;
@@ -604,16 +658,20 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       ++rep.n_launches;
       progressed = true;
     }
-    // ---- launch kernels: one group per free compute stream --------------------------------
-    for (int si = 0; si < ex->n_compute && status == TN_OK && !ready_k.empty(); ++si) {
-      Slot& sl = ex->slots[si];
-      if (sl.busy) continue;
+    // ---- launch kernels: one group per compute stream with room in its queue ---------------
+    while (status == TN_OK && !ready_k.empty()) {
+      int si = -1;
+      for (int k = 0; k < ex->n_compute; ++k)
+        if ((int)ex->cqueue[k].size() < depth && (si < 0 || ex->cqueue[k].size() < ex->cqueue[si].size())) si = k;
+      if (si < 0) break;
+      hipStream_t stream = ex->slots[si].stream;
       size_t i0;
       if (opt.max_gemm_inflight > 0) {
         // GEMM groups that overlap only share the compute units; holding the next one back until
         // a running one ends lets it gather more ready tiles and fill the chip on its own
         int inflight = 0;
-        for (int k = 0; k < ex->n_compute; ++k) inflight += ex->slots[k].busy && ex->slots[k].family == 0;
+        for (auto& q : ex->cqueue)
+          for (auto& g : q) inflight += g.family == 0;
         if (inflight >= opt.max_gemm_inflight) {
           cand.clear();
           for (size_t i = 0; i < ready_k.size(); ++i)
@@ -642,56 +700,102 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           for (size_t k = idx.size(); k > 1; --k) { rng = mix64(rng); std::swap(idx[k - 1], idx[rng % k]); }
         else if (opt.policy == TN_POLICY_BY_ORDER)
           std::sort(idx.begin(), idx.end(), [&](size_t a, size_t b) { return mg.v[ready_k[a]].order_pos < mg.v[ready_k[b]].order_pos; });
-        for (size_t k = 0; k < idx.size() && (int)same.size() < max_batch; ++k) same.push_back(ready_k[idx[k]]);
-      }
-      batch.n = (int32_t)same.size();
-      int32_t max_blocks = 0;
-      sl.flops = sl.bytes = 0;
-      for (int k = 0; k < batch.n; ++k) {
-        const VInfo& v = ex->info[same[k]];
-        batch.idx[k] = v.desc;
-        max_blocks = std::max(max_blocks, v.nblocks);
-        sl.flops += v.flops;
-        sl.bytes += v.bytes;
-      }
-      hipError_t e = hipSuccess;
-      sl.prof = -1;
-      if (opt.profile) {
-        hipEvent_t a, b;
-        if (prof_event(&a) && prof_event(&b)) {
-          sl.prof = (int)prof_used - 2;
-          e = hipEventRecord(a, sl.stream);
+        // the launch names its vertices by 16-bit offsets from the smallest descriptor index
+        uint32_t lo = (uint32_t)lead.desc, hi = (uint32_t)lead.desc;
+        for (size_t k = 0; k < idx.size() && (int)same.size() < max_batch; ++k) {
+          const uint32_t d = (uint32_t)ex->info[ready_k[idx[k]]].desc;
+          if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) continue;
+          lo = std::min(lo, d);
+          hi = std::max(hi, d);
+          same.push_back(ready_k[idx[k]]);
         }
       }
-      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, ex->tables, batch, max_blocks, sl.stream);
-      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof + 1], sl.stream);
-      if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
+      batch.n = (int32_t)same.size();
+      batch.base = (uint32_t)lead.desc;
+      for (int64_t m : same) batch.base = std::min(batch.base, (uint32_t)ex->info[m].desc);
+      int32_t max_blocks = 0;
+      double flops = 0, bytes = 0;
+      for (int k = 0; k < batch.n; ++k) {
+        const VInfo& v = ex->info[same[k]];
+        batch.idx[k] = (uint16_t)(v.desc - batch.base);
+        max_blocks = std::max(max_blocks, v.nblocks);
+        flops += v.flops;
+        bytes += v.bytes;
+      }
+      hipError_t e = hipSuccess;
+      // device-side waits for kernels this group depends on that are enqueued on other streams
+      if (ahead) {
+        waited.clear();
+        for (int64_t m : same)
+          for (int64_t i = ex->pred_start[m]; i < ex->pred_start[m + 1] && e == hipSuccess; ++i) {
+            const int64_t pv = ex->pred[i];
+            if (state[pv] != 1 || stream_of[pv] == si) continue;
+            if (std::find(waited.begin(), waited.end(), ev_of[pv]) != waited.end()) continue;
+            waited.push_back(ev_of[pv]);
+            e = hipStreamWaitEvent(stream, ev_of[pv], 0);
+          }
+      }
+      Group grp;
+      grp.family = family_of(lead.cls);
+      grp.done = ex->cevents[si][ring_next[si]];
+      ring_next[si] = (ring_next[si] + 1) % kMaxQueueDepth;
+      if (e == hipSuccess && opt.profile) {
+        hipEvent_t a, b;
+        if (prof_event(&a) && prof_event(&b)) {
+          grp.prof = (int)prof_used - 2;
+          e = hipEventRecord(a, stream);
+        }
+      }
+      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, ex->tables, batch, max_blocks, stream);
+      if (e == hipSuccess && grp.prof >= 0) e = hipEventRecord(ex->prof_events[grp.prof + 1], stream);
+      if (e == hipSuccess) e = hipEventRecord(grp.done, stream);
       if (e != hipSuccess) { hip_fail("kernel launch", e); break; }
       // remove the group from the ready list
       {
-        std::vector<char> taken;  // small: mark by sorting the group
         std::sort(same.begin(), same.end());
         size_t w = 0;
         for (size_t i = 0; i < ready_k.size(); ++i)
           if (!std::binary_search(same.begin(), same.end(), ready_k[i])) ready_k[w++] = ready_k[i];
         ready_k.resize(w);
       }
-      sl.busy = true;
-      sl.event_seen = false;
-      sl.family = family_of(lead.cls);
-      sl.verts = same;
-      for (int64_t m : same) ex->last_order.push_back(m);
+      for (int64_t m : same) {
+        ex->last_order.push_back(m);
+        state[m] = 1;
+        ev_of[m] = grp.done;
+        stream_of[m] = (int8_t)si;
+      }
+      if (ahead)  // kernels that only waited for these to be enqueued can follow
+        for (int64_t m : same)
+          for (int64_t i = ex->succ_start[m]; i < ex->succ_start[m + 1]; ++i) {
+            const int64_t w = ex->succ[i];
+            if (mg.v[w].kind == TN_MG_OP && --rem_enq[w] == 0) ready_k.push_back(w);
+          }
       ++rep.n_launches;
       ++rep.n_kernel_launches;
-      if (sl.family == 0) { ++rep.gemm_launches; rep.gemm_flops += sl.flops; }
-      else if (sl.family == 1) { ++rep.attn_launches; rep.attn_flops += sl.flops; }
-      else { ++rep.ewise_launches; rep.ewise_bytes += sl.bytes; }
-      if (sl.prof >= 0) ex->prof_family.push_back(sl.family), ex->prof_family.push_back(sl.prof);
+      if (grp.family == 0) { ++rep.gemm_launches; rep.gemm_flops += flops; }
+      else if (grp.family == 1) { ++rep.attn_launches; rep.attn_flops += flops; }
+      else { ++rep.ewise_launches; rep.ewise_bytes += bytes; }
+      if (grp.prof >= 0) ex->prof_family.push_back(grp.family), ex->prof_family.push_back(grp.prof);
+      grp.verts = same;
+      ex->cqueue[si].push_back(std::move(grp));
       progressed = true;
     }
     if (status != TN_OK) break;
     // ---- completions -----------------------------------------------------------------------
-    for (auto& sl : ex->slots) {
+    for (int si = 0; si < ex->n_compute && status == TN_OK; ++si) {
+      auto& q = ex->cqueue[si];
+      while (!q.empty()) {  // a stream finishes its groups in order
+        hipError_t e = hipEventQuery(q.front().done);
+        if (e == hipErrorNotReady) break;
+        if (e != hipSuccess) { hip_fail("hipEventQuery", e); break; }
+        Group g = std::move(q.front());
+        q.pop_front();
+        for (int64_t m : g.verts) complete(m);
+        progressed = true;
+      }
+    }
+    for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
+      Slot& sl = ex->slots[ex->n_compute + dir];
       if (!sl.busy) continue;
       if (!sl.event_seen) {
         hipError_t e = hipEventQuery(sl.done);
@@ -699,7 +803,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         if (e != hipSuccess) { hip_fail("hipEventQuery", e); break; }
         sl.event_seen = true;
         sl.release = Clock::now();
-        if (sl.family >= 3 && opt.max_delay_us) {
+        if (opt.max_delay_us) {
           // injected transfer delay: the completion is reported late; the copy itself ran normally
           const uint64_t us = mix64(opt.delay_seed ^ (uint64_t)sl.verts[0] * 0x9E3779B1ull) % (opt.max_delay_us + 1ull);
           sl.release += std::chrono::microseconds(us);
@@ -722,6 +826,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     if (!progressed) {
       bool any_busy = false;
       for (auto& sl : ex->slots) any_busy |= sl.busy;
+      for (auto& q : ex->cqueue) any_busy |= !q.empty();
       if (!any_busy && ready_k.empty() && ready_h2d.empty() && ready_d2h.empty() && completed < nv) {
         status = fail(TN_ERR_CYCLE, "no vertex is ready and none is running: %lld of %lld completed",
                       (long long)completed, (long long)nv);
@@ -734,6 +839,11 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     if (sl.busy) {
       (void)hipStreamSynchronize(sl.stream);
       sl.busy = false;
+    }
+  for (int si = 0; si < ex->n_compute; ++si)
+    if (!ex->cqueue[si].empty()) {
+      (void)hipStreamSynchronize(ex->slots[si].stream);
+      ex->cqueue[si].clear();
     }
   rep.wall_ms = std::chrono::duration<double, std::milli>(Clock::now() - t_start).count();
   rep.n_vertices = completed;

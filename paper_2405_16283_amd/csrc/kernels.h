@@ -43,11 +43,16 @@ enum LaunchClass {
   LC_COUNT
 };
 
-constexpr int kMaxBatch = 240;  // vertices per launch (the list travels in the kernel arguments)
+// Vertices per launch.  The list travels in the kernel arguments (4 KiB at most), as 16-bit
+// offsets from the smallest descriptor index of the group.
+constexpr int kMaxBatch = 1920;
+constexpr uint32_t kMaxBatchSpan = 65535;  // largest descriptor index distance inside one group
 
 struct Batch {
   int32_t n;
-  int32_t idx[kMaxBatch];  // indices into the descriptor table
+  uint32_t base;            // smallest descriptor index of the group
+  uint16_t idx[kMaxBatch];  // descriptor index minus base
+  __host__ __device__ uint32_t at(uint32_t i) const { return base + idx[i]; }
 };
 
 struct DeviceTables {

@@ -34,7 +34,7 @@ template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p 
 // ---------------------------------------------------------------------------------------------
 template <typename T, bool SILU>
 __global__ void __launch_bounds__(256) ewise2_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const T* x = (const T*)t.ptrs[d.ptr0];
   const T* y = (const T*)t.ptrs[d.ptr0 + 1];
@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(256) ewise2_kernel(DeviceTables t, Batch b) {
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) rms_stat_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= d.rows) return;
@@ -114,7 +114,7 @@ __global__ void __launch_bounds__(256) rms_stat_kernel(DeviceTables t, Batch b) 
 // RMSNorm apply: out = x * stat[row] * gain[col]
 template <typename T>
 __global__ void __launch_bounds__(256) rms_apply_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const T* x = (const T*)t.ptrs[d.ptr0];
   const float* stat = (const float*)t.ptrs[d.ptr0 + 1];
@@ -133,7 +133,7 @@ __global__ void __launch_bounds__(256) rms_apply_kernel(DeviceTables t, Batch b)
 // sequences lose no accuracy, then the single-precision sincos is taken of the reduced angle
 template <typename T>
 __global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const T* x = (const T*)t.ptrs[d.ptr0];
   T* o = (T*)d.out;
@@ -155,7 +155,7 @@ __global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
 // Attention combine: merge the partials of one query block (j ascending) and normalise
 template <typename T>
 __global__ void __launch_bounds__(256) attn_combine_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const int id = blockIdx.x * 256 + threadIdx.x;
   if (id >= d.rows * d.cols) return;
@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(DeviceTables t, Batch
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   __shared__ float As[16][68];
   __shared__ float Bs[16][68];
@@ -286,7 +286,7 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[TI][TJ], bf16_
 constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_LD = GB_K + 8;
 
 __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   __shared__ __attribute__((aligned(16))) bf16_t As[GB_M * GB_LD];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[GB_N * GB_LD];
@@ -409,7 +409,7 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
   constexpr int WNS = NW / 2;             // wavefronts along N
   int bx, by;
   xcd_remap(bx, by);
-  const OpDesc& d = t.descs[b.idx[by]];
+  const OpDesc& d = t.descs[b.at(by)];
   if (bx >= d.nblocks) return;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int M = d.rows, N = d.cols, nk = d.p.nk;
@@ -555,7 +555,7 @@ __device__ __forceinline__ const T* tile_elem_t(void* const* tiles, int nc, int 
 
 template <typename T, int HD>
 __global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const int* ax = t.aux + d.aux0;
   const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
@@ -612,7 +612,7 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch 
 // ---------------------------------------------------------------------------------------------
 template <int HD>
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.idx[blockIdx.y]];
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   constexpr int KC = 64;                   // keys per iteration
   constexpr int CPR = HD / 8;              // 16-byte chunks per K row

@@ -67,8 +67,9 @@ def test_twenty_dispatch_orders_and_transfer_delays_give_identical_bits(name):
             delay = (0, 50, 500)[seed % 3]
             batch = (1, 4, 0)[(seed // 3) % 3]
             print(f"[case] {name} order_seed {seed} delay {delay} batch {batch}", flush=True)
+            depth = (1, 3, 8)[(seed // 2) % 3]
             out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, delay_seed=100 + seed,
-                                            max_delay_us=delay, max_batch=batch))
+                                            max_delay_us=delay, max_batch=batch, queue_depth=depth))
             np.testing.assert_array_equal(out["y"], ref["y"])
             orders.add(tuple(s.last_order()))
         assert len(orders) >= 15, "the seeds must really perturb the dispatch order"
@@ -84,6 +85,10 @@ def test_launch_order_respects_every_dependency():
     s = H.GpuSession(cfg, make_llama_inputs(cfg, 0))
     try:
         s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=5, max_batch=3))
+        order = s.last_order()
+        B.tn_memgraph_simulate(s.mg, order)
+        # with kernels enqueued ahead of the completion of their predecessors, too
+        s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=6, max_batch=5, queue_depth=4))
         order = s.last_order()
         e = H.export_memgraph(s.mg)
         assert sorted(order) == list(range(len(e["kind"])))
