@@ -98,15 +98,16 @@ def forward(cfg, inputs_f64, n_tokens_prefix=None):
     return np.concatenate(out, axis=0)
 
 
+def widen_array(a: np.ndarray) -> np.ndarray:
+    """One storage-dtype buffer (float32, or bfloat16 bit patterns as uint16) -> exact float64."""
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
 def widen(cfg, inputs):
     """Storage-dtype host buffers -> exact float64 copies."""
-    out = {}
-    for k, a in inputs.items():
-        if a.dtype == np.uint16:
-            out[k] = (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
-        else:
-            out[k] = a.astype(np.float64)
-    return out
+    return {k: widen_array(a) for k, a in inputs.items()}
 
 
 def rel_err(a: np.ndarray, b: np.ndarray) -> float:

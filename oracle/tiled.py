@@ -180,11 +180,17 @@ def evaluate(tg: TaskGraph, input_values: Dict[int, np.ndarray],
     done = [False] * n
     for v in order:
         if tg.kind[v] == "input":
+            if not keep_all and v not in keep:
+                done[v] = True  # fetched when its first consumer runs, so that unused tiles hold no memory
+                continue
             r = np.asarray(input_values[v], dtype=np.float64).reshape(tg.shape[v])
         else:
             for u in tg.inputs[v]:
                 if not done[u]:
                     raise ValueError(f"order is not topological at vertex {v}")
+                if u not in val:
+                    val[u] = round_store(np.asarray(input_values[u], dtype=np.float64).reshape(tg.shape[u]),
+                                         tg.dtype[u])
             r = _eval_vertex(tg.kind[v], tg.params[v], [val[u] for u in tg.inputs[v]])
             assert r.shape == tg.shape[v], (tg.kind[v], r.shape, tg.shape[v])
         val[v] = round_store(r, tg.dtype[v])
@@ -334,6 +340,23 @@ def cut_inputs(tg: TaskGraph, full_f64: Dict[str, np.ndarray]) -> Dict[int, np.n
         a = a.reshape(1, -1) if a.ndim == 1 else a
         out[v] = a[r0:r1, c0:c1].T if len(bnd) > 5 and bnd[5] else a[r0:r1, c0:c1]
     return out
+
+
+class LazyInputs:
+    """Mapping vid -> float64 tile that slices and widens the full storage-type tensors on demand
+    (for inputs too large to hold widened all at once).  `widen` turns a storage-type array into
+    float64 exactly."""
+
+    def __init__(self, tg: TaskGraph, full_storage: Dict[str, np.ndarray], widen):
+        self.tg, self.full, self.widen = tg, full_storage, widen
+
+    def __getitem__(self, v: int) -> np.ndarray:
+        bnd = self.tg.binding[v]
+        name, r0, r1, c0, c1 = bnd[:5]
+        a = self.full[name]
+        a = a.reshape(1, -1) if a.ndim == 1 else a
+        t = self.widen(np.ascontiguousarray(a[r0:r1, c0:c1]))
+        return t.T if len(bnd) > 5 and bnd[5] else t
 
 
 def assemble_outputs(tg: TaskGraph, values: Dict[int, np.ndarray], tokens: int, d: int) -> np.ndarray:

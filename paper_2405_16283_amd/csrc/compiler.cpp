@@ -16,6 +16,7 @@
 #include <climits>
 #include <cstring>
 #include <map>
+#include <set>
 #include <unordered_set>
 
 #include "graph.h"
@@ -50,6 +51,8 @@ struct Compiler {
   std::unordered_set<uint64_t> edge_set[3];
   std::map<uint64_t, Block> blocks;                          // offset -> block, covers [0, cap)
   std::map<uint64_t, std::pair<uint64_t, int64_t>> history;  // offset -> (end, last dead occupant)
+  std::map<uint64_t, uint64_t> free_at;                      // the free blocks alone: offset -> size
+  std::multiset<uint64_t> free_sizes;                        // their sizes, to refuse a hopeless search at once
   int64_t execHzn = 0, allocHzn = 0, lookahead_blocked_until = -1, compacted_at = -1;
   uint64_t lookahead_bytes = 0, live_bytes = 0;
   std::vector<int64_t> step_pre;  // offloads and reloads inserted just before V[execHzn], in the order made
@@ -93,19 +96,33 @@ struct Compiler {
   bool produced(int64_t m) const { return m >= n || pos[m] < execHzn; }
 
   // ---- simulated memory ------------------------------------------------------------------
+  void free_add(uint64_t off, uint64_t size) {
+    free_at[off] = size;
+    free_sizes.insert(size);
+  }
+  void free_del(uint64_t off, uint64_t size) {
+    free_at.erase(off);
+    free_sizes.erase(free_sizes.find(size));
+  }
+
+  // `it` has just become free: merge it with free neighbours and enter the result in the index
   void coalesce(std::map<uint64_t, Block>::iterator it) {
     auto nx = std::next(it);
     if (nx != blocks.end() && nx->second.owner < 0) {
+      free_del(nx->first, nx->second.size);
       it->second.size += nx->second.size;
       blocks.erase(nx);
     }
     if (it != blocks.begin()) {
       auto pv = std::prev(it);
       if (pv->second.owner < 0) {
+        free_del(pv->first, pv->second.size);
         pv->second.size += it->second.size;
         blocks.erase(it);
+        it = pv;
       }
     }
+    free_add(it->first, it->second.size);
   }
 
   void history_set(uint64_t a, uint64_t b, int64_t owner) {
@@ -134,9 +151,16 @@ struct Compiler {
   void place(std::map<uint64_t, Block>::iterator it, uint64_t off, int64_t m) {
     const uint64_t size = vbytes(m), b0 = it->first, bsz = it->second.size;
     blocks.erase(it);
-    if (off > b0) blocks[b0] = {off - b0, -1};
+    free_del(b0, bsz);
+    if (off > b0) {
+      blocks[b0] = {off - b0, -1};
+      free_add(b0, off - b0);
+    }
     blocks[off] = {size, m};
-    if (off + size < b0 + bsz) blocks[off + size] = {b0 + bsz - off - size, -1};
+    if (off + size < b0 + bsz) {
+      blocks[off + size] = {b0 + bsz - off - size, -1};
+      free_add(off + size, b0 + bsz - off - size);
+    }
     mg.v[m].offset = (int64_t)off;
     live_bytes += size;
     mg.stats.peak_live_bytes = std::max(mg.stats.peak_live_bytes, live_bytes);
@@ -157,17 +181,18 @@ struct Compiler {
   // simMalloc: find an open range or fail
   bool sim_malloc(int64_t m) {
     const uint64_t size = vbytes(m);
-    if (size >= kSmallTensor) {
-      for (auto it = blocks.begin(); it != blocks.end(); ++it)
-        if (it->second.owner < 0 && it->second.size >= size) {
-          place(it, it->first, m);
+    if (free_sizes.empty() || *free_sizes.rbegin() < size) return false;
+    if (size >= kSmallTensor) {  // first fit from the bottom
+      for (auto f = free_at.begin(); f != free_at.end(); ++f)
+        if (f->second >= size) {
+          place(blocks.find(f->first), f->first, m);
           return true;
         }
-    } else {
-      for (auto it = blocks.rbegin(); it != blocks.rend(); ++it)
-        if (it->second.owner < 0 && it->second.size >= size) {
-          auto fwd = std::prev(it.base());
-          place(fwd, fwd->first + fwd->second.size - size, m);
+    } else {  // small tensors: first fit from the top, at the top end of the hole
+      for (auto f = free_at.rbegin(); f != free_at.rend(); ++f)
+        if (f->second >= size) {
+          const uint64_t b0 = f->first, bsz = f->second;
+          place(blocks.find(b0), b0 + bsz - size, m);
           return true;
         }
     }
@@ -387,6 +412,7 @@ struct Compiler {
     cap = mg.cap / align * align;
     if (cap == 0) return fail(TN_ERR_CAP_TOO_SMALL, "cap is smaller than one allocation unit");
     blocks[0] = {cap, -1};
+    free_add(0, cap);
     pos.assign(n, -1);
     for (int64_t i = 0; i < n; ++i) pos[V[i]] = i;
     cons.assign(n, {});

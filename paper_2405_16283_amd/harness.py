@@ -97,6 +97,20 @@ def cut_host_tiles(tg, full: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
     return out
 
 
+def output_vertices(tg):
+    """(vids in output-index order, their (rows, cols), {vid: binding}) of the marked outputs."""
+    bind = {b[0]: b for b in bindings(tg) if b[1].split(".")[0] in ("y", "k", "v")}
+    n_out = B.tn_taskgraph_num_outputs(tg)
+    cand = list(bind) if len(bind) == n_out else range(B.tn_taskgraph_num_vertices(tg))
+    vids, shapes = [0] * n_out, [(0, 0)] * n_out
+    for v in cand:
+        x = B.tn_taskgraph_vertex(tg, v)
+        if x.output_index >= 0:
+            vids[x.output_index] = v
+            shapes[x.output_index] = (x.desc.rows, x.desc.cols)
+    return vids, shapes, bind
+
+
 def uncapped_peak(tg) -> int:
     """Peak bytes of the serial run with unlimited memory and no run-ahead allocation."""
     opts = B.tn_compile_opts(max_lookahead_bytes=0, drop_clean_inputs=1)
@@ -133,24 +147,37 @@ class GpuSession:
         self.stats = B.tn_memgraph_stats(self.mg)
         self.n_task = B.tn_taskgraph_num_vertices(self.tg)
         self.elem = np.float32 if cfg.dtype == "f32" else np.uint16
-        # inputs: one pinned slab, tiles back to back (256-byte aligned)
-        tiles = cut_host_tiles(self.tg, full_inputs)
-        offs, total = {}, 0
-        for v, a in tiles.items():
-            offs[v] = total
-            total += (a.nbytes + 255) // 256 * 256
+        # inputs: one pinned slab, tiles back to back (256-byte aligned); input vertices bound to
+        # the same region of the same array (layers that share their weights) share one copy
+        es = np.dtype(self.elem).itemsize
+        offs, seen, total = {}, {}, 0
+        cuts = []
+        for vid, name, r0, r1, c0, c1, tr in bindings(self.tg):
+            if name.split(".")[0] in ("y", "k", "v"):
+                continue
+            a = full_inputs[name]
+            key = (id(a), r0, r1, c0, c1, tr)
+            if key not in seen:
+                seen[key] = total
+                cuts.append((total, a, r0, r1, c0, c1, tr))
+                total += ((r1 - r0) * (c1 - c0) * es + 255) // 256 * 256
+            offs[vid] = seen[key]
         self.in_slab = torch.empty(max(total, 256), dtype=torch.uint8).pin_memory()
         slab_np = self.in_slab.numpy()
+        for off, a, r0, r1, c0, c1, tr in cuts:
+            a = a.reshape(1, -1) if a.ndim == 1 else a
+            tile = a[r0:r1, c0:c1]
+            dst = slab_np[off:off + tile.size * es].view(self.elem)
+            if tr:
+                np.copyto(dst.reshape(c1 - c0, r1 - r0), tile.T)
+            else:
+                np.copyto(dst.reshape(r1 - r0, c1 - c0), tile)
         self.in_ptrs = [0] * self.n_task
-        for v, a in tiles.items():
-            slab_np[offs[v]:offs[v] + a.nbytes] = a.view(np.uint8).reshape(-1)
-            self.in_ptrs[v] = self.in_slab.data_ptr() + offs[v]
+        base = self.in_slab.data_ptr()
+        for v, off in offs.items():
+            self.in_ptrs[v] = base + off
         # outputs: one pinned slab
-        e = export_taskgraph(self.tg)
-        self.out_vids = e["outputs"]
-        self.out_shapes = [e["shape"][v] for v in self.out_vids]
-        self.out_bind = {b[0]: b for b in e["bindings"] if b[1].split(".")[0] in ("y", "k", "v")}
-        es = np.dtype(self.elem).itemsize
+        self.out_vids, self.out_shapes, self.out_bind = output_vertices(self.tg)
         self.out_offs, total = [], 0
         for (r, c) in self.out_shapes:
             self.out_offs.append(total)
@@ -171,21 +198,26 @@ class GpuSession:
     def execute(self, opts: Optional[B.tn_exec_opts] = None) -> B.tn_exec_report:
         return B.tn_execute(self.ex, self.in_ptrs, self.out_ptrs, opts)
 
-    def run(self, opts: Optional[B.tn_exec_opts] = None, poison: bool = True):
+    def run(self, opts: Optional[B.tn_exec_opts] = None, poison: bool = True,
+            only: Optional[Sequence[str]] = None):
         """place inputs, execute, and return ({"y": array, ["k.l", "v.l": arrays]}, report)."""
         if poison:
             self.out_slab.fill_(0xFF)
         self.place_inputs()
         rep = self.execute(opts)
-        return self.outputs(), rep
+        return self.outputs(only), rep
 
-    def outputs(self) -> Dict[str, np.ndarray]:
+    def outputs(self, only: Optional[Sequence[str]] = None) -> Dict[str, np.ndarray]:
+        """Assembles the output tensors ("y", and "k.l" / "v.l" with kv_outputs) from the pinned
+        tiles; `only` restricts the result to the named tensors."""
         cfg = self.cfg
         out: Dict[str, np.ndarray] = {}
         slab = self.out_slab.numpy()
         es = np.dtype(self.elem).itemsize
         for i, v in enumerate(self.out_vids):
             _, name, r0, r1, c0, c1, tr = self.out_bind[v]
+            if only is not None and name not in only:
+                continue
             if name not in out:
                 out[name] = np.zeros((cfg.tokens, cfg.d_model), dtype=self.elem)
             r, c = self.out_shapes[i]

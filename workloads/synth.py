@@ -131,22 +131,43 @@ def _tensor(seed, cfg, kind, layer, shape, mean, std, chunk=1 << 22):
     return out.reshape(shape)
 
 
-def make_llama_inputs(cfg: LlamaConfig, seed: int) -> Dict[str, np.ndarray]:
+def make_llama_inputs(cfg: LlamaConfig, seed: int, distinct_layers: int = 0, workers: int = 0) -> Dict[str, np.ndarray]:
     """Full (untiled) input tensors in storage dtype.
 
     Keys: "x" [tokens, d]; per layer l: "wq.l", "wk.l", "wv.l", "wo.l" [d, d], "w1.l", "w3.l"
     [d, F], "w2.l" [F, d] (all right-multiplied: y = x @ W, row-major [in, out]); "g1.l",
     "g2.l" [d].  Weights ~ N(0, 0.02), x ~ N(0, 1), gains 1 + 0.02 N(0, 1).  bf16 tensors are
     uint16 bit patterns.
+
+    distinct_layers = k > 0: only the first k layers get tensors of their own; layer l uses the
+    very arrays of layer l mod k (same objects), which keeps the host footprint of the deep
+    workloads small without changing any shape, vertex count or transfer.
+    workers > 1 generates the tensors on that many threads (same bits: every element is a pure
+    function of its index).
     """
     d, f = cfg.d_model, cfg.ffn
-    t: Dict[str, np.ndarray] = {"x": _tensor(seed, cfg, "x", -1, (cfg.tokens, d), 0.0, 1.0)}
-    for l in range(cfg.layers):
-        for k, shape in (("wq", (d, d)), ("wk", (d, d)), ("wv", (d, d)), ("wo", (d, d)),
-                         ("w1", (d, f)), ("w3", (d, f)), ("w2", (f, d))):
-            t[f"{k}.{l}"] = _tensor(seed, cfg, k, l, shape, 0.0, 0.02)
-        t[f"g1.{l}"] = _tensor(seed, cfg, "g1", l, (d,), 1.0, 0.02)
-        t[f"g2.{l}"] = _tensor(seed, cfg, "g2", l, (d,), 1.0, 0.02)
+    k = cfg.layers if distinct_layers <= 0 else min(distinct_layers, cfg.layers)
+    jobs = [("x", "x", -1, (cfg.tokens, d), 0.0, 1.0)]
+    for l in range(k):
+        for kind, shape in (("wq", (d, d)), ("wk", (d, d)), ("wv", (d, d)), ("wo", (d, d)),
+                            ("w1", (d, f)), ("w3", (d, f)), ("w2", (f, d))):
+            jobs.append((f"{kind}.{l}", kind, l, shape, 0.0, 0.02))
+        jobs.append((f"g1.{l}", "g1", l, (d,), 1.0, 0.02))
+        jobs.append((f"g2.{l}", "g2", l, (d,), 1.0, 0.02))
+
+    def make(j):
+        return _tensor(seed, cfg, j[1], j[2], j[3], j[4], j[5])
+
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            arrays = list(pool.map(make, jobs))
+    else:
+        arrays = [make(j) for j in jobs]
+    t: Dict[str, np.ndarray] = {j[0]: a for j, a in zip(jobs, arrays)}
+    for l in range(k, cfg.layers):
+        for kind in ("wq", "wk", "wv", "wo", "w1", "w3", "w2", "g1", "g2"):
+            t[f"{kind}.{l}"] = t[f"{kind}.{l % k}"]
     return t
 
 
