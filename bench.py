@@ -36,7 +36,11 @@ def cpu_baseline(cfg, full, budget_tokens):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    w = R.widen(cfg, full)
+    seen, w = {}, {}
+    for k, a in full.items():  # layers that share their weights share the widened copy
+        if id(a) not in seen:
+            seen[id(a)] = R.widen_array(a)
+        w[k] = seen[id(a)]
     t0 = time.perf_counter()
     y = R.forward(cfg, w, n_tokens_prefix=budget_tokens)
     dt = time.perf_counter() - t0
@@ -52,14 +56,19 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
-    ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--streams", type=int, default=2)
     ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
     ap.add_argument("--max-gemm-inflight", type=int, default=2)
     ap.add_argument("--queue-depth", type=int, default=3)
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order"])
-    ap.add_argument("--cpu-tokens", type=int, default=512, help="tokens of the CPU-oracle sample; 0 = skip")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample; 0 = skip")
     ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
+    ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
+    ap.add_argument("--copy-workgroups", type=int, default=0)
+    ap.add_argument("--distinct-layers", type=int, default=-1,
+                    help="layers with weights of their own (the others reuse them); default: all up to 8 layers, else 4")
+    ap.add_argument("--kv-outputs", type=int, default=-1, help="K/V of every layer are outputs; default: only when weights are streamed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -76,7 +85,9 @@ def main():
         sys.exit(1)
     cfg = config(args.workload)
     t0 = time.perf_counter()
-    full = make_llama_inputs(cfg, 0)
+    distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
+    kv_outputs = bool(args.kv_outputs) if args.kv_outputs >= 0 else (cfg.layers > 1 and not cfg.weights_resident)
+    full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     t_gen = time.perf_counter() - t0
 
     def timed(session, steps, warmup, opts):
@@ -93,20 +104,23 @@ def main():
         return reps
 
     t0 = time.perf_counter()
-    s = H.GpuSession(cfg, full, n_compute=args.streams)
+    s = H.GpuSession(cfg, full, n_compute=args.streams, kv_outputs=kv_outputs)
     t_compile = time.perf_counter() - t0
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER}[args.policy]
+    engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
     opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
-                          max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth)
+                          max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
+                          copy_workgroups=args.copy_workgroups)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
     plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
                                                                 max_transfers=args.max_transfers,
-                                                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth))
+                                                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth,
+                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
-    y = s.outputs()["y"]
+    y = s.outputs(only=["y"])["y"]
     st = s.stats
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
     gemm_ms = sum(r.gemm_ms for _, r in reps)
@@ -135,9 +149,10 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.layers}-layer LLaMA-7B-shaped prefill, d {cfg.d_model}, "
                                f"{cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, batch {cfg.batch}, "
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
+                   "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
@@ -153,6 +168,11 @@ def main():
             "elementwise_GBs": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
             "kernel_launches_per_step": int(rep0.n_kernel_launches),
             "gpu_idle_frac": rep0.idle_frac,
+            "kernel_busy_ms": rep0.kernel_busy_ms, "gemm_ms": rep0.gemm_ms, "attn_ms": rep0.attn_ms,
+            "ewise_ms": rep0.ewise_ms, "h2d_ms": rep0.h2d_ms, "d2h_ms": rep0.d2h_ms,
+            "h2d_GBs_while_copying": rep0.h2d_bytes / (rep0.h2d_ms * 1e-3) / 1e9 if rep0.h2d_ms > 0 else None,
+            "d2h_GBs_while_copying": rep0.d2h_bytes / (rep0.d2h_ms * 1e-3) / 1e9 if rep0.d2h_ms > 0 else None,
+            "launches_per_step": int(rep0.n_launches),
             "d2h_GBs_over_wall": rep0.d2h_bytes / (ms * 1e-3) / 1e9,
             "h2d_GBs_over_wall": rep0.h2d_bytes / (ms * 1e-3) / 1e9,
             "input_generation_s": t_gen, "build_and_compile_s": t_compile,
@@ -168,7 +188,7 @@ def main():
         r2 = timed(s2, max(3, args.steps // 4), 1, opts)
         ms2 = 1e3 * sum(dt for dt, _ in r2) / len(r2)
         rr = r2[-1][1]
-        y2 = s2.outputs()["y"]
+        y2 = s2.outputs(only=["y"])["y"]
         line["capped40"] = {
             "gpu_cap_bytes": s2.cap, "ms_per_step": ms2, "tokens_per_s": cfg.tokens / (ms2 * 1e-3),
             "offloads": int(s2.stats.n_offload), "reloads": int(s2.stats.n_reload), "loads": int(s2.stats.n_load),

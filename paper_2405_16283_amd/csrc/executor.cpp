@@ -587,6 +587,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       sl.verts.clear();
       sl.bytes = 0;
       copies.n = 0;
+      copies.total_blocks = 0;
       hipError_t e = hipSuccess;
       while (!r.empty() && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
         const size_t i = pick(r);
@@ -620,7 +621,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           ++rep.n_offload;
         }
         if (use_copy_kernel) {
-          copies.it[copies.n++] = {src, dst, (uint32_t)x.bytes, (uint32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes)};
+          copies.it[copies.n++] = {src, dst, (uint32_t)x.bytes, (uint32_t)copies.total_blocks};
+          copies.total_blocks += (int32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes);
         } else {
           e = hipMemcpyAsync(dst, src, x.bytes, dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
           if (e != hipSuccess) break;
@@ -644,7 +646,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         }
       }
       if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof], sl.stream);
-      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, sl.stream);
+      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, opt.copy_workgroups, sl.stream);
       if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof + 1], sl.stream);
       if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }

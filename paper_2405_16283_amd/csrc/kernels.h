@@ -67,19 +67,23 @@ struct DeviceTables {
 // the runtime spends a launch and a gap per tensor, which at tile sizes of a few hundred KiB
 // leaves half of the host link idle.
 constexpr int kMaxCopies = 128;
-constexpr uint32_t kCopyBlockBytes = 32768;  // bytes one workgroup moves
+constexpr int kCopyThreads = 1024;
+constexpr int kCopyLoads = 2;  // 16-byte loads in flight per lane
+constexpr uint32_t kCopyBlockBytes = kCopyLoads * 16 * kCopyThreads;  // bytes one workgroup moves per step: 32 KiB
+constexpr int kDefaultCopyWorkgroups = 8;
 struct CopyItem {
   const void* src;
   void* dst;
   uint32_t bytes;
-  uint32_t nblocks;
+  uint32_t first_block;  // index of its first 32 KiB piece among the pieces of the group
 };
 struct CopyBatch {
   int32_t n;
-  int32_t pad;
+  int32_t total_blocks;
   CopyItem it[kMaxCopies];
 };
-hipError_t launch_copies(const CopyBatch& b, hipStream_t stream);
+// max_workgroups <= 0 selects kDefaultCopyWorkgroups
+hipError_t launch_copies(const CopyBatch& b, int max_workgroups, hipStream_t stream);
 
 // Workgroups a vertex needs in the given class (host side, used to fill OpDesc::nblocks).
 int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux);

@@ -802,30 +802,37 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
 }
 
 // ---------------------------------------------------------------------------------------------
-// grouped tensor copy (see kernels.h): a workgroup moves 32 KiB with eight 16-byte loads in
-// flight per lane, which is what it takes to keep the host link busy in the reload direction
+// grouped tensor copy (see kernels.h).  The copies of a group are cut into 32 KiB pieces; a
+// small, fixed number of 1024-lane workgroups walks over them, two 16-byte loads in flight per
+// lane.  What keeps the host link busy is the number of waves with a load outstanding, not the
+// loads per wave (measured: 8 such workgroups reach 56 GB/s, the rate of the copy engines).
+// The large GEMM kernel needs a whole compute unit for one workgroup, so every compute unit
+// that holds a copy wave is lost to it: hence few, wide workgroups.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) copy_kernel(CopyBatch b) {
-  const CopyItem it = b.it[blockIdx.y];
-  if (blockIdx.x >= it.nblocks) return;
-  const uint32_t off = blockIdx.x * kCopyBlockBytes;
-  const uint32_t len = min(kCopyBlockBytes, it.bytes - off);
-  const char* src = (const char*)it.src + off;
-  char* dst = (char*)it.dst + off;
-  const uint32_t vec = len / 16;  // whole 16-byte pieces (tensor locations are 256-byte aligned)
-  uint4 v[8];
+__global__ void __launch_bounds__(kCopyThreads) copy_kernel(CopyBatch b) {
+  int item = 0;
+  for (uint32_t g = blockIdx.x; g < (uint32_t)b.total_blocks; g += gridDim.x) {
+    while (item + 1 < b.n && g >= b.it[item + 1].first_block) ++item;
+    const CopyItem it = b.it[item];
+    const uint32_t off = (g - it.first_block) * kCopyBlockBytes;
+    const uint32_t len = min(kCopyBlockBytes, it.bytes - off);
+    const char* src = (const char*)it.src + off;
+    char* dst = (char*)it.dst + off;
+    const uint32_t vec = len / 16;  // whole 16-byte pieces (tensor locations are 256-byte aligned)
+    uint4 v[kCopyLoads];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const uint32_t i = threadIdx.x + 256 * k;
-    if (i < vec) v[k] = ((const uint4*)src)[i];
-  }
+    for (int k = 0; k < kCopyLoads; ++k) {
+      const uint32_t i = threadIdx.x + kCopyThreads * k;
+      if (i < vec) v[k] = ((const uint4*)src)[i];
+    }
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const uint32_t i = threadIdx.x + 256 * k;
-    if (i < vec) ((uint4*)dst)[i] = v[k];
+    for (int k = 0; k < kCopyLoads; ++k) {
+      const uint32_t i = threadIdx.x + kCopyThreads * k;
+      if (i < vec) ((uint4*)dst)[i] = v[k];
+    }
+    const uint32_t tail = vec * 16 + threadIdx.x;
+    if (tail < len) dst[tail] = src[tail];
   }
-  const uint32_t tail = vec * 16 + threadIdx.x;
-  if (tail < len) dst[tail] = src[tail];
 }
 
 }  // namespace
@@ -858,12 +865,10 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
   }
 }
 
-hipError_t launch_copies(const CopyBatch& b, hipStream_t s) {
-  if (b.n <= 0) return hipSuccess;
-  uint32_t max_blocks = 0;
-  for (int i = 0; i < b.n; ++i) max_blocks = b.it[i].nblocks > max_blocks ? b.it[i].nblocks : max_blocks;
-  if (max_blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(copy_kernel, dim3(max_blocks, (unsigned)b.n), dim3(256), 0, s, b);
+hipError_t launch_copies(const CopyBatch& b, int max_workgroups, hipStream_t s) {
+  if (b.n <= 0 || b.total_blocks <= 0) return hipSuccess;
+  const int wgs = std::min(b.total_blocks, max_workgroups > 0 ? max_workgroups : kDefaultCopyWorkgroups);
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)wgs), dim3(kCopyThreads), 0, s, b);
   return hipGetLastError();
 }
 
