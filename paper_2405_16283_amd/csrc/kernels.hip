@@ -7,6 +7,8 @@
 // order, no atomics, so any dispatch order gives the same bits.
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace tn {
 namespace {
 
@@ -402,6 +404,30 @@ __device__ __forceinline__ void xcd_remap(int& bx, int& by) {
 
 // NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two
 // per SIMD, so that one wavefront's MFMAs fill the time the other spends issuing its loads).
+// MFMA with the accumulator held in the accumulation registers.  Left to itself the compiler
+// keeps the accumulators of this kernel in ordinary vector registers, where the matrix unit's
+// result traffic competes with the fragment reads arriving from LDS.  The asm statements are
+// volatile so that they, and the wait states that follow the last one, keep their order; the
+// same accumulator is not touched again for at least seven other MFMAs.
+#ifndef TN_MFMA_AGPR
+#define TN_MFMA_AGPR 0
+#endif
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+#if TN_MFMA_AGPR
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+#else
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+#endif
+}
+__device__ __forceinline__ void mfma_acc_drain() {
+#if TN_MFMA_AGPR
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");  // the last results reach the registers
+#endif
+}
+
+#ifndef TN_GEMM_STAGGER
+#define TN_GEMM_STAGGER(w) (((w) >> 2) & 1)  // wavefronts w and w + 4 share a SIMD
+#endif
 template <int NW>
 __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
   constexpr int TJ = 16 / NW;             // 32-column MFMA tiles per wavefront (TI = 4 row tiles)
@@ -487,9 +513,27 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
   const int c0 = ((0 + g) ^ sw) * 16, c1 = ((2 + g) ^ sw) * 16;
 
   for (int s = 0; s < G2_STAGES - 1 && s < nsteps; ++s) issue(s);
-  // The second half of a step's MFMAs is deferred to the next iteration, where it runs while
-  // that iteration's fragment reads are in flight and its loads are being issued.
-  bf16x8 a1[4], b1[TJ];
+  // Each step covers two MFMA slabs of 16 along K, held in the register sets (xa, xb) and
+  // (ya, yb).  While the eight MFMAs of one slab run, the fragments of the next slab are read,
+  // one LDS read after each MFMA: a wavefront can issue a short instruction in the shadow of
+  // its own MFMA, so the reads cost no matrix-unit time, and both register sets keep their role
+  // from step to step (no copies).  The second slab of a step is multiplied after the barrier
+  // of the next step.
+  bf16x8 xa[4], xb[TJ], ya[4], yb[TJ];
+  const bool loads_first = __builtin_amdgcn_readfirstlane(TN_GEMM_STAGGER(w)) != 0;
+#define TN_READ_SLAB(DA, DB, COL)                                                                      \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) DA[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + COL);  \
+  _Pragma("unroll") for (int j = 0; j < TJ; ++j) DB[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + COL);
+#define TN_MFMA_SLAB(SA, SB)                                  \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)               \
+  _Pragma("unroll") for (int j = 0; j < TJ; ++j) mfma_acc(acc[i][j], SA[i], SB[j]);
+  // one MFMA, then one LDS read, for as many reads as a slab has; the remaining MFMAs follow
+#define TN_INTERLEAVE()                                                          \
+  _Pragma("unroll") for (int q = 0; q < 4 + TJ; ++q) {                           \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                           \
+  }                                                                              \
+  __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ - (4 + TJ), 0);
   for (int s = 0; s < nsteps; ++s) {
     // stage s must have landed: at most the loads of the next two steps may still be in flight
     if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(NW == 4 ? 0x4F70 : 0x0F78);       // vmcnt(16 | 8)
@@ -497,37 +541,33 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
     else __builtin_amdgcn_s_waitcnt(0x0F70);                                         // vmcnt(0)
     __syncthreads();
     const char* st_ = lds + (s % G2_STAGES) * G2_STAGE_BYTES;
-    bf16x8 a0[4], b0[TJ], an[4], bn[TJ];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a0[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c0);
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) b0[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + c0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) an[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + c1);
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) bn[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + c1);
+    const bool more = s + G2_STAGES - 1 < nsteps;
+    // Issuing a load stalls a wavefront for as long as the address path is busy with the loads
+    // of the others, so the two wavefronts of a SIMD issue theirs at different points of a step.
+    if (loads_first && more) issue((s + G2_STAGES - 1) % G2_STAGES);
+    __builtin_amdgcn_sched_barrier(0);
     if (s > 0) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+      TN_MFMA_SLAB(ya, yb)
+      TN_READ_SLAB(xa, xb, c0)
+      TN_INTERLEAVE()
+    } else {
+      TN_READ_SLAB(xa, xb, c0)
     }
-    if (s + G2_STAGES - 1 < nsteps) issue((s + G2_STAGES - 1) % G2_STAGES);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a1[i] = an[i];
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) b1[j] = bn[j];
+    __builtin_amdgcn_sched_barrier(0);
+    if (!loads_first && more) issue((s + G2_STAGES - 1) % G2_STAGES);
+    __builtin_amdgcn_sched_barrier(0);
+    TN_MFMA_SLAB(xa, xb)
+    TN_READ_SLAB(ya, yb, c1)
+    TN_INTERLEAVE()
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (nsteps > 0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+    TN_MFMA_SLAB(ya, yb)
   }
+#undef TN_READ_SLAB
+#undef TN_MFMA_SLAB
+#undef TN_INTERLEAVE
+  mfma_acc_drain();
 
   store_c_tiles<4, TJ>(acc, Cp, M, N, m0 + wm * 128, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
 }
