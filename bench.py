@@ -61,7 +61,8 @@ def main():
     ap.add_argument("--max-transfers", type=int, default=0)
     ap.add_argument("--max-gemm-inflight", type=int, default=2)
     ap.add_argument("--queue-depth", type=int, default=3)
-    ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order"])
+    ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order", "in_order"])
+    ap.add_argument("--max-delay-us", type=int, default=0, help="inject a pseudo-random delay of up to this many microseconds into every transfer group")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample; 0 = skip")
     ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
@@ -107,18 +108,18 @@ def main():
     s = H.GpuSession(cfg, full, n_compute=args.streams, kv_outputs=kv_outputs)
     t_compile = time.perf_counter() - t0
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
-              "by_order": B.TN_POLICY_BY_ORDER}[args.policy]
+              "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
     engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
     opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
                           max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
-                          copy_workgroups=args.copy_workgroups)
+                          copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
     plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
                                                                 max_transfers=args.max_transfers,
                                                                 max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth,
-                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups))
+                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs(only=["y"])["y"]
     st = s.stats
@@ -152,7 +153,7 @@ def main():
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

@@ -278,7 +278,10 @@ tn_status tn_memgraph_simulate(const tn_memgraph* mg, const int64_t* order, int6
 /* Execute (GPU)                                                                               */
 /* ------------------------------------------------------------------------------------------ */
 
-enum { TN_POLICY_FIFO = 0, TN_POLICY_LIFO = 1, TN_POLICY_RANDOM = 2, TN_POLICY_BY_ORDER = 3 };
+/* IN_ORDER is the deterministic executor of the ablation in Section 8 (item 3): kernels are launched
+ * strictly in the serial order the memgraph was compiled for, and so are the transfers of each
+ * direction; a vertex whose turn has come but which is not ready holds back everything behind it. */
+enum { TN_POLICY_FIFO = 0, TN_POLICY_LIFO = 1, TN_POLICY_RANDOM = 2, TN_POLICY_BY_ORDER = 3, TN_POLICY_IN_ORDER = 4 };
 /* How transfers are carried out.  MEMCPY: one hipMemcpyAsync per tensor on the copy streams.
  * KERNEL: one grouped copy kernel per group of ready transfers, on the same streams; needs every
  * host buffer to be pinned memory the GPU can address (hipHostMalloc), else TN_ERR_INVALID.

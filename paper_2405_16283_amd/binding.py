@@ -10,7 +10,8 @@ import os
 from typing import List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libturnip.so")
+# TURNIP_LIB names another build of the same library (a build with different compile-time tuning)
+LIB_PATH = os.environ.get("TURNIP_LIB") or os.path.join(_HERE, "libturnip.so")
 
 TN_OK, TN_ERR_INVALID, TN_ERR_NOT_TOPOLOGICAL, TN_ERR_CYCLE = 0, -1, -2, -3
 TN_ERR_CAP_TOO_SMALL, TN_ERR_ARENA, TN_ERR_HIP, TN_ERR_SHAPE = -4, -5, -6, -7
@@ -22,7 +23,7 @@ TN_HOST, TN_DEVICE = 0, 1
  TN_T_Y, TN_T_K, TN_T_V) = range(13)
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE) = range(7)
 TN_EDGE_DATA, TN_EDGE_MEM, TN_EDGE_ORDER = 0, 1, 2
-TN_POLICY_FIFO, TN_POLICY_LIFO, TN_POLICY_RANDOM, TN_POLICY_BY_ORDER = 0, 1, 2, 3
+TN_POLICY_FIFO, TN_POLICY_LIFO, TN_POLICY_RANDOM, TN_POLICY_BY_ORDER, TN_POLICY_IN_ORDER = 0, 1, 2, 3, 4
 TN_COPY_AUTO, TN_COPY_MEMCPY, TN_COPY_KERNEL = 0, 1, 2
 UINT64_MAX = (1 << 64) - 1
 

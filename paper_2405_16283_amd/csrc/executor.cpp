@@ -34,6 +34,7 @@ struct VInfo {
   int8_t cls = -1;  // LaunchClass, or -1 for non-kernel vertices
   int8_t dtype = 0;
   int16_t head_dim = 0;
+  int16_t group = -1;  // index of its (cls, dtype, head_dim) combination: vertices of one group can share a launch
   int32_t desc = -1;
   int32_t nblocks = 0;
   double flops = 0, bytes = 0;
@@ -68,6 +69,50 @@ inline uint64_t mix64(uint64_t z) {
   return z ^ (z >> 31);
 }
 
+// Ready vertices of one kind, handed out in the order the policy asks for: oldest first, newest
+// first, at random, or smallest position in the serial order first (a binary heap).
+struct ReadyQueue {
+  int policy = TN_POLICY_FIFO;
+  const int64_t* key = nullptr;  // TN_POLICY_BY_ORDER: position of every vertex in the serial order
+  std::deque<int64_t> q;         // FIFO / LIFO
+  std::vector<int64_t> v;        // RANDOM (unordered) / BY_ORDER (heap)
+  size_t sel = 0;                // RANDOM: index chosen by peek()
+
+  bool heap_less(int64_t a, int64_t b) const { return key[a] > key[b]; }  // min-heap through std::*_heap
+  size_t size() const { return policy == TN_POLICY_FIFO || policy == TN_POLICY_LIFO ? q.size() : v.size(); }
+  bool empty() const { return size() == 0; }
+  void clear() { q.clear(); v.clear(); }
+  void push(int64_t m) {
+    if (policy == TN_POLICY_FIFO || policy == TN_POLICY_LIFO) {
+      q.push_back(m);
+    } else {
+      v.push_back(m);
+      if (policy == TN_POLICY_BY_ORDER)
+        std::push_heap(v.begin(), v.end(), [this](int64_t a, int64_t b) { return heap_less(a, b); });
+    }
+  }
+  // the vertex pop() would remove; rng is advanced by the random policy only
+  int64_t peek(uint64_t& rng) {
+    switch (policy) {
+      case TN_POLICY_FIFO: return q.front();
+      case TN_POLICY_LIFO: return q.back();
+      case TN_POLICY_RANDOM: rng = mix64(rng); sel = (size_t)(rng % v.size()); return v[sel];
+      default: return v.front();
+    }
+  }
+  void pop() {
+    switch (policy) {
+      case TN_POLICY_FIFO: q.pop_front(); break;
+      case TN_POLICY_LIFO: q.pop_back(); break;
+      case TN_POLICY_RANDOM: v[sel] = v.back(); v.pop_back(); break;
+      default:
+        std::pop_heap(v.begin(), v.end(), [this](int64_t a, int64_t b) { return heap_less(a, b); });
+        v.pop_back();
+    }
+  }
+};
+
+
 }  // namespace
 }  // namespace tn
 
@@ -94,6 +139,11 @@ struct tn_executor {
   std::vector<VInfo> info;
   // dependency structure (CSR of successors)
   std::vector<int64_t> succ_start, succ, indeg;
+  // kernel vertices, host-to-device transfers and device-to-host transfers, each in the serial
+  // order the memgraph was compiled for (TN_POLICY_IN_ORDER dispatches along these)
+  std::vector<int64_t> serial[3];
+  std::vector<int64_t> order_key;  // position of every vertex in that order
+  std::vector<VInfo> groups;       // one representative per launch group (cls, dtype, head_dim)
   // per run
   std::vector<int64_t> remaining, last_order, arena_off;
   std::map<uint64_t, ArenaBlock> arena_map;
@@ -397,6 +447,30 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
   ex->arena_off.assign(nv, -1);
   tn_status s = build_tables(*ex);
   if (s != TN_OK) return bail(s);
+  {
+    ex->order_key.resize(nv);
+    std::vector<int64_t> by_pos(nv);
+    for (int64_t m = 0; m < nv; ++m) {
+      ex->order_key[m] = mg->v[m].order_pos;
+      by_pos[m] = m;
+    }
+    std::stable_sort(by_pos.begin(), by_pos.end(), [&](int64_t a, int64_t b) { return ex->order_key[a] < ex->order_key[b]; });
+    for (int64_t m : by_pos) {
+      const int32_t k = mg->v[m].kind;
+      if (k == TN_MG_OP) ex->serial[0].push_back(m);
+      else if (k == TN_MG_LOAD || k == TN_MG_RELOAD) ex->serial[1].push_back(m);
+      else if (k == TN_MG_OFFLOAD || k == TN_MG_STORE) ex->serial[2].push_back(m);
+    }
+    for (int64_t m = 0; m < nv; ++m) {
+      VInfo& vi = ex->info[m];
+      if (vi.cls < 0) continue;
+      size_t g = 0;
+      while (g < ex->groups.size() && !(ex->groups[g].cls == vi.cls && ex->groups[g].dtype == vi.dtype &&
+                                        ex->groups[g].head_dim == vi.head_dim)) ++g;
+      if (g == ex->groups.size()) ex->groups.push_back(vi);
+      vi.group = (int16_t)g;
+    }
+  }
   *out = ex;
   return TN_OK;
 }
@@ -484,7 +558,34 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     sl.verts.clear();
   }
   tn_exec_report rep{};
-  std::vector<int64_t> ready_k, ready_h2d, ready_d2h, work, cand;
+  if (opt.policy < TN_POLICY_FIFO || opt.policy > TN_POLICY_IN_ORDER) return fail(TN_ERR_INVALID, "unknown policy %d", opt.policy);
+  const bool in_order = opt.policy == TN_POLICY_IN_ORDER;
+  // ready vertices: one queue per launch group of kernels, one per transfer direction.  The
+  // in-order policy walks the serial lists instead and only needs to know who is ready.
+  const size_t n_groups = ex->groups.size();
+  std::vector<ReadyQueue> rq(n_groups + 2);
+  for (auto& q : rq) {
+    q.policy = in_order ? TN_POLICY_FIFO : opt.policy;
+    q.key = ex->order_key.data();
+  }
+  ReadyQueue* const rq_x = rq.data() + n_groups;  // [0] host to device, [1] device to host
+  std::vector<char> is_ready(in_order ? nv : 0, 0);
+  std::vector<uint64_t> arrival(opt.policy <= TN_POLICY_LIFO ? nv : 0, 0);  // when a vertex became ready
+  uint64_t n_arrived = 0;
+  int64_t n_ready_k = 0, n_ready_x[2] = {0, 0};
+  size_t serial_next[3] = {0, 0, 0};
+  std::vector<int64_t> work;
+  auto make_ready = [&](int64_t w) {
+    const int32_t k = mg.v[w].kind;
+    const int which = k == TN_MG_OP ? -1 : (k == TN_MG_LOAD || k == TN_MG_RELOAD) ? 0 : 1;
+    if (which < 0) ++n_ready_k; else ++n_ready_x[which];
+    if (in_order) {
+      is_ready[w] = 1;
+      return;
+    }
+    if (!arrival.empty()) arrival[w] = n_arrived++;
+    (which < 0 ? rq[ex->info[w].group] : rq_x[which]).push(w);
+  };
   int64_t completed = 0;
   uint64_t rng = mix64(opt.order_seed ^ 0x7475726E6970ull);
   uint64_t arena_used = 0;
@@ -518,48 +619,31 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         const int32_t k = mg.v[w].kind;
         if (k == TN_MG_OP) {
           if (ahead) {
-            if (!was_enqueued_kernel && --rem_enq[w] == 0) ready_k.push_back(w);
+            if (!was_enqueued_kernel && --rem_enq[w] == 0) make_ready(w);
           } else if (all_done) {
-            ready_k.push_back(w);
+            make_ready(w);
           }
           continue;
         }
         if (!all_done) continue;
-        switch (k) {
-          case TN_MG_INPUT:
-          case TN_MG_DROP: ex->last_order.push_back(w); work.push_back(w); break;
-          case TN_MG_LOAD:
-          case TN_MG_RELOAD: ready_h2d.push_back(w); break;
-          default: ready_d2h.push_back(w); break;
+        if (k == TN_MG_INPUT || k == TN_MG_DROP) {
+          ex->last_order.push_back(w);
+          work.push_back(w);
+        } else {
+          make_ready(w);
         }
       }
     }
   };
   for (int64_t m = 0; m < nv; ++m) {
     if (ex->indeg[m] != 0) continue;
-    switch (mg.v[m].kind) {
-      case TN_MG_INPUT:
-      case TN_MG_DROP: ex->last_order.push_back(m); complete(m); break;
-      case TN_MG_OP: ready_k.push_back(m); break;
-      case TN_MG_LOAD:
-      case TN_MG_RELOAD: ready_h2d.push_back(m); break;
-      default: ready_d2h.push_back(m); break;
+    if (mg.v[m].kind == TN_MG_INPUT || mg.v[m].kind == TN_MG_DROP) {
+      ex->last_order.push_back(m);
+      complete(m);
+    } else {
+      make_ready(m);
     }
   }
-
-  auto pick = [&](const std::vector<int64_t>& r) -> size_t {
-    switch (opt.policy) {
-      case TN_POLICY_LIFO: return r.size() - 1;
-      case TN_POLICY_RANDOM: rng = mix64(rng); return (size_t)(rng % r.size());
-      case TN_POLICY_BY_ORDER: {
-        size_t best = 0;
-        for (size_t i = 1; i < r.size(); ++i)
-          if (mg.v[r[i]].order_pos < mg.v[r[best]].order_pos) best = i;
-        return best;
-      }
-      default: return 0;
-    }
-  };
 
   auto hip_fail = [&](const char* what, hipError_t e) {
     ex->poisoned = true;
@@ -582,16 +666,22 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     // ---- launch transfers: per direction one group of copies at a time
     for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
       Slot& sl = ex->slots[ex->n_compute + dir];
-      auto& r = dir == 0 ? ready_h2d : ready_d2h;
-      if (sl.busy || r.empty()) continue;
+      ReadyQueue& r = rq_x[dir];
+      const std::vector<int64_t>& serial = ex->serial[1 + dir];
+      if (sl.busy || n_ready_x[dir] == 0) continue;
       sl.verts.clear();
       sl.bytes = 0;
       copies.n = 0;
       copies.total_blocks = 0;
       hipError_t e = hipSuccess;
-      while (!r.empty() && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
-        const size_t i = pick(r);
-        const int64_t m = r[i];
+      while (n_ready_x[dir] > 0 && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
+        int64_t m;
+        if (in_order) {  // the next transfer of this direction in the serial order, or none
+          m = serial[serial_next[1 + dir]];
+          if (!is_ready[m]) break;
+        } else {
+          m = r.peek(rng);
+        }
         const MVertex& x = mg.v[m];
         const void* src;
         void* dst;
@@ -608,7 +698,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           uint64_t off;
           if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
             if (!sl.verts.empty()) break;  // let the copies already queued (and later reloads) free slots
-            if (ex->slots[ex->n_compute].busy || !ready_h2d.empty()) break;
+            if (ex->slots[ex->n_compute].busy || n_ready_x[0] > 0) break;
             status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
                           (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
             break;
@@ -627,7 +717,13 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           e = hipMemcpyAsync(dst, src, x.bytes, dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
           if (e != hipSuccess) break;
         }
-        r.erase(r.begin() + i);
+        if (in_order) {
+          is_ready[m] = 0;
+          ++serial_next[1 + dir];
+        } else {
+          r.pop();
+        }
+        --n_ready_x[dir];
         sl.verts.push_back(m);
         sl.bytes += (double)x.bytes;
         (dir == 0 ? rep.h2d_bytes : rep.d2h_bytes) += x.bytes;
@@ -661,59 +757,84 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       progressed = true;
     }
     // ---- launch kernels: one group per compute stream with room in its queue ---------------
-    while (status == TN_OK && !ready_k.empty()) {
+    while (status == TN_OK && n_ready_k > 0) {
       int si = -1;
       for (int k = 0; k < ex->n_compute; ++k)
         if ((int)ex->cqueue[k].size() < depth && (si < 0 || ex->cqueue[k].size() < ex->cqueue[si].size())) si = k;
       if (si < 0) break;
       hipStream_t stream = ex->slots[si].stream;
-      size_t i0;
-      if (opt.max_gemm_inflight > 0) {
-        // GEMM groups that overlap only share the compute units; holding the next one back until
-        // a running one ends lets it gather more ready tiles and fill the chip on its own
+      // GEMM groups that overlap only share the compute units; holding the next one back until a
+      // running one ends lets it gather more ready tiles and fill the chip on its own
+      bool gemm_ok = true;
+      if (opt.max_gemm_inflight > 0 && !in_order) {
         int inflight = 0;
         for (auto& q : ex->cqueue)
           for (auto& g : q) inflight += g.family == 0;
-        if (inflight >= opt.max_gemm_inflight) {
-          cand.clear();
-          for (size_t i = 0; i < ready_k.size(); ++i)
-            if (family_of(ex->info[ready_k[i]].cls) != 0) cand.push_back(ready_k[i]);
-          if (cand.empty()) break;
-          const int64_t chosen = cand[pick(cand)];
-          i0 = std::find(ready_k.begin(), ready_k.end(), chosen) - ready_k.begin();
-        } else {
-          i0 = pick(ready_k);
-        }
-      } else {
-        i0 = pick(ready_k);
+        gemm_ok = inflight < opt.max_gemm_inflight;
       }
-      const VInfo lead = ex->info[ready_k[i0]];
       same.clear();
-      same.push_back(ready_k[i0]);
-      // the rest of the group: ready vertices of the same family, in the policy's order
-      if (max_batch > 1) {
-        std::vector<size_t> idx;
-        for (size_t i = 0; i < ready_k.size(); ++i) {
-          const VInfo& v = ex->info[ready_k[i]];
-          if (i != i0 && v.cls == lead.cls && v.dtype == lead.dtype && v.head_dim == lead.head_dim) idx.push_back(i);
-        }
-        if (opt.policy == TN_POLICY_LIFO) std::reverse(idx.begin(), idx.end());
-        else if (opt.policy == TN_POLICY_RANDOM)
-          for (size_t k = idx.size(); k > 1; --k) { rng = mix64(rng); std::swap(idx[k - 1], idx[rng % k]); }
-        else if (opt.policy == TN_POLICY_BY_ORDER)
-          std::sort(idx.begin(), idx.end(), [&](size_t a, size_t b) { return mg.v[ready_k[a]].order_pos < mg.v[ready_k[b]].order_pos; });
-        // the launch names its vertices by 16-bit offsets from the smallest descriptor index
-        uint32_t lo = (uint32_t)lead.desc, hi = (uint32_t)lead.desc;
-        for (size_t k = 0; k < idx.size() && (int)same.size() < max_batch; ++k) {
-          const uint32_t d = (uint32_t)ex->info[ready_k[idx[k]]].desc;
-          if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) continue;
+      int gi = -1;  // launch group of the lead vertex
+      if (in_order) {
+        // the next kernel of the serial order leads; the kernels right behind it join while they
+        // are ready and of its launch group
+        const std::vector<int64_t>& serial = ex->serial[0];
+        size_t at = serial_next[0];
+        if (!is_ready[serial[at]]) break;
+        gi = ex->info[serial[at]].group;
+        uint32_t lo = (uint32_t)ex->info[serial[at]].desc, hi = lo;
+        while (at < serial.size() && (int)same.size() < max_batch && is_ready[serial[at]] &&
+               ex->info[serial[at]].group == gi) {
+          const uint32_t d = (uint32_t)ex->info[serial[at]].desc;
+          if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) break;
           lo = std::min(lo, d);
           hi = std::max(hi, d);
-          same.push_back(ready_k[idx[k]]);
+          is_ready[serial[at]] = 0;
+          same.push_back(serial[at++]);
+        }
+        serial_next[0] = at;
+      } else {
+        // lead: what the policy would take first among all ready kernels
+        uint64_t total = 0;
+        for (size_t g = 0; g < n_groups; ++g) {
+          if (rq[g].empty() || (!gemm_ok && family_of(ex->groups[g].cls) == 0)) continue;
+          total += rq[g].size();
+          if (gi < 0) { gi = (int)g; continue; }
+          switch (opt.policy) {
+            case TN_POLICY_FIFO: if (arrival[rq[g].q.front()] < arrival[rq[gi].q.front()]) gi = (int)g; break;
+            case TN_POLICY_LIFO: if (arrival[rq[g].q.back()] > arrival[rq[gi].q.back()]) gi = (int)g; break;
+            case TN_POLICY_BY_ORDER: if (ex->order_key[rq[g].v.front()] < ex->order_key[rq[gi].v.front()]) gi = (int)g; break;
+            default: break;
+          }
+        }
+        if (gi < 0) break;  // only GEMMs are ready and enough of them are running
+        if (opt.policy == TN_POLICY_RANDOM) {  // a ready kernel drawn uniformly decides the group
+          rng = mix64(rng);
+          uint64_t pick = rng % total;
+          for (size_t g = 0; g < n_groups; ++g) {
+            if (rq[g].empty() || (!gemm_ok && family_of(ex->groups[g].cls) == 0)) continue;
+            if (pick < rq[g].size()) { gi = (int)g; break; }
+            pick -= rq[g].size();
+          }
+        }
+        // the group: ready vertices of the lead's launch group, in the policy's order; a launch
+        // names its vertices by 16-bit offsets from the smallest descriptor index
+        ReadyQueue& q = rq[gi];
+        uint32_t lo = 0, hi = 0;
+        while (!q.empty() && (int)same.size() < max_batch) {
+          const int64_t m = q.peek(rng);
+          const uint32_t d = (uint32_t)ex->info[m].desc;
+          if (same.empty()) lo = hi = d;
+          if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) break;
+          lo = std::min(lo, d);
+          hi = std::max(hi, d);
+          q.pop();
+          same.push_back(m);
         }
       }
+      n_ready_k -= (int64_t)same.size();
+      const VInfo lead = ex->groups[gi];
       batch.n = (int32_t)same.size();
-      batch.base = (uint32_t)lead.desc;
+      batch.base = (uint32_t)ex->info[same[0]].desc;
       for (int64_t m : same) batch.base = std::min(batch.base, (uint32_t)ex->info[m].desc);
       int32_t max_blocks = 0;
       double flops = 0, bytes = 0;
@@ -752,14 +873,6 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       if (e == hipSuccess && grp.prof >= 0) e = hipEventRecord(ex->prof_events[grp.prof + 1], stream);
       if (e == hipSuccess) e = hipEventRecord(grp.done, stream);
       if (e != hipSuccess) { hip_fail("kernel launch", e); break; }
-      // remove the group from the ready list
-      {
-        std::sort(same.begin(), same.end());
-        size_t w = 0;
-        for (size_t i = 0; i < ready_k.size(); ++i)
-          if (!std::binary_search(same.begin(), same.end(), ready_k[i])) ready_k[w++] = ready_k[i];
-        ready_k.resize(w);
-      }
       for (int64_t m : same) {
         ex->last_order.push_back(m);
         state[m] = 1;
@@ -770,7 +883,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         for (int64_t m : same)
           for (int64_t i = ex->succ_start[m]; i < ex->succ_start[m + 1]; ++i) {
             const int64_t w = ex->succ[i];
-            if (mg.v[w].kind == TN_MG_OP && --rem_enq[w] == 0) ready_k.push_back(w);
+            if (mg.v[w].kind == TN_MG_OP && --rem_enq[w] == 0) make_ready(w);
           }
       ++rep.n_launches;
       ++rep.n_kernel_launches;
@@ -829,7 +942,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       bool any_busy = false;
       for (auto& sl : ex->slots) any_busy |= sl.busy;
       for (auto& q : ex->cqueue) any_busy |= !q.empty();
-      if (!any_busy && ready_k.empty() && ready_h2d.empty() && ready_d2h.empty() && completed < nv) {
+      if (!any_busy && n_ready_k == 0 && n_ready_x[0] == 0 && n_ready_x[1] == 0 && completed < nv) {
         status = fail(TN_ERR_CYCLE, "no vertex is ready and none is running: %lld of %lld completed",
                       (long long)completed, (long long)nv);
         break;

@@ -73,9 +73,10 @@ def test_twenty_dispatch_orders_and_transfer_delays_give_identical_bits(name):
             np.testing.assert_array_equal(out["y"], ref["y"])
             orders.add(tuple(s.last_order()))
         assert len(orders) >= 15, "the seeds must really perturb the dispatch order"
-        for policy in (B.TN_POLICY_FIFO, B.TN_POLICY_LIFO):
-            out, _ = s.run(B.tn_exec_opts(policy=policy))
-            np.testing.assert_array_equal(out["y"], ref["y"])
+        for policy in (B.TN_POLICY_FIFO, B.TN_POLICY_LIFO, B.TN_POLICY_IN_ORDER):
+            for depth in (1, 3):
+                out, _ = s.run(B.tn_exec_opts(policy=policy, queue_depth=depth, max_delay_us=50, delay_seed=policy))
+                np.testing.assert_array_equal(out["y"], ref["y"])
     finally:
         s.close()
 
@@ -93,6 +94,15 @@ def test_launch_order_respects_every_dependency():
         e = H.export_memgraph(s.mg)
         assert sorted(order) == list(range(len(e["kind"])))
         # the launch order is a valid order for the library's own dry run, too
+        B.tn_memgraph_simulate(s.mg, order)
+        # the in-order policy launches kernels, and the transfers of each direction, exactly in
+        # the serial order the memgraph was compiled for
+        s.run(B.tn_exec_opts(policy=B.TN_POLICY_IN_ORDER, max_batch=7, queue_depth=2, max_delay_us=100, delay_seed=3))
+        order = s.last_order()
+        pos = {v: i for i, v in enumerate(e["order"])}
+        for kinds in (("op",), ("load", "reload"), ("offload", "store")):
+            launched = [v for v in order if e["kind"][v] in kinds]
+            assert launched == sorted(launched, key=pos.get), kinds
         B.tn_memgraph_simulate(s.mg, order)
     finally:
         s.close()
