@@ -64,7 +64,11 @@ def main():
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order", "in_order"])
     ap.add_argument("--max-delay-us", type=int, default=0, help="inject a pseudo-random delay of up to this many microseconds into every transfer group")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample; 0 = skip")
-    ap.add_argument("--no-capped", action="store_true", help="skip the extra run at 40 %% of the uncapped peak")
+    ap.add_argument("--capped", action="store_true",
+                    help="add a run with everything streamed from the host under 40 %% of the uncapped peak (offload path)")
+    ap.add_argument("--no-capped", action="store_true", help=argparse.SUPPRESS)  # the default now
+    ap.add_argument("--order", default="tiler", choices=["tiler", "level"],
+                    help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
     ap.add_argument("--distinct-layers", type=int, default=-1,
@@ -105,7 +109,15 @@ def main():
         return reps
 
     t0 = time.perf_counter()
-    s = H.GpuSession(cfg, full, n_compute=args.streams, kv_outputs=kv_outputs)
+    def session(c):
+        order = None
+        if args.order == "level":
+            tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs))
+            order = H.level_major_order(tg)
+            B.tn_taskgraph_destroy(tg)
+        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order)
+
+    s = session(cfg)
     t_compile = time.perf_counter() - t0
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
@@ -153,7 +165,7 @@ def main():
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
@@ -183,9 +195,9 @@ def main():
 
     # the same shape with everything streamed from the host and the cap at 40 % of the uncapped
     # peak, so that the offload/reload path carries real traffic
-    if not args.no_capped and cfg.cap_bytes:
+    if args.capped and cfg.cap_bytes:
         cfg2 = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
-        s2 = H.GpuSession(cfg2, full, n_compute=args.streams)
+        s2 = session(cfg2)
         r2 = timed(s2, max(3, args.steps // 4), 1, opts)
         ms2 = 1e3 * sum(dt for dt, _ in r2) / len(r2)
         rr = r2[-1][1]
