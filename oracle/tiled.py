@@ -345,17 +345,25 @@ def cut_inputs(tg: TaskGraph, full_f64: Dict[str, np.ndarray]) -> Dict[int, np.n
 class LazyInputs:
     """Mapping vid -> float64 tile that slices and widens the full storage-type tensors on demand
     (for inputs too large to hold widened all at once).  `widen` turns a storage-type array into
-    float64 exactly."""
+    float64 exactly.  Tiles cut from the same region of the same array (layers that share their
+    weights) are kept and reused while they fit `cache_bytes`."""
 
-    def __init__(self, tg: TaskGraph, full_storage: Dict[str, np.ndarray], widen):
+    def __init__(self, tg: TaskGraph, full_storage: Dict[str, np.ndarray], widen, cache_bytes: int = 0):
         self.tg, self.full, self.widen = tg, full_storage, widen
+        self.cache, self.room = {}, cache_bytes
 
     def __getitem__(self, v: int) -> np.ndarray:
         bnd = self.tg.binding[v]
         name, r0, r1, c0, c1 = bnd[:5]
         a = self.full[name]
-        a = a.reshape(1, -1) if a.ndim == 1 else a
-        t = self.widen(np.ascontiguousarray(a[r0:r1, c0:c1]))
+        key = (id(a), r0, r1, c0, c1)
+        t = self.cache.get(key)
+        if t is None:
+            a = a.reshape(1, -1) if a.ndim == 1 else a
+            t = self.widen(np.ascontiguousarray(a[r0:r1, c0:c1]))
+            if t.nbytes <= self.room:
+                self.room -= t.nbytes
+                self.cache[key] = t
         return t.T if len(bnd) > 5 and bnd[5] else t
 
 
