@@ -12,5 +12,6 @@ from .synth import (  # noqa: F401
     to_bf16_bits,
     bf16_bits_to_f32,
     make_llama_inputs,
+    make_lora_inputs,
     random_dag,
 )

@@ -114,7 +114,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 # LLaMA-shaped inputs
 # --------------------------------------------------------------------------------------
 
-_KIND_ID = {"x": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "w1": 6, "w3": 7, "w2": 8, "g1": 9, "g2": 10}
+_KIND_ID = {"x": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "w1": 6, "w3": 7, "w2": 8, "g1": 9, "g2": 10,
+            "aq": 11, "bq": 12, "av": 13, "bv": 14, "probe": 15}
 
 
 def _tensor(seed, cfg, kind, layer, shape, mean, std, chunk=1 << 22):
@@ -168,6 +169,23 @@ def make_llama_inputs(cfg: LlamaConfig, seed: int, distinct_layers: int = 0, wor
     for l in range(k, cfg.layers):
         for kind in ("wq", "wk", "wv", "wo", "w1", "w3", "w2", "g1", "g2"):
             t[f"{kind}.{l}"] = t[f"{kind}.{l % k}"]
+    return t
+
+
+def make_lora_inputs(cfg: LlamaConfig, seed: int, rank: int = 16, b_std: float = 0.0) -> Dict[str, np.ndarray]:
+    """Adapter matrices and the probe of the fine-tuning workload, in storage dtype.
+
+    Keys per layer l: "aq.l", "av.l" [d, rank] ~ N(0, 0.02); "bq.l", "bv.l" [rank, d], zero as at
+    the start of fine-tuning unless b_std > 0 (then N(0, b_std): a later step, where the gradient
+    of A does not vanish); "probe" [tokens, d] ~ N(0, 1), the fixed tensor the loss sums y against.
+    """
+    d = cfg.d_model
+    t: Dict[str, np.ndarray] = {"probe": _tensor(seed, cfg, "probe", -1, (cfg.tokens, d), 0.0, 1.0)}
+    for l in range(cfg.layers):
+        for kind in ("aq", "av"):
+            t[f"{kind}.{l}"] = _tensor(seed, cfg, kind, l, (d, rank), 0.0, 0.02)
+        for kind in ("bq", "bv"):
+            t[f"{kind}.{l}"] = _tensor(seed, cfg, kind, l, (rank, d), 0.0, b_std)
     return t
 
 
