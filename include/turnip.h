@@ -67,7 +67,12 @@ enum {
   TN_OP_ATTN_BLOCK = 5,   /* Q tiles, K tiles, V tiles -> fp32 partial [rows, gw + 2*hpg]          */
   TN_OP_ATTN_COMBINE = 6, /* partial_0..partial_j -> normalised attention output tile              */
   TN_OP_SILU_MUL = 7,     /* gate, up -> gate / (1 + exp(-gate)) * up                              */
-  TN_OP_ADD = 8           /* a, b -> a + b                                                          */
+  TN_OP_ADD = 8,          /* a, b -> a + b                                                          */
+  /* reverse-mode counterparts, for the fine-tuning workload (Section 8, item 2) */
+  TN_OP_SILU_MUL_BWD = 9,   /* dact, gate, up -> gradient of gate (mode 0) or of up (mode 1)         */
+  TN_OP_RMS_BWD_STAT = 10,  /* dy tiles, x tiles, gain tiles of a row block -> fp32 [rows,1]: sum dy*gain*x */
+  TN_OP_RMS_BWD_APPLY = 11, /* dy, x, stat, dot, gain[, residual gradient] -> gradient of x            */
+  TN_OP_ATTN_BWD = 12       /* Q, K, V, dO tiles[, statistics] -> statistics, dQ, dK or dV (mode)      */
 };
 
 typedef struct {
@@ -98,7 +103,24 @@ typedef struct {
  *                                       [columns of the tile, key rows of the tile]
  *   ATTN_COMBINE row0, col0, head_dim, hpg
  *                                       output tile = rows [row0, row0 + rows) and columns
- *                                       [col0, col0 + cols) of the merged, normalised block. */
+ *                                       [col0, col0 + cols) of the merged, normalised block.
+ *   GEMM         trans_a                != 0: A_k is stored transposed, [K_k, rows]
+ *   ROPE         mode                   != 0: the inverse rotation (which is also the rotation's gradient)
+ *   SILU_MUL_BWD mode                   with s = 1/(1 + exp(-gate)): mode 0 -> dact * up * s * (1 + gate * (1 - s)),
+ *                                       mode 1 -> dact * gate * s
+ *   RMS_BWD_STAT nk                     operands: nk tiles of dy, then the nk tiles of x, then the nk gain tiles
+ *   RMS_BWD_APPLY d                     stat = the forward RMS_STAT of x, dot = RMS_BWD_STAT; result
+ *                                       stat * gain * dy - x * stat^3 * dot / d, plus the sixth operand if given
+ *   ATTN_BWD     mode, n_q_tiles, n_kv_tiles, n_col_tiles, head_dim, q_pos0, k_pos0, causal, scale, v_trans
+ *                                       operands: Q, K, V tiles as for ATTN_BLOCK, then the dO tiles (like Q), then,
+ *                                       except in mode 0, one statistics tensor per Q row tile.  With
+ *                                       p = exp(scale q.k - lse), dp = dO.v:
+ *                                       mode 0 -> fp32 [q rows, 2*hpg]: per head lse = log sum_k exp(scale q.k)
+ *                                                 over the visible keys, then D = sum_k p dp;
+ *                                       mode 1 -> dQ [q rows, gw] = scale * sum_k p (dp - D) k;
+ *                                       mode 2 -> dK [kv rows, gw] = scale * sum_q p (dp - D) q;
+ *                                       mode 3 -> dV [kv rows, gw] = sum_q p dO.
+ *                                       Sums run over keys (queries) in ascending order. */
 typedef struct {
   int32_t nk;
   int32_t d;
@@ -119,6 +141,8 @@ typedef struct {
   int32_t trans_b;
   int32_t trans_c;
   int32_t v_trans;
+  int32_t trans_a;
+  int32_t mode;
 } tn_op_params;
 
 /* ------------------------------------------------------------------------------------------ */

@@ -18,7 +18,8 @@ TN_ERR_CAP_TOO_SMALL, TN_ERR_ARENA, TN_ERR_HIP, TN_ERR_SHAPE = -4, -5, -6, -7
 TN_F32, TN_BF16 = 0, 1
 TN_HOST, TN_DEVICE = 0, 1
 (TN_OP_INPUT, TN_OP_GEMM, TN_OP_RMS_STAT, TN_OP_RMS_APPLY, TN_OP_ROPE, TN_OP_ATTN_BLOCK,
- TN_OP_ATTN_COMBINE, TN_OP_SILU_MUL, TN_OP_ADD) = range(9)
+ TN_OP_ATTN_COMBINE, TN_OP_SILU_MUL, TN_OP_ADD, TN_OP_SILU_MUL_BWD, TN_OP_RMS_BWD_STAT, TN_OP_RMS_BWD_APPLY,
+ TN_OP_ATTN_BWD) = range(13)
 (TN_T_X, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2,
  TN_T_Y, TN_T_K, TN_T_V) = range(13)
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE) = range(7)
@@ -45,7 +46,7 @@ class tn_op_params(C.Structure):
                 ("n_q_tiles", C.c_int32), ("n_kv_tiles", C.c_int32), ("n_col_tiles", C.c_int32),
                 ("q_pos0", C.c_int32), ("k_pos0", C.c_int32), ("causal", C.c_int32),
                 ("scale", C.c_float), ("row0", C.c_int32), ("hpg", C.c_int32), ("trans_b", C.c_int32),
-                ("trans_c", C.c_int32), ("v_trans", C.c_int32)]
+                ("trans_c", C.c_int32), ("v_trans", C.c_int32), ("trans_a", C.c_int32), ("mode", C.c_int32)]
 
 
 class tn_tg_vertex(C.Structure):

@@ -206,13 +206,14 @@ tn_status build_tables(tn_executor& ex) {
     switch (x.op_kind) {
       case TN_OP_GEMM: {
         if (x.p.trans_c) std::swap(d.rows, d.cols);  // the kernels work on the logical [rows, cols] product
-        bool mfma = d.dtype == TN_BF16 && d.trans_b, k32 = true;
+        bool mfma = d.dtype == TN_BF16 && d.trans_b && !x.p.trans_a, k32 = true;
         double K = 0;
         for (int k = 0; k < x.p.nk; ++k) {
-          aux.push_back(odesc(k).cols);
-          K += odesc(k).cols;
-          if (odesc(k).cols % 8) mfma = false;
-          if (odesc(k).cols % 32) k32 = false;
+          const int32_t kk = x.p.trans_a ? odesc(k).rows : odesc(k).cols;
+          aux.push_back(kk);
+          K += kk;
+          if (kk % 8) mfma = false;
+          if (kk % 32) k32 = false;
         }
         vi.cls = !mfma ? LC_GEMM_F32 : (k32 && d.rows >= 256 && d.cols >= 256) ? LC_GEMM_BF16_NT256 : LC_GEMM_BF16_NT;
         vi.flops = 2.0 * d.rows * d.cols * K;
@@ -280,6 +281,42 @@ tn_status build_tables(tn_executor& ex) {
         vi.cls = x.op_kind == TN_OP_ADD ? LC_ADD : LC_SILU_MUL;
         vi.bytes = 3.0 * x.bytes;
         break;
+      case TN_OP_SILU_MUL_BWD:
+        vi.cls = LC_SILU_BWD;
+        vi.bytes = 4.0 * x.bytes;
+        break;
+      case TN_OP_RMS_BWD_STAT:
+        for (int i = 0; i < x.p.nk; ++i) aux.push_back(odesc(i).cols);
+        vi.cls = LC_RMS_BWD_STAT;
+        for (int i = 0; i < x.p.nk; ++i) vi.bytes += 2.0 * d.rows * odesc(i).cols * elem_bytes(d.dtype);
+        break;
+      case TN_OP_RMS_BWD_APPLY:
+        vi.cls = LC_RMS_BWD_APPLY;
+        vi.bytes = (d.n_in == 6 ? 4.0 : 3.0) * x.bytes + d.rows * 8.0;
+        break;
+      case TN_OP_ATTN_BWD: {
+        const int nq = x.p.n_q_tiles, nkv = x.p.n_kv_tiles, nc = x.p.n_col_tiles, hd = x.p.head_dim;
+        const int tq = odesc(0).rows, tk = odesc(nq * nc).rows, tc = odesc(0).cols;
+        int q_rows = 0, kv_rows = 0;
+        for (int r = 0; r < nq; ++r) {
+          q_rows += odesc(r * nc).rows;
+          if ((r + 1 < nq && odesc(r * nc).rows != tq) || odesc(r * nc).rows > tq)
+            return fail(TN_ERR_SHAPE, "attn_bwd %lld: Q row tiles are not uniform", (long long)m);
+        }
+        for (int r = 0; r < nkv; ++r) {
+          kv_rows += odesc(nq * nc + r * nc).rows;
+          if ((r + 1 < nkv && odesc(nq * nc + r * nc).rows != tk) || odesc(nq * nc + r * nc).rows > tk)
+            return fail(TN_ERR_SHAPE, "attn_bwd %lld: K/V row tiles are not uniform", (long long)m);
+        }
+        for (int c = 0; c < nc; ++c)
+          if (odesc(c).cols != tc) return fail(TN_ERR_SHAPE, "attn_bwd %lld: column tiles are not uniform", (long long)m);
+        if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_bwd %lld: head_dim must be 64 or 128", (long long)m);
+        aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
+        vi.cls = LC_ATTN_BWD;
+        vi.head_dim = (int16_t)hd;
+        vi.flops = (x.p.mode == 3 ? 4.0 : 6.0) * q_rows * kv_rows * (double)(nc * tc);
+        break;
+      }
       default: return fail(TN_ERR_INVALID, "vertex %lld has an unknown kind", (long long)m);
     }
     d.nblocks = blocks_for(vi.cls, d, aux.data());
@@ -367,7 +404,8 @@ int family_of(int cls) {
     case LC_GEMM_BF16_NT:
     case LC_GEMM_BF16_NT256: return 0;
     case LC_ATTN_F32:
-    case LC_ATTN_BF16: return 1;
+    case LC_ATTN_BF16:
+    case LC_ATTN_BWD: return 1;
     default: return 2;
   }
 }

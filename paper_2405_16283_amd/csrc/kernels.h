@@ -40,6 +40,10 @@ enum LaunchClass {
   LC_ATTN_COMBINE,
   LC_SILU_MUL,
   LC_ADD,
+  LC_SILU_BWD,
+  LC_RMS_BWD_STAT,
+  LC_RMS_BWD_APPLY,
+  LC_ATTN_BWD,       // attention backward on the vector ALUs (statistics, dQ, dK, dV)
   LC_COUNT
 };
 

@@ -148,6 +148,7 @@ __global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
   ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
   float sn, cs;
   sincosf((float)ang, &sn, &cs);
+  if (d.p.mode) sn = -sn;  // the inverse rotation
   const size_t e = (size_t)row * d.cols + 2 * pc;
   const float xe = ld(x + e), xo = ld(x + e + 1);
   st(o + e, xe * cs - xo * sn);
@@ -178,6 +179,73 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(DeviceTables t, Batch
 }
 
 // ---------------------------------------------------------------------------------------------
+// reverse-mode elementwise and RMSNorm kernels (fine-tuning workload)
+// ---------------------------------------------------------------------------------------------
+// gradient of silu(gate) * up with respect to gate (mode 0) or up (mode 1)
+template <typename T>
+__global__ void __launch_bounds__(256) silu_bwd_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* dact = (const T*)t.ptrs[d.ptr0];
+  const T* gate = (const T*)t.ptrs[d.ptr0 + 1];
+  const T* up = (const T*)t.ptrs[d.ptr0 + 2];
+  T* o = (T*)d.out;
+  const int n = d.rows * d.cols;
+  const int i0 = (blockIdx.x * 256 + threadIdx.x) * 8;
+  for (int i = i0; i < min(i0 + 8, n); ++i) {
+    const float da = ld(dact + i), g = ld(gate + i), u = ld(up + i);
+    const float s = 1.f / (1.f + __expf(-g));
+    st(o + i, d.p.mode == 0 ? da * u * s * (1.f + g * (1.f - s)) : da * g * s);
+  }
+}
+
+// sum over the columns of a row block of dy * gain * x: one wavefront per row
+template <typename T>
+__global__ void __launch_bounds__(256) rms_bwd_stat_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= d.rows) return;
+  const int nk = d.p.nk;
+  float ss = 0.f;
+  for (int j = 0; j < nk; ++j) {
+    const int cols = t.aux[d.aux0 + j];
+    const T* dy = (const T*)t.ptrs[d.ptr0 + j] + (size_t)row * cols;
+    const T* x = (const T*)t.ptrs[d.ptr0 + nk + j] + (size_t)row * cols;
+    const T* g = (const T*)t.ptrs[d.ptr0 + 2 * nk + j];
+    for (int c = lane; c < cols; c += 64) ss += ld(dy + c) * ld(g + c) * ld(x + c);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if (lane == 0) ((float*)d.out)[row] = ss;
+}
+
+// gradient of x through y = x * stat * gain: stat * gain * dy - x * stat^3 * dot / d (+ residual gradient)
+template <typename T>
+__global__ void __launch_bounds__(256) rms_bwd_apply_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* dy = (const T*)t.ptrs[d.ptr0];
+  const T* x = (const T*)t.ptrs[d.ptr0 + 1];
+  const float* stat = (const float*)t.ptrs[d.ptr0 + 2];
+  const float* dot = (const float*)t.ptrs[d.ptr0 + 3];
+  const T* g = (const T*)t.ptrs[d.ptr0 + 4];
+  const T* res = d.n_in == 6 ? (const T*)t.ptrs[d.ptr0 + 5] : nullptr;
+  T* o = (T*)d.out;
+  const int segs = (d.cols + 7) / 8;
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= d.rows * segs) return;
+  const int row = id / segs, c0 = (id % segs) * 8;
+  const float r = stat[row], k = r * r * r * dot[row] / (float)d.p.d;
+  for (int c = c0; c < min(c0 + 8, d.cols); ++c) {
+    const size_t e = (size_t)row * d.cols + c;
+    float v = r * ld(g + c) * ld(dy + e) - ld(x + e) * k;
+    if (res) v += ld(res + e);
+    st(o + e, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // generic GEMM on the vector ALUs (fp32 accumulate): 64x64 output tile per workgroup
 // ---------------------------------------------------------------------------------------------
 template <typename T>
@@ -201,7 +269,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int gr = m0 + r, gk = k0 + kk + i;
-          As[kk + i][r] = (gr < M && gk < K) ? ld(A + (size_t)gr * K + gk) : 0.f;
+          As[kk + i][r] = (gr < M && gk < K) ? ld(d.p.trans_a ? A + (size_t)gk * M + gr : A + (size_t)gr * K + gk) : 0.f;
         }
         if (d.trans_b) {
 #pragma unroll
@@ -639,6 +707,105 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(DeviceTables t, Batch 
 }
 
 // ---------------------------------------------------------------------------------------------
+// attention backward on the vector ALUs.  Modes 0 (statistics) and 1 (dQ): one thread per (query
+// row, head), keys ascending.  Modes 2 (dK) and 3 (dV): one thread per (key row, head), queries
+// ascending.  Scores are recomputed from Q and K; p = exp(scale q.k - lse).
+// aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
+// ---------------------------------------------------------------------------------------------
+template <typename T, int HD>
+__global__ void __launch_bounds__(64) attn_bwd_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int* ax = t.aux + d.aux0;
+  const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
+  const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD, mode = d.p.mode;
+  const int nq = d.p.n_q_tiles, nkv = d.p.n_kv_tiles;
+  void* const* Qt = t.ptrs + d.ptr0;
+  void* const* Kt = Qt + nq * nc;
+  void* const* Vt = Kt + nkv * nc;
+  void* const* Dt = Vt + nkv * nc;   // dO tiles
+  void* const* St = Dt + nq * nc;    // statistics, one tensor per Q row tile (modes 1..3)
+  const int my_rows = mode <= 1 ? q_rows : kv_rows;
+  const int rblocks = (my_rows + 63) / 64;
+  const int h = blockIdx.x / rblocks, row = (blockIdx.x % rblocks) * 64 + threadIdx.x;
+  if (row >= my_rows) return;
+  const float scale = d.p.scale;
+  auto vel = [&](int j, int c) -> float {  // V[j, h*HD + c]
+    return d.p.v_trans ? ld(tile_elem_t<T>(Vt, nc, tk, tc, kv_rows, j, h * HD + c))
+                       : ld(tile_elem<T>(Vt, nc, tk, tc, j, h * HD + c));
+  };
+  auto stat = [&](int r, int which) -> float {  // which 0: lse, 1: D
+    const int rt = r / tq;
+    const float* s = (const float*)St[rt];
+    return s[(size_t)(r - rt * tq) * (2 * hpg) + which * hpg + h];
+  };
+  if (mode <= 1) {
+    const int qpos = d.p.q_pos0 + row;
+    float acc[HD];
+#pragma unroll
+    for (int c = 0; c < HD; ++c) acc[c] = 0.f;
+    float m = -INFINITY, l = 0.f, dsum = 0.f;  // mode 0: running maximum, sum of exp, sum of exp * dp
+    const float lse = mode == 1 ? stat(row, 0) : 0.f, D = mode == 1 ? stat(row, 1) : 0.f;
+    for (int j = 0; j < kv_rows; ++j) {
+      if (d.p.causal && d.p.k_pos0 + j > qpos) break;
+      float s = 0.f, dp = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < HD; ++c) {
+        s = fmaf(ld(tile_elem<T>(Qt, nc, tq, tc, row, h * HD + c)), ld(tile_elem<T>(Kt, nc, tk, tc, j, h * HD + c)), s);
+        dp = fmaf(ld(tile_elem<T>(Dt, nc, tq, tc, row, h * HD + c)), vel(j, c), dp);
+      }
+      s *= scale;
+      if (mode == 0) {
+        const float mn = fmaxf(m, s);
+        const float alpha = __expf(m - mn), p = __expf(s - mn);
+        l = l * alpha + p;
+        dsum = dsum * alpha + p * dp;
+        m = mn;
+      } else {
+        const float ds = __expf(s - lse) * (dp - D) * scale;
+#pragma unroll 8
+        for (int c = 0; c < HD; ++c) acc[c] = fmaf(ds, ld(tile_elem<T>(Kt, nc, tk, tc, j, h * HD + c)), acc[c]);
+      }
+    }
+    if (mode == 0) {
+      float* out = (float*)d.out + (size_t)row * (2 * hpg);
+      out[h] = m + __logf(l);
+      out[hpg + h] = dsum / l;
+    } else {
+      T* out = (T*)d.out + (size_t)row * gw + h * HD;
+#pragma unroll 8
+      for (int c = 0; c < HD; ++c) st(out + c, acc[c]);
+    }
+  } else {
+    const int kpos = d.p.k_pos0 + row;
+    float acc[HD];
+#pragma unroll
+    for (int c = 0; c < HD; ++c) acc[c] = 0.f;
+    for (int r = 0; r < q_rows; ++r) {
+      if (d.p.causal && kpos > d.p.q_pos0 + r) continue;
+      float s = 0.f, dp = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < HD; ++c) {
+        s = fmaf(ld(tile_elem<T>(Qt, nc, tq, tc, r, h * HD + c)), ld(tile_elem<T>(Kt, nc, tk, tc, row, h * HD + c)), s);
+        if (mode == 2) dp = fmaf(ld(tile_elem<T>(Dt, nc, tq, tc, r, h * HD + c)), vel(row, c), dp);
+      }
+      const float p = __expf(s * scale - stat(r, 0));
+      if (mode == 2) {
+        const float ds = p * (dp - stat(r, 1)) * scale;
+#pragma unroll 8
+        for (int c = 0; c < HD; ++c) acc[c] = fmaf(ds, ld(tile_elem<T>(Qt, nc, tq, tc, r, h * HD + c)), acc[c]);
+      } else {
+#pragma unroll 8
+        for (int c = 0; c < HD; ++c) acc[c] = fmaf(p, ld(tile_elem<T>(Dt, nc, tq, tc, r, h * HD + c)), acc[c]);
+      }
+    }
+    T* out = (T*)d.out + (size_t)row * gw + h * HD;
+#pragma unroll 8
+    for (int c = 0; c < HD; ++c) st(out + c, acc[c]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // MFMA attention block (bf16 storage, V given as V^T tiles).  One workgroup = one head x 128 query
 // rows; each of its 4 wavefronts owns 32 query rows; two workgroups share a compute unit.
 //
@@ -900,7 +1067,14 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     }
     case LC_ATTN_COMBINE: return cdiv((int64_t)d.rows * d.cols, 256);
     case LC_SILU_MUL:
-    case LC_ADD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
+    case LC_ADD:
+    case LC_SILU_BWD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
+    case LC_RMS_BWD_STAT: return cdiv(d.rows, 4);
+    case LC_RMS_BWD_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
+    case LC_ATTN_BWD: {
+      const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
+      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], 64);
+    }
     default: return 0;
   }
 }
@@ -943,6 +1117,20 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
     case LC_ADD:
       if (bf) hipLaunchKernelGGL((ewise2_kernel<bf16_t, false>), grid, wg, 0, s, t, b);
       else hipLaunchKernelGGL((ewise2_kernel<float, false>), grid, wg, 0, s, t, b);
+      break;
+    case LC_SILU_BWD: TN_LAUNCH_T(silu_bwd_kernel); break;
+    case LC_RMS_BWD_STAT: TN_LAUNCH_T(rms_bwd_stat_kernel); break;
+    case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;
+    case LC_ATTN_BWD:
+      if (head_dim == 64) {
+        if (bf) hipLaunchKernelGGL((attn_bwd_kernel<bf16_t, 64>), grid, dim3(64), 0, s, t, b);
+        else hipLaunchKernelGGL((attn_bwd_kernel<float, 64>), grid, dim3(64), 0, s, t, b);
+      } else if (head_dim == 128) {
+        if (bf) hipLaunchKernelGGL((attn_bwd_kernel<bf16_t, 128>), grid, dim3(64), 0, s, t, b);
+        else hipLaunchKernelGGL((attn_bwd_kernel<float, 128>), grid, dim3(64), 0, s, t, b);
+      } else {
+        return hipErrorInvalidValue;
+      }
       break;
     case LC_ATTN_F32:
       if (head_dim == 64) {

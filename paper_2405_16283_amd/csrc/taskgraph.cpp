@@ -45,7 +45,9 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
       tn_tensor_desc lo = out;  // logical [rows, cols] of the product
       if (p.trans_c) std::swap(lo.rows, lo.cols);
       for (int k = 0; k < p.nk; ++k) {
-        const auto &a = D(k), &b = D(p.nk + k);
+        tn_tensor_desc a = D(k);
+        const auto& b = D(p.nk + k);
+        if (p.trans_a) std::swap(a.rows, a.cols);
         const int32_t bk = p.trans_b ? b.cols : b.rows, bn = p.trans_b ? b.rows : b.cols;
         if (a.rows != lo.rows || bn != lo.cols || a.cols != bk || a.dtype != out.dtype ||
             b.dtype != out.dtype)
@@ -125,6 +127,66 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
       if (n_in != 2 || !same(D(0), out) || !same(D(1), out))
         return fail(TN_ERR_SHAPE, "elementwise: two operands of the output's shape and type");
       return TN_OK;
+    case TN_OP_SILU_MUL_BWD:
+      if (n_in != 3 || !same(D(0), out) || !same(D(1), out) || !same(D(2), out) || (p.mode != 0 && p.mode != 1))
+        return fail(TN_ERR_SHAPE, "silu_mul_bwd: dact, gate, up of the output's shape and type; mode 0 or 1");
+      return TN_OK;
+    case TN_OP_RMS_BWD_STAT: {
+      if (p.nk < 1 || n_in != 3 * p.nk || out.dtype != TN_F32 || out.cols != 1)
+        return fail(TN_ERR_SHAPE, "rms_bwd_stat: 3*nk operands, output fp32 [rows,1]");
+      for (int i = 0; i < p.nk; ++i) {
+        const auto &dy = D(i), &x = D(p.nk + i), &g = D(2 * p.nk + i);
+        if (dy.rows != out.rows || !same(dy, x) || g.rows != 1 || g.cols != dy.cols || g.dtype != dy.dtype ||
+            dy.dtype != D(0).dtype)
+          return fail(TN_ERR_SHAPE, "rms_bwd_stat: column tile %d does not fit", i);
+      }
+      return TN_OK;
+    }
+    case TN_OP_RMS_BWD_APPLY: {
+      if (n_in != 5 && n_in != 6) return fail(TN_ERR_SHAPE, "rms_bwd_apply: dy, x, stat, dot, gain[, residual gradient]");
+      if (!same(D(0), out) || !same(D(1), out) || D(2).dtype != TN_F32 || D(2).rows != out.rows || D(2).cols != 1 ||
+          D(3).dtype != TN_F32 || D(3).rows != out.rows || D(3).cols != 1 || D(4).rows != 1 ||
+          D(4).cols != out.cols || D(4).dtype != out.dtype || (n_in == 6 && !same(D(5), out)) || p.d < out.cols)
+        return fail(TN_ERR_SHAPE, "rms_bwd_apply: operand shapes do not fit");
+      return TN_OK;
+    }
+    case TN_OP_ATTN_BWD: {
+      const int nq = p.n_q_tiles, nkv = p.n_kv_tiles, nc = p.n_col_tiles;
+      if (nq < 1 || nkv < 1 || nc < 1 || p.head_dim < 1 || p.mode < 0 || p.mode > 3 ||
+          n_in != (2 * nq + 2 * nkv) * nc + (p.mode ? nq : 0))
+        return fail(TN_ERR_SHAPE, "attn_bwd: needs (2 n_q_tiles + 2 n_kv_tiles) * n_col_tiles operands, plus n_q_tiles "
+                                  "statistics unless mode is 0");
+      int64_t gw = 0, qrows = 0, kvrows = 0;
+      for (int c = 0; c < nc; ++c) gw += D(c).cols;
+      if (gw % p.head_dim) return fail(TN_ERR_SHAPE, "attn_bwd: columns are not whole heads");
+      const int64_t hpg = gw / p.head_dim;
+      const int32_t dt = D(0).dtype;
+      const int d0 = (nq + 2 * nkv) * nc, s0 = d0 + nq * nc;
+      for (int r = 0; r < nq; ++r) {
+        qrows += D(r * nc).rows;
+        for (int c = 0; c < nc; ++c)
+          if (D(r * nc + c).rows != D(r * nc).rows || D(r * nc + c).cols != D(c).cols || D(r * nc + c).dtype != dt ||
+              !same(D(d0 + r * nc + c), D(r * nc + c)))
+            return fail(TN_ERR_SHAPE, "attn_bwd: Q / dO tile (%d,%d) does not fit the grid", r, c);
+        if (p.mode && (D(s0 + r).dtype != TN_F32 || D(s0 + r).rows != D(r * nc).rows || D(s0 + r).cols != 2 * hpg))
+          return fail(TN_ERR_SHAPE, "attn_bwd: statistics of Q row tile %d must be fp32 [rows, 2*hpg]", r);
+      }
+      for (int r = 0; r < nkv; ++r) {
+        kvrows += D(nq * nc + r * nc).rows;
+        for (int c = 0; c < nc; ++c) {
+          const auto& k = D(nq * nc + r * nc + c);
+          tn_tensor_desc v = D((nq + nkv) * nc + r * nc + c);
+          if (p.v_trans) std::swap(v.rows, v.cols);
+          if (k.cols != D(c).cols || !same(k, v) || k.rows != D(nq * nc + r * nc).rows || k.dtype != dt)
+            return fail(TN_ERR_SHAPE, "attn_bwd: K/V tile (%d,%d) does not fit the grid", r, c);
+        }
+      }
+      const bool ok = p.mode == 0 ? (out.dtype == TN_F32 && out.rows == qrows && out.cols == 2 * hpg)
+                    : p.mode == 1 ? (out.dtype == dt && out.rows == qrows && out.cols == gw)
+                                  : (out.dtype == dt && out.rows == kvrows && out.cols == gw);
+      if (!ok) return fail(TN_ERR_SHAPE, "attn_bwd: output shape does not fit mode %d", p.mode);
+      return TN_OK;
+    }
     default:
       return fail(TN_ERR_INVALID, "unknown vertex kind %d", kind);
   }

@@ -14,7 +14,9 @@ _TENSOR_NAMES = {B.TN_T_X: "x", B.TN_T_WQ: "wq", B.TN_T_WK: "wk", B.TN_T_WV: "wv
                  B.TN_T_Y: "y", B.TN_T_K: "k", B.TN_T_V: "v"}
 OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms_stat",
             B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
-            B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add"}
+            B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
+            B.TN_OP_SILU_MUL_BWD: "silu_mul_bwd", B.TN_OP_RMS_BWD_STAT: "rms_bwd_stat",
+            B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd"}
 MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op", B.TN_MG_OFFLOAD: "offload",
                  B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store"}
 EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}
