@@ -198,12 +198,23 @@ typedef struct {
   int32_t kv_outputs; /* != 0: post-rotary K and V tiles of every layer are marked outputs too */
   int32_t weights_transposed; /* != 0: weight tiles are stored [out, in] and GEMMs use trans_b */
   int32_t v_transposed;       /* != 0: the V projection stores V^T tiles (trans_c) and attention reads them (v_trans) */
+  /* Fine-tuning workload (Section 8, item 2): low-rank adapters on the query and value
+   * projections, q = a Wq + (a Aq) Bq and v = a Wv + (a Av) Bv with Aq, Av [d_model, lora_rank] and
+   * Bq, Bv [lora_rank, d_model]; 0 = no adapters. */
+  int32_t lora_rank;
+  /* != 0 (needs lora_rank > 0 and max(tile, head_dim) == tile): after the forward pass, the reverse pass for
+   * the loss sum(y * probe) through the frozen base weights; outputs, besides y: the gradients of the adapter
+   * matrices of every layer and of x.  The reverse pass reads the base weights as [in, out] tiles (bindings
+   * with transposed == 0), which are input vertices of their own when weights_transposed != 0. */
+  int32_t train;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */
 enum {
   TN_T_X = 0, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2,
-  TN_T_Y, TN_T_K, TN_T_V
+  TN_T_Y, TN_T_K, TN_T_V,
+  TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE,          /* adapter matrices and the probe (inputs)      */
+  TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX            /* their gradients and that of x (outputs)      */
 };
 typedef struct {
   tn_vid vid;

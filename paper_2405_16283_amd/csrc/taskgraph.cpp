@@ -273,24 +273,57 @@ struct Tiler {
     return op(TN_OP_GEMM, p, std::move(in), trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
   }
 
-  std::vector<tn_vid> rmsnorm(const std::vector<tn_vid>& xrow, const std::vector<tn_vid>& gns, int32_t m) {
+  std::vector<tn_vid> rmsnorm(const std::vector<tn_vid>& xrow, const std::vector<tn_vid>& gns, int32_t m,
+                              tn_vid* stat = nullptr) {
     tn_op_params p{};
     p.d = c.d_model;
     p.eps = c.eps;
     tn_vid st = op(TN_OP_RMS_STAT, p, xrow, {TN_F32, m, 1});
+    if (stat) *stat = st;
     std::vector<tn_vid> out;
     for (size_t j = 0; j < xrow.size(); ++j)
       out.push_back(op(TN_OP_RMS_APPLY, tn_op_params{}, {xrow[j], st, gns[j]}, {c.dtype, m, dcols[j].len()}));
     return out;
   }
 
-  tn_vid rope(tn_vid x, int32_t pos0, int32_t col_start, int32_t m, int32_t n) {
+  tn_vid rope(tn_vid x, int32_t pos0, int32_t col_start, int32_t m, int32_t n, bool inverse = false) {
     tn_op_params p{};
     p.pos0 = pos0;
     p.col0 = col_start % c.head_dim;
     p.head_dim = c.head_dim;
     p.rope_base = c.rope_base;
+    p.mode = inverse ? 1 : 0;
     return op(TN_OP_ROPE, p, {x}, {c.dtype, m, n});
+  }
+
+  // weight tiles in [in, out] layout, for the reverse pass: grid[i][j] = rows rr[i], columns cc[j]
+  Grid natural(int32_t tensor, int32_t layer, const std::vector<Range>& rr, const std::vector<Range>& cc) {
+    Grid w(rr.size(), std::vector<tn_vid>(cc.size()));
+    for (size_t i = 0; i < rr.size(); ++i)
+      for (size_t j = 0; j < cc.size(); ++j)
+        w[i][j] = input(rr[i].len(), cc[j].len(), c.weights_residency, tensor, layer, rr[i], cc[j]);
+    return w;
+  }
+
+  // sum_k A_k B_k with explicit operand lists; B_k stored [cols, K_k] if trans_b, A_k stored [K_k, rows] if trans_a
+  tn_vid gemm_list(const std::vector<tn_vid>& a, const std::vector<tn_vid>& b, int32_t m, int32_t n, bool trans_a,
+                   bool trans_b, bool trans_c = false) {
+    tn_op_params p{};
+    p.nk = (int32_t)a.size();
+    p.trans_a = trans_a ? 1 : 0;
+    p.trans_b = trans_b ? 1 : 0;
+    p.trans_c = trans_c ? 1 : 0;
+    std::vector<tn_vid> in(a);
+    in.insert(in.end(), b.begin(), b.end());
+    return op(TN_OP_GEMM, p, std::move(in), trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
+  }
+
+  tn_vid add(tn_vid a, tn_vid b, int32_t m, int32_t n) { return op(TN_OP_ADD, tn_op_params{}, {a, b}, {c.dtype, m, n}); }
+
+  void mark_output(tn_vid id, int32_t tensor, int32_t layer, Range rr, Range cr) {
+    g.v[id].output_index = (int32_t)g.outputs.size();
+    g.outputs.push_back(id);
+    g.bindings.push_back({id, tensor, layer, rr.a, rr.b, cr.a, cr.b, 0});
   }
 };
 
@@ -401,6 +434,9 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   const int32_t gw = std::max(c.tile, c.head_dim);  // columns of a head group
   if (c.d_model % gw) return fail(TN_ERR_SHAPE, "d_model must be a multiple of max(tile, head_dim)");
   if (c.dtype != TN_F32 && c.dtype != TN_BF16) return fail(TN_ERR_INVALID, "bad dtype");
+  if (c.lora_rank < 0 || (c.train && c.lora_rank < 1)) return fail(TN_ERR_INVALID, "train needs lora_rank > 0");
+  if (c.train && gw != c.tile) return fail(TN_ERR_SHAPE, "train needs head_dim <= tile (one column tile per head group)");
+  if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
 
   auto* tg = new (std::nothrow) tn_taskgraph();
   if (!tg) return fail(TN_ERR_INVALID, "out of host memory");
@@ -420,14 +456,43 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
       }
   }
 
+  // what the reverse pass needs of the forward pass, per layer and sequence, indexed by row tile
+  struct Saved {
+    Grid xin, a, q, k, v, h1, gate, up;
+    std::vector<tn_vid> rstd1, rstd2, tq, tv;
+  };
+  std::vector<std::vector<Saved>> saved(c.train ? c.layers : 0, std::vector<Saved>(c.batch));
+  struct LayerInputs {
+    Grid wq, wk, wv, wo, w1, w3, w2;
+    std::vector<tn_vid> g1, g2, aq, bq, av, bv;
+  };
+  std::vector<LayerInputs> lin(c.train ? c.layers : 0);
+  const int32_t rk = c.lora_rank;
+  const Range rkr{0, rk};
+
   for (int l = 0; l < c.layers; ++l) {
     Grid wq = t.weight(TN_T_WQ, l, t.dcols, t.dcols), wk = t.weight(TN_T_WK, l, t.dcols, t.dcols);
     Grid wv = t.weight(TN_T_WV, l, t.dcols, t.dcols), wo = t.weight(TN_T_WO, l, t.dcols, t.dcols);
     Grid w1 = t.weight(TN_T_W1, l, t.dcols, t.fcols), w3 = t.weight(TN_T_W3, l, t.dcols, t.fcols);
     Grid w2 = t.weight(TN_T_W2, l, t.fcols, t.dcols);
     auto g1 = t.gain(TN_T_G1, l), g2 = t.gain(TN_T_G2, l);
+    std::vector<tn_vid> aq, bq, av, bv;  // adapter tiles: A cut along its rows, B along its columns
+    if (rk > 0)
+      for (size_t j = 0; j < nd; ++j) {
+        aq.push_back(t.input(t.dcols[j].len(), rk, c.weights_residency, TN_T_AQ, l, t.dcols[j], rkr));
+        bq.push_back(t.input(rk, t.dcols[j].len(), c.weights_residency, TN_T_BQ, l, rkr, t.dcols[j]));
+        av.push_back(t.input(t.dcols[j].len(), rk, c.weights_residency, TN_T_AV, l, t.dcols[j], rkr));
+        bv.push_back(t.input(rk, t.dcols[j].len(), c.weights_residency, TN_T_BV, l, rkr, t.dcols[j]));
+      }
+    if (c.train) lin[l] = {wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv};
 
     for (int b = 0; b < c.batch; ++b) {
+      if (c.train) {
+        Saved& sv = saved[l][b];
+        sv.xin = x[b];
+        for (Grid* gp : {&sv.a, &sv.q, &sv.k, &sv.v, &sv.h1, &sv.gate, &sv.up}) gp->assign(t.rows.size(), {});
+        for (auto* vp : {&sv.rstd1, &sv.rstd2, &sv.tq, &sv.tv}) vp->assign(t.rows.size(), -1);
+      }
       Grid kk(t.rows.size()), vv(t.rows.size());  // K, V of the stripes done so far
       for (size_t s = 0; s < stripes.size(); ++s) {
         std::vector<size_t> rt;  // row tiles of this stripe
@@ -436,12 +501,29 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         Grid q(t.rows.size());
         for (size_t i : rt) {
           const int32_t m = t.rows[i].len();
-          auto a = t.rmsnorm(x[b][i], g1, m);
+          tn_vid st1 = -1, tq = -1, tv = -1;
+          auto a = t.rmsnorm(x[b][i], g1, m, &st1);
+          if (rk > 0) {  // the low-rank activations a Aq and a Av
+            tq = t.gemm_list(a, aq, m, rk, false, false);
+            tv = t.gemm_list(a, av, m, rk, false, false);
+          }
           for (size_t j = 0; j < nd; ++j) {
             const int32_t n = t.dcols[j].len();
-            q[i].push_back(t.rope(t.gemm(a, wq, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
+            tn_vid qj = t.gemm(a, wq, j, m, n), vj = t.gemm(a, wv, j, m, n, c.v_transposed != 0);
+            if (rk > 0) {
+              qj = t.add(qj, t.gemm_list({tq}, {bq[j]}, m, n, false, false), m, n);
+              const bool vt = c.v_transposed != 0;
+              vj = t.op(TN_OP_ADD, tn_op_params{}, {vj, t.gemm_list({tv}, {bv[j]}, m, n, false, false, vt)},
+                        vt ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
+            }
+            q[i].push_back(t.rope(qj, t.rows[i].a, t.dcols[j].a, m, n));
             kk[i].push_back(t.rope(t.gemm(a, wk, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
-            vv[i].push_back(t.gemm(a, wv, j, m, n, c.v_transposed != 0));
+            vv[i].push_back(vj);
+            if (c.train && j + 1 == nd) {
+              Saved& sv = saved[l][b];
+              sv.a[i] = a; sv.q[i] = q[i]; sv.k[i] = kk[i]; sv.v[i] = vv[i];
+              sv.rstd1[i] = st1; sv.tq[i] = tq; sv.tv[i] = tv;
+            }
             if (c.kv_outputs) {
               Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
               for (int which = 0; which < 2; ++which) {
@@ -497,12 +579,19 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
             const int32_t n = t.dcols[j].len();
             h[j] = t.op(TN_OP_ADD, tn_op_params{}, {x[b][i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
           }
-          auto bn = t.rmsnorm(h, g2, m);
-          std::vector<tn_vid> act(nf);
+          tn_vid st2 = -1;
+          auto bn = t.rmsnorm(h, g2, m, &st2);
+          std::vector<tn_vid> act(nf), gates(nf), ups(nf);
           for (size_t j = 0; j < nf; ++j) {
             const int32_t n = t.fcols[j].len();
             tn_vid gate = t.gemm(bn, w1, j, m, n), up = t.gemm(bn, w3, j, m, n);
+            gates[j] = gate;
+            ups[j] = up;
             act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {gate, up}, {c.dtype, m, n});
+          }
+          if (c.train) {
+            Saved& sv = saved[l][b];
+            sv.h1[i] = h; sv.gate[i] = gates; sv.up[i] = ups; sv.rstd2[i] = st2;
           }
           for (size_t j = 0; j < nd; ++j) {
             const int32_t n = t.dcols[j].len();
@@ -521,6 +610,166 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         tg->bindings.push_back({id, TN_T_Y, -1, b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b,
                                 t.dcols[j].a, t.dcols[j].b, 0});
       }
+  if (c.train) {
+    // ---- reverse pass for L = sum(y * probe): dL/dy is the probe itself ------------------------
+    const size_t nr = t.rows.size();
+    std::vector<Grid> dy(c.batch);
+    for (int b = 0; b < c.batch; ++b) {
+      dy[b].assign(nr, std::vector<tn_vid>(nd));
+      for (size_t i = 0; i < nr; ++i)
+        for (size_t j = 0; j < nd; ++j) {
+          Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
+          dy[b][i][j] = t.input(t.rows[i].len(), t.dcols[j].len(), c.x_residency, TN_T_PROBE, -1, rr, t.dcols[j]);
+        }
+    }
+    for (int l = c.layers - 1; l >= 0; --l) {
+      const LayerInputs& w = lin[l];
+      // base weights as [in, out] tiles: the forward pass's own if it uses that layout
+      const bool own = c.weights_transposed != 0;
+      Grid wqn = own ? t.natural(TN_T_WQ, l, t.dcols, t.dcols) : w.wq, wkn = own ? t.natural(TN_T_WK, l, t.dcols, t.dcols) : w.wk;
+      Grid wvn = own ? t.natural(TN_T_WV, l, t.dcols, t.dcols) : w.wv, won = own ? t.natural(TN_T_WO, l, t.dcols, t.dcols) : w.wo;
+      Grid w1n = own ? t.natural(TN_T_W1, l, t.dcols, t.fcols) : w.w1, w3n = own ? t.natural(TN_T_W3, l, t.dcols, t.fcols) : w.w3;
+      Grid w2n = own ? t.natural(TN_T_W2, l, t.fcols, t.dcols) : w.w2;
+      // operands of the adapter gradients, summed over all rows of all sequences
+      std::vector<tn_vid> all_tq, all_tv, all_dtq, all_dtv;
+      std::vector<std::vector<tn_vid>> a_cols(nd), dq_cols(nd), dv_cols(nd);
+      for (int b = 0; b < c.batch; ++b) {
+        const Saved& sv = saved[l][b];
+        Grid dh1(nr, std::vector<tn_vid>(nd)), dO(nr, std::vector<tn_vid>(nd));
+        for (size_t i = 0; i < nr; ++i) {
+          const int32_t m = t.rows[i].len();
+          // feed-forward block: y = h1 + (silu(gate) * up) W2, gate = bn W1, up = bn W3, bn = RMSNorm(h1; g2)
+          std::vector<tn_vid> dgate(nf), dup(nf);
+          for (size_t f = 0; f < nf; ++f) {
+            const int32_t n = t.fcols[f].len();
+            tn_vid dact = t.gemm_list(dy[b][i], w2n[f], m, n, false, true);
+            tn_op_params p{};
+            dgate[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, sv.gate[i][f], sv.up[i][f]}, {c.dtype, m, n});
+            p.mode = 1;
+            dup[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, sv.gate[i][f], sv.up[i][f]}, {c.dtype, m, n});
+          }
+          std::vector<tn_vid> dbn(nd);
+          for (size_t j = 0; j < nd; ++j) {
+            std::vector<tn_vid> av(dgate), bv(w1n[j]);
+            av.insert(av.end(), dup.begin(), dup.end());
+            bv.insert(bv.end(), w3n[j].begin(), w3n[j].end());
+            dbn[j] = t.gemm_list(av, bv, m, t.dcols[j].len(), false, true);
+          }
+          tn_op_params ps{};
+          ps.nk = (int32_t)nd;
+          std::vector<tn_vid> sin(dbn);
+          sin.insert(sin.end(), sv.h1[i].begin(), sv.h1[i].end());
+          sin.insert(sin.end(), w.g2.begin(), w.g2.end());
+          tn_vid dot2 = t.op(TN_OP_RMS_BWD_STAT, ps, std::move(sin), {TN_F32, m, 1});
+          tn_op_params pa{};
+          pa.d = c.d_model;
+          for (size_t j = 0; j < nd; ++j)
+            dh1[i][j] = t.op(TN_OP_RMS_BWD_APPLY, pa, {dbn[j], sv.h1[i][j], sv.rstd2[i], dot2, w.g2[j], dy[b][i][j]},
+                             {c.dtype, m, t.dcols[j].len()});
+          // output projection: h1 = x + o Wo
+          for (size_t j = 0; j < nd; ++j) dO[i][j] = t.gemm_list(dh1[i], won[j], m, t.dcols[j].len(), false, true);
+        }
+        // attention, one head group (= one column tile) at a time
+        Grid dq(nr, std::vector<tn_vid>(nd)), dk(nr, std::vector<tn_vid>(nd)), dv(nr, std::vector<tn_vid>(nd));
+        for (size_t j = 0; j < nd; ++j) {
+          tn_op_params p{};
+          p.n_col_tiles = 1;
+          p.head_dim = c.head_dim;
+          p.causal = 1;
+          p.scale = 1.0f / std::sqrt((float)c.head_dim);
+          p.v_trans = c.v_transposed ? 1 : 0;
+          const int32_t n = t.dcols[j].len(), hpg_ = n / c.head_dim;
+          std::vector<tn_vid> stats(nr);
+          for (size_t i = 0; i < nr; ++i) {  // query tile i against the key tiles 0..i
+            std::vector<tn_vid> in{sv.q[i][j]};
+            for (size_t r = 0; r <= i; ++r) in.push_back(sv.k[r][j]);
+            for (size_t r = 0; r <= i; ++r) in.push_back(sv.v[r][j]);
+            in.push_back(dO[i][j]);
+            p.n_q_tiles = 1;
+            p.n_kv_tiles = (int32_t)i + 1;
+            p.q_pos0 = t.rows[i].a;
+            p.k_pos0 = 0;
+            p.mode = 0;
+            stats[i] = t.op(TN_OP_ATTN_BWD, p, in, {TN_F32, t.rows[i].len(), 2 * hpg_});
+            in.push_back(stats[i]);
+            p.mode = 1;
+            dq[i][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in), {c.dtype, t.rows[i].len(), n});
+          }
+          for (size_t r = 0; r < nr; ++r) {  // key tile r against the query tiles r..end
+            std::vector<tn_vid> in;
+            for (size_t i = r; i < nr; ++i) in.push_back(sv.q[i][j]);
+            in.push_back(sv.k[r][j]);
+            in.push_back(sv.v[r][j]);
+            for (size_t i = r; i < nr; ++i) in.push_back(dO[i][j]);
+            for (size_t i = r; i < nr; ++i) in.push_back(stats[i]);
+            p.n_q_tiles = (int32_t)(nr - r);
+            p.n_kv_tiles = 1;
+            p.q_pos0 = t.rows[r].a;
+            p.k_pos0 = t.rows[r].a;
+            p.mode = 2;
+            dk[r][j] = t.op(TN_OP_ATTN_BWD, p, in, {c.dtype, t.rows[r].len(), n});
+            p.mode = 3;
+            dv[r][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in), {c.dtype, t.rows[r].len(), n});
+          }
+        }
+        // projections with adapters, first normalisation, residual
+        for (size_t i = 0; i < nr; ++i) {
+          const int32_t m = t.rows[i].len();
+          std::vector<tn_vid> big;  // dq, dk (before the rotation), dv: operands of the gradient of a
+          for (size_t j = 0; j < nd; ++j) {
+            dq[i][j] = t.rope(dq[i][j], t.rows[i].a, t.dcols[j].a, m, t.dcols[j].len(), true);
+            dk[i][j] = t.rope(dk[i][j], t.rows[i].a, t.dcols[j].a, m, t.dcols[j].len(), true);
+          }
+          big = dq[i];
+          big.insert(big.end(), dk[i].begin(), dk[i].end());
+          big.insert(big.end(), dv[i].begin(), dv[i].end());
+          // gradients of the low-rank activations: dq Bq^T and dv Bv^T
+          tn_vid dtq = t.gemm_list(dq[i], w.bq, m, rk, false, true), dtv = t.gemm_list(dv[i], w.bv, m, rk, false, true);
+          std::vector<tn_vid> da(nd);
+          for (size_t j = 0; j < nd; ++j) {
+            std::vector<tn_vid> bw(wqn[j]);
+            bw.insert(bw.end(), wkn[j].begin(), wkn[j].end());
+            bw.insert(bw.end(), wvn[j].begin(), wvn[j].end());
+            const int32_t n = t.dcols[j].len();
+            da[j] = t.add(t.gemm_list(big, bw, m, n, false, true),
+                          t.gemm_list({dtq, dtv}, {w.aq[j], w.av[j]}, m, n, false, true), m, n);
+          }
+          tn_op_params ps{};
+          ps.nk = (int32_t)nd;
+          std::vector<tn_vid> sin(da);
+          sin.insert(sin.end(), sv.xin[i].begin(), sv.xin[i].end());
+          sin.insert(sin.end(), w.g1.begin(), w.g1.end());
+          tn_vid dot1 = t.op(TN_OP_RMS_BWD_STAT, ps, std::move(sin), {TN_F32, m, 1});
+          tn_op_params pa{};
+          pa.d = c.d_model;
+          for (size_t j = 0; j < nd; ++j)
+            dy[b][i][j] = t.op(TN_OP_RMS_BWD_APPLY, pa, {da[j], sv.xin[i][j], sv.rstd1[i], dot1, w.g1[j], dh1[i][j]},
+                               {c.dtype, m, t.dcols[j].len()});
+          all_tq.push_back(sv.tq[i]);
+          all_tv.push_back(sv.tv[i]);
+          all_dtq.push_back(dtq);
+          all_dtv.push_back(dtv);
+          for (size_t j = 0; j < nd; ++j) {
+            a_cols[j].push_back(sv.a[i][j]);
+            dq_cols[j].push_back(dq[i][j]);
+            dv_cols[j].push_back(dv[i][j]);
+          }
+        }
+      }
+      // adapter gradients: dA = a^T dt, dB = t^T dq, summed over every row of every sequence
+      for (size_t j = 0; j < nd; ++j) {
+        const int32_t n = t.dcols[j].len();
+        t.mark_output(t.gemm_list(a_cols[j], all_dtq, n, rk, true, false), TN_T_DAQ, l, t.dcols[j], rkr);
+        t.mark_output(t.gemm_list(all_tq, dq_cols[j], rk, n, true, false), TN_T_DBQ, l, rkr, t.dcols[j]);
+        t.mark_output(t.gemm_list(a_cols[j], all_dtv, n, rk, true, false), TN_T_DAV, l, t.dcols[j], rkr);
+        t.mark_output(t.gemm_list(all_tv, dv_cols[j], rk, n, true, false), TN_T_DBV, l, rkr, t.dcols[j]);
+      }
+    }
+    for (int b = 0; b < c.batch; ++b)
+      for (size_t i = 0; i < nr; ++i)
+        for (size_t j = 0; j < nd; ++j)
+          t.mark_output(dy[b][i][j], TN_T_DX, -1, {b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b}, t.dcols[j]);
+  }
   // every vertex the tiler emitted must satisfy the same rules a caller's would
   for (size_t v = 0; v < tg->v.size(); ++v) {
     const Vertex& x_ = tg->v[v];

@@ -11,7 +11,10 @@ from . import binding as B
 
 _TENSOR_NAMES = {B.TN_T_X: "x", B.TN_T_WQ: "wq", B.TN_T_WK: "wk", B.TN_T_WV: "wv", B.TN_T_WO: "wo",
                  B.TN_T_W1: "w1", B.TN_T_W3: "w3", B.TN_T_W2: "w2", B.TN_T_G1: "g1", B.TN_T_G2: "g2",
-                 B.TN_T_Y: "y", B.TN_T_K: "k", B.TN_T_V: "v"}
+                 B.TN_T_Y: "y", B.TN_T_K: "k", B.TN_T_V: "v", B.TN_T_AQ: "aq", B.TN_T_BQ: "bq", B.TN_T_AV: "av",
+                 B.TN_T_BV: "bv", B.TN_T_PROBE: "probe", B.TN_T_DAQ: "daq", B.TN_T_DBQ: "dbq", B.TN_T_DAV: "dav",
+                 B.TN_T_DBV: "dbv", B.TN_T_DX: "dx"}
+OUTPUT_TENSORS = ("y", "k", "v", "daq", "dbq", "dav", "dbv", "dx")
 OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms_stat",
             B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
             B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
@@ -23,7 +26,7 @@ EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "or
 
 
 def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
-                        v_transposed: bool = True) -> B.tn_llama_config:
+                        v_transposed: bool = True, lora_rank: int = 0, train: bool = False) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -31,7 +34,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         attn_block=cfg.attn_block, eps=cfg.eps, rope_base=cfg.rope_base,
         weights_residency=B.TN_DEVICE if cfg.weights_resident else B.TN_HOST,
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
-        weights_transposed=int(weights_transposed), v_transposed=int(v_transposed))
+        weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
+        lora_rank=int(lora_rank), train=int(train))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -91,7 +95,7 @@ def cut_host_tiles(tg, full: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
     """vid -> contiguous tile (storage dtype) for every input vertex, cut from the full tensors."""
     out = {}
     for vid, name, r0, r1, c0, c1, tr in bindings(tg):
-        if name.split(".")[0] in ("y", "k", "v"):
+        if name.split(".")[0] in OUTPUT_TENSORS:
             continue
         a = full[name]
         a = a.reshape(1, -1) if a.ndim == 1 else a
@@ -101,7 +105,7 @@ def cut_host_tiles(tg, full: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
 
 def output_vertices(tg):
     """(vids in output-index order, their (rows, cols), {vid: binding}) of the marked outputs."""
-    bind = {b[0]: b for b in bindings(tg) if b[1].split(".")[0] in ("y", "k", "v")}
+    bind = {b[0]: b for b in bindings(tg) if b[1].split(".")[0] in OUTPUT_TENSORS}
     n_out = B.tn_taskgraph_num_outputs(tg)
     cand = list(bind) if len(bind) == n_out else range(B.tn_taskgraph_num_vertices(tg))
     vids, shapes = [0] * n_out, [(0, 0)] * n_out
@@ -162,13 +166,15 @@ class GpuSession:
     def __init__(self, cfg, full_inputs: Dict[str, np.ndarray], cap: Optional[int] = None,
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
-                 weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True):
+                 weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
+                 lora_rank: int = 0, train: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
         self.torch = torch
         self.cfg = cfg
-        self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed))
+        self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
+                                                       lora_rank, train))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         self.mg = B.tn_compile(self.tg, order, self.cap, compile_opts)
         self.stats = B.tn_memgraph_stats(self.mg)
@@ -180,7 +186,7 @@ class GpuSession:
         offs, seen, total = {}, {}, 0
         cuts = []
         for vid, name, r0, r1, c0, c1, tr in bindings(self.tg):
-            if name.split(".")[0] in ("y", "k", "v"):
+            if name.split(".")[0] in OUTPUT_TENSORS:
                 continue
             a = full_inputs[name]
             key = (id(a), r0, r1, c0, c1, tr)
@@ -246,7 +252,9 @@ class GpuSession:
             if only is not None and name not in only:
                 continue
             if name not in out:
-                out[name] = np.zeros((cfg.tokens, cfg.d_model), dtype=self.elem)
+                shape = (max(b[3] for b in self.out_bind.values() if b[1] == name),
+                         max(b[5] for b in self.out_bind.values() if b[1] == name))
+                out[name] = np.zeros(shape, dtype=self.elem)
             r, c = self.out_shapes[i]
             tile = slab[self.out_offs[i]:self.out_offs[i] + r * c * es].view(self.elem).reshape(r, c)
             out[name][r0:r1, c0:c1] = tile.T if tr else tile
