@@ -71,6 +71,9 @@ def main():
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
+    ap.add_argument("--train", type=int, default=-1,
+                    help="1: fine-tuning step (adapters of rank 16 on q and v, probe loss, reverse pass); default: only for c5")
+    ap.add_argument("--layers", type=int, default=0, help="run the workload's shape with this many layers instead of its own")
     ap.add_argument("--distinct-layers", type=int, default=-1,
                     help="layers with weights of their own (the others reuse them); default: all up to 8 layers, else 4")
     ap.add_argument("--kv-outputs", type=int, default=-1, help="K/V of every layer are outputs; default: only when weights are streamed")
@@ -83,16 +86,22 @@ def main():
     import torch
     from paper_2405_16283_amd import binding as B
     from paper_2405_16283_amd import harness as H
-    from workloads import bf16_bits_to_f32, config, make_llama_inputs
+    from workloads import bf16_bits_to_f32, config, make_llama_inputs, make_lora_inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     cfg = config(args.workload)
+    if args.layers > 0:
+        cfg = cfg.with_(layers=args.layers)
+    train = bool(args.train) if args.train >= 0 else cfg.name == "c5"
     t0 = time.perf_counter()
     distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
     kv_outputs = bool(args.kv_outputs) if args.kv_outputs >= 0 else (cfg.layers > 1 and not cfg.weights_resident)
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
+    if train:
+        kv_outputs = False
+        full.update(make_lora_inputs(cfg, 0, rank=16, b_std=0.0))
     t_gen = time.perf_counter() - t0
 
     def timed(session, steps, warmup, opts):
@@ -112,10 +121,11 @@ def main():
     def session(c):
         order = None
         if args.order == "level":
-            tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs))
+            tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train))
             order = H.level_major_order(tg)
             B.tn_taskgraph_destroy(tg)
-        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order)
+        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order,
+                            lora_rank=16 if train else 0, train=train)
 
     s = session(cfg)
     t_compile = time.perf_counter() - t0
@@ -159,7 +169,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.layers}-layer LLaMA-7B-shaped prefill, d {cfg.d_model}, "
+        "config": {"workload": f"{cfg.name}: {cfg.layers}-layer LLaMA-shaped "
+                               + ("fine-tuning step (rank-16 adapters on q and v, forward + backward)" if train else "prefill")
+                               + f", d {cfg.d_model}, "
                                f"{cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, batch {cfg.batch}, "
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,

@@ -51,8 +51,11 @@ struct Compiler {
   std::unordered_set<uint64_t> edge_set[3];
   std::map<uint64_t, Block> blocks;                          // offset -> block, covers [0, cap)
   std::map<uint64_t, std::pair<uint64_t, int64_t>> history;  // offset -> (end, last dead occupant)
+  // tensors that hold data on the GPU, ordered by their next use: the eviction candidates
+  std::set<std::pair<int64_t, tn_vid>> by_use;
+  std::vector<int64_t> use_key;  // key under which tensor t is in by_use, or -1
   std::map<uint64_t, uint64_t> free_at;                      // the free blocks alone: offset -> size
-  std::multiset<uint64_t> free_sizes;                        // their sizes, to refuse a hopeless search at once
+  std::map<uint64_t, std::set<uint64_t>> free_by_size;       // size -> offsets of the free blocks of that size
   int64_t execHzn = 0, allocHzn = 0, lookahead_blocked_until = -1, compacted_at = -1;
   uint64_t lookahead_bytes = 0, live_bytes = 0;
   std::vector<int64_t> step_pre;  // offloads and reloads inserted just before V[execHzn], in the order made
@@ -95,14 +98,30 @@ struct Compiler {
 
   bool produced(int64_t m) const { return m >= n || pos[m] < execHzn; }
 
+  void use_erase(tn_vid t) {
+    if (use_key[t] >= 0) by_use.erase({use_key[t], t});
+    use_key[t] = -1;
+  }
+  // (re-)enters tensor t, resident and holding data, under its current next use
+  void use_insert(tn_vid t) {
+    use_erase(t);
+    // tiny tensors (statistics, low-rank activations) are not worth evicting for a tile; they stay
+    // out of the candidate list and are only ever moved by the exhaustive search
+    if (aligned(tensor_bytes(tg.v[t].desc)) < kSmallTensor) return;
+    use_key[t] = next_use(t);
+    by_use.insert({use_key[t], t});
+  }
+
   // ---- simulated memory ------------------------------------------------------------------
   void free_add(uint64_t off, uint64_t size) {
     free_at[off] = size;
-    free_sizes.insert(size);
+    free_by_size[size].insert(off);
   }
   void free_del(uint64_t off, uint64_t size) {
     free_at.erase(off);
-    free_sizes.erase(free_sizes.find(size));
+    auto it = free_by_size.find(size);
+    it->second.erase(off);
+    if (it->second.empty()) free_by_size.erase(it);
   }
 
   // `it` has just become free: merge it with free neighbours and enter the result in the index
@@ -181,22 +200,24 @@ struct Compiler {
   // simMalloc: find an open range or fail
   bool sim_malloc(int64_t m) {
     const uint64_t size = vbytes(m);
-    if (free_sizes.empty() || *free_sizes.rbegin() < size) return false;
-    if (size >= kSmallTensor) {  // first fit from the bottom
-      for (auto f = free_at.begin(); f != free_at.end(); ++f)
-        if (f->second >= size) {
-          place(blocks.find(f->first), f->first, m);
-          return true;
+    // first fit = the lowest (for small tensors: the highest) address among the free blocks that
+    // are large enough; free blocks come in few distinct sizes, so the search goes size by size
+    auto from = free_by_size.lower_bound(size);
+    if (from == free_by_size.end()) return false;
+    if (size >= kSmallTensor) {
+      uint64_t best = UINT64_MAX;
+      for (auto it = from; it != free_by_size.end(); ++it) best = std::min(best, *it->second.begin());
+      place(blocks.find(best), best, m);
+    } else {  // at the top end of the highest hole
+      uint64_t best = 0, bsz = 0;
+      for (auto it = from; it != free_by_size.end(); ++it)
+        if (bsz == 0 || *it->second.rbegin() > best) {
+          best = *it->second.rbegin();
+          bsz = it->first;
         }
-    } else {  // small tensors: first fit from the top, at the top end of the hole
-      for (auto f = free_at.rbegin(); f != free_at.rend(); ++f)
-        if (f->second >= size) {
-          const uint64_t b0 = f->first, bsz = f->second;
-          place(blocks.find(b0), b0 + bsz - size, m);
-          return true;
-        }
+      place(blocks.find(best), best + bsz - size, m);
     }
-    return false;
+    return true;
   }
 
   // simFree: the range becomes open and remembers its occupant
@@ -266,6 +287,7 @@ struct Compiler {
     readers[victim].push_back(off);  // the offload reads the range; it precedes whoever takes it
     step_pre.push_back(off);
     sim_free(victim);
+    use_erase(t);
     name[t] = -1;
     evicted_by[t] = off;
   }
@@ -274,7 +296,7 @@ struct Compiler {
   tn_status sim_malloc_offld(int64_t m, const std::vector<int64_t>& pinned) {
     const uint64_t size = vbytes(m);
     auto evictable = [&](int64_t o) {
-      return produced(o) && std::find(pinned.begin(), pinned.end(), o) == pinned.end();
+      return produced(o) && !std::binary_search(pinned.begin(), pinned.end(), o);
     };
     for (;;) {
       if (sim_malloc(m)) return TN_OK;
@@ -282,7 +304,57 @@ struct Compiler {
       bool found = false;
       uint64_t best_start = 0, best_bytes = 0;
       int64_t best_use = -1;
-      for (auto i = blocks.begin(); i != blocks.end(); ++i) {
+      // Shortcut: instead of trying every window of memory, grow a window around each of the
+      // candidates with the furthest next use -- towards the neighbour that is free or, failing
+      // that, the evictable neighbour that is needed later -- and keep the best of these.  Only
+      // if none of them can be grown to `size` is every window tried.
+      int looked = 0;
+      for (auto c = by_use.rbegin(); c != by_use.rend() && looked < 64; ++c, ++looked) {
+        const int64_t w = name[c->second];
+        if (w < 0 || !evictable(w)) continue;
+        if (found && c->first <= best_use) break;  // no later candidate can beat the window we have
+        auto lo = blocks.find((uint64_t)mg.v[w].offset), hi = lo;  // window = [lo, hi]
+        uint64_t total = lo->second.size, ev_bytes = total;
+        int64_t min_use = c->first;
+        auto usable = [&](std::map<uint64_t, Block>::iterator b, int64_t* use) {
+          if (b->second.owner < 0) { *use = LLONG_MAX; return true; }
+          if (!evictable(b->second.owner)) return false;
+          *use = next_use(mg.v[b->second.owner].src);
+          return true;
+        };
+        int steps = 0;  // a window of many tiny tensors is not worth its transfers: give up on it
+        while (total < size && ++steps <= 16) {
+          int64_t ul = -1, ur = -1;
+          const bool okl = lo != blocks.begin() && usable(std::prev(lo), &ul);
+          auto nx = std::next(hi);
+          const bool okr = nx != blocks.end() && usable(nx, &ur);
+          if (!okl && !okr) break;
+          if (okl && (!okr || ul >= ur)) {
+            --lo;
+            if (lo->second.owner >= 0) ev_bytes += lo->second.size;
+            min_use = std::min(min_use, ul);
+            total += lo->second.size;
+          } else {
+            hi = nx;
+            if (hi->second.owner >= 0) ev_bytes += hi->second.size;
+            min_use = std::min(min_use, ur);
+            total += hi->second.size;
+          }
+        }
+        if (total < size) continue;
+        // free neighbours below the window belong to the hole that eviction will leave
+        if (!found || min_use > best_use || (min_use == best_use && ev_bytes < best_bytes)) {
+          found = true;
+          best_start = lo->first;
+          best_bytes = ev_bytes;
+          best_use = min_use;
+        }
+      }
+      const bool shortcut = found;
+#ifdef TN_COMPILE_DEBUG
+      { static long n_short = 0, n_full = 0; (shortcut ? n_short : n_full)++; if (((n_short + n_full) % 5000) == 0) fprintf(stderr, "shortcut %ld full %ld size %llu by_use %zu blocks %zu\n", n_short, n_full, (unsigned long long)size, by_use.size(), blocks.size()); }
+#endif
+      for (auto i = blocks.begin(); i != blocks.end() && !shortcut; ++i) {
         uint64_t total = 0, ev_bytes = 0;
         int64_t min_use = LLONG_MAX;
         for (auto j = i; j != blocks.end(); ++j) {
@@ -320,7 +392,15 @@ struct Compiler {
         place(it, off, m);
         return TN_OK;
       }
-      if (!revoke_newest_preallocation()) {
+      // nothing can be evicted to make room: take back reservations made ahead of the execution,
+      // as many as it takes to free `size` bytes, and try again
+      uint64_t before = live_bytes;
+      bool revoked = false;
+      while (revoke_newest_preallocation()) {
+        revoked = true;
+        if (before - live_bytes >= size) break;
+      }
+      if (!revoked) {
         if (compacted_at != execHzn) {
           compacted_at = execHzn;
           if (compact_and_place(m) == TN_OK) return TN_OK;
@@ -345,6 +425,7 @@ struct Compiler {
     std::vector<int64_t> p;
     for (tn_vid u : tg.v[v].in)
       if (name[u] >= 0) p.push_back(name[u]);
+    std::sort(p.begin(), p.end());  // sim_malloc_offld searches it
     return p;
   }
 
@@ -365,6 +446,7 @@ struct Compiler {
         tn_status s = sim_malloc_offld(r, pinned_for(v));
         if (s != TN_OK) return s;
         name[u] = r;
+        use_insert(u);
         evicted_by[u] = -1;
         step_pre.push_back(r);
         if (mg.stats.n_compactions != compactions) again = true;
@@ -385,6 +467,7 @@ struct Compiler {
     if (counted_ahead[v]) lookahead_bytes -= vbytes(v);
     counted_ahead[v] = 0;
     ++execHzn;
+    use_insert(v);
     // a wanted result leaves for the caller's buffer right away
     if (tv.output_index >= 0) {
       const int64_t s = new_vertex(TN_MG_STORE, v);
@@ -399,11 +482,16 @@ struct Compiler {
     d.push_back(v);
     std::sort(d.begin(), d.end());
     d.erase(std::unique(d.begin(), d.end()), d.end());
-    for (tn_vid u : d)
-      if (next_use(u) == LLONG_MAX && name[u] >= 0) {
+    for (tn_vid u : d) {
+      if (name[u] < 0) continue;
+      if (next_use(u) == LLONG_MAX) {
         sim_free(name[u]);
+        use_erase(u);
         name[u] = -1;
+      } else {
+        use_insert(u);  // its next use has moved on
       }
+    }
     return TN_OK;
   }
 
@@ -421,6 +509,7 @@ struct Compiler {
         if (cons[u].empty() || cons[u].back() != i) cons[u].push_back(i);
     cons_ptr.assign(n, 0);
     name.assign(n, -1);
+    use_key.assign(n, -1);
     evicted_by.assign(n, -1);
     counted_ahead.assign(n, 0);
     mg.v.reserve(n + n / 4);

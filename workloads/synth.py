@@ -61,6 +61,9 @@ CONFIGS: Dict[str, LlamaConfig] = {
     # 65B-shaped prefill, 48 GB cap
     "c4": LlamaConfig("c4", 80, 8192, 64, 128, 22016, 8192, 1, "bf16", 1024, 1024,
                       48_000_000_000, 0.0, False, False),
+    # LoRA fine-tuning step on the 7B shape: 4 sequences of 4096 tokens, forward + backward, 32 GB cap
+    "c5": LlamaConfig("c5", 32, 4096, 32, 128, 11008, 4096, 4, "bf16", 512, 1024,
+                      32_000_000_000, 0.0, False, False),
     # small shapes with ragged row, column and K tails, used by the parity tests
     "ragged_f32": LlamaConfig("ragged_f32", 2, 192, 3, 64, 272, 160, 1, "f32", 64, 128,
                               0, 0.40, False, False),
