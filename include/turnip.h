@@ -72,7 +72,8 @@ enum {
   TN_OP_SILU_MUL_BWD = 9,   /* dact, gate, up -> gradient of gate (mode 0) or of up (mode 1)         */
   TN_OP_RMS_BWD_STAT = 10,  /* dy tiles, x tiles, gain tiles of a row block -> fp32 [rows,1]: sum dy*gain*x */
   TN_OP_RMS_BWD_APPLY = 11, /* dy, x, stat, dot, gain[, residual gradient] -> gradient of x            */
-  TN_OP_ATTN_BWD = 12       /* Q, K, V, dO tiles[, statistics] -> statistics, dQ, dK or dV (mode)      */
+  TN_OP_ATTN_BWD = 12,      /* Q, K, V, dO tiles[, statistics][, transposed tiles] -> statistics, dQ, dK or dV (mode) */
+  TN_OP_TRANSPOSE = 13      /* X [rows, cols] -> X^T [cols, rows]                                      */
 };
 
 typedef struct {
@@ -120,7 +121,12 @@ typedef struct {
  *                                       mode 1 -> dQ [q rows, gw] = scale * sum_k p (dp - D) k;
  *                                       mode 2 -> dK [kv rows, gw] = scale * sum_q p (dp - D) q;
  *                                       mode 3 -> dV [kv rows, gw] = sum_q p dO.
- *                                       Sums run over keys (queries) in ascending order. */
+ *                                       Sums run over keys (queries) in ascending order.
+ *                                       trans_a != 0 (modes 1..3, needs v_trans == 0): one more grid of operands
+ *                                       follows, the transposes the matrix units want as row-major tiles:
+ *                                       mode 1 -> K^T tiles, mode 2 -> Q^T tiles, mode 3 -> dO^T tiles, each
+ *                                       [columns of the tile, rows of the tile], in the order of the grid
+ *                                       they mirror. */
 typedef struct {
   int32_t nk;
   int32_t d;

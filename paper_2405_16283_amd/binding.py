@@ -19,7 +19,7 @@ TN_F32, TN_BF16 = 0, 1
 TN_HOST, TN_DEVICE = 0, 1
 (TN_OP_INPUT, TN_OP_GEMM, TN_OP_RMS_STAT, TN_OP_RMS_APPLY, TN_OP_ROPE, TN_OP_ATTN_BLOCK,
  TN_OP_ATTN_COMBINE, TN_OP_SILU_MUL, TN_OP_ADD, TN_OP_SILU_MUL_BWD, TN_OP_RMS_BWD_STAT, TN_OP_RMS_BWD_APPLY,
- TN_OP_ATTN_BWD) = range(13)
+ TN_OP_ATTN_BWD, TN_OP_TRANSPOSE) = range(14)
 (TN_T_X, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2, TN_T_Y, TN_T_K, TN_T_V,
  TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE, TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX) = range(23)
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE) = range(7)

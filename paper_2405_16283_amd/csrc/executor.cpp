@@ -281,6 +281,10 @@ tn_status build_tables(tn_executor& ex) {
         vi.cls = x.op_kind == TN_OP_ADD ? LC_ADD : LC_SILU_MUL;
         vi.bytes = 3.0 * x.bytes;
         break;
+      case TN_OP_TRANSPOSE:
+        vi.cls = LC_TRANSPOSE;
+        vi.bytes = 2.0 * x.bytes;
+        break;
       case TN_OP_SILU_MUL_BWD:
         vi.cls = LC_SILU_BWD;
         vi.bytes = 4.0 * x.bytes;
@@ -312,7 +316,11 @@ tn_status build_tables(tn_executor& ex) {
           if (odesc(c).cols != tc) return fail(TN_ERR_SHAPE, "attn_bwd %lld: column tiles are not uniform", (long long)m);
         if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_bwd %lld: head_dim must be 64 or 128", (long long)m);
         aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
-        vi.cls = LC_ATTN_BWD;
+        // the MFMA kernel wants plain V tiles, the transposed grid (except for the statistics), whole
+        // heads inside one column tile, and 8-row groups that straddle nothing
+        vi.cls = (d.dtype == TN_BF16 && !x.p.v_trans && (x.p.mode == 0 || x.p.trans_a) && tc % hd == 0 && tq % 8 == 0 &&
+                  tk % 8 == 0 && q_rows % 8 == 0 && kv_rows % 8 == 0 && q_rows >= 8 && kv_rows >= 8)
+                     ? LC_ATTN_BWD_BF16 : LC_ATTN_BWD;
         vi.head_dim = (int16_t)hd;
         vi.flops = (x.p.mode == 3 ? 4.0 : 6.0) * q_rows * kv_rows * (double)(nc * tc);
         break;
@@ -405,7 +413,8 @@ int family_of(int cls) {
     case LC_GEMM_BF16_NT256: return 0;
     case LC_ATTN_F32:
     case LC_ATTN_BF16:
-    case LC_ATTN_BWD: return 1;
+    case LC_ATTN_BWD:
+    case LC_ATTN_BWD_BF16: return 1;
     default: return 2;
   }
 }

@@ -44,6 +44,8 @@ enum LaunchClass {
   LC_RMS_BWD_STAT,
   LC_RMS_BWD_APPLY,
   LC_ATTN_BWD,       // attention backward on the vector ALUs (statistics, dQ, dK, dV)
+  LC_ATTN_BWD_BF16,  // MFMA attention backward
+  LC_TRANSPOSE,
   LC_COUNT
 };
 

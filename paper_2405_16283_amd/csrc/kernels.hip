@@ -245,6 +245,25 @@ __global__ void __launch_bounds__(256) rms_bwd_apply_kernel(DeviceTables t, Batc
   }
 }
 
+// out[c, r] = in[r, c]: 64x64 pieces through LDS, so that both the reads and the writes are row-wise
+template <typename T>
+__global__ void __launch_bounds__(256) transpose_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  __shared__ T tile[64][65];
+  const int R = d.cols, C = d.rows;  // the operand is [R, C]; the output [C, R]
+  const int tc = (C + 63) / 64;
+  const int r0 = (blockIdx.x / tc) * 64, c0 = (blockIdx.x % tc) * 64;
+  const T* x = (const T*)t.ptrs[d.ptr0];
+  T* o = (T*)d.out;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4)
+    if (r0 + i < R && c0 + tx < C) tile[i][tx] = x[(size_t)(r0 + i) * C + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4)
+    if (c0 + i < C && r0 + tx < R) o[(size_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
 // ---------------------------------------------------------------------------------------------
 // generic GEMM on the vector ALUs (fp32 accumulate): 64x64 output tile per workgroup
 // ---------------------------------------------------------------------------------------------
@@ -806,6 +825,197 @@ __global__ void __launch_bounds__(64) attn_bwd_kernel(DeviceTables t, Batch b) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// MFMA attention backward (bf16 storage, V given as plain [keys, columns] tiles).
+//
+// Modes 0 (statistics) and 1 (dQ): one workgroup = one head x 128 queries, a wavefront owns 32
+// queries and a lane one of them (its MFMA column), exactly as in the forward kernel: per 32 keys
+// it forms S^T = K Q^T and dP^T = V dO^T with the key rows fed in the permuted order that leaves a
+// lane with 8 consecutive keys per 16-key slab, so that dS^T is directly the B operand of
+// dQ^T += K^T dS^T; the A operand is a 16-byte read of a row of a K^T tile.
+// Modes 2 (dK) and 3 (dV): one workgroup = one head x 128 keys, a lane owns a key; per 32 queries
+// S = Q K^T and dP = dO V^T with the query rows permuted likewise, and dK^T += Q^T dS,
+// dV^T += dO^T P read rows of Q^T / dO^T tiles.
+// Fragments are read straight from global memory (the four wavefronts of a workgroup read the
+// same tiles, so they meet in the L1); probabilities and dS enter the MFMA as single bf16.
+// aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
+// ---------------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256) attn_bwd_bf16_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int* ax = t.aux + d.aux0;
+  const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
+  const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD, mode = d.p.mode;
+  const int nq = d.p.n_q_tiles, nkv = d.p.n_kv_tiles;
+  void* const* Qt = t.ptrs + d.ptr0;
+  void* const* Kt = Qt + nq * nc;
+  void* const* Vt = Kt + nkv * nc;
+  void* const* Dt = Vt + nkv * nc;  // dO tiles
+  void* const* St = Dt + nq * nc;   // statistics per Q row tile (modes 1..3)
+  void* const* Tt = St + nq;        // transposed grid (modes 1..3)
+  const int my_rows = mode <= 1 ? q_rows : kv_rows;
+  const int rblocks = (my_rows + 127) / 128;
+  const int h = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
+  const int myrow = rb * 128 + w * 32 + l32;  // this lane's query (modes 0, 1) or key (modes 2, 3)
+  const bool valid = myrow < my_rows;
+  constexpr float LOG2E = 1.44269504088896340736f, LN2 = 0.69314718055994530942f;
+  const float scale = d.p.scale, scale2 = scale * LOG2E;
+  const int causal = d.p.causal;
+  const int a_ = l32 >> 3, b_ = l32 & 3, g_ = (l32 >> 2) & 1;
+  const int perm = 16 * (a_ >> 1) + 8 * g_ + 4 * (a_ & 1) + b_;  // row i of an MFMA tile is fed row perm(i)
+  auto frag = [&](void* const* grid, int t_rows, int row, int col) -> bf16x8 {
+    uint4 v = *(const uint4*)tile_elem<bf16_t>(grid, nc, t_rows, tc, row, col);
+    return *(bf16x8*)&v;
+  };
+  auto stat = [&](int r, int which) -> float {
+    const int rt = r / tq;
+    return ((const float*)St[rt])[(size_t)(r - rt * tq) * (2 * hpg) + which * hpg + h];
+  };
+  f32x16 acc[HD / 32];
+#pragma unroll
+  for (int i = 0; i < HD / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  if (mode <= 1) {
+    const int qrow = min(myrow, q_rows - 1), qpos = d.p.q_pos0 + myrow;
+    bf16x8 qf[HD / 16], dof[HD / 16];
+#pragma unroll
+    for (int s = 0; s < HD / 16; ++s) {
+      qf[s] = frag(Qt, tq, qrow, h * HD + s * 16 + g * 8);
+      dof[s] = frag(Dt, tq, qrow, h * HD + s * 16 + g * 8);
+    }
+    const float lse2 = mode == 1 ? stat(qrow, 0) * LOG2E : 0.f, Dq = mode == 1 ? stat(qrow, 1) : 0.f;
+    float m = -INFINITY, l = 0.f, dsum = 0.f;
+    int kv_end = kv_rows;
+    if (causal) kv_end = min(kv_rows, d.p.q_pos0 + rb * 128 + 128 - d.p.k_pos0);
+    for (int kv0 = 0; kv0 < kv_end; kv0 += 32) {
+      const int krow = min(kv0 + perm, kv_rows - 1);
+      f32x16 sT, dpT;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < HD / 16; ++s) {
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Kt, tk, krow, h * HD + s * 16 + g * 8), qf[s], sT, 0, 0, 0);
+        dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Vt, tk, krow, h * HD + s * 16 + g * 8), dof[s], dpT, 0, 0, 0);
+      }
+      // register r of this lane: key kv0 + 16*(r>>3) + 8*g + (r&7)
+      if (mode == 0) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kv0 + 16 * (r >> 3) + 8 * g + (r & 7);
+          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > qpos);
+          sT[r] = ok ? sT[r] * scale2 : -INFINITY;
+          mx = fmaxf(mx, sT[r]);
+        }
+        const float mn = fmaxf(m, mx);
+        if (mn != -INFINITY) {
+          const float alpha = __builtin_amdgcn_exp2f(m - mn);
+          float ls = 0.f, ds = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(sT[r] - mn);
+            ls += p;
+            ds = fmaf(p, dpT[r], ds);
+          }
+          l = l * alpha + ls;
+          dsum = dsum * alpha + ds;
+          m = mn;
+        }
+      } else {
+        bf16x8 s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kv0 + 16 * (r >> 3) + 8 * g + (r & 7);
+          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > qpos);
+          const float p = ok ? __builtin_amdgcn_exp2f(sT[r] * scale2 - lse2) : 0.f;
+          const __bf16 v = (__bf16)(p * (dpT[r] - Dq) * scale);
+          if (r < 8) s0[r] = v; else s1[r - 8] = v;
+        }
+        const int k0 = min(kv0 + 8 * g, kv_rows - 8), k1 = min(kv0 + 16 + 8 * g, kv_rows - 8);
+#pragma unroll
+        for (int i = 0; i < HD / 32; ++i) {
+          const int col = h * HD + i * 32 + l32;
+          uint4 u0 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tk, tc, kv_rows, k0, col);
+          uint4 u1 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tk, tc, kv_rows, k1, col);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u0, s0, acc[i], 0, 0, 0);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u1, s1, acc[i], 0, 0, 0);
+        }
+      }
+    }
+    if (mode == 0) {
+      // the two halves of the wavefront saw different keys of the same query: merge their states
+      const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64), d2 = __shfl_xor(dsum, 32, 64);
+      const float mn = fmaxf(m, m2);
+      const float w1 = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mn), w2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+      const float lt = l * w1 + l2 * w2, dt = dsum * w1 + d2 * w2;
+      if (valid && g == 0) {
+        float* out = (float*)d.out + (size_t)myrow * (2 * hpg);
+        out[h] = (mn + __builtin_amdgcn_logf(lt)) * LN2;
+        out[hpg + h] = dt / lt;
+      }
+      return;
+    }
+  } else {
+    const int krow = min(myrow, kv_rows - 1), kpos = d.p.k_pos0 + myrow;
+    bf16x8 kf[HD / 16], vf[HD / 16];
+#pragma unroll
+    for (int s = 0; s < HD / 16; ++s) {
+      kf[s] = frag(Kt, tk, krow, h * HD + s * 16 + g * 8);
+      vf[s] = frag(Vt, tk, krow, h * HD + s * 16 + g * 8);
+    }
+    int q_start = 0;  // queries before the first key of this workgroup see none of its keys
+    if (causal) q_start = max(0, d.p.k_pos0 + rb * 128 - d.p.q_pos0) & ~31;
+    for (int q0 = q_start; q0 < q_rows; q0 += 32) {
+      const int qrow = min(q0 + perm, q_rows - 1);
+      f32x16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < HD / 16; ++s) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Qt, tq, qrow, h * HD + s * 16 + g * 8), kf[s], sc, 0, 0, 0);
+        if (mode == 2)
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Dt, tq, qrow, h * HD + s * 16 + g * 8), vf[s], dp, 0, 0, 0);
+      }
+      // register r of this lane: query q0 + 16*(r>>3) + 8*g + (r&7)
+      bf16x8 s0, s1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int q = q0 + 16 * (r >> 3) + 8 * g + (r & 7);
+        const bool ok = valid && q < q_rows && !(causal && kpos > d.p.q_pos0 + q);
+        const int qc = min(q, q_rows - 1);
+        const float p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - stat(qc, 0) * LOG2E) : 0.f;
+        const __bf16 v = (__bf16)(mode == 3 ? p : p * (dp[r] - stat(qc, 1)) * scale);
+        if (r < 8) s0[r] = v; else s1[r - 8] = v;
+      }
+      const int r0 = min(q0 + 8 * g, q_rows - 8), r1 = min(q0 + 16 + 8 * g, q_rows - 8);
+#pragma unroll
+      for (int i = 0; i < HD / 32; ++i) {
+        const int col = h * HD + i * 32 + l32;
+        uint4 u0 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tq, tc, q_rows, r0, col);
+        uint4 u1 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tq, tc, q_rows, r1, col);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u0, s0, acc[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u1, s1, acc[i], 0, 0, 0);
+      }
+    }
+  }
+  if (!valid) return;
+  // accumulator tile i: this lane holds column myrow and rows (= head columns) 8a + 4g + k of it
+  bf16_t* out = (bf16_t*)d.out + (size_t)myrow * gw + h * HD;
+#pragma unroll
+  for (int i = 0; i < HD / 32; ++i)
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      uint2 v;
+      v.x = (uint32_t)f2bf(acc[i][4 * a]) | ((uint32_t)f2bf(acc[i][4 * a + 1]) << 16);
+      v.y = (uint32_t)f2bf(acc[i][4 * a + 2]) | ((uint32_t)f2bf(acc[i][4 * a + 3]) << 16);
+      *(uint2*)(out + i * 32 + 8 * a + 4 * g) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // MFMA attention block (bf16 storage, V given as V^T tiles).  One workgroup = one head x 128 query
 // rows; each of its 4 wavefronts owns 32 query rows; two workgroups share a compute unit.
 //
@@ -1069,11 +1279,16 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     case LC_SILU_MUL:
     case LC_ADD:
     case LC_SILU_BWD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
+    case LC_TRANSPOSE: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
     case LC_RMS_BWD_STAT: return cdiv(d.rows, 4);
     case LC_RMS_BWD_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ATTN_BWD: {
       const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
       return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], 64);
+    }
+    case LC_ATTN_BWD_BF16: {
+      const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
+      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], 128);
     }
     default: return 0;
   }
@@ -1118,9 +1333,15 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
       if (bf) hipLaunchKernelGGL((ewise2_kernel<bf16_t, false>), grid, wg, 0, s, t, b);
       else hipLaunchKernelGGL((ewise2_kernel<float, false>), grid, wg, 0, s, t, b);
       break;
+    case LC_TRANSPOSE: TN_LAUNCH_T(transpose_kernel); break;
     case LC_SILU_BWD: TN_LAUNCH_T(silu_bwd_kernel); break;
     case LC_RMS_BWD_STAT: TN_LAUNCH_T(rms_bwd_stat_kernel); break;
     case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;
+    case LC_ATTN_BWD_BF16:
+      if (head_dim == 64) hipLaunchKernelGGL(attn_bwd_bf16_kernel<64>, grid, wg, 0, s, t, b);
+      else if (head_dim == 128) hipLaunchKernelGGL(attn_bwd_bf16_kernel<128>, grid, wg, 0, s, t, b);
+      else return hipErrorInvalidValue;
+      break;
     case LC_ATTN_BWD:
       if (head_dim == 64) {
         if (bf) hipLaunchKernelGGL((attn_bwd_kernel<bf16_t, 64>), grid, dim3(64), 0, s, t, b);

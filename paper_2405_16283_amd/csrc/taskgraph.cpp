@@ -150,12 +150,17 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
         return fail(TN_ERR_SHAPE, "rms_bwd_apply: operand shapes do not fit");
       return TN_OK;
     }
+    case TN_OP_TRANSPOSE:
+      if (n_in != 1 || D(0).rows != out.cols || D(0).cols != out.rows || D(0).dtype != out.dtype)
+        return fail(TN_ERR_SHAPE, "transpose: one operand [cols, rows] of the output's type");
+      return TN_OK;
     case TN_OP_ATTN_BWD: {
       const int nq = p.n_q_tiles, nkv = p.n_kv_tiles, nc = p.n_col_tiles;
       if (nq < 1 || nkv < 1 || nc < 1 || p.head_dim < 1 || p.mode < 0 || p.mode > 3 ||
-          n_in != (2 * nq + 2 * nkv) * nc + (p.mode ? nq : 0))
+          (p.trans_a && (p.mode == 0 || p.v_trans)) ||
+          n_in != (2 * nq + 2 * nkv) * nc + (p.mode ? nq : 0) + (p.trans_a ? (p.mode == 1 ? nkv : nq) * nc : 0))
         return fail(TN_ERR_SHAPE, "attn_bwd: needs (2 n_q_tiles + 2 n_kv_tiles) * n_col_tiles operands, plus n_q_tiles "
-                                  "statistics unless mode is 0");
+                                  "statistics unless mode is 0, plus the transposed grid if trans_a is set");
       int64_t gw = 0, qrows = 0, kvrows = 0;
       for (int c = 0; c < nc; ++c) gw += D(c).cols;
       if (gw % p.head_dim) return fail(TN_ERR_SHAPE, "attn_bwd: columns are not whole heads");
@@ -179,6 +184,14 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
           if (p.v_trans) std::swap(v.rows, v.cols);
           if (k.cols != D(c).cols || !same(k, v) || k.rows != D(nq * nc + r * nc).rows || k.dtype != dt)
             return fail(TN_ERR_SHAPE, "attn_bwd: K/V tile (%d,%d) does not fit the grid", r, c);
+        }
+      }
+      if (p.trans_a) {
+        const int t0 = s0 + nq, src0 = p.mode == 1 ? nq * nc : p.mode == 2 ? 0 : d0, cnt = (p.mode == 1 ? nkv : nq) * nc;
+        for (int i = 0; i < cnt; ++i) {
+          tn_tensor_desc tt = D(t0 + i);
+          std::swap(tt.rows, tt.cols);
+          if (!same(tt, D(src0 + i))) return fail(TN_ERR_SHAPE, "attn_bwd: transposed tile %d does not mirror its tile", i);
         }
       }
       const bool ok = p.mode == 0 ? (out.dtype == TN_F32 && out.rows == qrows && out.cols == 2 * hpg)
@@ -669,7 +682,11 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           // output projection: h1 = x + o Wo
           for (size_t j = 0; j < nd; ++j) dO[i][j] = t.gemm_list(dh1[i], won[j], m, t.dcols[j].len(), false, true);
         }
-        // attention, one head group (= one column tile) at a time
+        // attention, one head group (= one column tile) at a time.  The reverse kernels read V as
+        // plain tiles and K^T, Q^T, dO^T as row-major tiles of their own.
+        auto transposed = [&](tn_vid x, int32_t rws, int32_t cls) {  // x is [rws, cls]
+          return t.op(TN_OP_TRANSPOSE, tn_op_params{}, {x}, {c.dtype, cls, rws});
+        };
         Grid dq(nr, std::vector<tn_vid>(nd)), dk(nr, std::vector<tn_vid>(nd)), dv(nr, std::vector<tn_vid>(nd));
         for (size_t j = 0; j < nd; ++j) {
           tn_op_params p{};
@@ -677,39 +694,52 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           p.head_dim = c.head_dim;
           p.causal = 1;
           p.scale = 1.0f / std::sqrt((float)c.head_dim);
-          p.v_trans = c.v_transposed ? 1 : 0;
           const int32_t n = t.dcols[j].len(), hpg_ = n / c.head_dim;
-          std::vector<tn_vid> stats(nr);
+          std::vector<tn_vid> vn(nr), kT(nr), qT(nr), dOT(nr), stats(nr);
+          for (size_t i = 0; i < nr; ++i) {
+            const int32_t m = t.rows[i].len();
+            vn[i] = c.v_transposed ? transposed(sv.v[i][j], n, m) : sv.v[i][j];
+            kT[i] = transposed(sv.k[i][j], m, n);
+            qT[i] = transposed(sv.q[i][j], m, n);
+            dOT[i] = transposed(dO[i][j], m, n);
+          }
           for (size_t i = 0; i < nr; ++i) {  // query tile i against the key tiles 0..i
             std::vector<tn_vid> in{sv.q[i][j]};
             for (size_t r = 0; r <= i; ++r) in.push_back(sv.k[r][j]);
-            for (size_t r = 0; r <= i; ++r) in.push_back(sv.v[r][j]);
+            for (size_t r = 0; r <= i; ++r) in.push_back(vn[r]);
             in.push_back(dO[i][j]);
             p.n_q_tiles = 1;
             p.n_kv_tiles = (int32_t)i + 1;
             p.q_pos0 = t.rows[i].a;
             p.k_pos0 = 0;
             p.mode = 0;
+            p.trans_a = 0;
             stats[i] = t.op(TN_OP_ATTN_BWD, p, in, {TN_F32, t.rows[i].len(), 2 * hpg_});
             in.push_back(stats[i]);
+            for (size_t r = 0; r <= i; ++r) in.push_back(kT[r]);
             p.mode = 1;
+            p.trans_a = 1;
             dq[i][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in), {c.dtype, t.rows[i].len(), n});
           }
           for (size_t r = 0; r < nr; ++r) {  // key tile r against the query tiles r..end
             std::vector<tn_vid> in;
             for (size_t i = r; i < nr; ++i) in.push_back(sv.q[i][j]);
             in.push_back(sv.k[r][j]);
-            in.push_back(sv.v[r][j]);
+            in.push_back(vn[r]);
             for (size_t i = r; i < nr; ++i) in.push_back(dO[i][j]);
             for (size_t i = r; i < nr; ++i) in.push_back(stats[i]);
             p.n_q_tiles = (int32_t)(nr - r);
             p.n_kv_tiles = 1;
             p.q_pos0 = t.rows[r].a;
             p.k_pos0 = t.rows[r].a;
+            p.trans_a = 1;
+            std::vector<tn_vid> in_k(in), in_v(in);
+            for (size_t i = r; i < nr; ++i) in_k.push_back(qT[i]);
+            for (size_t i = r; i < nr; ++i) in_v.push_back(dOT[i]);
             p.mode = 2;
-            dk[r][j] = t.op(TN_OP_ATTN_BWD, p, in, {c.dtype, t.rows[r].len(), n});
+            dk[r][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in_k), {c.dtype, t.rows[r].len(), n});
             p.mode = 3;
-            dv[r][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in), {c.dtype, t.rows[r].len(), n});
+            dv[r][j] = t.op(TN_OP_ATTN_BWD, p, std::move(in_v), {c.dtype, t.rows[r].len(), n});
           }
         }
         // projections with adapters, first normalisation, residual

@@ -19,7 +19,7 @@ OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms
             B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
             B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
             B.TN_OP_SILU_MUL_BWD: "silu_mul_bwd", B.TN_OP_RMS_BWD_STAT: "rms_bwd_stat",
-            B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd"}
+            B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd", B.TN_OP_TRANSPOSE: "transpose"}
 MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op", B.TN_MG_OFFLOAD: "offload",
                  B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store"}
 EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}

@@ -141,8 +141,18 @@ def test_rmsnorm_backward(dtype, residual):
     assert R.rel_err(got, ref) < TOL[dtype]
 
 
-@pytest.mark.parametrize("dtype,hd,v_trans", [("f32", 64, 0), ("f32", 64, 1), ("bf16", 128, 1), ("bf16", 64, 0)])
-def test_attention_backward(dtype, hd, v_trans):
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_transpose(dtype):
+    rng = np.random.default_rng(5)
+    g = Graph(dtype)
+    x, X = g.inp(rng.standard_normal((70, 150)))
+    (out,) = g.run([g.op(B.TN_OP_TRANSPOSE, [x], 150, 70)])
+    np.testing.assert_array_equal(out, X.T)
+
+
+@pytest.mark.parametrize("dtype,hd,v_trans,aux", [("f32", 64, 0, 0), ("f32", 64, 1, 0), ("bf16", 128, 1, 0), ("bf16", 64, 0, 0),
+                                                  ("bf16", 128, 0, 1), ("bf16", 64, 0, 1), ("f32", 64, 0, 1)])
+def test_attention_backward(dtype, hd, v_trans, aux):
     """Two heads, 96 queries at positions 64.. against 160 keys from position 0, causal; Q rows in
     tiles of 64 (ragged), K/V rows in tiles of 64, one column tile per head."""
     rng = np.random.default_rng(4)
@@ -174,9 +184,17 @@ def test_attention_backward(dtype, hd, v_trans):
         ins = q[i * hpg:(i + 1) * hpg] + k + v + do[i * hpg:(i + 1) * hpg]
         p = dict(common, n_q_tiles=1, q_pos0=q_pos0 + r0)
         stats.append(g.op(B.TN_OP_ATTN_BWD, ins, r1 - r0, 2 * hpg, f32=True, mode=0, **p))
-    dq = g.op(B.TN_OP_ATTN_BWD, q + k + v + do + stats, nq_rows, gw, mode=1, **common)
-    dk = g.op(B.TN_OP_ATTN_BWD, q + k + v + do + stats, nkv_rows, gw, mode=2, **common)
-    dv = g.op(B.TN_OP_ATTN_BWD, q + k + v + do + stats, nkv_rows, gw, mode=3, **common)
+    def tr(vs, ranges):  # transposes of a grid's tiles, as vertices (aux: what the MFMA kernels read)
+        out = []
+        for i, (r0, r1) in enumerate(ranges):
+            for h in range(hpg):
+                out.append(g.op(B.TN_OP_TRANSPOSE, [vs[i * hpg + h]], hd, r1 - r0))
+        return out
+
+    base = q + k + v + do + stats
+    dq = g.op(B.TN_OP_ATTN_BWD, base + (tr(k, kt) if aux else []), nq_rows, gw, mode=1, trans_a=aux, **common)
+    dk = g.op(B.TN_OP_ATTN_BWD, base + (tr(q, qt) if aux else []), nkv_rows, gw, mode=2, trans_a=aux, **common)
+    dv = g.op(B.TN_OP_ATTN_BWD, base + (tr(do, qt) if aux else []), nkv_rows, gw, mode=3, trans_a=aux, **common)
     got = g.run(stats + [dq, dk, dv])
     got_stats = np.concatenate(got[:len(qt)], axis=0)
     tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (Q, K, V))
