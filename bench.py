@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--no-capped", action="store_true", help=argparse.SUPPRESS)  # the default now
     ap.add_argument("--order", default="tiler", choices=["tiler", "level"],
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
+    ap.add_argument("--evict-ahead-mb", type=int, default=0, help="compile option evict_ahead_bytes in MiB")
+    ap.add_argument("--cap-gb", type=float, default=0.0, help="GPU-memory cap in GB instead of the workload's own")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
     ap.add_argument("--train", type=int, default=-1,
@@ -91,9 +93,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+    t_begin = time.perf_counter()
     cfg = config(args.workload)
     if args.layers > 0:
         cfg = cfg.with_(layers=args.layers)
+    if args.cap_gb > 0:
+        cfg = cfg.with_(cap_bytes=int(args.cap_gb * 1e9), cap_frac=0.0)
     train = bool(args.train) if args.train >= 0 else cfg.name == "c5"
     t0 = time.perf_counter()
     distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
@@ -104,6 +109,9 @@ def main():
         full.update(make_lora_inputs(cfg, 0, rank=16, b_std=0.0))
     t_gen = time.perf_counter() - t0
 
+    def note(msg):
+        print(f"[bench {time.perf_counter() - t_begin:7.1f}s] {msg}", file=sys.stderr, flush=True)
+
     def timed(session, steps, warmup, opts):
         reps = []
         for i in range(warmup + steps):
@@ -113,6 +121,7 @@ def main():
             rep = session.execute(opts)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t
+            note(f"step {i + 1} of {warmup + steps}: {dt * 1e3:.1f} ms")
             if i >= warmup:
                 reps.append((dt, rep))
         return reps
@@ -124,11 +133,16 @@ def main():
             tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train))
             order = H.level_major_order(tg)
             B.tn_taskgraph_destroy(tg)
-        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order,
-                            lora_rank=16 if train else 0, train=train)
+        ahead = args.evict_ahead_mb << 20
+        copts = B.tn_compile_opts(max_lookahead_bytes=(1 << 64) - 1, drop_clean_inputs=1, evict_ahead_bytes=ahead)
+        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
+                            lora_rank=16 if train else 0, train=train, progress=note)
 
+    note("inputs generated")
     s = session(cfg)
     t_compile = time.perf_counter() - t0
+    note(f"compiled and executor created: {int(s.stats.n_vertices)} memgraph vertices, {int(s.stats.n_offload)} offloads, "
+         f"{int(s.stats.n_load)} loads")
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
     engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
@@ -138,7 +152,7 @@ def main():
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
-    plain = timed(s, max(3, args.steps // 4), 1, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
+    plain = timed(s, max(1, min(3, args.steps), args.steps // 4), 1 if args.steps > 1 else 0, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
                                                                 max_transfers=args.max_transfers,
                                                                 max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth,
                                                                 copy_engine=engine, copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7))

@@ -253,6 +253,13 @@ typedef struct {
    * superfluous). */
   int32_t prune_superfluous;
   uint32_t alignment; /* location granularity in bytes, power of two; 0 = 256 */
+  /* When room has to be made for a tensor, evict this many bytes more than it needs, taking the
+   * resident tensors whose next use lies furthest ahead (and at least a few thousand vertices
+   * ahead).  Algorithm 2 evicts exactly what one tensor needs, which under a tight cap turns the
+   * run into a chain of evict-one, produce-one steps, each a round trip through the host; evicting
+   * a batch lets the transfers of the batch, and then the kernels that take the freed places, go
+   * together.  0 = as in Algorithm 2. */
+  uint64_t evict_ahead_bytes;
 } tn_compile_opts;
 
 /* Compiles tg for gpu_cap_bytes of GPU memory.  order: a permutation of all vertex ids that

@@ -292,6 +292,22 @@ struct Compiler {
     evicted_by[t] = off;
   }
 
+  // evict more than the allocation at hand needs (tn_compile_opts::evict_ahead_bytes)
+  void evict_ahead(const std::vector<int64_t>& pinned) {
+    if (!opt.evict_ahead_bytes) return;
+    constexpr int64_t kFarAhead = 4096;  // vertices of the serial order
+    uint64_t freed = 0;
+    std::vector<int64_t> victims;
+    for (auto c = by_use.rbegin(); c != by_use.rend() && freed < opt.evict_ahead_bytes; ++c) {
+      if (c->first - execHzn < kFarAhead) break;
+      const int64_t w = name[c->second];
+      if (w < 0 || !produced(w) || std::binary_search(pinned.begin(), pinned.end(), w)) continue;
+      victims.push_back(w);
+      freed += vbytes(w);
+    }
+    for (int64_t w : victims) evict(w);
+  }
+
   // simMallocOffld: make room by evicting a window of adjacent blocks, none of them pinned
   tn_status sim_malloc_offld(int64_t m, const std::vector<int64_t>& pinned) {
     const uint64_t size = vbytes(m);
@@ -390,6 +406,7 @@ struct Compiler {
                                             : it->first + it->second.size - size;
         if (off < it->first || off + size > it->first + it->second.size) off = it->first;
         place(it, off, m);
+        evict_ahead(pinned);
         return TN_OK;
       }
       // nothing can be evicted to make room: take back reservations made ahead of the execution,

@@ -20,6 +20,7 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <set>
 
 #include "graph.h"
 #include "kernels.h"
@@ -147,6 +148,7 @@ struct tn_executor {
   // per run
   std::vector<int64_t> remaining, last_order, arena_off;
   std::map<uint64_t, ArenaBlock> arena_map;
+  std::map<uint64_t, std::set<uint64_t>> arena_free;  // size -> offsets of the free blocks of that size
   std::vector<hipEvent_t> prof_events;
   std::vector<int> prof_family;
   // host buffers already found to be GPU-addressable pinned memory (start, end)
@@ -347,18 +349,29 @@ tn_status build_tables(tn_executor& ex) {
   return TN_OK;
 }
 
-// first-fit host arena with coalescing; offsets are 256-byte aligned
+// host arena with coalescing; offsets are 256-byte aligned.  Free blocks are indexed by size, so
+// that an allocation takes the lowest free block of the smallest sufficient size in O(log n): a
+// run that offloads tens of thousands of tensors cannot afford to walk over the used ones.
+void arena_index_add(tn_executor& ex, uint64_t off, uint64_t size) { ex.arena_free[size].insert(off); }
+void arena_index_del(tn_executor& ex, uint64_t off, uint64_t size) {
+  auto it = ex.arena_free.find(size);
+  it->second.erase(off);
+  if (it->second.empty()) ex.arena_free.erase(it);
+}
+
 bool arena_alloc(tn_executor& ex, uint64_t size, uint64_t* off) {
   size = (size + 255) / 256 * 256;
-  for (auto it = ex.arena_map.begin(); it != ex.arena_map.end(); ++it) {
-    if (it->second.used || it->second.size < size) continue;
-    const uint64_t o = it->first, rest = it->second.size - size;
-    it->second = {size, true};
-    if (rest) ex.arena_map[o + size] = {rest, false};
-    *off = o;
-    return true;
+  auto f = ex.arena_free.lower_bound(size);
+  if (f == ex.arena_free.end()) return false;
+  const uint64_t o = *f->second.begin(), have = f->first;
+  arena_index_del(ex, o, have);
+  ex.arena_map[o] = {size, true};
+  if (have > size) {
+    ex.arena_map[o + size] = {have - size, false};
+    arena_index_add(ex, o + size, have - size);
   }
-  return false;
+  *off = o;
+  return true;
 }
 
 void arena_free(tn_executor& ex, uint64_t off) {
@@ -366,16 +379,20 @@ void arena_free(tn_executor& ex, uint64_t off) {
   it->second.used = false;
   auto nx = std::next(it);
   if (nx != ex.arena_map.end() && !nx->second.used) {
+    arena_index_del(ex, nx->first, nx->second.size);
     it->second.size += nx->second.size;
     ex.arena_map.erase(nx);
   }
   if (it != ex.arena_map.begin()) {
     auto pv = std::prev(it);
     if (!pv->second.used) {
+      arena_index_del(ex, pv->first, pv->second.size);
       pv->second.size += it->second.size;
       ex.arena_map.erase(it);
+      it = pv;
     }
   }
+  arena_index_add(ex, it->first, it->second.size);
 }
 
 // True if [p, p+bytes) is pinned host memory that kernels can address.  Ranges found once are
@@ -598,7 +615,11 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   ex->last_order.clear();
   ex->last_order.reserve(nv);
   ex->arena_map.clear();
-  if (ex->arena_bytes) ex->arena_map[0] = {ex->arena_bytes, false};
+  ex->arena_free.clear();
+  if (ex->arena_bytes) {
+    ex->arena_map[0] = {ex->arena_bytes, false};
+    ex->arena_free[ex->arena_bytes].insert(0);
+  }
   std::fill(ex->arena_off.begin(), ex->arena_off.end(), -1);
   for (auto& sl : ex->slots) {
     sl.busy = false;

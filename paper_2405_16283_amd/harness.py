@@ -167,7 +167,7 @@ class GpuSession:
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
-                 lora_rank: int = 0, train: bool = False):
+                 lora_rank: int = 0, train: bool = False, progress=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -176,8 +176,11 @@ class GpuSession:
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
                                                        lora_rank, train))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
+        say = progress or (lambda msg: None)
+        say("taskgraph built")
         self.mg = B.tn_compile(self.tg, order, self.cap, compile_opts)
         self.stats = B.tn_memgraph_stats(self.mg)
+        say("memgraph compiled")
         self.n_task = B.tn_taskgraph_num_vertices(self.tg)
         self.elem = np.float32 if cfg.dtype == "f32" else np.uint16
         # inputs: one pinned slab, tiles back to back (256-byte aligned); input vertices bound to
@@ -205,6 +208,7 @@ class GpuSession:
                 np.copyto(dst.reshape(c1 - c0, r1 - r0), tile.T)
             else:
                 np.copyto(dst.reshape(r1 - r0, c1 - c0), tile)
+        say("input tiles cut into pinned memory")
         self.in_ptrs = [0] * self.n_task
         base = self.in_slab.data_ptr()
         for v, off in offs.items():
@@ -222,6 +226,7 @@ class GpuSession:
         self.streams = [torch.cuda.Stream(device="cuda:0") for _ in range(n_compute + 2)]
         torch.cuda.synchronize()
         handles = [s.cuda_stream for s in self.streams]
+        say("device buffer and streams ready")
         self.ex = B.tn_executor_create(self.mg, self.dev.data_ptr(), self.cap, 0, arena_bytes,
                                        handles[:n_compute], handles[n_compute], handles[n_compute + 1])
 
