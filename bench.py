@@ -69,7 +69,9 @@ def main():
     ap.add_argument("--no-capped", action="store_true", help=argparse.SUPPRESS)  # the default now
     ap.add_argument("--order", default="tiler", choices=["tiler", "level"],
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
-    ap.add_argument("--evict-ahead-mb", type=int, default=0, help="compile option evict_ahead_bytes in MiB")
+    ap.add_argument("--evict-ahead-mb", type=int, default=-1,
+                    help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/32 of the cap")
+    ap.add_argument("--next-fit", type=int, default=-1, help="compile option next_fit; default 0, for the fine-tuning step 1")
     ap.add_argument("--cap-gb", type=float, default=0.0, help="GPU-memory cap in GB instead of the workload's own")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
@@ -133,8 +135,9 @@ def main():
             tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train))
             order = H.level_major_order(tg)
             B.tn_taskgraph_destroy(tg)
-        ahead = args.evict_ahead_mb << 20
-        copts = B.tn_compile_opts(max_lookahead_bytes=(1 << 64) - 1, drop_clean_inputs=1, evict_ahead_bytes=ahead)
+        ahead = args.evict_ahead_mb << 20 if args.evict_ahead_mb >= 0 else ((c.cap_bytes or 0) // 32 if train else 0)
+        next_fit = args.next_fit if args.next_fit >= 0 else int(train)
+        copts = B.tn_compile_opts(max_lookahead_bytes=(1 << 64) - 1, drop_clean_inputs=1, evict_ahead_bytes=ahead, next_fit=next_fit)
         return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                             lora_rank=16 if train else 0, train=train, progress=note)
 

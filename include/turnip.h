@@ -260,6 +260,12 @@ typedef struct {
    * a batch lets the transfers of the batch, and then the kernels that take the freed places, go
    * together.  0 = as in Algorithm 2. */
   uint64_t evict_ahead_bytes;
+  /* Where simMalloc looks for an open range (Algorithm 2 leaves it open).  0: first fit, the lowest
+   * address, which packs memory tightly but hands a tensor the place that was vacated most recently
+   * in that region, so that consecutive parts of the computation wait on each other's memory.
+   * 1: next fit, the lowest address above the place given out last, wrapping round, so that a place
+   * rests for as long as possible before it is used again. */
+  int32_t next_fit;
 } tn_compile_opts;
 
 /* Compiles tg for gpu_cap_bytes of GPU memory.  order: a permutation of all vertex ids that

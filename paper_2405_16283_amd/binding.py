@@ -70,7 +70,7 @@ class tn_llama_binding(C.Structure):
 class tn_compile_opts(C.Structure):
     _fields_ = [("max_lookahead_bytes", C.c_uint64), ("drop_clean_inputs", C.c_int32),
                 ("fix_order", C.c_int32), ("prune_superfluous", C.c_int32), ("alignment", C.c_uint32),
-                ("evict_ahead_bytes", C.c_uint64)]
+                ("evict_ahead_bytes", C.c_uint64), ("next_fit", C.c_int32)]
 
 
 class tn_mg_vertex(C.Structure):

@@ -57,7 +57,7 @@ struct Compiler {
   std::map<uint64_t, uint64_t> free_at;                      // the free blocks alone: offset -> size
   std::map<uint64_t, std::set<uint64_t>> free_by_size;       // size -> offsets of the free blocks of that size
   int64_t execHzn = 0, allocHzn = 0, lookahead_blocked_until = -1, compacted_at = -1;
-  uint64_t lookahead_bytes = 0, live_bytes = 0;
+  uint64_t lookahead_bytes = 0, live_bytes = 0, cursor = 0;
   std::vector<int64_t> step_pre;  // offloads and reloads inserted just before V[execHzn], in the order made
 
   Compiler(const TaskGraph& t, const tn_compile_opts& o, MemGraph& m)
@@ -206,7 +206,15 @@ struct Compiler {
     if (from == free_by_size.end()) return false;
     if (size >= kSmallTensor) {
       uint64_t best = UINT64_MAX;
-      for (auto it = from; it != free_by_size.end(); ++it) best = std::min(best, *it->second.begin());
+      if (opt.next_fit) {  // lowest address at or above the cursor, else wrap round
+        for (auto it = from; it != free_by_size.end(); ++it) {
+          auto lb = it->second.lower_bound(cursor);
+          if (lb != it->second.end()) best = std::min(best, *lb);
+        }
+      }
+      if (best == UINT64_MAX)
+        for (auto it = from; it != free_by_size.end(); ++it) best = std::min(best, *it->second.begin());
+      cursor = best + size;
       place(blocks.find(best), best, m);
     } else {  // at the top end of the highest hole
       uint64_t best = 0, bsz = 0;
@@ -295,7 +303,7 @@ struct Compiler {
   // evict more than the allocation at hand needs (tn_compile_opts::evict_ahead_bytes)
   void evict_ahead(const std::vector<int64_t>& pinned) {
     if (!opt.evict_ahead_bytes) return;
-    constexpr int64_t kFarAhead = 4096;  // vertices of the serial order
+    constexpr int64_t kFarAhead = 30000;  // vertices of the serial order
     uint64_t freed = 0;
     std::vector<int64_t> victims;
     for (auto c = by_use.rbegin(); c != by_use.rend() && freed < opt.evict_ahead_bytes; ++c) {
