@@ -144,12 +144,35 @@ def test_c1_thousand_random_orders():
         B.tn_taskgraph_destroy(tg)
 
 
+@pytest.mark.parametrize("name", ["c1", "batch2_f32", "ragged_bf16"])
+def test_fine_tuning_memgraph_under_the_cap_is_correct_in_every_sampled_order(name):
+    """Forward with adapters + reverse pass: saved activations are what the cap pushes out."""
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=8, train=True))
+    try:
+        cap = H.cap_for(cfg, tg)
+        for opts in (None, B.tn_compile_opts(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, next_fit=1,
+                                             evict_ahead_bytes=cap // 16)):
+            mg = B.tn_compile(tg, None, cap, opts)
+            try:
+                st = B.tn_memgraph_stats(mg)
+                assert st.n_offload > 0 and st.high_water <= cap
+                check_all(task_preds(tg), oracle_memgraph(mg), n_random=12, seed=3)
+            finally:
+                B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
 @pytest.mark.parametrize("opts", [
     dict(max_lookahead_bytes=0, drop_clean_inputs=1),
     dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=0),
     dict(max_lookahead_bytes=200_000, drop_clean_inputs=1, prune_superfluous=1),
     dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, fix_order=1),
     dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, alignment=4096),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, next_fit=1),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, evict_ahead_bytes=100_000),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=0, evict_ahead_bytes=300_000, next_fit=1),
 ])
 def test_compile_options_keep_the_memgraph_correct(opts):
     cfg, tg, mg, cap = _compile_llama("ragged_f32", opts=B.tn_compile_opts(**opts))
@@ -265,7 +288,8 @@ def test_every_order_of_tiny_random_graphs(seed):
     need = max(sum(sizes[u] for u in set(preds[v])) + sizes[v] for v in range(n))
     try:
         mg = B.tn_compile(tg, None, need + unit * int(rng.integers(0, 2)),
-                          B.tn_compile_opts(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=seed % 2, alignment=64))
+                          B.tn_compile_opts(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=seed % 2, alignment=64,
+                                            next_fit=(seed // 2) % 2, evict_ahead_bytes=unit * ((seed // 4) % 2)))
         omg = oracle_memgraph(mg)
         B.tn_memgraph_destroy(mg)
         if len(omg) > 11:

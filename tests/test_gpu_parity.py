@@ -112,6 +112,7 @@ def test_launch_order_respects_every_dependency():
     dict(max_lookahead_bytes=0, drop_clean_inputs=1),
     dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=0),
     dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, fix_order=1),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, next_fit=1, evict_ahead_bytes=200_000),
 ])
 def test_compile_variants_on_the_gpu(opts):
     cfg = config("ragged_f32")
