@@ -37,7 +37,7 @@ def _f64(a):
     return bf16_bits_to_f32(a).astype(np.float64)
 
 
-@pytest.mark.parametrize("name,PREFIX,distinct,kv", [("c3", 256, 4, True), ("c4", 64, 2, False)])
+@pytest.mark.parametrize("name,PREFIX,distinct,kv", [("c3", 256, 4, True), ("c4", 16, 2, False)])
 def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, kv):
     cfg = config(name)
     last = cfg.layers - 1
