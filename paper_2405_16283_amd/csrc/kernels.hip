@@ -1,5 +1,6 @@
 // gfx950 task kernels of the memgraph runtime: tile GEMMs, blocked attention with online
-// softmax, attention combine, RMSNorm (statistic + apply), rotary embedding, SiLU*mul, add.
+// softmax, attention combine, RMSNorm (statistic + apply), rotary embedding, SiLU*mul, add, their
+// reverse-mode counterparts for the fine-tuning workload, transposition, and grouped copies.
 //
 // The paper runs such vertices through a vendor tensor library plus a few hand-written kernels
 // (Appendix A); here every vertex kind has its own kernel, written for 64-wide wavefronts and
