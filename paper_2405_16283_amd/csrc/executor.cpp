@@ -322,7 +322,7 @@ tn_status build_tables(tn_executor& ex) {
         // heads inside one column tile, and 8-row groups that straddle nothing
         vi.cls = (d.dtype == TN_BF16 && !x.p.v_trans && (x.p.mode == 0 || x.p.trans_a) && tc % hd == 0 && tq % 8 == 0 &&
                   tk % 8 == 0 && q_rows % 8 == 0 && kv_rows % 8 == 0 && q_rows >= 8 && kv_rows >= 8)
-                     ? LC_ATTN_BWD_BF16 : LC_ATTN_BWD;
+                     ? (int8_t)(LC_ATTN_BWD_BF16 + x.p.mode) : (int8_t)LC_ATTN_BWD;
         vi.head_dim = (int16_t)hd;
         vi.flops = (x.p.mode == 3 ? 4.0 : 6.0) * q_rows * kv_rows * (double)(nc * tc);
         break;
@@ -431,7 +431,10 @@ int family_of(int cls) {
     case LC_ATTN_F32:
     case LC_ATTN_BF16:
     case LC_ATTN_BWD:
-    case LC_ATTN_BWD_BF16: return 1;
+    case LC_ATTN_BWD_BF16:
+    case LC_ATTN_BWD_BF16_DQ:
+    case LC_ATTN_BWD_BF16_DK:
+    case LC_ATTN_BWD_BF16_DV: return 1;
     default: return 2;
   }
 }

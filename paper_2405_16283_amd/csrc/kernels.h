@@ -44,7 +44,10 @@ enum LaunchClass {
   LC_RMS_BWD_STAT,
   LC_RMS_BWD_APPLY,
   LC_ATTN_BWD,       // attention backward on the vector ALUs (statistics, dQ, dK, dV)
-  LC_ATTN_BWD_BF16,  // MFMA attention backward
+  LC_ATTN_BWD_BF16,  // MFMA attention backward: statistics; the next three values are its dQ, dK and dV forms
+  LC_ATTN_BWD_BF16_DQ,
+  LC_ATTN_BWD_BF16_DK,
+  LC_ATTN_BWD_BF16_DV,
   LC_TRANSPOSE,
   LC_COUNT
 };

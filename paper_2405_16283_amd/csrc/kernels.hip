@@ -836,17 +836,26 @@ __global__ void __launch_bounds__(64) attn_bwd_kernel(DeviceTables t, Batch b) {
 // Modes 2 (dK) and 3 (dV): one workgroup = one head x 128 keys, a lane owns a key; per 32 queries
 // S = Q K^T and dP = dO V^T with the query rows permuted likewise, and dK^T += Q^T dS,
 // dV^T += dO^T P read rows of Q^T / dO^T tiles.
-// Fragments are read straight from global memory (the four wavefronts of a workgroup read the
-// same tiles, so they meet in the L1); probabilities and dS enter the MFMA as single bf16.
+// The four wavefronts of a workgroup need the same rows of the other side: the workgroup brings
+// them in 64 rows at a time through LDS (rows padded by 16 bytes against bank conflicts), together
+// with the statistics of those rows.  Probabilities and dS enter the MFMA as single bf16.
 // aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
 // ---------------------------------------------------------------------------------------------
-template <int HD>
-__global__ void __launch_bounds__(256) attn_bwd_bf16_kernel(DeviceTables t, Batch b) {
+constexpr int kAttnBwdThreads = 512, kAttnBwdRows = 256;  // eight wavefronts of 32 rows
+template <int HD, int mode>
+__global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
+  constexpr int CH = 64;             // rows of the other side per round
+  constexpr int LDA = HD + 8;        // padded row of a [CH][HD] chunk, in elements
+  constexpr int LDT = CH + 8;        // padded row of a transposed [HD][CH] chunk
+  __shared__ __attribute__((aligned(16))) bf16_t bufA[CH * LDA];  // K (modes 0, 1) or Q (modes 2, 3)
+  __shared__ __attribute__((aligned(16))) bf16_t bufB[CH * LDA];  // V or dO
+  __shared__ __attribute__((aligned(16))) bf16_t bufT[HD * LDT];  // K^T, Q^T or dO^T
+  __shared__ float bufS[CH * 2];                                  // lse * log2(e), D of the chunk's queries
   const int* ax = t.aux + d.aux0;
   const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
-  const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD, mode = d.p.mode;
+  const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD;  // mode (template) == d.p.mode: its own launch class
   const int nq = d.p.n_q_tiles, nkv = d.p.n_kv_tiles;
   void* const* Qt = t.ptrs + d.ptr0;
   void* const* Kt = Qt + nq * nc;
@@ -855,10 +864,10 @@ __global__ void __launch_bounds__(256) attn_bwd_bf16_kernel(DeviceTables t, Batc
   void* const* St = Dt + nq * nc;   // statistics per Q row tile (modes 1..3)
   void* const* Tt = St + nq;        // transposed grid (modes 1..3)
   const int my_rows = mode <= 1 ? q_rows : kv_rows;
-  const int rblocks = (my_rows + 127) / 128;
+  const int rblocks = (my_rows + kAttnBwdRows - 1) / kAttnBwdRows;
   const int h = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
-  const int myrow = rb * 128 + w * 32 + l32;  // this lane's query (modes 0, 1) or key (modes 2, 3)
+  const int myrow = rb * kAttnBwdRows + w * 32 + l32;  // this lane's query (modes 0, 1) or key (modes 2, 3)
   const bool valid = myrow < my_rows;
   constexpr float LOG2E = 1.44269504088896340736f, LN2 = 0.69314718055994530942f;
   const float scale = d.p.scale, scale2 = scale * LOG2E;
@@ -873,43 +882,86 @@ __global__ void __launch_bounds__(256) attn_bwd_bf16_kernel(DeviceTables t, Batc
     const int rt = r / tq;
     return ((const float*)St[rt])[(size_t)(r - rt * tq) * (2 * hpg) + which * hpg + h];
   };
+  // the other side: keys for modes 0 and 1, queries for modes 2 and 3
+  void* const* gridA = mode <= 1 ? Kt : Qt;
+  void* const* gridB = mode <= 1 ? Vt : Dt;
+  const int o_trows = mode <= 1 ? tk : tq, o_rows = mode <= 1 ? kv_rows : q_rows;
+  auto stage = [&](int row0) {  // rows [row0, row0 + CH) of the other side into LDS
+    constexpr int CPR = HD / 8;
+#pragma unroll
+    for (int k = 0; k < CH * CPR / kAttnBwdThreads; ++k) {
+      const int c = threadIdx.x + kAttnBwdThreads * k, r = c / CPR, c8 = (c % CPR) * 8;
+      const int gr = min(row0 + r, o_rows - 1);
+      *(uint4*)(bufA + r * LDA + c8) = *(const uint4*)tile_elem<bf16_t>(gridA, nc, o_trows, tc, gr, h * HD + c8);
+      if (mode != 3) *(uint4*)(bufB + r * LDA + c8) = *(const uint4*)tile_elem<bf16_t>(gridB, nc, o_trows, tc, gr, h * HD + c8);
+    }
+    if (mode >= 1) {
+#pragma unroll
+      for (int k = 0; k < HD * (CH / 8) / kAttnBwdThreads; ++k) {
+        const int c = threadIdx.x + kAttnBwdThreads * k, dd = c / (CH / 8), r8 = (c % (CH / 8)) * 8;
+        const int gr = min(row0 + r8, o_rows - 8);  // 8 rows at once; past the end any valid rows do (zero weights)
+        *(uint4*)(bufT + dd * LDT + r8) = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, o_trows, tc, o_rows, gr, h * HD + dd);
+      }
+    }
+    if (mode >= 2 && threadIdx.x < 2 * CH) {
+      const int r = threadIdx.x >> 1, which = threadIdx.x & 1;
+      const float v = stat(min(row0 + r, q_rows - 1), which);
+      bufS[r * 2 + which] = which ? v : v * LOG2E;
+    }
+  };
   f32x16 acc[HD / 32];
 #pragma unroll
   for (int i = 0; i < HD / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  if (mode <= 1) {
-    const int qrow = min(myrow, q_rows - 1), qpos = d.p.q_pos0 + myrow;
-    bf16x8 qf[HD / 16], dof[HD / 16];
+  bf16x8 mine[HD / 16], mine2[HD / 16];  // this lane's own row: Q and dO (modes 0, 1) or K and V (modes 2, 3)
+  {
+    const int r = min(myrow, my_rows - 1);
 #pragma unroll
     for (int s = 0; s < HD / 16; ++s) {
-      qf[s] = frag(Qt, tq, qrow, h * HD + s * 16 + g * 8);
-      dof[s] = frag(Dt, tq, qrow, h * HD + s * 16 + g * 8);
+      mine[s] = frag(mode <= 1 ? Qt : Kt, mode <= 1 ? tq : tk, r, h * HD + s * 16 + g * 8);
+      mine2[s] = frag(mode <= 1 ? Dt : Vt, mode <= 1 ? tq : tk, r, h * HD + s * 16 + g * 8);
     }
-    const float lse2 = mode == 1 ? stat(qrow, 0) * LOG2E : 0.f, Dq = mode == 1 ? stat(qrow, 1) : 0.f;
-    float m = -INFINITY, l = 0.f, dsum = 0.f;
-    int kv_end = kv_rows;
-    if (causal) kv_end = min(kv_rows, d.p.q_pos0 + rb * 128 + 128 - d.p.k_pos0);
-    for (int kv0 = 0; kv0 < kv_end; kv0 += 32) {
-      const int krow = min(kv0 + perm, kv_rows - 1);
-      f32x16 sT, dpT;
+  }
+  const int mypos = (mode <= 1 ? d.p.q_pos0 : d.p.k_pos0) + myrow;
+  float lse2 = 0.f, Dq = 0.f, m = -INFINITY, l = 0.f, dsum = 0.f;
+  if (mode == 1) {
+    lse2 = stat(min(myrow, q_rows - 1), 0) * LOG2E;
+    Dq = stat(min(myrow, q_rows - 1), 1);
+  }
+  // range of the other side that this workgroup can see at all
+  int begin = 0, end = o_rows;
+  if (causal && mode <= 1) end = min(kv_rows, d.p.q_pos0 + rb * kAttnBwdRows + kAttnBwdRows - d.p.k_pos0);
+  if (causal && mode >= 2) begin = max(0, d.p.k_pos0 + rb * kAttnBwdRows - d.p.q_pos0) & ~(CH - 1);
+
+  for (int row0 = begin; row0 < end; row0 += CH) {
+    __syncthreads();  // everybody is done with the previous chunk
+    stage(row0);
+    __syncthreads();
+#pragma unroll 1
+    for (int sub = 0; sub < CH / 32; ++sub) {
+      const int base = row0 + sub * 32;
+      if (base >= end) break;
+      const bf16_t* ra = bufA + (sub * 32 + perm) * LDA + g * 8;
+      const bf16_t* rbp = bufB + (sub * 32 + perm) * LDA + g * 8;
+      f32x16 sc, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int s = 0; s < HD / 16; ++s) {
-        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Kt, tk, krow, h * HD + s * 16 + g * 8), qf[s], sT, 0, 0, 0);
-        dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Vt, tk, krow, h * HD + s * 16 + g * 8), dof[s], dpT, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(ra + s * 16), mine[s], sc, 0, 0, 0);
+        if (mode != 3) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(rbp + s * 16), mine2[s], dp, 0, 0, 0);
       }
-      // register r of this lane: key kv0 + 16*(r>>3) + 8*g + (r&7)
+      // register r of this lane: row base + 16*(r>>3) + 8*g + (r&7) of the other side
       if (mode == 0) {
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int kv = kv0 + 16 * (r >> 3) + 8 * g + (r & 7);
-          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > qpos);
-          sT[r] = ok ? sT[r] * scale2 : -INFINITY;
-          mx = fmaxf(mx, sT[r]);
+          const int kv = base + 16 * (r >> 3) + 8 * g + (r & 7);
+          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > mypos);
+          sc[r] = ok ? sc[r] * scale2 : -INFINITY;
+          mx = fmaxf(mx, sc[r]);
         }
         const float mn = fmaxf(m, mx);
         if (mn != -INFINITY) {
@@ -917,90 +969,51 @@ __global__ void __launch_bounds__(256) attn_bwd_bf16_kernel(DeviceTables t, Batc
           float ls = 0.f, ds = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(sT[r] - mn);
+            const float p = __builtin_amdgcn_exp2f(sc[r] - mn);
             ls += p;
-            ds = fmaf(p, dpT[r], ds);
+            ds = fmaf(p, dp[r], ds);
           }
           l = l * alpha + ls;
           dsum = dsum * alpha + ds;
           m = mn;
         }
-      } else {
-        bf16x8 s0, s1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = kv0 + 16 * (r >> 3) + 8 * g + (r & 7);
-          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > qpos);
-          const float p = ok ? __builtin_amdgcn_exp2f(sT[r] * scale2 - lse2) : 0.f;
-          const __bf16 v = (__bf16)(p * (dpT[r] - Dq) * scale);
-          if (r < 8) s0[r] = v; else s1[r - 8] = v;
-        }
-        const int k0 = min(kv0 + 8 * g, kv_rows - 8), k1 = min(kv0 + 16 + 8 * g, kv_rows - 8);
-#pragma unroll
-        for (int i = 0; i < HD / 32; ++i) {
-          const int col = h * HD + i * 32 + l32;
-          uint4 u0 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tk, tc, kv_rows, k0, col);
-          uint4 u1 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tk, tc, kv_rows, k1, col);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u0, s0, acc[i], 0, 0, 0);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u1, s1, acc[i], 0, 0, 0);
-        }
+        continue;
       }
-    }
-    if (mode == 0) {
-      // the two halves of the wavefront saw different keys of the same query: merge their states
-      const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64), d2 = __shfl_xor(dsum, 32, 64);
-      const float mn = fmaxf(m, m2);
-      const float w1 = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mn), w2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
-      const float lt = l * w1 + l2 * w2, dt = dsum * w1 + d2 * w2;
-      if (valid && g == 0) {
-        float* out = (float*)d.out + (size_t)myrow * (2 * hpg);
-        out[h] = (mn + __builtin_amdgcn_logf(lt)) * LN2;
-        out[hpg + h] = dt / lt;
-      }
-      return;
-    }
-  } else {
-    const int krow = min(myrow, kv_rows - 1), kpos = d.p.k_pos0 + myrow;
-    bf16x8 kf[HD / 16], vf[HD / 16];
-#pragma unroll
-    for (int s = 0; s < HD / 16; ++s) {
-      kf[s] = frag(Kt, tk, krow, h * HD + s * 16 + g * 8);
-      vf[s] = frag(Vt, tk, krow, h * HD + s * 16 + g * 8);
-    }
-    int q_start = 0;  // queries before the first key of this workgroup see none of its keys
-    if (causal) q_start = max(0, d.p.k_pos0 + rb * 128 - d.p.q_pos0) & ~31;
-    for (int q0 = q_start; q0 < q_rows; q0 += 32) {
-      const int qrow = min(q0 + perm, q_rows - 1);
-      f32x16 sc, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int s = 0; s < HD / 16; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Qt, tq, qrow, h * HD + s * 16 + g * 8), kf[s], sc, 0, 0, 0);
-        if (mode == 2)
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Dt, tq, qrow, h * HD + s * 16 + g * 8), vf[s], dp, 0, 0, 0);
-      }
-      // register r of this lane: query q0 + 16*(r>>3) + 8*g + (r&7)
       bf16x8 s0, s1;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int q = q0 + 16 * (r >> 3) + 8 * g + (r & 7);
-        const bool ok = valid && q < q_rows && !(causal && kpos > d.p.q_pos0 + q);
-        const int qc = min(q, q_rows - 1);
-        const float p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - stat(qc, 0) * LOG2E) : 0.f;
-        const __bf16 v = (__bf16)(mode == 3 ? p : p * (dp[r] - stat(qc, 1)) * scale);
-        if (r < 8) s0[r] = v; else s1[r - 8] = v;
+        const int lr = sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7), o = row0 + lr;
+        float p;
+        if (mode == 1) {
+          const bool ok = o < kv_rows && !(causal && d.p.k_pos0 + o > mypos);
+          p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - lse2) * (dp[r] - Dq) * scale : 0.f;
+        } else {
+          const bool ok = valid && o < q_rows && !(causal && mypos > d.p.q_pos0 + o);
+          p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - bufS[lr * 2]) : 0.f;
+          if (mode == 2) p *= (dp[r] - bufS[lr * 2 + 1]) * scale;
+        }
+        if (r < 8) s0[r] = (__bf16)p; else s1[r - 8] = (__bf16)p;
       }
-      const int r0 = min(q0 + 8 * g, q_rows - 8), r1 = min(q0 + 16 + 8 * g, q_rows - 8);
 #pragma unroll
       for (int i = 0; i < HD / 32; ++i) {
-        const int col = h * HD + i * 32 + l32;
-        uint4 u0 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tq, tc, q_rows, r0, col);
-        uint4 u1 = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, tq, tc, q_rows, r1, col);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u0, s0, acc[i], 0, 0, 0);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8*)&u1, s1, acc[i], 0, 0, 0);
+        const bf16_t* tr = bufT + (i * 32 + l32) * LDT + sub * 32 + 8 * g;
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)tr, s0, acc[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(tr + 16), s1, acc[i], 0, 0, 0);
       }
     }
+  }
+  if (mode == 0) {
+    // the two halves of the wavefront saw different keys of the same query: merge their states
+    const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64), d2 = __shfl_xor(dsum, 32, 64);
+    const float mn = fmaxf(m, m2);
+    const float w1 = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mn), w2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+    const float lt = l * w1 + l2 * w2, dt = dsum * w1 + d2 * w2;
+    if (valid && g == 0) {
+      float* out = (float*)d.out + (size_t)myrow * (2 * hpg);
+      out[h] = (mn + __builtin_amdgcn_logf(lt)) * LN2;
+      out[hpg + h] = dt / lt;
+    }
+    return;
   }
   if (!valid) return;
   // accumulator tile i: this lane holds column myrow and rows (= head columns) 8a + 4g + k of it
@@ -1287,9 +1300,12 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
       const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
       return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], 64);
     }
-    case LC_ATTN_BWD_BF16: {
+    case LC_ATTN_BWD_BF16:
+    case LC_ATTN_BWD_BF16_DQ:
+    case LC_ATTN_BWD_BF16_DK:
+    case LC_ATTN_BWD_BF16_DV: {
       const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
-      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], 128);
+      return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + (d.p.mode <= 1 ? 3 : 4)], kAttnBwdRows);
     }
     default: return 0;
   }
@@ -1338,11 +1354,17 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
     case LC_SILU_BWD: TN_LAUNCH_T(silu_bwd_kernel); break;
     case LC_RMS_BWD_STAT: TN_LAUNCH_T(rms_bwd_stat_kernel); break;
     case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;
-    case LC_ATTN_BWD_BF16:
-      if (head_dim == 64) hipLaunchKernelGGL(attn_bwd_bf16_kernel<64>, grid, wg, 0, s, t, b);
-      else if (head_dim == 128) hipLaunchKernelGGL(attn_bwd_bf16_kernel<128>, grid, wg, 0, s, t, b);
-      else return hipErrorInvalidValue;
-      break;
+#define TN_LAUNCH_ATTN_BWD(MODE)                                                                                  \
+  do {                                                                                                            \
+    if (head_dim == 64) hipLaunchKernelGGL((attn_bwd_bf16_kernel<64, MODE>), grid, dim3(kAttnBwdThreads), 0, s, t, b);        \
+    else if (head_dim == 128) hipLaunchKernelGGL((attn_bwd_bf16_kernel<128, MODE>), grid, dim3(kAttnBwdThreads), 0, s, t, b); \
+    else return hipErrorInvalidValue;                                                                             \
+  } while (0)
+    case LC_ATTN_BWD_BF16: TN_LAUNCH_ATTN_BWD(0); break;
+    case LC_ATTN_BWD_BF16_DQ: TN_LAUNCH_ATTN_BWD(1); break;
+    case LC_ATTN_BWD_BF16_DK: TN_LAUNCH_ATTN_BWD(2); break;
+    case LC_ATTN_BWD_BF16_DV: TN_LAUNCH_ATTN_BWD(3); break;
+#undef TN_LAUNCH_ATTN_BWD
     case LC_ATTN_BWD:
       if (head_dim == 64) {
         if (bf) hipLaunchKernelGGL((attn_bwd_kernel<bf16_t, 64>), grid, dim3(64), 0, s, t, b);
