@@ -644,6 +644,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
       Grid w1n = own ? t.natural(TN_T_W1, l, t.dcols, t.fcols) : w.w1, w3n = own ? t.natural(TN_T_W3, l, t.dcols, t.fcols) : w.w3;
       Grid w2n = own ? t.natural(TN_T_W2, l, t.fcols, t.dcols) : w.w2;
       // operands of the adapter gradients, summed over all rows of all sequences
+      // (all transposed, so that the sums over the rows are plain A B^T products over K = rows)
       std::vector<tn_vid> all_tq, all_tv, all_dtq, all_dtv;
       std::vector<std::vector<tn_vid>> a_cols(nd), dq_cols(nd), dv_cols(nd);
       for (int b = 0; b < c.batch; ++b) {
@@ -775,24 +776,29 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           for (size_t j = 0; j < nd; ++j)
             dy[b][i][j] = t.op(TN_OP_RMS_BWD_APPLY, pa, {da[j], sv.xin[i][j], sv.rstd1[i], dot1, w.g1[j], dh1[i][j]},
                                {c.dtype, m, t.dcols[j].len()});
-          all_tq.push_back(sv.tq[i]);
-          all_tv.push_back(sv.tv[i]);
-          all_dtq.push_back(dtq);
-          all_dtv.push_back(dtv);
+          auto tr = [&](tn_vid x, int32_t rws, int32_t cls) {  // x is [rws, cls]
+            return t.op(TN_OP_TRANSPOSE, tn_op_params{}, {x}, {c.dtype, cls, rws});
+          };
+          all_tq.push_back(tr(sv.tq[i], m, rk));
+          all_tv.push_back(tr(sv.tv[i], m, rk));
+          all_dtq.push_back(tr(dtq, m, rk));
+          all_dtv.push_back(tr(dtv, m, rk));
           for (size_t j = 0; j < nd; ++j) {
-            a_cols[j].push_back(sv.a[i][j]);
-            dq_cols[j].push_back(dq[i][j]);
-            dv_cols[j].push_back(dv[i][j]);
+            const int32_t n = t.dcols[j].len();
+            a_cols[j].push_back(tr(sv.a[i][j], m, n));
+            dq_cols[j].push_back(tr(dq[i][j], m, n));
+            dv_cols[j].push_back(tr(dv[i][j], m, n));
           }
         }
       }
-      // adapter gradients: dA = a^T dt, dB = t^T dq, summed over every row of every sequence
+      // adapter gradients: dA = a^T dt = (a^T)(dt^T)^T, dB = t^T dq = (t^T)(dq^T)^T, summed over every row of
+      // every sequence
       for (size_t j = 0; j < nd; ++j) {
         const int32_t n = t.dcols[j].len();
-        t.mark_output(t.gemm_list(a_cols[j], all_dtq, n, rk, true, false), TN_T_DAQ, l, t.dcols[j], rkr);
-        t.mark_output(t.gemm_list(all_tq, dq_cols[j], rk, n, true, false), TN_T_DBQ, l, rkr, t.dcols[j]);
-        t.mark_output(t.gemm_list(a_cols[j], all_dtv, n, rk, true, false), TN_T_DAV, l, t.dcols[j], rkr);
-        t.mark_output(t.gemm_list(all_tv, dv_cols[j], rk, n, true, false), TN_T_DBV, l, rkr, t.dcols[j]);
+        t.mark_output(t.gemm_list(a_cols[j], all_dtq, n, rk, false, true), TN_T_DAQ, l, t.dcols[j], rkr);
+        t.mark_output(t.gemm_list(all_tq, dq_cols[j], rk, n, false, true), TN_T_DBQ, l, rkr, t.dcols[j]);
+        t.mark_output(t.gemm_list(a_cols[j], all_dtv, n, rk, false, true), TN_T_DAV, l, t.dcols[j], rkr);
+        t.mark_output(t.gemm_list(all_tv, dv_cols[j], rk, n, false, true), TN_T_DBV, l, rkr, t.dcols[j]);
       }
     }
     for (int b = 0; b < c.batch; ++b)
