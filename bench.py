@@ -75,6 +75,7 @@ def main():
     ap.add_argument("--cap-gb", type=float, default=0.0, help="GPU-memory cap in GB instead of the workload's own")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
+    ap.add_argument("--transfer-depth", type=int, default=0)
     ap.add_argument("--train", type=int, default=-1,
                     help="1: fine-tuning step (adapters of rank 16 on q and v, probe loss, reverse pass); default: only for c5")
     ap.add_argument("--layers", type=int, default=0, help="run the workload's shape with this many layers instead of its own")
@@ -151,14 +152,16 @@ def main():
     engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
     opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
                           max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
-                          copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7)
+                          copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
+                          transfer_depth=args.transfer_depth)
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
     plain = timed(s, max(1, min(3, args.steps), args.steps // 4), 1 if args.steps > 1 else 0, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
                                                                 max_transfers=args.max_transfers,
                                                                 max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth,
-                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7))
+                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
+                          transfer_depth=args.transfer_depth))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs(only=["y"])["y"]
     st = s.stats

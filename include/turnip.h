@@ -356,6 +356,8 @@ typedef struct {
                             launched when its dependencies have completed.  >1: it may be enqueued once the
                             kernels it depends on are enqueued, ordered on the device by stream events;
                             dependencies on transfers are always awaited on the host. */
+  int32_t transfer_depth;  /* groups of copies in flight per direction (1..8; 0 = 3): the next group is enqueued
+                              while the host has not yet seen the previous one complete */
   int32_t copy_workgroups; /* TN_COPY_KERNEL: workgroups of a copy launch (each walks over 32 KiB pieces of the
                               group's tensors); 0 = default (8) */
 } tn_exec_opts;

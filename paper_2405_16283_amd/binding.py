@@ -95,7 +95,8 @@ class tn_exec_opts(C.Structure):
     _fields_ = [("policy", C.c_int32), ("order_seed", C.c_uint64), ("delay_seed", C.c_uint64),
                 ("max_delay_us", C.c_uint32), ("max_batch", C.c_int32), ("profile", C.c_int32),
                 ("max_transfers", C.c_int32), ("copy_engine", C.c_int32),
-                ("max_gemm_inflight", C.c_int32), ("queue_depth", C.c_int32), ("copy_workgroups", C.c_int32)]
+                ("max_gemm_inflight", C.c_int32), ("queue_depth", C.c_int32), ("transfer_depth", C.c_int32),
+                ("copy_workgroups", C.c_int32)]
 
 
 class tn_exec_report(C.Structure):

@@ -58,6 +58,14 @@ struct Group {  // one grouped kernel launch in flight on a compute stream
   int family = 0, prof = -1;
 };
 
+struct XGroup {  // one group of copies in flight on a copy stream
+  std::vector<int64_t> verts;
+  hipEvent_t done = nullptr;
+  int prof = -1;
+  bool event_seen = false;
+  Clock::time_point release;
+};
+
 struct ArenaBlock {
   uint64_t size;
   bool used;
@@ -129,6 +137,7 @@ struct tn_executor {
   int n_compute = 0;
   std::vector<Slot> slots;  // compute streams, then h2d, then d2h
   std::vector<std::vector<hipEvent_t>> cevents;  // per compute stream: ring of completion events
+  hipEvent_t xevents[2][kMaxQueueDepth] = {};    // per copy direction: ring of completion events
   std::vector<std::deque<Group>> cqueue;         // per compute stream: groups in flight, oldest first
   std::vector<int64_t> pred_start, pred;         // CSR of predecessors
   // device tables
@@ -511,6 +520,11 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
       if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)));
       ex->cevents[i].push_back(ev);
     }
+  for (int dir = 0; dir < 2; ++dir)
+    for (int k = 0; k < kMaxQueueDepth; ++k) {
+      hipError_t e = hipEventCreateWithFlags(&ex->xevents[dir][k], hipEventDisableTiming);
+      if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)));
+    }
   ex->arena_off.assign(nv, -1);
   tn_status s = build_tables(*ex);
   if (s != TN_OK) return bail(s);
@@ -549,6 +563,9 @@ void tn_executor_destroy(tn_executor* ex) {
   for (auto e : ex->prof_events) (void)hipEventDestroy(e);
   for (auto& ring : ex->cevents)
     for (auto e : ring) (void)hipEventDestroy(e);
+  for (auto& ring : ex->xevents)
+    for (auto e : ring)
+      if (e) (void)hipEventDestroy(e);
   if (ex->d_descs) (void)hipFree(ex->d_descs);
   if (ex->d_ptrs) (void)hipFree(ex->d_ptrs);
   if (ex->d_aux) (void)hipFree(ex->d_aux);
@@ -729,23 +746,27 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   const auto t_start = Clock::now();
   Batch batch;
   CopyBatch copies;
-  std::vector<int64_t> same;
+  std::deque<XGroup> xq[2];  // copy groups in flight, host to device and device to host
+  int xring[2] = {0, 0};
+  const int xdepth = std::max(1, std::min<int>(opt.transfer_depth > 0 ? opt.transfer_depth : 3, kMaxQueueDepth));
+  std::vector<int64_t> same, xverts;
   std::vector<hipEvent_t> waited;
 
   while (completed < nv && status == TN_OK) {
     bool progressed = false;
-    // ---- launch transfers: per direction one group of copies at a time
+    // ---- launch transfers: per direction a few groups of copies in flight, so that the stream
+    // does not run dry while the host looks at the completion of the previous group
     for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
       Slot& sl = ex->slots[ex->n_compute + dir];
       ReadyQueue& r = rq_x[dir];
       const std::vector<int64_t>& serial = ex->serial[1 + dir];
-      if (sl.busy || n_ready_x[dir] == 0) continue;
-      sl.verts.clear();
-      sl.bytes = 0;
+      if ((int)xq[dir].size() >= xdepth || n_ready_x[dir] == 0) continue;
+      std::vector<int64_t>& tv = xverts;
+      tv.clear();
       copies.n = 0;
       copies.total_blocks = 0;
       hipError_t e = hipSuccess;
-      while (n_ready_x[dir] > 0 && (int)sl.verts.size() < max_xfer && e == hipSuccess) {
+      while (n_ready_x[dir] > 0 && (int)tv.size() < max_xfer && e == hipSuccess) {
         int64_t m;
         if (in_order) {  // the next transfer of this direction in the serial order, or none
           m = serial[serial_next[1 + dir]];
@@ -768,8 +789,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         } else {  // offload
           uint64_t off;
           if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
-            if (!sl.verts.empty()) break;  // let the copies already queued (and later reloads) free slots
-            if (ex->slots[ex->n_compute].busy || n_ready_x[0] > 0) break;
+            if (!tv.empty() || !xq[1].empty()) break;  // let the copies already queued (and later reloads) free slots
+            if (!xq[0].empty() || n_ready_x[0] > 0) break;
             status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
                           (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
             break;
@@ -795,35 +816,33 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           r.pop();
         }
         --n_ready_x[dir];
-        sl.verts.push_back(m);
-        sl.bytes += (double)x.bytes;
+        tv.push_back(m);
         (dir == 0 ? rep.h2d_bytes : rep.d2h_bytes) += x.bytes;
         rep.n_reload += x.kind == TN_MG_RELOAD;
         ex->last_order.push_back(m);
       }
       if (status != TN_OK) break;
-      if (sl.verts.empty() && e == hipSuccess) continue;
-      sl.prof = -1;
+      if (tv.empty() && e == hipSuccess) continue;
+      XGroup xg;
+      xg.done = ex->xevents[dir][xring[dir]];
+      xring[dir] = (xring[dir] + 1) % kMaxQueueDepth;
       if (e == hipSuccess && opt.profile) {
         hipEvent_t a, b2;
-        if (prof_event(&a) && prof_event(&b2)) {
-          sl.prof = (int)prof_used - 2;
-          // the start stamp goes after whatever the stream still carries; a group's copies are
-          // queued behind it
-        }
+        // the start stamp goes after whatever the stream still carries; the group's copies are
+        // queued behind it
+        if (prof_event(&a) && prof_event(&b2)) xg.prof = (int)prof_used - 2;
       }
-      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof], sl.stream);
+      if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
       if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, opt.copy_workgroups, sl.stream);
-      if (e == hipSuccess && sl.prof >= 0) e = hipEventRecord(ex->prof_events[sl.prof + 1], sl.stream);
-      if (e == hipSuccess) e = hipEventRecord(sl.done, sl.stream);
+      if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof + 1], sl.stream);
+      if (e == hipSuccess) e = hipEventRecord(xg.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }
-      sl.busy = true;
-      sl.event_seen = false;
-      sl.family = 3 + dir;
-      if (sl.prof >= 0) {
-        ex->prof_family.push_back(sl.family);
-        ex->prof_family.push_back(sl.prof);
+      if (xg.prof >= 0) {
+        ex->prof_family.push_back(3 + dir);
+        ex->prof_family.push_back(xg.prof);
       }
+      xg.verts = tv;
+      xq[dir].push_back(std::move(xg));
       ++rep.n_launches;
       progressed = true;
     }
@@ -981,37 +1000,39 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       }
     }
     for (int dir = 0; dir < 2 && status == TN_OK; ++dir) {
-      Slot& sl = ex->slots[ex->n_compute + dir];
-      if (!sl.busy) continue;
-      if (!sl.event_seen) {
-        hipError_t e = hipEventQuery(sl.done);
-        if (e == hipErrorNotReady) continue;
-        if (e != hipSuccess) { hip_fail("hipEventQuery", e); break; }
-        sl.event_seen = true;
-        sl.release = Clock::now();
-        if (opt.max_delay_us) {
-          // injected transfer delay: the completion is reported late; the copy itself ran normally
-          const uint64_t us = mix64(opt.delay_seed ^ (uint64_t)sl.verts[0] * 0x9E3779B1ull) % (opt.max_delay_us + 1ull);
-          sl.release += std::chrono::microseconds(us);
+      while (!xq[dir].empty()) {  // a stream finishes its groups in order
+        XGroup& g = xq[dir].front();
+        if (!g.event_seen) {
+          hipError_t e = hipEventQuery(g.done);
+          if (e == hipErrorNotReady) break;
+          if (e != hipSuccess) { hip_fail("hipEventQuery", e); break; }
+          g.event_seen = true;
+          g.release = Clock::now();
+          if (opt.max_delay_us) {
+            // injected transfer delay: the completion is reported late; the copy itself ran normally
+            const uint64_t us = mix64(opt.delay_seed ^ (uint64_t)g.verts[0] * 0x9E3779B1ull) % (opt.max_delay_us + 1ull);
+            g.release += std::chrono::microseconds(us);
+          }
         }
-      }
-      if (Clock::now() < sl.release) continue;
-      sl.busy = false;
-      for (int64_t m : sl.verts) {
-        const MVertex& x = mg.v[m];
-        if (x.kind == TN_MG_RELOAD) {
-          const int64_t o = x.operands[0];
-          arena_free(*ex, (uint64_t)ex->arena_off[o]);
-          arena_used -= (mg.v[o].bytes + 255) / 256 * 256;
-          ex->arena_off[o] = -1;
+        if (Clock::now() < g.release) break;
+        XGroup done = std::move(g);
+        xq[dir].pop_front();
+        for (int64_t m : done.verts) {
+          const MVertex& x = mg.v[m];
+          if (x.kind == TN_MG_RELOAD) {
+            const int64_t o = x.operands[0];
+            arena_free(*ex, (uint64_t)ex->arena_off[o]);
+            arena_used -= (mg.v[o].bytes + 255) / 256 * 256;
+            ex->arena_off[o] = -1;
+          }
+          complete(m);
         }
-        complete(m);
+        progressed = true;
       }
-      progressed = true;
     }
     if (!progressed) {
       bool any_busy = false;
-      for (auto& sl : ex->slots) any_busy |= sl.busy;
+      any_busy = !xq[0].empty() || !xq[1].empty();
       for (auto& q : ex->cqueue) any_busy |= !q.empty();
       if (!any_busy && n_ready_k == 0 && n_ready_x[0] == 0 && n_ready_x[1] == 0 && completed < nv) {
         status = fail(TN_ERR_CYCLE, "no vertex is ready and none is running: %lld of %lld completed",
@@ -1021,10 +1042,10 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     }
   }
   // drain whatever is still in flight (error paths): every stream the run used is idle on return
-  for (auto& sl : ex->slots)
-    if (sl.busy) {
-      (void)hipStreamSynchronize(sl.stream);
-      sl.busy = false;
+  for (int dir = 0; dir < 2; ++dir)
+    if (!xq[dir].empty()) {
+      (void)hipStreamSynchronize(ex->slots[ex->n_compute + dir].stream);
+      xq[dir].clear();
     }
   for (int si = 0; si < ex->n_compute; ++si)
     if (!ex->cqueue[si].empty()) {
