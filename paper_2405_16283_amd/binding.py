@@ -318,8 +318,18 @@ def tn_executor_destroy(ex):
     lib().tn_executor_destroy(ex)
 
 
-def _ptr_array(ptrs: Sequence[int]):
-    return (_P * max(1, len(ptrs)))(*[_P(p) if p else None for p in ptrs])
+def ptr_array(ptrs: Sequence[int]):
+    """A C array of pointers from integer addresses (0 = NULL).  Callers that execute the same
+    graph many times build it once and pass it in place of the list."""
+    a = (_P * max(1, len(ptrs)))()
+    for i, p in enumerate(ptrs):
+        if p:
+            a[i] = p
+    return a
+
+
+def _ptr_array(ptrs):
+    return ptrs if isinstance(ptrs, C.Array) else ptr_array(ptrs)
 
 
 def tn_executor_place_inputs(ex, host_inputs: Sequence[int]):

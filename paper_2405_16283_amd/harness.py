@@ -213,6 +213,7 @@ class GpuSession:
         base = self.in_slab.data_ptr()
         for v, off in offs.items():
             self.in_ptrs[v] = base + off
+        self.in_ptrs = B.ptr_array(self.in_ptrs)  # marshalled once, not on every execute
         # outputs: one pinned slab
         self.out_vids, self.out_shapes, self.out_bind = output_vertices(self.tg)
         self.out_offs, total = [], 0
@@ -220,7 +221,7 @@ class GpuSession:
             self.out_offs.append(total)
             total += (r * c * es + 255) // 256 * 256
         self.out_slab = torch.empty(max(total, 256), dtype=torch.uint8).pin_memory()
-        self.out_ptrs = [self.out_slab.data_ptr() + o for o in self.out_offs]
+        self.out_ptrs = B.ptr_array([self.out_slab.data_ptr() + o for o in self.out_offs])
         # device memory and streams
         self.dev = torch.empty(self.cap, dtype=torch.uint8, device="cuda:0")
         self.streams = [torch.cuda.Stream(device="cuda:0") for _ in range(n_compute + 2)]
