@@ -193,11 +193,23 @@ __global__ void __launch_bounds__(256) silu_bwd_kernel(DeviceTables t, Batch b) 
   T* o = (T*)d.out;
   const int n = d.rows * d.cols;
   const int i0 = (blockIdx.x * 256 + threadIdx.x) * 8;
-  for (int i = i0; i < min(i0 + 8, n); ++i) {
-    const float da = ld(dact + i), g = ld(gate + i), u = ld(up + i);
+  if (i0 >= n) return;
+  auto grad = [&](float da, float g, float u) {
     const float s = 1.f / (1.f + __expf(-g));
-    st(o + i, d.p.mode == 0 ? da * u * s * (1.f + g * (1.f - s)) : da * g * s);
+    return d.p.mode == 0 ? da * u * s * (1.f + g * (1.f - s)) : da * g * s;
+  };
+  if constexpr (sizeof(T) == 2) {
+    if (i0 + 8 <= n) {  // 16-byte accesses
+      uint4 va = *(const uint4*)(dact + i0), vg = *(const uint4*)(gate + i0), vu = *(const uint4*)(up + i0), vo;
+      const bf16_t *pa = (const bf16_t*)&va, *pg = (const bf16_t*)&vg, *pu = (const bf16_t*)&vu;
+      bf16_t* po = (bf16_t*)&vo;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) po[k] = f2bf(grad(bf2f(pa[k]), bf2f(pg[k]), bf2f(pu[k])));
+      *(uint4*)(o + i0) = vo;
+      return;
+    }
   }
+  for (int i = i0; i < min(i0 + 8, n); ++i) st(o + i, grad(ld(dact + i), ld(gate + i), ld(up + i)));
 }
 
 // sum over the columns of a row block of dy * gain * x: one wavefront per row

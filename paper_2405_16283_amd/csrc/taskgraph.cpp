@@ -497,6 +497,16 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         av.push_back(t.input(t.dcols[j].len(), rk, c.weights_residency, TN_T_AV, l, t.dcols[j], rkr));
         bv.push_back(t.input(rk, t.dcols[j].len(), c.weights_residency, TN_T_BV, l, rkr, t.dcols[j]));
       }
+    // transposed copies of the adapter tiles, so that the adapter products are A B^T products like
+    // every other projection (the form the MFMA kernels take)
+    std::vector<tn_vid> aqT, bqT, avT, bvT;
+    for (size_t j = 0; j < aq.size(); ++j) {
+      const int32_t n = t.dcols[j].len();
+      aqT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {aq[j]}, {c.dtype, rk, n}));
+      avT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {av[j]}, {c.dtype, rk, n}));
+      bqT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {bq[j]}, {c.dtype, n, rk}));
+      bvT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {bv[j]}, {c.dtype, n, rk}));
+    }
     if (c.train) lin[l] = {wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv};
 
     for (int b = 0; b < c.batch; ++b) {
@@ -517,16 +527,16 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           tn_vid st1 = -1, tq = -1, tv = -1;
           auto a = t.rmsnorm(x[b][i], g1, m, &st1);
           if (rk > 0) {  // the low-rank activations a Aq and a Av
-            tq = t.gemm_list(a, aq, m, rk, false, false);
-            tv = t.gemm_list(a, av, m, rk, false, false);
+            tq = t.gemm_list(a, aqT, m, rk, false, true);
+            tv = t.gemm_list(a, avT, m, rk, false, true);
           }
           for (size_t j = 0; j < nd; ++j) {
             const int32_t n = t.dcols[j].len();
             tn_vid qj = t.gemm(a, wq, j, m, n), vj = t.gemm(a, wv, j, m, n, c.v_transposed != 0);
             if (rk > 0) {
-              qj = t.add(qj, t.gemm_list({tq}, {bq[j]}, m, n, false, false), m, n);
+              qj = t.add(qj, t.gemm_list({tq}, {bqT[j]}, m, n, false, true), m, n);
               const bool vt = c.v_transposed != 0;
-              vj = t.op(TN_OP_ADD, tn_op_params{}, {vj, t.gemm_list({tv}, {bv[j]}, m, n, false, false, vt)},
+              vj = t.op(TN_OP_ADD, tn_op_params{}, {vj, t.gemm_list({tv}, {bvT[j]}, m, n, false, true, vt)},
                         vt ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
             }
             q[i].push_back(t.rope(qj, t.rows[i].a, t.dcols[j].a, m, n));
