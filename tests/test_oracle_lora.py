@@ -102,3 +102,45 @@ def test_gradients_are_linear_in_the_probe():
     _, g2 = L.loss_and_grads(CFG, w, lo, w["x"], -2.5 * probe)
     for k in g1:
         np.testing.assert_allclose(g2[k], -2.5 * g1[k], rtol=1e-12, atol=1e-15)
+
+
+def test_bf16_rounding_against_hand_worked_values():
+    import torch
+    # bf16 keeps 8 significant bits: the spacing in [1, 2) is 2**-7
+    cases = [(1.0, 1.0),
+             (1 + 2.0 ** -8, 1.0),                       # half way, lower neighbour even
+             (1 + 3 * 2.0 ** -8, 1 + 2.0 ** -6),         # half way, upper neighbour even
+             (1 + 2.0 ** -8 + 2.0 ** -20, 1 + 2.0 ** -7),  # just above half way
+             (-(1 + 2.0 ** -8 + 2.0 ** -20), -(1 + 2.0 ** -7)),
+             (3.1415926, 3.140625),                      # float32 0x40490FDB -> 0x4049
+             (0.0, 0.0), (float("inf"), float("inf"))]
+    got = L.round_bf16(torch.tensor([c[0] for c in cases], dtype=torch.float64)).numpy()
+    np.testing.assert_array_equal(got, np.array([c[1] for c in cases]))
+    # the same as the workload generator's conversion (written independently of this one)
+    from workloads import bf16_bits_to_f32, to_bf16_bits
+    x = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    np.testing.assert_array_equal(L.round_bf16(torch.tensor(x.astype(np.float64))).numpy(),
+                                  bf16_bits_to_f32(to_bf16_bits(x)).astype(np.float64))
+
+
+def test_stored_tensor_rounds_the_value_forward_and_the_gradient_back():
+    import torch
+    x = torch.tensor([1 + 2.0 ** -8 + 2.0 ** -20], dtype=torch.float64, requires_grad=True)
+    c = torch.tensor([3.1415926], dtype=torch.float64)
+    y = torch.sum(L._Stored.apply(x) * c)
+    y.backward()
+    assert float(y) == (1 + 2.0 ** -7) * 3.1415926
+    assert float(x.grad[0]) == 3.140625
+
+
+def test_bf16_storage_is_a_small_perturbation_and_none_is_the_plain_form():
+    w, lo, probe = _inputs(0.05)
+    y0, g0 = L.loss_and_grads(CFG, w, lo, w["x"], probe)
+    y1, g1 = L.loss_and_grads(CFG, w, lo, w["x"], probe, storage=None)
+    np.testing.assert_array_equal(y0, y1)
+    yb, gb = L.loss_and_grads(CFG, w, lo, w["x"], probe, storage="bf16")
+    assert 1e-4 < R.rel_err(yb, y0) < 2e-2          # rounded, and by no more than a few bf16 ulps
+    for k in g0:
+        assert 1e-4 < R.rel_err(gb[k], g0[k]) < 4e-2, k
+    with pytest.raises(ValueError):
+        L.loss_and_grads(CFG, w, lo, w["x"], probe, storage="fp8")
