@@ -73,7 +73,15 @@ enum {
   TN_OP_RMS_BWD_STAT = 10,  /* dy tiles, x tiles, gain tiles of a row block -> fp32 [rows,1]: sum dy*gain*x */
   TN_OP_RMS_BWD_APPLY = 11, /* dy, x, stat, dot, gain[, residual gradient] -> gradient of x            */
   TN_OP_ATTN_BWD = 12,      /* Q, K, V, dO tiles[, statistics][, transposed tiles] -> statistics, dQ, dK or dV (mode) */
-  TN_OP_TRANSPOSE = 13      /* X [rows, cols] -> X^T [cols, rows]                                      */
+  TN_OP_TRANSPOSE = 13,     /* X [rows, cols] -> X^T [cols, rows]                                      */
+  /* Section 8 (resources): a sum of n tensors is run as n increment kernels into an output
+   * protected by a write lock.  P_0..P_{n-1}, all of the output's shape and type -> their sum.  In
+   * the memgraph the vertex becomes TN_OP_ZERO, one TN_OP_SUM_INTO per operand and TN_MG_JOIN; the
+   * increments run in whatever order their operands arrive, and each rounds the output to its
+   * storage type, so the result is order-independent only up to that rounding. */
+  TN_OP_SUM = 14,
+  TN_OP_ZERO = 15,          /* memgraph only: () -> zeros, the start of a sum's output               */
+  TN_OP_SUM_INTO = 16       /* memgraph only: P, accumulator -> accumulator += P, in place           */
 };
 
 typedef struct {
@@ -213,6 +221,11 @@ typedef struct {
    * matrices of every layer and of x.  The reverse pass reads the base weights as [in, out] tiles (bindings
    * with transposed == 0), which are input vertices of their own when weights_transposed != 0. */
   int32_t train;
+  /* > 1: every projection of the forward pass is cut along K into k_split partial products
+   * (contiguous runs of ceil(nk / k_split) K tiles, one GEMM vertex each) joined by a TN_OP_SUM
+   * vertex -- the k-split + sum-into form of a matrix product (Section 8, resources).  0 or 1:
+   * the whole K range inside one GEMM vertex. */
+  int32_t k_split;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */
@@ -284,7 +297,14 @@ enum {
   TN_MG_OFFLOAD = 3,
   TN_MG_RELOAD = 4,
   TN_MG_DROP = 5,  /* eviction without a copy                                          */
-  TN_MG_STORE = 6  /* GPU -> host copy of a marked output into the caller's buffer     */
+  TN_MG_STORE = 6, /* GPU -> host copy of a marked output into the caller's buffer     */
+  /* A TN_OP_SUM vertex: TN_MG_OP vertices with op_kind TN_OP_ZERO (clears the output at its
+   * location; the location's memory dependencies point at it) and TN_OP_SUM_INTO (one per operand;
+   * operands: the tensor to add, then the TN_OP_ZERO vertex, whose location it updates in place and
+   * whose offset it repeats; the executor runs at most one increment per location at a time) come
+   * first; the sum vertex itself is the join: no work, runs after every increment (data edges),
+   * operand: the TN_OP_ZERO vertex, and from then on stands for the tensor at that location. */
+  TN_MG_JOIN = 7
 };
 enum { TN_EDGE_DATA = 0, TN_EDGE_MEM = 1, TN_EDGE_ORDER = 2 /* only with fix_order */ };
 
@@ -313,6 +333,7 @@ typedef struct {
   uint64_t offload_bytes, reload_bytes, load_bytes, store_bytes;
   int64_t n_revoked;     /* run-ahead allocations that had to be undone */
   int64_t n_compactions; /* times memory had to be emptied to defeat fragmentation */
+  int64_t n_increment;   /* TN_OP_SUM_INTO vertices */
 } tn_mg_stats;
 
 int64_t tn_memgraph_num_vertices(const tn_memgraph* mg);

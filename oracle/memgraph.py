@@ -23,6 +23,13 @@ possible mapping"), so nothing here compares two memgraphs edge by edge.
 Memgraph vertex kinds: "input" (tensor already in GPU memory at start), "load" (host -> GPU copy
 of an input), "op" (kernel call), "offload", "reload", "drop" (eviction of a tensor whose host
 copy is still valid: no bytes move), "store" (GPU -> host copy of a wanted result).
+
+A taskgraph vertex that sums n tensors takes the form Section 8 (resources) gives a reduction: an
+output that several kernels increment under a write lock.  Its memgraph vertices are "zero" (the
+output is given its location and cleared; memory dependencies of the location point here),
+one "increment" per operand (operands: the tensor added, then the "zero" vertex; it owns no
+memory of its own) in any order, and "join" (the sum vertex itself: runs after every increment,
+moves no data, and from then on stands for the finished tensor at the same location).
 """
 from __future__ import annotations
 
@@ -283,14 +290,31 @@ def check_data_deps(task_preds: Sequence[Sequence[int]], mg: MemGraph):
     """Section 6, requirement (a): each taskgraph edge u -> w is in the memgraph, or is replaced
     by u -> offload -> reload (-> offload -> reload)* -> w."""
     eset = {(a, b) for a, b, _ in mg.edges}
+    incs_of: Dict[int, List[int]] = {}
+    for v in range(len(mg)):
+        if mg.kind[v] == "increment":
+            incs_of.setdefault(mg.operands[v][1], []).append(v)
     for w in range(mg.n_task):
         ops = mg.operands[w]
+        if mg.kind[w] == "join":
+            # the operands of a sum arrive through its increments: zero -> increment -> join
+            (z,) = ops
+            if mg.kind[z] != "zero" or mg.src[z] != w or mg.loc[z] != mg.loc[w]:
+                raise MemgraphError(f"join {w}: operand {z} is not its accumulator")
+            incs = incs_of.get(z, [])
+            for i in incs:
+                if (z, i) not in eset or (i, w) not in eset or mg.src[i] != w:
+                    raise MemgraphError(f"increment {i} of sum {w} lacks an edge from its accumulator or to the join")
+            ops = [mg.operands[i][0] for i in incs]
+            users = dict(zip(ops, incs))
+        else:
+            users = {x: w for x in ops}
         if sorted(mg.src[x] for x in ops) != sorted(task_preds[w]):
             raise MemgraphError(f"vertex {w}: operands {[mg.src[x] for x in ops]} differ from "
                                 f"taskgraph producers {list(task_preds[w])}")
         for x in ops:
-            if (x, w) not in eset:
-                raise MemgraphError(f"missing data edge {x}->{w}")
+            if (x, users[x]) not in eset:
+                raise MemgraphError(f"missing data edge {x}->{users[x]}")
             u, cur = mg.src[x], x
             while cur != u:  # walk the chain of copies back to the producer
                 if mg.kind[cur] not in ("reload", "load") or len(mg.operands[cur]) != 1:
@@ -425,6 +449,30 @@ def simulate(mg: MemGraph, order: Sequence[int], task_preds: Sequence[Sequence[i
             for x in mg.operands[v]:
                 read(v, x)
             assert sorted(mg.src[x] for x in mg.operands[v]) == sorted(task_preds[mg.src[v]])
+            write(v, expected[mg.src[v]])
+            current[mg.src[v]] = v
+        elif k == "zero":
+            write(v, ("partial sum",))
+        elif k == "increment":
+            x, z = mg.operands[v]
+            read(v, x)
+            off, size = mg.loc[z]
+            got = regions.get(off)
+            if got is None or got[0] != size or not isinstance(got[1], tuple) or val[z] is None:
+                raise MemgraphError(f"increment {v} finds {got} where its accumulator {z} should be")
+            regions[off] = (size, got[1] + (expected[mg.src[x]],))
+            remaining[z] -= 1
+        elif k == "join":
+            (z,) = mg.operands[v]
+            off, size = mg.loc[z]
+            got = regions.get(off)
+            want = sorted(expected[u] for u in task_preds[mg.src[v]])
+            if got is None or got[0] != size or not isinstance(got[1], tuple) or sorted(got[1][1:]) != want:
+                raise MemgraphError(f"join {v} finds {got}, not the sum of its operands")
+            remaining[z] -= 1
+            if remaining[z] != 0:
+                raise MemgraphError(f"join {v} runs while increments of {z} are outstanding")
+            live_bytes -= live.pop(z)[1]
             write(v, expected[mg.src[v]])
             current[mg.src[v]] = v
         elif k == "offload":

@@ -27,6 +27,14 @@ Vertex kinds (inputs -> output):
   attn_combine  partial_0..partial_j                 -> normalised attention output tile
   silu_mul      gate, up                             -> gate/(1+exp(-gate)) * up
   add           a, b                                 -> a + b
+  sum           p_0..p_{n-1}                         -> their sum, formed the way Section 8 (resources) describes a
+                                                        reduction: an output that starts at zero and receives the
+                                                        n operands as n increments, each increment rounding the
+                                                        output to its storage type.  The increments hold a write
+                                                        lock on the output and may come in any order, so this is
+                                                        the one kind whose result depends on the execution order
+                                                        (by rounding only); `evaluate` takes the order as an
+                                                        argument and uses ascending operand order by default.
 """
 from __future__ import annotations
 
@@ -158,12 +166,21 @@ def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
         return g / (1.0 + np.exp(-g)) * u
     if kind == "add":
         return ins[0] + ins[1]
+    if kind == "sum":
+        acc = np.zeros_like(ins[0])
+        for i in p.get("_increment_order", range(len(ins))):
+            acc = round_store(acc + ins[i], p["_storage"])
+        return acc
     raise ValueError(f"unknown vertex kind {kind}")
 
 
 def evaluate(tg: TaskGraph, input_values: Dict[int, np.ndarray],
-             order: Optional[Sequence[int]] = None, keep_all: bool = False) -> Dict[int, np.ndarray]:
+             order: Optional[Sequence[int]] = None, keep_all: bool = False,
+             increment_order=None) -> Dict[int, np.ndarray]:
     """Run the graph in `order` (default: vertex numbering, which must be topological).
+
+    increment_order: optional function (sum vertex id, number of operands) -> permutation of the
+    operand indices, the order in which that sum's increments take place.
 
     input_values: vid -> float64 tile for every input vertex.  Returns vid -> float64 value for
     the marked outputs (or for every vertex with keep_all).  Every value is rounded to its
@@ -191,7 +208,14 @@ def evaluate(tg: TaskGraph, input_values: Dict[int, np.ndarray],
                 if u not in val:
                     val[u] = round_store(np.asarray(input_values[u], dtype=np.float64).reshape(tg.shape[u]),
                                          tg.dtype[u])
-            r = _eval_vertex(tg.kind[v], tg.params[v], [val[u] for u in tg.inputs[v]])
+            p = tg.params[v]
+            if tg.kind[v] == "sum":
+                p = dict(p, _storage=tg.dtype[v])
+                if increment_order is not None:
+                    perm = list(increment_order(v, len(tg.inputs[v])))
+                    assert sorted(perm) == list(range(len(tg.inputs[v])))
+                    p["_increment_order"] = perm
+            r = _eval_vertex(tg.kind[v], p, [val[u] for u in tg.inputs[v]])
             assert r.shape == tg.shape[v], (tg.kind[v], r.shape, tg.shape[v])
         val[v] = round_store(r, tg.dtype[v])
         done[v] = True
@@ -211,8 +235,12 @@ def _splits(n: int, t: int) -> List[Tuple[int, int]]:
     return [(s, min(s + t, n)) for s in range(0, n, t)]
 
 
-def build_llama_taskgraph(cfg) -> TaskGraph:
+def build_llama_taskgraph(cfg, k_split: int = 1) -> TaskGraph:
     """Tile the decoder of `cfg` (a workloads.LlamaConfig) into a taskgraph.
+
+    k_split > 1: every projection is cut along K into that many partial products (contiguous runs
+    of ceil(nk / k_split) K tiles, each a gemm vertex stored in the storage type) joined by a sum
+    vertex -- the k-split + sum-into form of a matrix product.
 
     Tensors are cut into tile x tile pieces (ragged at the right and bottom edges); row blocks
     never straddle sequences.  Attention runs per (sequence, head group, q block, kv block <= q
@@ -253,9 +281,15 @@ def build_llama_taskgraph(cfg) -> TaskGraph:
         for arow in a_grid:
             line = []
             m = tg.shape[arow[0]][0]
+            nk = len(arow)
+            per = -(-nk // max(1, k_split))
             for j, (c0, c1) in enumerate(out_cols):
-                ins = list(arow) + [b_grid[k][j] for k in range(len(arow))]
-                line.append(tg.add("gemm", ins, (m, c1 - c0), dt, nk=len(arow)))
+                parts = []
+                for k0 in range(0, nk, per):
+                    ks = range(k0, min(k0 + per, nk))
+                    ins = [arow[k] for k in ks] + [b_grid[k][j] for k in ks]
+                    parts.append(tg.add("gemm", ins, (m, c1 - c0), dt, nk=len(ks)))
+                line.append(parts[0] if len(parts) == 1 else tg.add("sum", parts, (m, c1 - c0), dt))
             res.append(line)
         return res
 

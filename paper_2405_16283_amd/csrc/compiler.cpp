@@ -12,6 +12,14 @@
 // only mean that one allocation may evict several victims.  This file is that general case:
 // a byte-addressed first-fit allocator over [0, cap), an interval map of the last dead occupant
 // of every byte, and victim *windows* of adjacent blocks.
+//
+// Section 8 (resources): a vertex that sums n tensors runs as n increment kernels into an output
+// protected by a write lock.  Here the output gets its location when the first operand has been
+// produced (a vertex that clears it; the memory dependencies of the location point there), every
+// operand is added by an increment vertex placed right after its producer -- so a partial product
+// lives only until it has been added -- and the sum vertex itself is a join that runs after all
+// increments and then stands for the tensor.  Until the join the output cannot be evicted: an
+// increment that came late in some execution order would otherwise write to a stale location.
 #include <algorithm>
 #include <climits>
 #include <cstring>
@@ -59,6 +67,10 @@ struct Compiler {
   int64_t execHzn = 0, allocHzn = 0, lookahead_blocked_until = -1, compacted_at = -1;
   uint64_t lookahead_bytes = 0, live_bytes = 0, cursor = 0;
   std::vector<int64_t> step_pre;  // offloads and reloads inserted just before V[execHzn], in the order made
+  std::vector<std::vector<tn_vid>> sums_of;     // per tensor: the sum vertices it is an operand of
+  std::vector<int64_t> acc_of;                  // per sum vertex: the vertex that clears its output, or -1
+  std::vector<std::vector<int64_t>> incs_of;    // per sum vertex: its increments so far
+  std::vector<char> open_acc;                   // per memgraph vertex: an output still being summed into
 
   Compiler(const TaskGraph& t, const tn_compile_opts& o, MemGraph& m)
       : tg(t), opt(o), mg(m), n((int64_t)t.v.size()) {}
@@ -76,6 +88,7 @@ struct Compiler {
     mg.v.push_back(std::move(x));
     readers.emplace_back();
     malloc_edges.emplace_back();
+    open_acc.push_back(0);
     return (int64_t)mg.v.size() - 1;
   }
 
@@ -96,7 +109,8 @@ struct Compiler {
     return p < c.size() ? c[p] : LLONG_MAX;
   }
 
-  bool produced(int64_t m) const { return m >= n || pos[m] < execHzn; }
+  bool produced(int64_t m) const { return m >= n ? !open_acc[m] : pos[m] < execHzn; }
+  bool is_sum(tn_vid v) const { return tg.v[v].kind == TN_OP_SUM; }
 
   void use_erase(tn_vid t) {
     if (use_key[t] >= 0) by_use.erase({use_key[t], t});
@@ -260,6 +274,7 @@ struct Compiler {
   bool revoke_newest_preallocation() {
     if (allocHzn - 1 <= execHzn) return false;
     --allocHzn;
+    if (is_sum(V[allocHzn])) return true;  // a sum's output is placed by its first increment, not ahead
     unplace(V[allocHzn]);
     ++mg.stats.n_revoked;
     lookahead_blocked_until = execHzn + 1;
@@ -454,12 +469,52 @@ struct Compiler {
     return p;
   }
 
+  // tensor u, just produced, is added to the output of sum vertex s
+  tn_status increment(tn_vid s, tn_vid u) {
+    const std::vector<int64_t> pinned{name[u]};
+    if (acc_of[s] < 0) {
+      const int64_t z = new_vertex(TN_MG_OP, s);
+      mg.v[z].op_kind = TN_OP_ZERO;
+      open_acc[z] = 1;
+      tn_status st = sim_malloc_offld(z, pinned);
+      if (st != TN_OK) return st;
+      acc_of[s] = z;
+      for (int64_t o : step_pre) mg.order.push_back(o);  // what made room for it comes first
+      step_pre.clear();
+      mg.order.push_back(z);
+    }
+    const int64_t z = acc_of[s];
+    const int64_t i = new_vertex(TN_MG_OP, s);
+    mg.v[i].op_kind = TN_OP_SUM_INTO;
+    mg.v[i].operands = {name[u], z};
+    mg.v[i].offset = mg.v[z].offset;
+    add_edge(name[u], i, TN_EDGE_DATA, false);
+    add_edge(z, i, TN_EDGE_DATA, false);
+    readers[name[u]].push_back(i);
+    readers[z].push_back(i);
+    incs_of[s].push_back(i);
+    mg.order.push_back(i);
+    ++mg.stats.n_increment;
+    return TN_OK;
+  }
+
   tn_status execute_next() {
     const tn_vid v = V[execHzn];
     const Vertex& tv = tg.v[v];
+    if (is_sum(v)) {
+      // the join: every operand has been added by an increment placed after its producer; the
+      // cleared-and-summed output now counts as this vertex's, at the same location
+      const int64_t z = acc_of[v];
+      mg.v[v].operands = {z};
+      for (int64_t i : incs_of[v]) add_edge(i, v, TN_EDGE_DATA, false);
+      readers[z].push_back(v);
+      blocks.find((uint64_t)mg.v[z].offset)->second.owner = v;
+      mg.v[v].offset = mg.v[z].offset;
+      open_acc[z] = 0;
+    }
     // (1) bring back every evicted operand; operands already here and v's output stay pinned.
     // A compaction in the middle of this may push out operands that were here: go round again.
-    for (bool again = true; again;) {
+    for (bool again = !is_sum(v); again;) {
       again = false;
       for (tn_vid u : tv.in) {
         if (name[u] >= 0) continue;
@@ -479,6 +534,7 @@ struct Compiler {
     }
     // (2) data dependencies, from whatever now stands for each operand
     for (tn_vid u : tv.in) {
+      if (is_sum(v)) break;
       mg.v[v].operands.push_back(name[u]);
       add_edge(name[u], v, TN_EDGE_DATA, false);
       if (readers[name[u]].empty() || readers[name[u]].back() != v) readers[name[u]].push_back(v);
@@ -501,6 +557,11 @@ struct Compiler {
       add_edge(v, s, TN_EDGE_DATA, false);
       readers[v].push_back(s);
       mg.order.push_back(s);
+    }
+    // operands of sums are added to them right away
+    for (tn_vid s : sums_of[v]) {
+      tn_status st = increment(s, v);
+      if (st != TN_OK) return st;
     }
     // (3) free what will not be used again
     std::vector<tn_vid> d(tv.in);
@@ -529,9 +590,17 @@ struct Compiler {
     pos.assign(n, -1);
     for (int64_t i = 0; i < n; ++i) pos[V[i]] = i;
     cons.assign(n, {});
+    sums_of.assign(n, {});
+    acc_of.assign(n, -1);
+    incs_of.assign(n, {});
     for (int64_t i = 0; i < n; ++i)
-      for (tn_vid u : tg.v[V[i]].in)
+      for (tn_vid u : tg.v[V[i]].in) {
+        if (is_sum(V[i])) {  // consumed by an increment right after u is produced, not at position i
+          sums_of[u].push_back(V[i]);
+          continue;
+        }
         if (cons[u].empty() || cons[u].back() != i) cons[u].push_back(i);
+      }
     cons_ptr.assign(n, 0);
     name.assign(n, -1);
     use_key.assign(n, -1);
@@ -544,6 +613,7 @@ struct Compiler {
                                                     : TN_MG_OP, (tn_vid)v);
       mg.v[m].op_kind = tv.kind;
       mg.v[m].p = tv.p;
+      if (tv.kind == TN_OP_SUM) mg.v[m].kind = TN_MG_JOIN;
     }
     // tensors that are on the GPU before execution starts occupy memory from the beginning
     while (allocHzn < n && mg.v[V[allocHzn]].kind == TN_MG_INPUT) {
@@ -553,6 +623,10 @@ struct Compiler {
       ++allocHzn;
     }
     while (execHzn < n) {
+      if (allocHzn < n && is_sum(V[allocHzn])) {  // placed by its first increment
+        ++allocHzn;
+        continue;
+      }
       bool ahead_ok = false;
       if (allocHzn < n) {
         const uint64_t sz = vbytes(V[allocHzn]);
@@ -666,6 +740,7 @@ extern "C" tn_status tn_compile(const tn_taskgraph* tg, const tn_vid* order, uin
     int64_t last[3] = {-1, -1, -1};
     for (int64_t m : mg->order) {
       const int32_t k = mg->v[m].kind;
+      if (k == TN_MG_OP && mg->v[m].op_kind == TN_OP_SUM_INTO) continue;  // reductions keep their freedom
       int cls = k == TN_MG_OP ? 0 : (k == TN_MG_LOAD || k == TN_MG_RELOAD) ? 1 : (k == TN_MG_OFFLOAD || k == TN_MG_STORE) ? 2 : -1;
       if (cls < 0) continue;
       if (last[cls] >= 0) c.add_edge(last[cls], m, TN_EDGE_ORDER, false);

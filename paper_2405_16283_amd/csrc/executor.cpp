@@ -20,6 +20,7 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <unordered_map>
 #include <set>
 
 #include "graph.h"
@@ -38,6 +39,7 @@ struct VInfo {
   int16_t group = -1;  // index of its (cls, dtype, head_dim) combination: vertices of one group can share a launch
   int32_t desc = -1;
   int32_t nblocks = 0;
+  int64_t lock = -1;  // increments: the vertex whose output they add to; one of them runs at a time
   double flops = 0, bytes = 0;
 };
 
@@ -203,8 +205,7 @@ tn_status build_tables(tn_executor& ex) {
     d.n_in = (int32_t)x.operands.size();
     d.p = x.p;
     d.trans_b = x.p.trans_b;
-    const MVertex& first = mg.v[x.operands[0]];
-    d.dtype = first.desc.dtype;
+    d.dtype = x.operands.empty() ? x.desc.dtype : mg.v[x.operands[0]].desc.dtype;
     for (int64_t o : x.operands) {
       void* p = nullptr;
       tn_status s = addr(o, tensor_bytes(mg.v[o].desc), &p);
@@ -295,6 +296,17 @@ tn_status build_tables(tn_executor& ex) {
       case TN_OP_TRANSPOSE:
         vi.cls = LC_TRANSPOSE;
         vi.bytes = 2.0 * x.bytes;
+        break;
+      case TN_OP_ZERO:
+        vi.cls = LC_ZERO;
+        vi.bytes = (double)x.bytes;
+        break;
+      case TN_OP_SUM_INTO:  // output = operand 0 + operand 1, written where operand 1 lies
+        if (x.operands.size() != 2 || mg.v[x.operands[1]].offset != x.offset)
+          return fail(TN_ERR_INVALID, "increment %lld does not name the output it adds to", (long long)m);
+        vi.cls = LC_ADD;
+        vi.bytes = 3.0 * x.bytes;
+        vi.lock = x.operands[1];
         break;
       case TN_OP_SILU_MUL_BWD:
         vi.cls = LC_SILU_BWD;
@@ -691,8 +703,13 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
     return true;
   };
 
+  // Section 8 (resources): the output of a sum is protected by a write lock; an increment takes
+  // it when it is launched and gives it back when it has completed, and increments that find it
+  // taken wait here, outside the ready lists
+  std::vector<char> lock_busy(nv, 0);
+  std::unordered_map<int64_t, std::vector<int64_t>> lock_wait;
   // a vertex whose dependencies are all complete joins a ready list; vertices with no work
-  // (inputs already in place, drops) complete on the spot
+  // (inputs already in place, drops, joins of sums) complete on the spot
   auto complete = [&](int64_t first) {
     work.push_back(first);
     while (!work.empty()) {
@@ -701,6 +718,14 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       ++completed;
       const bool was_enqueued_kernel = ahead && mg.v[m].kind == TN_MG_OP;  // its successors were told at enqueue time
       state[m] = 2;
+      if (const int64_t lk = ex->info[m].lock; lk >= 0) {
+        lock_busy[lk] = 0;
+        auto it = lock_wait.find(lk);
+        if (it != lock_wait.end()) {
+          for (int64_t w : it->second) make_ready(w);
+          lock_wait.erase(it);
+        }
+      }
       for (int64_t i = ex->succ_start[m]; i < ex->succ_start[m + 1]; ++i) {
         const int64_t w = ex->succ[i];
         const bool all_done = --ex->remaining[w] == 0;
@@ -714,7 +739,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           continue;
         }
         if (!all_done) continue;
-        if (k == TN_MG_INPUT || k == TN_MG_DROP) {
+        if (k == TN_MG_INPUT || k == TN_MG_DROP || k == TN_MG_JOIN) {
           ex->last_order.push_back(w);
           work.push_back(w);
         } else {
@@ -725,7 +750,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   };
   for (int64_t m = 0; m < nv; ++m) {
     if (ex->indeg[m] != 0) continue;
-    if (mg.v[m].kind == TN_MG_INPUT || mg.v[m].kind == TN_MG_DROP) {
+    if (mg.v[m].kind == TN_MG_INPUT || mg.v[m].kind == TN_MG_DROP || mg.v[m].kind == TN_MG_JOIN) {
       ex->last_order.push_back(m);
       complete(m);
     } else {
@@ -870,12 +895,17 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         const std::vector<int64_t>& serial = ex->serial[0];
         size_t at = serial_next[0];
         if (!is_ready[serial[at]]) break;
+        if (ex->info[serial[at]].lock >= 0 && lock_busy[ex->info[serial[at]].lock]) break;
         gi = ex->info[serial[at]].group;
         uint32_t lo = (uint32_t)ex->info[serial[at]].desc, hi = lo;
         while (at < serial.size() && (int)same.size() < max_batch && is_ready[serial[at]] &&
                ex->info[serial[at]].group == gi) {
           const uint32_t d = (uint32_t)ex->info[serial[at]].desc;
           if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) break;
+          if (const int64_t lk = ex->info[serial[at]].lock; lk >= 0) {
+            if (lock_busy[lk]) break;
+            lock_busy[lk] = 1;
+          }
           lo = std::min(lo, d);
           hi = std::max(hi, d);
           is_ready[serial[at]] = 0;
@@ -912,14 +942,23 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         uint32_t lo = 0, hi = 0;
         while (!q.empty() && (int)same.size() < max_batch) {
           const int64_t m = q.peek(rng);
+          const int64_t lk = ex->info[m].lock;
+          if (lk >= 0 && lock_busy[lk]) {  // its output is being added to: wait for the lock
+            q.pop();
+            lock_wait[lk].push_back(m);
+            --n_ready_k;
+            continue;
+          }
           const uint32_t d = (uint32_t)ex->info[m].desc;
           if (same.empty()) lo = hi = d;
           if (std::max(hi, d) - std::min(lo, d) > kMaxBatchSpan) break;
           lo = std::min(lo, d);
           hi = std::max(hi, d);
           q.pop();
+          if (lk >= 0) lock_busy[lk] = 1;
           same.push_back(m);
         }
+        if (same.empty()) continue;  // everything looked at waits for a lock
       }
       n_ready_k -= (int64_t)same.size();
       const VInfo lead = ex->groups[gi];

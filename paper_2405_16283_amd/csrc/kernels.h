@@ -49,6 +49,7 @@ enum LaunchClass {
   LC_ATTN_BWD_BF16_DK,
   LC_ATTN_BWD_BF16_DV,
   LC_TRANSPOSE,
+  LC_ZERO,           // clears a tensor: the start of a sum's output
   LC_COUNT
 };
 

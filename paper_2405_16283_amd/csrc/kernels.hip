@@ -35,6 +35,22 @@ template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p 
 // ---------------------------------------------------------------------------------------------
 // elementwise: add, silu*mul
 // ---------------------------------------------------------------------------------------------
+// zeros, the value a sum's output starts from; 16 bytes per lane, the tail element by element
+template <typename T>
+__global__ void __launch_bounds__(256) zero_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  T* o = (T*)d.out;
+  const int n = d.rows * d.cols;
+  constexpr int V = 16 / (int)sizeof(T);
+  const int i0 = (blockIdx.x * 256 + threadIdx.x) * V;
+  if (i0 + V <= n) {
+    *(uint4*)(o + i0) = make_uint4(0, 0, 0, 0);
+  } else {
+    for (int i = i0; i < n; ++i) o[i] = T(0);
+  }
+}
+
 template <typename T, bool SILU>
 __global__ void __launch_bounds__(256) ewise2_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
@@ -1306,6 +1322,7 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     case LC_ADD:
     case LC_SILU_BWD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
     case LC_TRANSPOSE: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
+    case LC_ZERO: return cdiv((int64_t)d.rows * d.cols * (d.dtype == TN_BF16 ? 2 : 4), 256 * 16);
     case LC_RMS_BWD_STAT: return cdiv(d.rows, 4);
     case LC_RMS_BWD_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ATTN_BWD: {
@@ -1363,6 +1380,7 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
       else hipLaunchKernelGGL((ewise2_kernel<float, false>), grid, wg, 0, s, t, b);
       break;
     case LC_TRANSPOSE: TN_LAUNCH_T(transpose_kernel); break;
+    case LC_ZERO: TN_LAUNCH_T(zero_kernel); break;
     case LC_SILU_BWD: TN_LAUNCH_T(silu_bwd_kernel); break;
     case LC_RMS_BWD_STAT: TN_LAUNCH_T(rms_bwd_stat_kernel); break;
     case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;

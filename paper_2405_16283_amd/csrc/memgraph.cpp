@@ -53,7 +53,7 @@ tn_status tn_memgraph_dump_json(const tn_memgraph* mg, const char* path) {
   if (!mg || !path) return fail(TN_ERR_INVALID, "NULL argument");
   FILE* f = fopen(path, "w");
   if (!f) return fail(TN_ERR_INVALID, "cannot open %s for writing", path);
-  static const char* kinds[] = {"input", "load", "op", "offload", "reload", "drop", "store"};
+  static const char* kinds[] = {"input", "load", "op", "offload", "reload", "drop", "store", "join"};
   static const char* ekinds[] = {"data", "mem", "order"};
   fprintf(f, "{\"n_task\": %lld, \"cap\": %llu,\n \"vertices\": [\n", (long long)mg->n_task, (unsigned long long)mg->cap);
   for (size_t i = 0; i < mg->v.size(); ++i) {
@@ -138,8 +138,27 @@ tn_status tn_memgraph_simulate(const tn_memgraph* mg, const int64_t* order, int6
       case TN_MG_OP:
         for (int64_t o : x.operands)
           if ((s = read(m, o)) != TN_OK) break;
+        if (s == TN_OK && x.op_kind == TN_OP_SUM_INTO) {  // updates its second operand in place, owns nothing
+          if (x.operands.size() != 2 || mg->v[x.operands[1]].op_kind != TN_OP_ZERO || mg->v[x.operands[1]].offset != x.offset)
+            s = fail(TN_ERR_INVALID, "increment %lld does not name the output it adds to", (long long)m);
+          break;
+        }
         if (s == TN_OK) s = write(m);
         break;
+      case TN_MG_JOIN: {  // the summed output changes its name; every increment has read it by now
+        const int64_t z = x.operands.empty() ? -1 : x.operands[0];
+        if (z < 0 || mg->v[z].op_kind != TN_OP_ZERO || mg->v[z].offset != x.offset) {
+          s = fail(TN_ERR_INVALID, "join %lld has no output to take over", (long long)m);
+          break;
+        }
+        if ((s = read(m, z)) != TN_OK) break;
+        if (nread[z] != 0) {
+          s = fail(TN_ERR_INVALID, "join %lld runs while increments are outstanding", (long long)m);
+          break;
+        }
+        mem[(uint64_t)x.offset].second = m;
+        break;
+      }
       case TN_MG_OFFLOAD:
       case TN_MG_STORE:
         s = read(m, x.operands[0]);

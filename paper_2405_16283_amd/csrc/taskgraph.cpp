@@ -150,6 +150,17 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
         return fail(TN_ERR_SHAPE, "rms_bwd_apply: operand shapes do not fit");
       return TN_OK;
     }
+    case TN_OP_SUM:
+      for (int i = 0; i < n_in; ++i) {
+        if (D(i).rows != out.rows || D(i).cols != out.cols || D(i).dtype != out.dtype)
+          return fail(TN_ERR_SHAPE, "sum: operand %d is not of the output's shape and type", i);
+        for (int k = 0; k < i; ++k)
+          if (in[k] == in[i]) return fail(TN_ERR_INVALID, "sum: operand %d repeats operand %d", i, k);
+      }
+      return TN_OK;
+    case TN_OP_ZERO:
+    case TN_OP_SUM_INTO:
+      return fail(TN_ERR_INVALID, "vertex kind %d exists in memgraphs only (see TN_OP_SUM)", kind);
     case TN_OP_TRANSPOSE:
       if (n_in != 1 || D(0).rows != out.cols || D(0).cols != out.rows || D(0).dtype != out.dtype)
         return fail(TN_ERR_SHAPE, "transpose: one operand [cols, rows] of the output's type");
@@ -274,16 +285,25 @@ struct Tiler {
     return gns;
   }
 
-  // one output tile of X(row tile) * W, full K inside the vertex
+  // one output tile of X(row tile) * W: full K inside one vertex, or (k_split) partial products
+  // over runs of K tiles joined by a sum vertex
   tn_vid gemm(const std::vector<tn_vid>& xrow, const Grid& w, size_t j, int32_t m, int32_t n,
               bool trans_c = false) {
-    tn_op_params p{};
-    p.nk = (int32_t)xrow.size();
-    p.trans_b = c.weights_transposed ? 1 : 0;
-    p.trans_c = trans_c ? 1 : 0;
-    std::vector<tn_vid> in(xrow);
-    for (size_t k = 0; k < xrow.size(); ++k) in.push_back(w[k][j]);
-    return op(TN_OP_GEMM, p, std::move(in), trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
+    const size_t nk = xrow.size();
+    const size_t per = c.k_split > 1 ? (nk + c.k_split - 1) / c.k_split : nk;
+    const tn_tensor_desc d = trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n};
+    std::vector<tn_vid> parts;
+    for (size_t k0 = 0; k0 < nk; k0 += per) {
+      const size_t k1 = std::min(nk, k0 + per);
+      tn_op_params p{};
+      p.nk = (int32_t)(k1 - k0);
+      p.trans_b = c.weights_transposed ? 1 : 0;
+      p.trans_c = trans_c ? 1 : 0;
+      std::vector<tn_vid> in(xrow.begin() + k0, xrow.begin() + k1);
+      for (size_t k = k0; k < k1; ++k) in.push_back(w[k][j]);
+      parts.push_back(op(TN_OP_GEMM, p, std::move(in), d));
+    }
+    return parts.size() == 1 ? parts[0] : op(TN_OP_SUM, tn_op_params{}, std::move(parts), d);
   }
 
   std::vector<tn_vid> rmsnorm(const std::vector<tn_vid>& xrow, const std::vector<tn_vid>& gns, int32_t m,
@@ -450,6 +470,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.lora_rank < 0 || (c.train && c.lora_rank < 1)) return fail(TN_ERR_INVALID, "train needs lora_rank > 0");
   if (c.train && gw != c.tile) return fail(TN_ERR_SHAPE, "train needs head_dim <= tile (one column tile per head group)");
   if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
+  if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
 
   auto* tg = new (std::nothrow) tn_taskgraph();
   if (!tg) return fail(TN_ERR_INVALID, "out of host memory");

@@ -19,14 +19,16 @@ OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms
             B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
             B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
             B.TN_OP_SILU_MUL_BWD: "silu_mul_bwd", B.TN_OP_RMS_BWD_STAT: "rms_bwd_stat",
-            B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd", B.TN_OP_TRANSPOSE: "transpose"}
+            B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd", B.TN_OP_TRANSPOSE: "transpose",
+            B.TN_OP_SUM: "sum"}
 MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op", B.TN_MG_OFFLOAD: "offload",
-                 B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store"}
+                 B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store", B.TN_MG_JOIN: "join"}
 EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}
 
 
 def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
-                        v_transposed: bool = True, lora_rank: int = 0, train: bool = False) -> B.tn_llama_config:
+                        v_transposed: bool = True, lora_rank: int = 0, train: bool = False,
+                        k_split: int = 0) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -35,7 +37,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         weights_residency=B.TN_DEVICE if cfg.weights_resident else B.TN_HOST,
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
         weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
-        lora_rank=int(lora_rank), train=int(train))
+        lora_rank=int(lora_rank), train=int(train), k_split=int(k_split))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -73,9 +75,15 @@ def export_memgraph(mg) -> dict:
     kind, src, loc, operands, order_pos = [], [], [], [], []
     for i in range(n):
         x = B.tn_memgraph_vertex(mg, i)
-        kind.append(MG_KIND_NAMES[x.kind])
+        name = MG_KIND_NAMES[x.kind]
+        if x.kind == B.TN_MG_OP and x.op_kind == B.TN_OP_ZERO:
+            name = "zero"
+        increment = x.kind == B.TN_MG_OP and x.op_kind == B.TN_OP_SUM_INTO
+        if increment:
+            name = "increment"
+        kind.append(name)
         src.append(x.src)
-        writes = x.kind in (B.TN_MG_INPUT, B.TN_MG_LOAD, B.TN_MG_OP, B.TN_MG_RELOAD)
+        writes = x.kind in (B.TN_MG_INPUT, B.TN_MG_LOAD, B.TN_MG_OP, B.TN_MG_RELOAD, B.TN_MG_JOIN) and not increment
         loc.append((x.offset, x.bytes) if writes and x.offset >= 0 else None)
         operands.append(B.tn_memgraph_operands(mg, i, x.n_operands) if x.n_operands else [])
         order_pos.append(x.order_pos)
@@ -187,14 +195,14 @@ class GpuSession:
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
-                 lora_rank: int = 0, train: bool = False, progress=None):
+                 lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
         self.torch = torch
         self.cfg = cfg
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
-                                                       lora_rank, train))
+                                                       lora_rank, train, k_split))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

@@ -1,0 +1,87 @@
+"""GPU parity of the k-split + sum-into form of the projections (Section 8, resources): partial
+products over runs of K tiles, added by increment kernels into a write-locked output, in whatever
+order they arrive.  Each increment rounds the output to its storage type, so dispatch orders agree
+with the oracle and with each other within the tolerance, not bit for bit; with two partial
+products per sum the order cannot matter (a + b = b + a) and the bits must agree."""
+import numpy as np
+import pytest
+
+from oracle import llama_ref as R
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import bf16_bits_to_f32, config, make_llama_inputs
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _f64(cfg, a):
+    return (bf16_bits_to_f32(a) if cfg.dtype == "bf16" else a).astype(np.float64)
+
+
+def _oracle(cfg, full, k_split):
+    w = R.widen(cfg, full)
+    tg = T.build_llama_taskgraph(cfg, k_split=k_split)
+    return T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model), max(
+        len(tg.inputs[v]) for v in range(len(tg)) if tg.kind[v] == "sum")
+
+
+@pytest.mark.parametrize("name,k_split", [("c1", 2), ("c1", 3), ("ragged_f32", 3), ("ragged_bf16", 2), ("batch2_f32", 2)])
+def test_k_split_forward_matches_the_oracle_in_twenty_orders(name, k_split):
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 0)
+    y_oracle, widest = _oracle(cfg, full, k_split)
+    s = H.GpuSession(cfg, full, k_split=k_split)
+    try:
+        print(f"[case] {name} k_split {k_split}: {s.stats.n_vertices} vertices, {s.stats.n_increment} increments, "
+              f"{s.stats.n_offload} offloads, widest sum {widest}", flush=True)
+        assert s.stats.n_increment > 0 and s.stats.n_offload > 0
+        ref, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
+        assert rep.n_vertices == s.stats.n_vertices
+        y_ref = _f64(cfg, ref["y"])
+        err = R.rel_err(y_ref, y_oracle)
+        print(f"  rel err vs tiled oracle {err:.3e}", flush=True)
+        assert np.isfinite(y_ref).all() and err < TOL[cfg.dtype]
+        differing = 0
+        for seed in range(20):
+            delay = (0, 50, 500)[seed % 3]
+            batch = (1, 4, 0)[(seed // 3) % 3]
+            depth = (1, 3, 8)[(seed // 2) % 3]
+            print(f"[case] {name} k_split {k_split} order_seed {seed} delay {delay} batch {batch} depth {depth}", flush=True)
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, delay_seed=100 + seed,
+                                            max_delay_us=delay, max_batch=batch, queue_depth=depth))
+            assert rep.n_vertices == s.stats.n_vertices
+            B.tn_memgraph_simulate(s.mg, s.last_order())  # the order taken respects every dependency
+            y = _f64(cfg, out["y"])
+            assert R.rel_err(y, y_oracle) < TOL[cfg.dtype]
+            differing += not np.array_equal(out["y"], ref["y"])
+        print(f"  {differing} of 20 orders differ from the first in some bit", flush=True)
+        if widest == 2:
+            assert differing == 0
+        for policy in (B.TN_POLICY_FIFO, B.TN_POLICY_LIFO, B.TN_POLICY_IN_ORDER):
+            for depth in (1, 3):
+                out, _ = s.run(B.tn_exec_opts(policy=policy, queue_depth=depth, max_delay_us=50, delay_seed=policy))
+                assert R.rel_err(_f64(cfg, out["y"]), y_oracle) < TOL[cfg.dtype]
+    finally:
+        s.close()
+
+
+def test_c2_with_k_split_two_matches_the_oracle():
+    cfg = config("c2")
+    full = make_llama_inputs(cfg, 0)
+    y_oracle, widest = _oracle(cfg, full, 2)
+    print("[case] c2 full size, k_split 2, bench configuration", flush=True)
+    s = H.GpuSession(cfg, full, k_split=2)
+    try:
+        opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
+        out, rep = s.run(opts)
+        y = _f64(cfg, out["y"])
+        err = R.rel_err(y, y_oracle)
+        print(f"  {s.stats.n_increment} increments; rel err vs tiled oracle over all {y.size} outputs: {err:.3e}; "
+              f"{rep.wall_ms:.2f} ms", flush=True)
+        assert np.isfinite(y).all() and err < 2e-2
+        o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=4, max_batch=64, max_delay_us=100))
+        np.testing.assert_array_equal(o2["y"], out["y"])  # two partial products per sum: order cannot matter
+    finally:
+        s.close()
