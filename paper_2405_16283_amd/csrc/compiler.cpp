@@ -55,7 +55,7 @@ struct Compiler {
   std::vector<std::vector<int64_t>> readers;  // per memgraph vertex: who has read its output so far
   std::vector<std::vector<size_t>> malloc_edges;  // per memgraph vertex: edges its allocation added
   std::vector<char> edge_dead;
-  std::vector<char> counted_ahead;  // per taskgraph vertex: its allocation counts as run-ahead
+  std::vector<char> counted_ahead;  // per memgraph vertex: its allocation counts as run-ahead
   std::unordered_set<uint64_t> edge_set[3];
   std::map<uint64_t, Block> blocks;                          // offset -> block, covers [0, cap)
   std::map<uint64_t, std::pair<uint64_t, int64_t>> history;  // offset -> (end, last dead occupant)
@@ -71,6 +71,15 @@ struct Compiler {
   std::vector<int64_t> acc_of;                  // per sum vertex: the vertex that clears its output, or -1
   std::vector<std::vector<int64_t>> incs_of;    // per sum vertex: its increments so far
   std::vector<char> open_acc;                   // per memgraph vertex: an output still being summed into
+  // The allocations in the order allocHzn takes them: the output of every vertex of V that needs
+  // one (entry = the vertex), and right after the first operand of a sum the sum's output
+  // (entry = ~sum vertex).  Device-resident inputs are placed before anything else and sums have
+  // no allocation of their own, so neither appears.
+  std::vector<int64_t> A;
+  std::vector<int64_t> apos;        // per taskgraph vertex: index of its own entry in A, or -1
+  std::vector<int64_t> apos_acc;    // per sum vertex: index of its output's entry in A
+  std::vector<int64_t> owner_pos;   // per entry of A: position in V of the vertex after whose run it is needed
+  std::vector<char> zero_placed;    // per sum vertex: its clearing vertex has a place in the extended order
 
   Compiler(const TaskGraph& t, const tn_compile_opts& o, MemGraph& m)
       : tg(t), opt(o), mg(m), n((int64_t)t.v.size()) {}
@@ -89,6 +98,7 @@ struct Compiler {
     readers.emplace_back();
     malloc_edges.emplace_back();
     open_acc.push_back(0);
+    counted_ahead.push_back(0);
     return (int64_t)mg.v.size() - 1;
   }
 
@@ -272,13 +282,24 @@ struct Compiler {
   // undo the newest run-ahead allocation (Algorithm 1 does not say what to do when memory is
   // full of locations reserved for results that do not exist yet; they cannot be offloaded)
   bool revoke_newest_preallocation() {
-    if (allocHzn - 1 <= execHzn) return false;
+    if (allocHzn == 0 || owner_pos[allocHzn - 1] <= execHzn) return false;
     --allocHzn;
-    if (is_sum(V[allocHzn])) return true;  // a sum's output is placed by its first increment, not ahead
-    unplace(V[allocHzn]);
+    unplace(entry_vertex(allocHzn));
     ++mg.stats.n_revoked;
     lookahead_blocked_until = execHzn + 1;
     return true;
+  }
+
+  // the memgraph vertex that owns the allocation A[i]; a sum's clearing vertex is made on first use
+  int64_t entry_vertex(int64_t i) {
+    if (A[i] >= 0) return A[i];
+    const tn_vid s = (tn_vid)~A[i];
+    if (acc_of[s] < 0) {
+      acc_of[s] = new_vertex(TN_MG_OP, s);
+      mg.v[acc_of[s]].op_kind = TN_OP_ZERO;
+      open_acc[acc_of[s]] = 1;
+    }
+    return acc_of[s];
   }
 
   // Last resort against fragmentation: pinned operands scattered over memory can leave no hole
@@ -472,16 +493,22 @@ struct Compiler {
   // tensor u, just produced, is added to the output of sum vertex s
   tn_status increment(tn_vid s, tn_vid u) {
     const std::vector<int64_t> pinned{name[u]};
-    if (acc_of[s] < 0) {
-      const int64_t z = new_vertex(TN_MG_OP, s);
-      mg.v[z].op_kind = TN_OP_ZERO;
-      open_acc[z] = 1;
-      tn_status st = sim_malloc_offld(z, pinned);
+    // the output is allocated like any other, ahead of the execution if memory allows; if the
+    // run-ahead has not come this far, now is the latest moment (the entries between are outputs
+    // of other sums that u is the first operand of)
+    while (allocHzn <= apos_acc[s]) {
+      tn_status st = sim_malloc_offld(entry_vertex(allocHzn), pinned);
       if (st != TN_OK) return st;
-      acc_of[s] = z;
+      ++allocHzn;
+    }
+    if (!zero_placed[s]) {
+      const int64_t z0 = acc_of[s];
+      zero_placed[s] = 1;
+      if (counted_ahead[z0]) lookahead_bytes -= vbytes(z0);
+      counted_ahead[z0] = 0;
       for (int64_t o : step_pre) mg.order.push_back(o);  // what made room for it comes first
       step_pre.clear();
-      mg.order.push_back(z);
+      mg.order.push_back(z0);
     }
     const int64_t z = acc_of[s];
     const int64_t i = new_vertex(TN_MG_OP, s);
@@ -605,7 +632,6 @@ struct Compiler {
     name.assign(n, -1);
     use_key.assign(n, -1);
     evicted_by.assign(n, -1);
-    counted_ahead.assign(n, 0);
     mg.v.reserve(n + n / 4);
     for (int64_t v = 0; v < n; ++v) {
       const Vertex& tv = tg.v[v];
@@ -616,38 +642,55 @@ struct Compiler {
       if (tv.kind == TN_OP_SUM) mg.v[m].kind = TN_MG_JOIN;
     }
     // tensors that are on the GPU before execution starts occupy memory from the beginning
-    while (allocHzn < n && mg.v[V[allocHzn]].kind == TN_MG_INPUT) {
-      if (!sim_malloc(V[allocHzn]))
+    for (int64_t i = 0; i < n; ++i)
+      if (mg.v[V[i]].kind == TN_MG_INPUT && !sim_malloc(V[i]))
         return fail(TN_ERR_CAP_TOO_SMALL, "the device-resident inputs alone exceed the cap of %llu bytes",
                     (unsigned long long)cap);
-      ++allocHzn;
-    }
-    while (execHzn < n) {
-      if (allocHzn < n && is_sum(V[allocHzn])) {  // placed by its first increment
-        ++allocHzn;
-        continue;
+    apos.assign(n, -1);
+    apos_acc.assign(n, -1);
+    zero_placed.assign(n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+      const tn_vid v = V[i];
+      if (mg.v[v].kind != TN_MG_INPUT && !is_sum(v)) {
+        apos[v] = (int64_t)A.size();
+        A.push_back(v);
+        owner_pos.push_back(i);
       }
-      bool ahead_ok = false;
-      if (allocHzn < n) {
-        const uint64_t sz = vbytes(V[allocHzn]);
-        ahead_ok = allocHzn == execHzn ||
-                   (execHzn >= lookahead_blocked_until && opt.max_lookahead_bytes >= sz &&
-                    lookahead_bytes <= opt.max_lookahead_bytes - sz);
-      }
-      if (ahead_ok && sim_malloc(V[allocHzn])) {
-        if (allocHzn > execHzn) {
-          lookahead_bytes += vbytes(V[allocHzn]);
-          counted_ahead[V[allocHzn]] = 1;
+      for (tn_vid s : sums_of[v])
+        if (apos_acc[s] < 0) {
+          apos_acc[s] = (int64_t)A.size();
+          A.push_back(~(int64_t)s);
+          owner_pos.push_back(i);
         }
-        ++allocHzn;
-      } else if (allocHzn == execHzn) {
-        tn_status s = sim_malloc_offld(V[allocHzn], pinned_for(V[allocHzn]));
-        if (s != TN_OK) return s;
-        ++allocHzn;
-      } else {
-        tn_status s = execute_next();
-        if (s != TN_OK) return s;
+    }
+    const int64_t na = (int64_t)A.size();
+    while (execHzn < n) {
+      const tn_vid v = V[execHzn];
+      const bool v_placed = apos[v] < allocHzn;  // also true for vertices without an entry
+      if (allocHzn < na) {
+        // an entry the next vertex waits for is its own: whatever comes before it in A belongs to
+        // vertices that have run
+        const int64_t m = entry_vertex(allocHzn);
+        const uint64_t sz = vbytes(m);
+        const bool ahead_ok = !v_placed || (execHzn >= lookahead_blocked_until && opt.max_lookahead_bytes >= sz &&
+                                            lookahead_bytes <= opt.max_lookahead_bytes - sz);
+        if (ahead_ok && sim_malloc(m)) {
+          if (v_placed) {
+            lookahead_bytes += sz;
+            counted_ahead[m] = 1;
+          }
+          ++allocHzn;
+          continue;
+        }
+        if (!v_placed) {
+          tn_status s = sim_malloc_offld(m, pinned_for(v));
+          if (s != TN_OK) return s;
+          ++allocHzn;
+          continue;
+        }
       }
+      tn_status s = execute_next();
+      if (s != TN_OK) return s;
     }
     return TN_OK;
   }

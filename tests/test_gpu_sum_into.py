@@ -68,19 +68,30 @@ def test_k_split_forward_matches_the_oracle_in_twenty_orders(name, k_split):
 
 
 def test_c2_with_k_split_two_matches_the_oracle():
+    """At the benchmark's size.  The unsplit c2 result stands 1.98e-2 (maximum measure) from the
+    tiled oracle, just inside the 2e-2 bar; the split form stores twice as many bf16 tensors on the
+    way, so its bar is the oracle's own: the GPU result must be as close to the exact float64
+    forward as the oracle's k-split form is (within the factor), and inside a widened 4e-2 of it."""
     cfg = config("c2")
     full = make_llama_inputs(cfg, 0)
     y_oracle, widest = _oracle(cfg, full, 2)
+    y_exact = R.forward(cfg, R.widen(cfg, full))
     print("[case] c2 full size, k_split 2, bench configuration", flush=True)
     s = H.GpuSession(cfg, full, k_split=2)
     try:
         opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
         out, rep = s.run(opts)
         y = _f64(cfg, out["y"])
+
+        def rms_err(a, b):
+            return float(np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2)))
+
+        max_o, max_g, rms_o, rms_g = R.rel_err(y_oracle, y_exact), R.rel_err(y, y_exact), rms_err(y_oracle, y_exact), rms_err(y, y_exact)
         err = R.rel_err(y, y_oracle)
-        print(f"  {s.stats.n_increment} increments; rel err vs tiled oracle over all {y.size} outputs: {err:.3e}; "
-              f"{rep.wall_ms:.2f} ms", flush=True)
-        assert np.isfinite(y).all() and err < 2e-2
+        print(f"  {s.stats.n_increment} increments; gpu vs tiled oracle {err:.3e}; against the exact forward: oracle "
+              f"{max_o:.3e} (rms {rms_o:.3e}), gpu {max_g:.3e} (rms {rms_g:.3e}); {rep.wall_ms:.2f} ms", flush=True)
+        assert np.isfinite(y).all() and err < 4e-2
+        assert max_g < 1.5 * max_o and rms_g < 1.5 * rms_o
         o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=4, max_batch=64, max_delay_us=100))
         np.testing.assert_array_equal(o2["y"], out["y"])  # two partial products per sum: order cannot matter
     finally:
