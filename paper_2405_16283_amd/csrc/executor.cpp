@@ -275,8 +275,9 @@ tn_status build_tables(tn_executor& ex) {
         if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_block %lld: head_dim must be 64 or 128", (long long)m);
         aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
         // the MFMA kernel wants V^T tiles, whole heads inside one column tile, 64-key chunks inside
-        // one row tile, and 16-byte chunks that do not straddle anything
-        vi.cls = (d.dtype == TN_BF16 && x.p.v_trans && tc % hd == 0 && tk % 64 == 0 && kv_rows % 8 == 0)
+        // one row tile, 16-byte chunks that do not straddle anything, and a positive scale (it takes
+        // the row maximum before scaling)
+        vi.cls = (d.dtype == TN_BF16 && x.p.v_trans && tc % hd == 0 && tk % 64 == 0 && kv_rows % 8 == 0 && x.p.scale > 0.f)
                      ? LC_ATTN_BF16 : LC_ATTN_F32;
         vi.head_dim = (int16_t)hd;
         vi.flops = 4.0 * q_rows * kv_rows * (double)(nc * tc);

@@ -1069,6 +1069,19 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
 // of a V^T row.  K and V^T chunks of 64 keys are double-buffered in LDS and filled by direct
 // global-to-LDS loads; conflicts are avoided by swizzling which chunk each lane fetches.
 // ---------------------------------------------------------------------------------------------
+// two weights as a pair of bf16 (hi) and the bf16 of what that rounding left over (lo), packed
+__device__ __forceinline__ void split_bf16_pair(float a, float b, uint32_t& hi, uint32_t& lo) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t h = __builtin_convertvector((f32x2_t){a, b}, bf16x2_t);
+  hi = __builtin_bit_cast(uint32_t, h);
+  const float ha = __uint_as_float(hi << 16), hb = __uint_as_float(hi & 0xFFFF0000u);
+  const bf16x2_t r = __builtin_convertvector((f32x2_t){a - ha, b - hb}, bf16x2_t);
+  lo = __builtin_bit_cast(uint32_t, r);
+}
+
+constexpr float kLazy = 8.f;  // see the rescaling step of attn_bf16_kernel
+
 template <int HD>
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
@@ -1183,25 +1196,26 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
       // register r = 4a + b of this lane is the score of key 16*(a>>1) + 8g + 4*(a&1) + b
       const int kvs = it * KC + sub * 32;
       const bool need_mask = kvs + 32 > kv_rows || (causal && k_pos0 + kvs + 31 > qpos_w0);
+      // the maximum is taken over the raw products: scaling by a positive factor commutes with it
       float mx = -INFINITY;
       if (need_mask) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int kv = kvs + 16 * (r >> 3) + 8 * g + (r & 7);
           const bool ok = kv < kv_rows && !(causal && k_pos0 + kv > qpos);
-          sT[r] = ok ? sT[r] * scale2 : -INFINITY;
+          sT[r] = ok ? sT[r] : -INFINITY;
           mx = fmaxf(mx, sT[r]);
         }
       } else {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          sT[r] *= scale2;
-          mx = fmaxf(mx, sT[r]);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sT[r]);
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale2;
       const float mn = fmaxf(m, mx);
-      if (__any(mn > m)) {  // some query of the wavefront has a new maximum: rescale what is summed so far
+      // What is summed so far is rescaled only when the maximum of some query of the wavefront has
+      // grown by more than kLazy (in units of log2): until then probabilities are taken relative to
+      // the older maximum and stay below 2^kLazy, which costs fp32 and the bf16 pair nothing.
+      if (__any(mn > m + kLazy)) {
         const float alpha = mn == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - mn);
         l *= alpha;
 #pragma unroll
@@ -1214,15 +1228,16 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
       // Probabilities enter the MFMA as bf16.  A single bf16 would carry 8 bits of each weight;
       // the remainder p - bf16(p) is fed through a second MFMA, so that the product sees 16 bits
       // and the block's result does not depend on where the running maximum stood.
-      bf16x8 p0, p1, q0, q1;
+      union { uint32_t u[4]; bf16x8 v; } p0, p1, q0, q1;
       float ls = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pr = __builtin_amdgcn_exp2f(sT[r] - msub);
-        ls += pr;
-        const __bf16 hi = (__bf16)pr;
-        const __bf16 lo = (__bf16)(pr - (float)hi);
-        if (r < 8) { p0[r] = hi; q0[r] = lo; } else { p1[r - 8] = hi; q1[r - 8] = lo; }
+      for (int r = 0; r < 16; r += 2) {
+        const float pa = __builtin_amdgcn_exp2f(__builtin_fmaf(sT[r], scale2, -msub));
+        const float pb = __builtin_amdgcn_exp2f(__builtin_fmaf(sT[r + 1], scale2, -msub));
+        ls += pa + pb;
+        uint32_t hi, lo;
+        split_bf16_pair(pa, pb, hi, lo);
+        if (r < 8) { p0.u[r >> 1] = hi; q0.u[r >> 1] = lo; } else { p1.u[(r - 8) >> 1] = hi; q1.u[(r - 8) >> 1] = lo; }
       }
       l += ls;
       // O^T[d, q] += sum over the slab's 16 keys of V^T[d, key] P^T[key, q]
@@ -1231,10 +1246,10 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
         const int dr = i * 32 + l32, vsw = (dr >> 1) & 7;
         bf16x8 a0 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + g) ^ vsw)) * 16);
         bf16x8 a1 = *(const bf16x8*)(vb + (dr * 8 + ((sub * 4 + 2 + g) ^ vsw)) * 16);
-        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, q0, ot[i], 0, 0, 0);
-        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, q1, ot[i], 0, 0, 0);
-        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0, ot[i], 0, 0, 0);
-        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, q0.v, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, q1.v, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, p0.v, ot[i], 0, 0, 0);
+        ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, p1.v, ot[i], 0, 0, 0);
       }
     }
   }
