@@ -864,23 +864,32 @@ __global__ void __launch_bounds__(64) attn_bwd_kernel(DeviceTables t, Batch b) {
 // Modes 2 (dK) and 3 (dV): one workgroup = one head x 128 keys, a lane owns a key; per 32 queries
 // S = Q K^T and dP = dO V^T with the query rows permuted likewise, and dK^T += Q^T dS,
 // dV^T += dO^T P read rows of Q^T / dO^T tiles.
-// The four wavefronts of a workgroup need the same rows of the other side: the workgroup brings
-// them in 64 rows at a time through LDS (rows padded by 16 bytes against bank conflicts), together
-// with the statistics of those rows.  Probabilities and dS enter the MFMA as single bf16.
+// The eight wavefronts of a workgroup need the same rows of the other side: the workgroup brings
+// them in 64 rows at a time through two LDS stages filled by direct global-to-LDS loads (the next
+// chunk arrives while the current one is multiplied), together with the statistics of those rows.
+// Probabilities and dS enter the MFMA as single bf16.
 // aux: [rows per Q tile, rows per K/V tile, columns per tile, q rows, kv rows]
 // ---------------------------------------------------------------------------------------------
+// two floats rounded to bf16 (nearest even), the first in the low half
+__device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, bf16x2_t));
+}
+
 constexpr int kAttnBwdThreads = 512, kAttnBwdRows = 256;  // eight wavefronts of 32 rows
+constexpr int kAttnBwdChunk = 64;                          // rows of the other side staged per round
+constexpr int attn_bwd_lds(int hd) { return 2 * 3 * kAttnBwdChunk * hd * 2 + 2 * 2 * kAttnBwdChunk * 4; }
 template <int HD, int mode>
 __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
-  constexpr int CH = 64;             // rows of the other side per round
-  constexpr int LDA = HD + 8;        // padded row of a [CH][HD] chunk, in elements
-  constexpr int LDT = CH + 8;        // padded row of a transposed [HD][CH] chunk
-  __shared__ __attribute__((aligned(16))) bf16_t bufA[CH * LDA];  // K (modes 0, 1) or Q (modes 2, 3)
-  __shared__ __attribute__((aligned(16))) bf16_t bufB[CH * LDA];  // V or dO
-  __shared__ __attribute__((aligned(16))) bf16_t bufT[HD * LDT];  // K^T, Q^T or dO^T
-  __shared__ float bufS[CH * 2];                                  // lse * log2(e), D of the chunk's queries
+  constexpr int CH = kAttnBwdChunk;  // rows of the other side per round
+  constexpr int CPR = HD / 8;        // 16-byte pieces per row of a [CH][HD] chunk
+  constexpr int ABYTES = CH * HD * 2, STAGE = 3 * ABYTES;  // K | V | K^T (or Q | dO | Q^T or dO^T): equal sizes
+  // two stages, then the statistics (lse * log2(e), D) of the queries of both stages
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  float* const bufS = (float*)(lds + 2 * STAGE);
   const int* ax = t.aux + d.aux0;
   const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
   const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD;  // mode (template) == d.p.mode: its own launch class
@@ -914,28 +923,53 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
   void* const* gridA = mode <= 1 ? Kt : Qt;
   void* const* gridB = mode <= 1 ? Vt : Dt;
   const int o_trows = mode <= 1 ? tk : tq, o_rows = mode <= 1 ? kv_rows : q_rows;
-  auto stage = [&](int row0) {  // rows [row0, row0 + CH) of the other side into LDS
-    constexpr int CPR = HD / 8;
+  // Rows [row0, row0 + CH) of the other side go to LDS stage `stg` by direct global-to-LDS loads:
+  // piece p = i*512 + tid of an operand lands at byte 16 p.  [CH][HD] chunks: row p / CPR, and the
+  // piece stored at p % CPR is piece (p % CPR) ^ swizzle(row) of that row; the transposed [HD][CH]
+  // chunk: row p / 8, stored piece p % 8 is piece (p % 8) ^ ((row >> 1) & 7).  The swizzles keep
+  // the fragment reads below free of bank conflicts without padding, which these loads cannot do.
+  // A head's columns lie inside one column tile and a chunk inside one row tile (the executor
+  // checks both), so the tile pointers are wavefront-uniform and change rarely.
+  const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
+  const int ct = (h * HD) / tc, cin0 = (h * HD) % tc;
+  int rt = -1, trows = 0;
+  const bf16_t* At = nullptr;
+  const bf16_t* Bt = nullptr;
+  const bf16_t* Tp = nullptr;
+  auto issue = [&](int row0, int stg) {
+    const int nrt = row0 / o_trows;
+    if (nrt != rt) {
+      rt = nrt;
+      At = (const bf16_t*)sload_ptr((const void* const*)(gridA + rt * nc + ct));
+      if (mode != 3) Bt = (const bf16_t*)sload_ptr((const void* const*)(gridB + rt * nc + ct));
+      if (mode >= 1) Tp = (const bf16_t*)sload_ptr((const void* const*)(Tt + rt * nc + ct));
+      trows = min(o_trows, o_rows - rt * o_trows);
+    }
+    const int rin = row0 - rt * o_trows;
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stg * STAGE + w * 1024);
 #pragma unroll
-    for (int k = 0; k < CH * CPR / kAttnBwdThreads; ++k) {
-      const int c = threadIdx.x + kAttnBwdThreads * k, r = c / CPR, c8 = (c % CPR) * 8;
-      const int gr = min(row0 + r, o_rows - 1);
-      *(uint4*)(bufA + r * LDA + c8) = *(const uint4*)tile_elem<bf16_t>(gridA, nc, o_trows, tc, gr, h * HD + c8);
-      if (mode != 3) *(uint4*)(bufB + r * LDA + c8) = *(const uint4*)tile_elem<bf16_t>(gridB, nc, o_trows, tc, gr, h * HD + c8);
+    for (int i = 0; i < CH * CPR / kAttnBwdThreads; ++i) {
+      const int p = i * kAttnBwdThreads + threadIdx.x, r = p / CPR;
+      const int col = cin0 + (((p % CPR) ^ (CPR == 16 ? (r & 15) : ((r >> 1) & 7))) * 8);
+      const int gr = min(rin + r, trows - 1);  // rows past the end: any valid row, their weights are zero
+      load_lds16(At + (size_t)gr * tc + col, dst + i * (kAttnBwdThreads * 16));
+      if (mode != 3) load_lds16(Bt + (size_t)gr * tc + col, dst + ABYTES + i * (kAttnBwdThreads * 16));
     }
     if (mode >= 1) {
 #pragma unroll
-      for (int k = 0; k < HD * (CH / 8) / kAttnBwdThreads; ++k) {
-        const int c = threadIdx.x + kAttnBwdThreads * k, dd = c / (CH / 8), r8 = (c % (CH / 8)) * 8;
-        const int gr = min(row0 + r8, o_rows - 8);  // 8 rows at once; past the end any valid rows do (zero weights)
-        *(uint4*)(bufT + dd * LDT + r8) = *(const uint4*)tile_elem_t<bf16_t>(Tt, nc, o_trows, tc, o_rows, gr, h * HD + dd);
+      for (int i = 0; i < HD * (CH / 8) / kAttnBwdThreads; ++i) {
+        const int p = i * kAttnBwdThreads + threadIdx.x, dd = p / 8;
+        const int r8 = min(rin + ((p % 8) ^ ((dd >> 1) & 7)) * 8, trows - 8);  // 8 rows at once
+        load_lds16(Tp + (size_t)(cin0 + dd) * trows + r8, dst + 2 * ABYTES + i * (kAttnBwdThreads * 16));
       }
     }
-    if (mode >= 2 && threadIdx.x < 2 * CH) {
-      const int r = threadIdx.x >> 1, which = threadIdx.x & 1;
-      const float v = stat(min(row0 + r, q_rows - 1), which);
-      bufS[r * 2 + which] = which ? v : v * LOG2E;
-    }
+  };
+  // the statistics of a chunk's queries (modes 2, 3) travel through a register of the first 2 CH lanes
+  auto load_stat = [&](int row0) -> float {
+    if (mode < 2 || threadIdx.x >= 2 * CH) return 0.f;
+    const int r = threadIdx.x >> 1, which = threadIdx.x & 1;
+    const float v = stat(min(row0 + r, q_rows - 1), which);
+    return which ? v : v * LOG2E;
   };
   f32x16 acc[HD / 32];
 #pragma unroll
@@ -963,23 +997,39 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
   if (causal && mode <= 1) end = min(kv_rows, d.p.q_pos0 + rb * kAttnBwdRows + kAttnBwdRows - d.p.k_pos0);
   if (causal && mode >= 2) begin = max(0, d.p.k_pos0 + rb * kAttnBwdRows - d.p.q_pos0) & ~(CH - 1);
 
-  for (int row0 = begin; row0 < end; row0 += CH) {
-    __syncthreads();  // everybody is done with the previous chunk
-    stage(row0);
-    __syncthreads();
+  // fragment addresses inside a stage (see the layouts above)
+  const int kx0 = (g ^ (CPR == 16 ? (perm & 15) : ((perm >> 1) & 7))) * 16;
+  const int vsw = (l32 >> 1) & 7;
+  float snext = 0.f;
+  if (begin < end) {
+    issue(begin, 0);
+    snext = load_stat(begin);
+  }
+  int stg = 0;
+  for (int row0 = begin; row0 < end; row0 += CH, stg ^= 1) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this chunk and its statistics have arrived
+    float* const sbuf = bufS + stg * (2 * CH);
+    if (mode >= 2 && threadIdx.x < 2 * CH) sbuf[threadIdx.x] = snext;
+    __syncthreads();  // ... for everybody, and everybody is done with the chunk before
+    if (row0 + CH < end) {
+      issue(row0 + CH, stg ^ 1);
+      snext = load_stat(row0 + CH);
+    }
+    const char* const bufA = lds + stg * STAGE;
 #pragma unroll 1
     for (int sub = 0; sub < CH / 32; ++sub) {
       const int base = row0 + sub * 32;
       if (base >= end) break;
-      const bf16_t* ra = bufA + (sub * 32 + perm) * LDA + g * 8;
-      const bf16_t* rbp = bufB + (sub * 32 + perm) * LDA + g * 8;
+      int kx = kx0;
+      asm volatile("" : "+v"(kx));  // formed where it is used, not kept ready for every s
+      const char* ra = bufA + (sub * 32 + perm) * (CPR * 16);
       f32x16 sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int s = 0; s < HD / 16; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(ra + s * 16), mine[s], sc, 0, 0, 0);
-        if (mode != 3) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(rbp + s * 16), mine2[s], dp, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(ra + (kx ^ (32 * s))), mine[s], sc, 0, 0, 0);
+        if (mode != 3) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(ra + ABYTES + (kx ^ (32 * s))), mine2[s], dp, 0, 0, 0);
       }
       // register r of this lane: row base + 16*(r>>3) + 8*g + (r&7) of the other side
       if (mode == 0) {
@@ -1007,26 +1057,53 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
         }
         continue;
       }
-      bf16x8 s0, s1;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int lr = sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7), o = row0 + lr;
-        float p;
-        if (mode == 1) {
-          const bool ok = o < kv_rows && !(causal && d.p.k_pos0 + o > mypos);
-          p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - lse2) * (dp[r] - Dq) * scale : 0.f;
-        } else {
-          const bool ok = valid && o < q_rows && !(causal && mypos > d.p.q_pos0 + o);
-          p = ok ? __builtin_amdgcn_exp2f(sc[r] * scale2 - bufS[lr * 2]) : 0.f;
-          if (mode == 2) p *= (dp[r] - bufS[lr * 2 + 1]) * scale;
-        }
-        if (r < 8) s0[r] = (__bf16)p; else s1[r - 8] = (__bf16)p;
+      // Weights of the 32 x 32 pairs of this slab: p (mode 3) or p (dp - D) (modes 1, 2; the factor
+      // `scale` of dS is applied to the finished sums).  A slab that lies wholly inside the matrix and
+      // on the visible side of the diagonal for every row of the wavefront needs no mask.
+      const int wrow0 = rb * kAttnBwdRows + w * 32;  // first row of this wavefront
+      bool need_mask;
+      if (mode == 1) {
+        need_mask = base + 32 > kv_rows || (causal && d.p.k_pos0 + base + 31 > d.p.q_pos0 + wrow0);
+      } else {
+        need_mask = wrow0 + 32 > my_rows || base + 32 > q_rows || (causal && d.p.k_pos0 + wrow0 + 31 > d.p.q_pos0 + base);
       }
+      float pr[16];
+      if (need_mask) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int lr = sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7), o = row0 + lr;
+          bool ok;
+          if (mode == 1) ok = o < kv_rows && !(causal && d.p.k_pos0 + o > mypos);
+          else ok = valid && o < q_rows && !(causal && mypos > d.p.q_pos0 + o);
+          float p;
+          if (mode == 1) p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale2, -lse2)) * (dp[r] - Dq);
+          else p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale2, -sbuf[lr * 2]));
+          if (mode == 2) p *= dp[r] - sbuf[lr * 2 + 1];
+          pr[r] = ok ? p : 0.f;
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int lr = sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
+          float p;
+          if (mode == 1) p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale2, -lse2)) * (dp[r] - Dq);
+          else p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale2, -sbuf[lr * 2]));
+          if (mode == 2) p *= dp[r] - sbuf[lr * 2 + 1];
+          pr[r] = p;
+        }
+      }
+      union { uint32_t u[4]; bf16x8 v; } s0u, s1u;
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const uint32_t pk = pack_bf16_pair(pr[r], pr[r + 1]);
+        if (r < 8) s0u.u[r >> 1] = pk; else s1u.u[(r - 8) >> 1] = pk;
+      }
+      const bf16x8 s0 = s0u.v, s1 = s1u.v;
 #pragma unroll
       for (int i = 0; i < HD / 32; ++i) {
-        const bf16_t* tr = bufT + (i * 32 + l32) * LDT + sub * 32 + 8 * g;
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)tr, s0, acc[i], 0, 0, 0);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(tr + 16), s1, acc[i], 0, 0, 0);
+        const char* tr = bufA + 2 * ABYTES + (i * 32 + l32) * 128;  // i * 32 leaves the swizzle of the row alone
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(tr + ((sub * 4 + g) ^ vsw) * 16), s0, acc[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(tr + ((sub * 4 + 2 + g) ^ vsw) * 16), s1, acc[i], 0, 0, 0);
       }
     }
   }
@@ -1046,13 +1123,14 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
   if (!valid) return;
   // accumulator tile i: this lane holds column myrow and rows (= head columns) 8a + 4g + k of it
   bf16_t* out = (bf16_t*)d.out + (size_t)myrow * gw + h * HD;
+  const float oscale = mode == 3 ? 1.f : scale;  // dS = scale * p (dp - D): the factor left out above
 #pragma unroll
   for (int i = 0; i < HD / 32; ++i)
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       uint2 v;
-      v.x = (uint32_t)f2bf(acc[i][4 * a]) | ((uint32_t)f2bf(acc[i][4 * a + 1]) << 16);
-      v.y = (uint32_t)f2bf(acc[i][4 * a + 2]) | ((uint32_t)f2bf(acc[i][4 * a + 3]) << 16);
+      v.x = (uint32_t)f2bf(acc[i][4 * a] * oscale) | ((uint32_t)f2bf(acc[i][4 * a + 1] * oscale) << 16);
+      v.y = (uint32_t)f2bf(acc[i][4 * a + 2] * oscale) | ((uint32_t)f2bf(acc[i][4 * a + 3] * oscale) << 16);
       *(uint2*)(out + i * 32 + 8 * a + 4 * g) = v;
     }
 }
@@ -1401,9 +1479,16 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
     case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;
 #define TN_LAUNCH_ATTN_BWD(MODE)                                                                                  \
   do {                                                                                                            \
-    if (head_dim == 64) hipLaunchKernelGGL((attn_bwd_bf16_kernel<64, MODE>), grid, dim3(kAttnBwdThreads), 0, s, t, b);        \
-    else if (head_dim == 128) hipLaunchKernelGGL((attn_bwd_bf16_kernel<128, MODE>), grid, dim3(kAttnBwdThreads), 0, s, t, b); \
-    else return hipErrorInvalidValue;                                                                             \
+    if (head_dim == 64) {                                                                                         \
+      hipLaunchKernelGGL((attn_bwd_bf16_kernel<64, MODE>), grid, dim3(kAttnBwdThreads), attn_bwd_lds(64), s, t, b); \
+    } else if (head_dim == 128) {                                                                                 \
+      static const hipError_t attr = hipFuncSetAttribute((const void*)attn_bwd_bf16_kernel<128, MODE>,            \
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, attn_bwd_lds(128)); \
+      if (attr != hipSuccess) return attr;                                                                        \
+      hipLaunchKernelGGL((attn_bwd_bf16_kernel<128, MODE>), grid, dim3(kAttnBwdThreads), attn_bwd_lds(128), s, t, b); \
+    } else {                                                                                                      \
+      return hipErrorInvalidValue;                                                                                \
+    }                                                                                                             \
   } while (0)
     case LC_ATTN_BWD_BF16: TN_LAUNCH_ATTN_BWD(0); break;
     case LC_ATTN_BWD_BF16_DQ: TN_LAUNCH_ATTN_BWD(1); break;
