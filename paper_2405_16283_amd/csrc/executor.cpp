@@ -341,9 +341,9 @@ tn_status build_tables(tn_executor& ex) {
         if (hd != 64 && hd != 128) return fail(TN_ERR_SHAPE, "attn_bwd %lld: head_dim must be 64 or 128", (long long)m);
         aux.insert(aux.end(), {tq, tk, tc, q_rows, kv_rows});
         // the MFMA kernel wants plain V tiles, the transposed grid (except for the statistics), whole
-        // heads inside one column tile, 64-row chunks inside one row tile, and 8-row groups that
-        // straddle nothing
-        vi.cls = (d.dtype == TN_BF16 && !x.p.v_trans && (x.p.mode == 0 || x.p.trans_a) && tc % hd == 0 && tq % 64 == 0 &&
+        // heads inside one column tile, 64-row chunks inside one row tile, 8-row groups that
+        // straddle nothing, and a positive scale (the row maximum is taken before scaling)
+        vi.cls = (d.dtype == TN_BF16 && !x.p.v_trans && x.p.scale > 0.f && (x.p.mode == 0 || x.p.trans_a) && tc % hd == 0 && tq % 64 == 0 &&
                   tk % 64 == 0 && q_rows % 8 == 0 && kv_rows % 8 == 0 && q_rows >= 8 && kv_rows >= 8)
                      ? (int8_t)(LC_ATTN_BWD_BF16 + x.p.mode) : (int8_t)LC_ATTN_BWD;
         vi.head_dim = (int16_t)hd;

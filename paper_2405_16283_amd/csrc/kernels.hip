@@ -1033,21 +1033,29 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
       }
       // register r of this lane: row base + 16*(r>>3) + 8*g + (r&7) of the other side
       if (mode == 0) {
+        // the maximum is taken over the raw products (a positive scale commutes with it); a slab
+        // inside the matrix and wholly visible to every query of the wavefront needs no mask
+        const int wq0 = d.p.q_pos0 + rb * kAttnBwdRows + w * 32;
         float mx = -INFINITY;
+        if (base + 32 > kv_rows || (causal && d.p.k_pos0 + base + 31 > wq0)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = base + 16 * (r >> 3) + 8 * g + (r & 7);
-          const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > mypos);
-          sc[r] = ok ? sc[r] * scale2 : -INFINITY;
-          mx = fmaxf(mx, sc[r]);
+          for (int r = 0; r < 16; ++r) {
+            const int kv = base + 16 * (r >> 3) + 8 * g + (r & 7);
+            const bool ok = kv < kv_rows && !(causal && d.p.k_pos0 + kv > mypos);
+            sc[r] = ok ? sc[r] : -INFINITY;
+            mx = fmaxf(mx, sc[r]);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[r]);
         }
-        const float mn = fmaxf(m, mx);
+        const float mn = fmaxf(m, mx * scale2);
         if (mn != -INFINITY) {
           const float alpha = __builtin_amdgcn_exp2f(m - mn);
           float ls = 0.f, ds = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(sc[r] - mn);
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale2, -mn));
             ls += p;
             ds = fmaf(p, dp[r], ds);
           }
