@@ -218,3 +218,49 @@ def test_a_join_that_runs_before_an_increment_is_caught():
             M.simulate(broken, order, preds, expected)
     finally:
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("opts", [
+    dict(max_lookahead_bytes=0, drop_clean_inputs=1),
+    dict(max_lookahead_bytes=64 * 1024, drop_clean_inputs=0),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, next_fit=1, evict_ahead_bytes=32 * 1024),
+    dict(max_lookahead_bytes=B.UINT64_MAX, drop_clean_inputs=1, prune_superfluous=1, alignment=4096),
+])
+def test_compile_options_keep_a_k_split_memgraph_correct(opts):
+    cfg = config("c1")
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, k_split=3))
+    cap = H.cap_for(cfg, tg)
+    mg = B.tn_compile(tg, None, cap, B.tn_compile_opts(**opts))
+    try:
+        st = B.tn_memgraph_stats(mg)
+        assert st.n_increment > 0 and st.high_water <= cap
+        omg = oracle_memgraph(mg)
+        check_all(task_preds(tg), omg, n_random=15, seed=2)
+        B.tn_memgraph_simulate(mg)
+    finally:
+        B.tn_memgraph_destroy(mg)
+        B.tn_taskgraph_destroy(tg)
+
+
+def test_k_split_lowers_the_smallest_cap_that_compiles():
+    """What the split buys: a partial product needs only its share of the K tiles next to the
+    output, so the largest per-vertex footprint -- the floor of the cap -- shrinks."""
+    cfg = config("c1").with_(weights_resident=False, x_resident=False)
+
+    def smallest_cap(k_split):
+        tg = B.tn_build_llama(H.llama_config_struct(cfg, k_split=k_split))
+        lo, hi = 1024, 1 << 24
+        try:
+            while hi - lo > 1024:
+                mid = (lo + hi) // 2
+                try:
+                    B.tn_memgraph_destroy(B.tn_compile(tg, None, mid, B.tn_compile_opts(max_lookahead_bytes=0, drop_clean_inputs=1)))
+                    hi = mid
+                except B.TurnipError:
+                    lo = mid
+        finally:
+            B.tn_taskgraph_destroy(tg)
+        return hi
+
+    whole, split = smallest_cap(0), smallest_cap(4)
+    assert split < 0.75 * whole, (whole, split)
