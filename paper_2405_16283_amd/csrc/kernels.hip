@@ -150,14 +150,63 @@ __global__ void __launch_bounds__(256) rms_apply_kernel(DeviceTables t, Batch b)
 
 // Rotary embedding on interleaved pairs; the angle is formed and reduced in double so that long
 // sequences lose no accuracy, then the single-precision sincos is taken of the reduced angle
+// Tiles that hold whole heads take the fast path: a thread owns 4 pairs (8 elements, one 16-byte
+// piece for bf16) of a row and walks over the heads of the tile, so the angles and their sines and
+// cosines -- the expensive part -- are formed once per row and pair, not once per head.
+__host__ __device__ __forceinline__ bool rope_whole_heads(const OpDesc& d) {
+  return d.p.head_dim % 8 == 0 && d.p.col0 % d.p.head_dim == 0 && d.cols % d.p.head_dim == 0;
+}
 template <typename T>
 __global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const T* x = (const T*)t.ptrs[d.ptr0];
   T* o = (T*)d.out;
-  const int pairs = d.cols / 2;
   const int id = blockIdx.x * 256 + threadIdx.x;
+  if (rope_whole_heads(d)) {
+    const int hd = d.p.head_dim, per_row = hd / 8;
+    if (id >= d.rows * per_row) return;
+    const int row = id / per_row, q8 = id % per_row;
+    float cs[4], sn[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      double ang = (double)(d.p.pos0 + row) * t.rope_theta[d.aux0 + 4 * q8 + k];
+      ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+      sincosf((float)ang, &sn[k], &cs[k]);
+      if (d.p.mode) sn[k] = -sn[k];  // the inverse rotation
+    }
+    for (int c0 = 8 * q8; c0 < d.cols; c0 += hd) {
+      const size_t e = (size_t)row * d.cols + c0;
+      float v[8];
+      if constexpr (sizeof(T) == 2) {
+        const uint4 u = *(const uint4*)(x + e);
+        const bf16_t* pu = (const bf16_t*)&u;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = bf2f(pu[k]);
+      } else {
+        const float4 a = *(const float4*)(x + e), c = *(const float4*)(x + e + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+      }
+      float r[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        r[2 * k] = v[2 * k] * cs[k] - v[2 * k + 1] * sn[k];
+        r[2 * k + 1] = v[2 * k] * sn[k] + v[2 * k + 1] * cs[k];
+      }
+      if constexpr (sizeof(T) == 2) {
+        uint4 u;
+        bf16_t* pu = (bf16_t*)&u;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) pu[k] = f2bf(r[k]);
+        *(uint4*)(o + e) = u;
+      } else {
+        *(float4*)(o + e) = make_float4(r[0], r[1], r[2], r[3]);
+        *(float4*)(o + e + 4) = make_float4(r[4], r[5], r[6], r[7]);
+      }
+    }
+    return;
+  }
+  const int pairs = d.cols / 2;
   if (id >= d.rows * pairs) return;
   const int row = id / pairs, pc = id % pairs;
   const int i = ((d.p.col0 + 2 * pc) % d.p.head_dim) / 2;
@@ -172,15 +221,56 @@ __global__ void __launch_bounds__(256) rope_kernel(DeviceTables t, Batch b) {
   st(o + e + 1, xe * sn + xo * cs);
 }
 
-// Attention combine: merge the partials of one query block (j ascending) and normalise
+// Attention combine: merge the partials of one query block (j ascending) and normalise.  Where the
+// shapes allow, a thread forms 4 neighbouring columns of a row (one head, so one set of weights).
+__host__ __device__ __forceinline__ bool combine_by_four(const OpDesc& d) {
+  return d.cols % 4 == 0 && d.p.col0 % 4 == 0 && d.p.head_dim % 4 == 0;
+}
 template <typename T>
 __global__ void __launch_bounds__(256) attn_combine_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
   const int id = blockIdx.x * 256 + threadIdx.x;
+  const int hd = d.p.head_dim, hpg = d.p.hpg, gw = hd * hpg, ldp = gw + 2 * hpg;
+  if (combine_by_four(d)) {
+    const int per_row = d.cols / 4;
+    if (id >= d.rows * per_row) return;
+    const int row = id / per_row, c = (id % per_row) * 4;
+    const int col = d.p.col0 + c, h = col / hd;
+    const size_t r = (size_t)(d.p.row0 + row) * ldp;
+    const bool wide = (ldp & 3) == 0;  // rows of a partial are 16-byte aligned
+    float mstar = -INFINITY;
+    for (int j = 0; j < d.n_in; ++j) mstar = fmaxf(mstar, ((const float*)t.ptrs[d.ptr0 + j])[r + gw + h]);
+    float num[4] = {0.f, 0.f, 0.f, 0.f}, den = 0.f;
+#pragma unroll 4
+    for (int j = 0; j < d.n_in; ++j) {
+      const float* p = (const float*)t.ptrs[d.ptr0 + j];
+      const float w = __expf(p[r + gw + h] - mstar);
+      float v[4];
+      if (wide) {
+        const float4 u = *(const float4*)(p + r + col);
+        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = p[r + col + k];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) num[k] += v[k] * w;
+      den += p[r + gw + hpg + h] * w;
+    }
+    T* out = (T*)d.out + (size_t)row * d.cols + c;
+    if constexpr (sizeof(T) == 2) {
+      uint2 u;
+      u.x = (uint32_t)f2bf(num[0] / den) | ((uint32_t)f2bf(num[1] / den) << 16);
+      u.y = (uint32_t)f2bf(num[2] / den) | ((uint32_t)f2bf(num[3] / den) << 16);
+      *(uint2*)out = u;
+    } else {
+      *(float4*)out = make_float4(num[0] / den, num[1] / den, num[2] / den, num[3] / den);
+    }
+    return;
+  }
   if (id >= d.rows * d.cols) return;
   const int row = id / d.cols, c = id % d.cols;
-  const int hd = d.p.head_dim, hpg = d.p.hpg, gw = hd * hpg, ldp = gw + 2 * hpg;
   const int col = d.p.col0 + c, h = col / hd;
   const size_t r = (size_t)(d.p.row0 + row) * ldp;
   float mstar = -INFINITY;
@@ -1409,7 +1499,8 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     case LC_GEMM_BF16_NT256: return cdiv(d.rows, G2_M) * cdiv(d.cols, G2_N);
     case LC_RMS_STAT: return cdiv(d.rows, 4);
     case LC_RMS_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
-    case LC_ROPE: return cdiv((int64_t)d.rows * (d.cols / 2), 256);
+    case LC_ROPE:
+      return rope_whole_heads(d) ? cdiv((int64_t)d.rows * (d.p.head_dim / 8), 256) : cdiv((int64_t)d.rows * (d.cols / 2), 256);
     case LC_ATTN_F32: {
       const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
       return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + 3], 64);
@@ -1418,7 +1509,7 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
       const int gw = d.p.n_col_tiles * aux[d.aux0 + 2];
       return (gw / d.p.head_dim) * cdiv(aux[d.aux0 + 3], 128);
     }
-    case LC_ATTN_COMBINE: return cdiv((int64_t)d.rows * d.cols, 256);
+    case LC_ATTN_COMBINE: return cdiv((int64_t)d.rows * d.cols / (combine_by_four(d) ? 4 : 1), 256);
     case LC_SILU_MUL:
     case LC_ADD:
     case LC_SILU_BWD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
