@@ -144,6 +144,28 @@ __global__ void __launch_bounds__(256) rms_apply_kernel(DeviceTables t, Batch b)
   if (id >= d.rows * segs) return;
   const int row = id / segs, c0 = (id % segs) * 8;
   const float s = stat[row];
+  if ((d.cols & 7) == 0) {  // whole 16-byte (bf16) or 32-byte (fp32) pieces
+    const size_t e = (size_t)row * d.cols + c0;
+    float v[8], gv[8];
+    if constexpr (sizeof(T) == 2) {
+      const uint4 u = *(const uint4*)(x + e), ug = *(const uint4*)(g + c0);
+      const bf16_t* pu = (const bf16_t*)&u;
+      const bf16_t* pg = (const bf16_t*)&ug;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { v[k] = bf2f(pu[k]); gv[k] = bf2f(pg[k]); }
+      uint4 r;
+      bf16_t* pr = (bf16_t*)&r;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) pr[k] = f2bf(v[k] * s * gv[k]);
+      *(uint4*)(o + e) = r;
+    } else {
+      const float4 a = *(const float4*)(x + e), b2 = *(const float4*)(x + e + 4);
+      const float4 ga = *(const float4*)(g + c0), gb = *(const float4*)(g + c0 + 4);
+      *(float4*)(o + e) = make_float4(a.x * s * ga.x, a.y * s * ga.y, a.z * s * ga.z, a.w * s * ga.w);
+      *(float4*)(o + e + 4) = make_float4(b2.x * s * gb.x, b2.y * s * gb.y, b2.z * s * gb.z, b2.w * s * gb.w);
+    }
+    return;
+  }
   for (int c = c0; c < min(c0 + 8, d.cols); ++c)
     st(o + (size_t)row * d.cols + c, ld(x + (size_t)row * d.cols + c) * s * ld(g + c));
 }
