@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
-    ap.add_argument("--streams", type=int, default=2)
+    ap.add_argument("--streams", type=int, default=0, help="compute streams; default: harness.BENCH_COMPUTE_STREAMS")
     ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
     ap.add_argument("--max-gemm-inflight", type=int, default=2)
@@ -97,6 +97,8 @@ def main():
     from paper_2405_16283_amd import binding as B
     from paper_2405_16283_amd import harness as H
     from workloads import bf16_bits_to_f32, config, make_llama_inputs, make_lora_inputs
+    if args.streams <= 0:
+        args.streams = H.BENCH_COMPUTE_STREAMS
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)

@@ -80,7 +80,7 @@ def test_full_step_in_the_benchmark_configuration():
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     full.update(make_lora_inputs(cfg, 0, rank=RANK, b_std=0.0))
     print(f"[c5] inputs generated {time.time() - t0:.1f}s", flush=True)
-    s = H.GpuSession(cfg, full, lora_rank=RANK, train=True, compile_opts=H.bench_compile_opts(cfg.cap_bytes, True),
+    s = H.GpuSession(cfg, full, lora_rank=RANK, train=True, compile_opts=H.bench_compile_opts(cfg.cap_bytes, True), n_compute=H.BENCH_COMPUTE_STREAMS,
                      progress=lambda m: print(f"[c5] {m} {time.time() - t0:.1f}s", flush=True))
     st = s.stats
     print(f"[c5] compiled and placed {time.time() - t0:.1f}s: {st.n_vertices} vertices, {st.n_load} loads "
