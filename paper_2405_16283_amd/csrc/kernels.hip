@@ -537,18 +537,29 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch
     const bf16_t* A = (const bf16_t*)t.ptrs[d.ptr0 + kt];
     const bf16_t* B = (const bf16_t*)t.ptrs[d.ptr0 + nk + kt];
     const int K = t.aux[d.aux0 + kt];
-    for (int k0 = 0; k0 < K; k0 += GB_K) {
-      // 128 rows x 8 segments of 16 bytes per operand; 4 segments per thread and operand
+    // 128 rows x 8 segments of 16 bytes per operand and K step; 4 segments per thread and operand.
+    // The segments of the next step are fetched into registers while this step is multiplied.
+    uint4 pa[4], pb[4];
+    auto fetch = [&](int k0) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int s = threadIdx.x + 256 * i, r = s >> 3, ks = (s & 7) * 8;
-        uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
-        if (m0 + r < M && k0 + ks < K) va = *(const uint4*)(A + (size_t)(m0 + r) * K + k0 + ks);
-        if (n0 + r < N && k0 + ks < K) vb = *(const uint4*)(B + (size_t)(n0 + r) * K + k0 + ks);
-        *(uint4*)(As + r * GB_LD + ks) = va;
-        *(uint4*)(Bs + r * GB_LD + ks) = vb;
+        pa[i] = make_uint4(0, 0, 0, 0);
+        pb[i] = make_uint4(0, 0, 0, 0);
+        if (m0 + r < M && k0 + ks < K) pa[i] = *(const uint4*)(A + (size_t)(m0 + r) * K + k0 + ks);
+        if (n0 + r < N && k0 + ks < K) pb[i] = *(const uint4*)(B + (size_t)(n0 + r) * K + k0 + ks);
+      }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += GB_K) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int s = threadIdx.x + 256 * i, r = s >> 3, ks = (s & 7) * 8;
+        *(uint4*)(As + r * GB_LD + ks) = pa[i];
+        *(uint4*)(Bs + r * GB_LD + ks) = pb[i];
       }
       __syncthreads();
+      if (k0 + GB_K < K) fetch(k0 + GB_K);
 #pragma unroll
       for (int s = 0; s < GB_K / 16; ++s) {
         bf16x8 a[2], bb[2];
