@@ -391,12 +391,35 @@ template <typename T>
 __global__ void __launch_bounds__(256) transpose_kernel(DeviceTables t, Batch b) {
   const OpDesc& d = t.descs[b.at(blockIdx.y)];
   if ((int)blockIdx.x >= d.nblocks) return;
-  __shared__ T tile[64][65];
   const int R = d.cols, C = d.rows;  // the operand is [R, C]; the output [C, R]
   const int tc = (C + 63) / 64;
   const int r0 = (blockIdx.x / tc) * 64, c0 = (blockIdx.x % tc) * 64;
   const T* x = (const T*)t.ptrs[d.ptr0];
   T* o = (T*)d.out;
+  if constexpr (sizeof(T) == 2) {
+    if ((R & 7) == 0 && (C & 7) == 0) {
+      // 16-byte pieces both ways: a piece of 8 elements of an input row is scattered into the
+      // transposed image in LDS, whose rows are then read back 8 elements at a time
+      __shared__ __attribute__((aligned(16))) bf16_t tt[64][72];
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int s = threadIdx.x + 256 * k, i = s >> 3, c8 = (s & 7) * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r0 + i < R && c0 + c8 < C) v = *(const uint4*)(x + (size_t)(r0 + i) * C + c0 + c8);
+        const bf16_t* pv = (const bf16_t*)&v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tt[c8 + e][i] = pv[e];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int s = threadIdx.x + 256 * k, j = s >> 3, r8 = (s & 7) * 8;
+        if (c0 + j < C && r0 + r8 < R) *(uint4*)(o + (size_t)(c0 + j) * R + r0 + r8) = *(const uint4*)&tt[j][r8];
+      }
+      return;
+    }
+  }
+  __shared__ T tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4)
     if (r0 + i < R && c0 + tx < C) tile[i][tx] = x[(size_t)(r0 + i) * C + c0 + tx];

@@ -144,10 +144,13 @@ def test_rmsnorm_backward(dtype, residual):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_transpose(dtype):
     rng = np.random.default_rng(5)
-    g = Graph(dtype)
-    x, X = g.inp(rng.standard_normal((70, 150)))
-    (out,) = g.run([g.op(B.TN_OP_TRANSPOSE, [x], 150, 70)])
-    np.testing.assert_array_equal(out, X.T)
+    # odd shapes (element by element), multiples of 8 that are ragged against the 64x64 pieces (16-byte
+    # pieces for bf16), and the skinny shapes of the adapter tiles
+    for rows, cols in ((70, 150), (72, 152), (512, 16), (16, 512), (128, 64)):
+        g = Graph(dtype)
+        x, X = g.inp(rng.standard_normal((rows, cols)))
+        (out,) = g.run([g.op(B.TN_OP_TRANSPOSE, [x], cols, rows)])
+        np.testing.assert_array_equal(out, X.T)
 
 
 @pytest.mark.parametrize("dtype,hd,v_trans,aux", [("f32", 64, 0, 0), ("f32", 64, 1, 0), ("bf16", 128, 1, 0), ("bf16", 64, 0, 0),
