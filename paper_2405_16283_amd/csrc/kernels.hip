@@ -354,7 +354,16 @@ __global__ void __launch_bounds__(256) rms_bwd_stat_kernel(DeviceTables t, Batch
     const T* dy = (const T*)t.ptrs[d.ptr0 + j] + (size_t)row * cols;
     const T* x = (const T*)t.ptrs[d.ptr0 + nk + j] + (size_t)row * cols;
     const T* g = (const T*)t.ptrs[d.ptr0 + 2 * nk + j];
-    for (int c = lane; c < cols; c += 64) ss += ld(dy + c) * ld(g + c) * ld(x + c);
+    if (sizeof(T) == 2 && (cols & 7) == 0) {  // 16-byte pieces
+      for (int c = lane * 8; c < cols; c += 512) {
+        const uint4 vd = *(const uint4*)(dy + c), vx = *(const uint4*)(x + c), vg = *(const uint4*)(g + c);
+        const bf16_t *pd = (const bf16_t*)&vd, *px = (const bf16_t*)&vx, *pg = (const bf16_t*)&vg;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ss += bf2f(pd[k]) * bf2f(pg[k]) * bf2f(px[k]);
+      }
+    } else {
+      for (int c = lane; c < cols; c += 64) ss += ld(dy + c) * ld(g + c) * ld(x + c);
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
@@ -378,6 +387,24 @@ __global__ void __launch_bounds__(256) rms_bwd_apply_kernel(DeviceTables t, Batc
   if (id >= d.rows * segs) return;
   const int row = id / segs, c0 = (id % segs) * 8;
   const float r = stat[row], k = r * r * r * dot[row] / (float)d.p.d;
+  if constexpr (sizeof(T) == 2) {
+    if ((d.cols & 7) == 0) {  // 16-byte pieces
+      const size_t e = (size_t)row * d.cols + c0;
+      const uint4 vd = *(const uint4*)(dy + e), vx = *(const uint4*)(x + e), vg = *(const uint4*)(g + c0);
+      uint4 vr = make_uint4(0, 0, 0, 0), vo;
+      if (res) vr = *(const uint4*)(res + e);
+      const bf16_t *pd = (const bf16_t*)&vd, *px = (const bf16_t*)&vx, *pg = (const bf16_t*)&vg, *pr = (const bf16_t*)&vr;
+      bf16_t* po = (bf16_t*)&vo;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        float v = r * bf2f(pg[q]) * bf2f(pd[q]) - bf2f(px[q]) * k;
+        if (res) v += bf2f(pr[q]);
+        po[q] = f2bf(v);
+      }
+      *(uint4*)(o + e) = vo;
+      return;
+    }
+  }
   for (int c = c0; c < min(c0 + 8, d.cols); ++c) {
     const size_t e = (size_t)row * d.cols + c;
     float v = r * ld(g + c) * ld(dy + e) - ld(x + e) * k;
