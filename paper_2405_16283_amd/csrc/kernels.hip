@@ -19,11 +19,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short bf16_t;  // storage of a bf16 value
 
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {  // round to nearest, ties to even
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// round to nearest, ties to even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values at once, the first in the low half
+__device__ __forceinline__ uint32_t f2bf2(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, bf16x2_t));
 }
 template <typename T> __device__ __forceinline__ float ld(const T* p);
 template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
@@ -542,12 +544,13 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[TI][TJ], bf16_
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         const int row = row0 + i * 32 + 8 * a + 4 * g;
-        const bf16_t h0 = f2bf(c[4 * a]), h1 = f2bf(c[4 * a + 1]), h2 = f2bf(c[4 * a + 2]), h3 = f2bf(c[4 * a + 3]);
+        const uint32_t h01 = f2bf2(c[4 * a], c[4 * a + 1]), h23 = f2bf2(c[4 * a + 2], c[4 * a + 3]);
+        const bf16_t h0 = (bf16_t)h01, h1 = (bf16_t)(h01 >> 16), h2 = (bf16_t)h23, h3 = (bf16_t)(h23 >> 16);
         if (wide) {
           if (col < N && row < M) {
             uint2 v;
-            v.x = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            v.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
+            v.x = h01;
+            v.y = h23;
             *(uint2*)(Cp + (size_t)col * M + row) = v;
           }
         } else if (col < N) {
