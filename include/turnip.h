@@ -81,7 +81,16 @@ enum {
    * storage type, so the result is order-independent only up to that rounding. */
   TN_OP_SUM = 14,
   TN_OP_ZERO = 15,          /* memgraph only: () -> zeros, the start of a sum's output               */
-  TN_OP_SUM_INTO = 16       /* memgraph only: P, accumulator -> accumulator += P, in place           */
+  TN_OP_SUM_INTO = 16,      /* memgraph only: P, accumulator -> accumulator += P, in place           */
+  /* Softmax "in portions" over materialised attention scores (Introduction, second paragraph;
+   * Section 8, kernel list): the score tiles S_0..S_{n-1} of one row block, left to right
+   * -> fp32 [rows, 2]: per row the maximum m of scale * s over the visible entries, then
+   * l = sum exp(scale * s - m) over them.  Entry (r, c), c counted across the tiles, is visible
+   * unless causal != 0 and k_pos0 + c > q_pos0 + r. */
+  TN_OP_SOFTMAX_STAT = 17,
+  /* S, the SOFTMAX_STAT of its row block -> exp(scale * s - m) / l where visible, else 0;
+   * k_pos0 is the position of this tile's first column. */
+  TN_OP_SOFTMAX_APPLY = 18
 };
 
 typedef struct {
@@ -226,6 +235,12 @@ typedef struct {
    * vertex -- the k-split + sum-into form of a matrix product (Section 8, resources).  0 or 1:
    * the whole K range inside one GEMM vertex. */
   int32_t k_split;
+  /* != 0 (needs tile == head_dim, so that a column tile is one head, and train == 0): attention
+   * with scores and probabilities as tensors of the taskgraph -- per head and pair of row tiles
+   * (i, j <= i) a GEMM S = Q_i K_j^T, per head and row tile a SOFTMAX_STAT over S_i0..S_ii, a
+   * SOFTMAX_APPLY per score tile, and O_i = sum_j P_ij V_j as one GEMM -- instead of the fused
+   * ATTN_BLOCK / ATTN_COMBINE vertices.  attn_block is ignored. */
+  int32_t materialize_scores;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -27,6 +27,14 @@ Vertex kinds (inputs -> output):
   attn_combine  partial_0..partial_j                 -> normalised attention output tile
   silu_mul      gate, up                             -> gate/(1+exp(-gate)) * up
   add           a, b                                 -> a + b
+  softmax_stat  S_0..S_{n-1} (score tiles of one row   -> [rows, 2]: per row the maximum m of scale * s over the visible
+                block, left to right)                   entries and l = sum exp(scale * s - m) over them; entry (r, c)
+                                                        is visible unless causal and k_pos0 + c > q_pos0 + r, c counted
+                                                        across the tiles.  With softmax_apply this is the softmax "in
+                                                        portions" of materialised attention scores (Introduction,
+                                                        second paragraph; Section 8, item 1 of the kernel list)
+  softmax_apply S, stat                              -> exp(scale * s - m) / l where visible, else 0; k_pos0 is the
+                                                        position of this tile's first column
   sum           p_0..p_{n-1}                         -> their sum, formed the way Section 8 (resources) describes a
                                                         reduction: an output that starts at zero and receives the
                                                         n operands as n increments, each increment rounding the
@@ -166,6 +174,24 @@ def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
         return g / (1.0 + np.exp(-g)) * u
     if kind == "add":
         return ins[0] + ins[1]
+    if kind == "softmax_stat":
+        s = np.concatenate(ins, axis=1) * p["scale"]
+        if p["causal"]:
+            r = p["q_pos0"] + np.arange(s.shape[0])
+            c = p["k_pos0"] + np.arange(s.shape[1])
+            s = np.where(c[None, :] > r[:, None], -np.inf, s)
+        m = np.max(s, axis=1)
+        msafe = np.where(np.isfinite(m), m, 0.0)
+        return np.stack([m, np.sum(np.exp(s - msafe[:, None]), axis=1)], axis=1)
+    if kind == "softmax_apply":
+        s, stat = ins
+        s = s * p["scale"]
+        if p["causal"]:
+            r = p["q_pos0"] + np.arange(s.shape[0])
+            c = p["k_pos0"] + np.arange(s.shape[1])
+            s = np.where(c[None, :] > r[:, None], -np.inf, s)
+        m = np.where(np.isfinite(stat[:, 0]), stat[:, 0], 0.0)
+        return np.exp(s - m[:, None]) / stat[:, 1][:, None]
     if kind == "sum":
         acc = np.zeros_like(ins[0])
         for i in p.get("_increment_order", range(len(ins))):
@@ -235,12 +261,17 @@ def _splits(n: int, t: int) -> List[Tuple[int, int]]:
     return [(s, min(s + t, n)) for s in range(0, n, t)]
 
 
-def build_llama_taskgraph(cfg, k_split: int = 1) -> TaskGraph:
+def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = False) -> TaskGraph:
     """Tile the decoder of `cfg` (a workloads.LlamaConfig) into a taskgraph.
 
     k_split > 1: every projection is cut along K into that many partial products (contiguous runs
     of ceil(nk / k_split) K tiles, each a gemm vertex stored in the storage type) joined by a sum
     vertex -- the k-split + sum-into form of a matrix product.
+
+    materialize_scores (needs tile == head_dim, so that a column tile is one head): attention with
+    the scores and probabilities as tensors of the graph -- per head and pair of row tiles (i, j <= i)
+    a gemm S = Q_i K_j^T, per head and row tile a softmax_stat over S_i0..S_ii, a softmax_apply per
+    score tile, and O_i = sum_j P_ij V_j as one gemm -- instead of the fused blocks and combines.
 
     Tensors are cut into tile x tile pieces (ragged at the right and bottom edges); row blocks
     never straddle sequences.  Attention runs per (sequence, head group, q block, kv block <= q
@@ -316,8 +347,24 @@ def build_llama_taskgraph(cfg, k_split: int = 1) -> TaskGraph:
                         head_dim=hd, base=cfg.rope_base)
                  for j, xv in enumerate(line)] for i, line in enumerate(grid)]
 
+    def attention_materialized(q, k, v):
+        assert t == hd
+        o = [[None] * len(dcols) for _ in rows]
+        scale = 1.0 / np.sqrt(hd)
+        for i, (r0, r1) in enumerate(rows):
+            for h in range(len(dcols)):
+                sc = [tg.add("gemm", [q[i][h], k[j][h]], (r1 - r0, rows[j][1] - rows[j][0]), dt, nk=1, trans_b=1)
+                      for j in range(i + 1)]
+                st = tg.add("softmax_stat", sc, (r1 - r0, 2), "f32", scale=scale, causal=1, q_pos0=r0, k_pos0=0)
+                pr = [tg.add("softmax_apply", [sc[j], st], tg.shape[sc[j]], dt, scale=scale, causal=1, q_pos0=r0,
+                             k_pos0=rows[j][0]) for j in range(i + 1)]
+                o[i][h] = tg.add("gemm", pr + [v[j][h] for j in range(i + 1)], (r1 - r0, hd), dt, nk=i + 1)
+        return o
+
     def attention(q, k, v):
         """Blocked causal attention of one sequence; returns the grid of output tiles."""
+        if materialize_scores:
+            return attention_materialized(q, k, v)
         o = [[None] * len(dcols) for _ in rows]
         for g in range(d // gw):
             cts = list(range(g * ctg, (g + 1) * ctg))

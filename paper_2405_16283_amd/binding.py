@@ -19,7 +19,7 @@ TN_F32, TN_BF16 = 0, 1
 TN_HOST, TN_DEVICE = 0, 1
 (TN_OP_INPUT, TN_OP_GEMM, TN_OP_RMS_STAT, TN_OP_RMS_APPLY, TN_OP_ROPE, TN_OP_ATTN_BLOCK,
  TN_OP_ATTN_COMBINE, TN_OP_SILU_MUL, TN_OP_ADD, TN_OP_SILU_MUL_BWD, TN_OP_RMS_BWD_STAT, TN_OP_RMS_BWD_APPLY,
- TN_OP_ATTN_BWD, TN_OP_TRANSPOSE, TN_OP_SUM, TN_OP_ZERO, TN_OP_SUM_INTO) = range(17)
+ TN_OP_ATTN_BWD, TN_OP_TRANSPOSE, TN_OP_SUM, TN_OP_ZERO, TN_OP_SUM_INTO, TN_OP_SOFTMAX_STAT, TN_OP_SOFTMAX_APPLY) = range(19)
 (TN_T_X, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2, TN_T_Y, TN_T_K, TN_T_V,
  TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE, TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX) = range(23)
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE, TN_MG_JOIN) = range(8)
@@ -59,7 +59,7 @@ class tn_llama_config(C.Structure):
                                           "dtype", "tile", "attn_block")] + \
                [("eps", C.c_float), ("rope_base", C.c_float), ("weights_residency", C.c_int32),
                 ("x_residency", C.c_int32), ("kv_outputs", C.c_int32), ("weights_transposed", C.c_int32),
-                ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32)]
+                ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32), ("materialize_scores", C.c_int32)]
 
 
 class tn_llama_binding(C.Structure):

@@ -298,6 +298,17 @@ tn_status build_tables(tn_executor& ex) {
         vi.cls = LC_TRANSPOSE;
         vi.bytes = 2.0 * x.bytes;
         break;
+      case TN_OP_SOFTMAX_STAT:
+        for (int i = 0; i < d.n_in; ++i) {
+          aux.push_back(odesc(i).cols);
+          vi.bytes += (double)d.rows * odesc(i).cols * elem_bytes(d.dtype);
+        }
+        vi.cls = LC_SOFTMAX_STAT;
+        break;
+      case TN_OP_SOFTMAX_APPLY:
+        vi.cls = LC_SOFTMAX_APPLY;
+        vi.bytes = 2.0 * x.bytes + d.rows * 8.0;
+        break;
       case TN_OP_ZERO:
         vi.cls = LC_ZERO;
         vi.bytes = (double)x.bytes;

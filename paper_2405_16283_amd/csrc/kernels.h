@@ -50,6 +50,8 @@ enum LaunchClass {
   LC_ATTN_BWD_BF16_DV,
   LC_TRANSPOSE,
   LC_ZERO,           // clears a tensor: the start of a sum's output
+  LC_SOFTMAX_STAT,   // row maximum and sum of exponentials over the score tiles of a row block
+  LC_SOFTMAX_APPLY,  // probabilities of one score tile
   LC_COUNT
 };
 

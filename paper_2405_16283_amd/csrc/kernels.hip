@@ -8,6 +8,7 @@
 // order, no atomics, so any dispatch order gives the same bits.
 #include "kernels.h"
 
+#include <climits>
 #include <type_traits>
 
 namespace tn {
@@ -130,6 +131,64 @@ __global__ void __launch_bounds__(256) rms_stat_kernel(DeviceTables t, Batch b) 
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
   if (lane == 0) ((float*)d.out)[row] = 1.0f / sqrtf(ss / (float)d.p.d + d.p.eps);
+}
+
+// Softmax over materialised scores, first portion: one wavefront per row walks over the score
+// tiles of the row block twice (maximum, then the sum of exponentials), columns counted across
+// the tiles.  aux: the tiles' widths.
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_stat_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= d.rows) return;
+  const float scale = d.p.scale;
+  const int last = d.p.causal ? d.p.q_pos0 + row - d.p.k_pos0 : INT_MAX;  // last visible column
+  float m = -INFINITY;
+  for (int j = 0, c0 = 0; j < d.n_in; ++j) {
+    const int cols = t.aux[d.aux0 + j];
+    const T* x = (const T*)t.ptrs[d.ptr0 + j] + (size_t)row * cols;
+    for (int c = lane; c < cols && c0 + c <= last; c += 64) m = fmaxf(m, ld(x + c) * scale);
+    c0 += cols;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  const float msafe = m == -INFINITY ? 0.f : m;
+  float l = 0.f;
+  for (int j = 0, c0 = 0; j < d.n_in; ++j) {
+    const int cols = t.aux[d.aux0 + j];
+    const T* x = (const T*)t.ptrs[d.ptr0 + j] + (size_t)row * cols;
+    for (int c = lane; c < cols && c0 + c <= last; c += 64) l += __expf(ld(x + c) * scale - msafe);
+    c0 += cols;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, 64);
+  if (lane == 0) {
+    float* out = (float*)d.out + (size_t)row * 2;
+    out[0] = m;
+    out[1] = l;
+  }
+}
+
+// second portion: the probabilities of one score tile, 8 columns per thread
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_apply_kernel(DeviceTables t, Batch b) {
+  const OpDesc& d = t.descs[b.at(blockIdx.y)];
+  if ((int)blockIdx.x >= d.nblocks) return;
+  const T* x = (const T*)t.ptrs[d.ptr0];
+  const float* stat = (const float*)t.ptrs[d.ptr0 + 1];
+  T* o = (T*)d.out;
+  const int segs = (d.cols + 7) / 8;
+  const int id = blockIdx.x * 256 + threadIdx.x;
+  if (id >= d.rows * segs) return;
+  const int row = id / segs, c0 = (id % segs) * 8;
+  const float m = stat[row * 2], inv = 1.f / stat[row * 2 + 1], scale = d.p.scale;
+  const float msafe = m == -INFINITY ? 0.f : m;
+  const int last = d.p.causal ? d.p.q_pos0 + row - d.p.k_pos0 : INT_MAX;
+  for (int c = c0; c < min(c0 + 8, d.cols); ++c) {
+    const size_t e = (size_t)row * d.cols + c;
+    st(o + e, c <= last ? __expf(ld(x + e) * scale - msafe) * inv : 0.f);
+  }
 }
 
 // RMSNorm apply: out = x * stat[row] * gain[col]
@@ -1601,6 +1660,8 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     case LC_SILU_BWD: return cdiv((int64_t)d.rows * d.cols, 256 * 8);
     case LC_TRANSPOSE: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
     case LC_ZERO: return cdiv((int64_t)d.rows * d.cols * (d.dtype == TN_BF16 ? 2 : 4), 256 * 16);
+    case LC_SOFTMAX_STAT: return cdiv(d.rows, 4);
+    case LC_SOFTMAX_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_RMS_BWD_STAT: return cdiv(d.rows, 4);
     case LC_RMS_BWD_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ATTN_BWD: {
@@ -1659,6 +1720,8 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
       break;
     case LC_TRANSPOSE: TN_LAUNCH_T(transpose_kernel); break;
     case LC_ZERO: TN_LAUNCH_T(zero_kernel); break;
+    case LC_SOFTMAX_STAT: TN_LAUNCH_T(softmax_stat_kernel); break;
+    case LC_SOFTMAX_APPLY: TN_LAUNCH_T(softmax_apply_kernel); break;
     case LC_SILU_BWD: TN_LAUNCH_T(silu_bwd_kernel); break;
     case LC_RMS_BWD_STAT: TN_LAUNCH_T(rms_bwd_stat_kernel); break;
     case LC_RMS_BWD_APPLY: TN_LAUNCH_T(rms_bwd_apply_kernel); break;

@@ -150,6 +150,18 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
         return fail(TN_ERR_SHAPE, "rms_bwd_apply: operand shapes do not fit");
       return TN_OK;
     }
+    case TN_OP_SOFTMAX_STAT:
+      if (out.dtype != TN_F32 || out.cols != 2 || !(p.scale > 0.f))
+        return fail(TN_ERR_SHAPE, "softmax_stat: output is fp32 [rows, 2] and scale is positive");
+      for (int i = 0; i < n_in; ++i)
+        if (D(i).rows != out.rows || D(i).dtype != D(0).dtype)
+          return fail(TN_ERR_SHAPE, "softmax_stat: operand %d is not a score tile of this row block", i);
+      return TN_OK;
+    case TN_OP_SOFTMAX_APPLY:
+      if (n_in != 2 || !same(D(0), out) || D(1).dtype != TN_F32 || D(1).rows != out.rows || D(1).cols != 2 ||
+          !(p.scale > 0.f))
+        return fail(TN_ERR_SHAPE, "softmax_apply: a score tile of the output's shape and type, then fp32 [rows, 2]");
+      return TN_OK;
     case TN_OP_SUM:
       for (int i = 0; i < n_in; ++i) {
         if (D(i).rows != out.rows || D(i).cols != out.cols || D(i).dtype != out.dtype)
@@ -471,6 +483,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.train && gw != c.tile) return fail(TN_ERR_SHAPE, "train needs head_dim <= tile (one column tile per head group)");
   if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
   if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
+  if (c.materialize_scores && (c.tile != c.head_dim || c.train || c.kv_outputs))
+    return fail(TN_ERR_INVALID, "materialize_scores needs tile == head_dim and neither train nor kv_outputs");
 
   auto* tg = new (std::nothrow) tn_taskgraph();
   if (!tg) return fail(TN_ERR_INVALID, "out of host memory");
@@ -582,7 +596,38 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         }
         // attention of this stripe against stripes 0..s, one partial per pair, per head group
         Grid o(t.rows.size(), std::vector<tn_vid>(nd, -1));
-        for (int32_t gi = 0; gi < n_groups; ++gi) {
+        if (c.materialize_scores) {
+          // scores and probabilities as tensors: per head (= column tile) and row tile i the score
+          // tiles against the row tiles 0..i, the softmax over them in two portions, and P V
+          const float scale = 1.0f / std::sqrt((float)c.head_dim);
+          for (size_t i : rt)
+            for (size_t h = 0; h < nd; ++h) {
+              const int32_t m = t.rows[i].len();
+              std::vector<tn_vid> sc, pv;
+              for (size_t j = 0; j <= i; ++j) {
+                tn_op_params p{};
+                p.nk = 1;
+                p.trans_b = 1;
+                sc.push_back(t.op(TN_OP_GEMM, p, {q[i][h], kk[j][h]}, {c.dtype, m, t.rows[j].len()}));
+              }
+              tn_op_params ps{};
+              ps.scale = scale;
+              ps.causal = 1;
+              ps.q_pos0 = t.rows[i].a;
+              ps.k_pos0 = 0;
+              const tn_vid st = t.op(TN_OP_SOFTMAX_STAT, ps, sc, {TN_F32, m, 2});
+              for (size_t j = 0; j <= i; ++j) {
+                ps.k_pos0 = t.rows[j].a;
+                pv.push_back(t.op(TN_OP_SOFTMAX_APPLY, ps, {sc[j], st}, {c.dtype, m, t.rows[j].len()}));
+              }
+              tn_op_params pg{};
+              pg.nk = (int32_t)(i + 1);
+              pg.trans_b = c.v_transposed ? 1 : 0;
+              for (size_t j = 0; j <= i; ++j) pv.push_back(vv[j][h]);
+              o[i][h] = t.op(TN_OP_GEMM, pg, std::move(pv), {c.dtype, m, t.dcols[h].len()});
+            }
+        }
+        for (int32_t gi = 0; gi < (c.materialize_scores ? 0 : n_groups); ++gi) {
           std::vector<tn_vid> parts;
           for (size_t s2 = 0; s2 <= s; ++s2) {
             std::vector<size_t> kt;

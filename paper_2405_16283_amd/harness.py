@@ -20,7 +20,7 @@ OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms
             B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
             B.TN_OP_SILU_MUL_BWD: "silu_mul_bwd", B.TN_OP_RMS_BWD_STAT: "rms_bwd_stat",
             B.TN_OP_RMS_BWD_APPLY: "rms_bwd_apply", B.TN_OP_ATTN_BWD: "attn_bwd", B.TN_OP_TRANSPOSE: "transpose",
-            B.TN_OP_SUM: "sum"}
+            B.TN_OP_SUM: "sum", B.TN_OP_SOFTMAX_STAT: "softmax_stat", B.TN_OP_SOFTMAX_APPLY: "softmax_apply"}
 MG_KIND_NAMES = {B.TN_MG_INPUT: "input", B.TN_MG_LOAD: "load", B.TN_MG_OP: "op", B.TN_MG_OFFLOAD: "offload",
                  B.TN_MG_RELOAD: "reload", B.TN_MG_DROP: "drop", B.TN_MG_STORE: "store", B.TN_MG_JOIN: "join"}
 EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "order"}
@@ -28,7 +28,7 @@ EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "or
 
 def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
                         v_transposed: bool = True, lora_rank: int = 0, train: bool = False,
-                        k_split: int = 0) -> B.tn_llama_config:
+                        k_split: int = 0, materialize_scores: bool = False) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -37,7 +37,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         weights_residency=B.TN_DEVICE if cfg.weights_resident else B.TN_HOST,
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
         weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
-        lora_rank=int(lora_rank), train=int(train), k_split=int(k_split))
+        lora_rank=int(lora_rank), train=int(train), k_split=int(k_split),
+        materialize_scores=int(materialize_scores))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -202,14 +203,15 @@ class GpuSession:
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
-                 lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0):
+                 lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
+                 materialize_scores: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
         self.torch = torch
         self.cfg = cfg
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
-                                                       lora_rank, train, k_split))
+                                                       lora_rank, train, k_split, materialize_scores))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

@@ -1,0 +1,116 @@
+"""Materialised-score attention (scores and probabilities as taskgraph tensors, softmax in two
+portions): the oracle's vertex kinds against scipy's softmax, the workload against the fused form
+and the untiled model, the library's tiler against the oracle's, and the compiled memgraph."""
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from oracle import llama_ref as R
+from oracle import memgraph as M
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import config, make_llama_inputs
+
+from util import check_all, oracle_memgraph, oracle_taskgraph, task_preds
+
+
+@pytest.mark.parametrize("causal,q_pos0", [(0, 0), (1, 40), (1, 70)])
+def test_softmax_in_portions_is_scipys_softmax(causal, q_pos0):
+    rng = np.random.default_rng(3)
+    rows, widths, scale = 24, (32, 32, 17), 0.37
+    tg = T.TaskGraph()
+    tiles = [tg.add("input", [], (rows, w), "f32") for w in widths]
+    st = tg.add("softmax_stat", tiles, (rows, 2), "f32", scale=scale, causal=causal, q_pos0=q_pos0, k_pos0=0)
+    k0 = np.concatenate([[0], np.cumsum(widths)[:-1]])
+    pr = [tg.add("softmax_apply", [tiles[j], st], (rows, widths[j]), "f32", scale=scale, causal=causal, q_pos0=q_pos0,
+                 k_pos0=int(k0[j])) for j in range(len(widths))]
+    tg.outputs = pr + [st]
+    vals = {v: rng.standard_normal((rows, w)).astype(np.float32).astype(np.float64) for v, w in zip(tiles, widths)}
+    out = T.evaluate(tg, vals)
+    s = np.concatenate([vals[v] for v in tiles], axis=1) * scale
+    if causal:
+        s = np.where(np.arange(s.shape[1])[None, :] > (q_pos0 + np.arange(rows))[:, None], -np.inf, s)
+    want = softmax(s, axis=1)
+    got = np.concatenate([out[v] for v in pr], axis=1)
+    np.testing.assert_allclose(got, want, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-5)
+    if causal:
+        assert not got[np.arange(s.shape[1])[None, :] > (q_pos0 + np.arange(rows))[:, None]].any()
+    np.testing.assert_allclose(out[st][:, 0], np.max(s, axis=1), rtol=1e-6)
+
+
+@pytest.mark.parametrize("name,tol", [("c1", 1e-5), ("ragged_f32", 1e-5), ("batch2_f32", 1e-5), ("ragged_bf16", 2e-2)])
+def test_materialized_forward_equals_the_untiled_model_and_the_fused_form(name, tol):
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    fused, mat = T.build_llama_taskgraph(cfg), T.build_llama_taskgraph(cfg, materialize_scores=True)
+    assert "softmax_stat" in mat.kind and "attn_block" not in mat.kind
+    y_exact = R.forward(cfg, w)
+    y_f = T.assemble_outputs(fused, T.evaluate(fused, T.cut_inputs(fused, w)), cfg.tokens, cfg.d_model)
+    y_m = T.assemble_outputs(mat, T.evaluate(mat, T.cut_inputs(mat, w)), cfg.tokens, cfg.d_model)
+    assert R.rel_err(y_m, y_exact) < tol and R.rel_err(y_m, y_f) < 2 * tol
+
+
+def test_materialized_needs_one_head_per_column_tile():
+    cfg = config("c2")  # tile 512, head_dim 128
+    with pytest.raises(B.TurnipError, match="tile == head_dim"):
+        B.tn_build_llama(H.llama_config_struct(cfg, materialize_scores=True))
+
+
+def test_add_op_validates_the_softmax_kinds():
+    tg = B.tn_taskgraph_create()
+    try:
+        s0 = B.tn_taskgraph_add_input(tg, B.TN_F32, 8, 16, B.TN_HOST)
+        s1 = B.tn_taskgraph_add_input(tg, B.TN_F32, 8, 5, B.TN_HOST)
+        bad = B.tn_taskgraph_add_input(tg, B.TN_F32, 9, 16, B.TN_HOST)
+        p = B.tn_op_params(scale=0.5, causal=1, q_pos0=3)
+        st = B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_STAT, p, [s0, s1], B.TN_F32, 8, 2)
+        B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_APPLY, p, [s1, st], B.TN_F32, 8, 5)
+        with pytest.raises(B.TurnipError):
+            B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_STAT, p, [s0, bad], B.TN_F32, 8, 2)
+        with pytest.raises(B.TurnipError):
+            B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_STAT, p, [s0], B.TN_F32, 8, 3)
+        with pytest.raises(B.TurnipError):
+            B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_STAT, B.tn_op_params(scale=0.0), [s0], B.TN_F32, 8, 2)
+        with pytest.raises(B.TurnipError):
+            B.tn_taskgraph_add_op(tg, B.TN_OP_SOFTMAX_APPLY, p, [s0, s1], B.TN_F32, 8, 16)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_library_materialized_taskgraph_equals_the_oracles(name):
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, weights_transposed=False, v_transposed=False, materialize_scores=True))
+    try:
+        otg = oracle_taskgraph(tg)
+        mine = T.build_llama_taskgraph(cfg, materialize_scores=True)
+        for k in ("gemm", "softmax_stat", "softmax_apply"):
+            assert otg.kind.count(k) == mine.kind.count(k) > 0
+        y_lib = T.assemble_outputs(otg, T.evaluate(otg, T.cut_inputs(otg, w)), cfg.tokens, cfg.d_model)
+        y_own = T.assemble_outputs(mine, T.evaluate(mine, T.cut_inputs(mine, w)), cfg.tokens, cfg.d_model)
+        np.testing.assert_array_equal(y_lib, y_own)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_f32", "ragged_bf16"])
+def test_materialized_memgraph_under_the_cap_is_correct_in_every_sampled_order(name):
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, materialize_scores=True))
+    cap = H.cap_for(cfg, tg)
+    mg = B.tn_compile(tg, None, cap)
+    try:
+        st = B.tn_memgraph_stats(mg)
+        assert st.n_offload > 0 and st.high_water <= cap
+        omg = oracle_memgraph(mg)
+        check_all(task_preds(tg), omg, n_random=25, seed=4)
+        B.tn_memgraph_simulate(mg)
+        rng = np.random.default_rng(6)
+        for _ in range(5):
+            B.tn_memgraph_simulate(mg, M.random_topological_order(omg, rng))
+    finally:
+        B.tn_memgraph_destroy(mg)
+        B.tn_taskgraph_destroy(tg)
