@@ -71,6 +71,9 @@ def main():
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
     ap.add_argument("--evict-ahead-mb", type=int, default=-1,
                     help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/32 of the cap")
+    ap.add_argument("--materialize-scores", action="store_true",
+                    help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
+                         "sets the tile to the head dimension (one head per column tile)")
     ap.add_argument("--k-split", type=int, default=0,
                     help="cut every projection along K into this many partial products joined by a sum vertex (increments "
                          "into a write-locked output); 0 = the whole K range inside one GEMM vertex")
@@ -109,6 +112,8 @@ def main():
         cfg = cfg.with_(layers=args.layers)
     if args.cap_gb > 0:
         cfg = cfg.with_(cap_bytes=int(args.cap_gb * 1e9), cap_frac=0.0)
+    if args.materialize_scores:
+        cfg = cfg.with_(tile=cfg.head_dim)
     train = bool(args.train) if args.train >= 0 else cfg.name == "c5"
     t0 = time.perf_counter()
     distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
@@ -141,7 +146,7 @@ def main():
         order = None
         if args.order == "level":
             tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train,
-                                                        k_split=args.k_split))
+                                                        k_split=args.k_split, materialize_scores=args.materialize_scores))
             order = H.level_major_order(tg)
             B.tn_taskgraph_destroy(tg)
         cap = c.cap_bytes or 0  # only the fine-tuning workload uses it, and that one states its cap in bytes
@@ -150,7 +155,8 @@ def main():
                                      evict_ahead=args.evict_ahead_mb << 20 if args.evict_ahead_mb >= 0 else None,
                                      next_fit=args.next_fit if args.next_fit >= 0 else None)
         return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
-                            lora_rank=16 if train else 0, train=train, progress=note, k_split=args.k_split)
+                            lora_rank=16 if train else 0, train=train, progress=note, k_split=args.k_split,
+                            materialize_scores=args.materialize_scores)
 
     note("inputs generated")
     s = session(cfg)
@@ -207,7 +213,7 @@ def main():
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "materialize_scores": bool(args.materialize_scores), "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "loads": int(st.n_load),
                    "offload_GB": st.offload_bytes / 1e9, "load_GB": st.load_bytes / 1e9, "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
