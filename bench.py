@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--materialize-scores", action="store_true",
                     help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
                          "sets the tile to the head dimension (one head per column tile)")
+    ap.add_argument("--host-inputs", action="store_true",
+                    help="weights and x start in pinned host memory and are loaded under the cap (c2 keeps them on the GPU)")
     ap.add_argument("--k-split", type=int, default=0,
                     help="cut every projection along K into this many partial products joined by a sum vertex (increments "
                          "into a write-locked output); 0 = the whole K range inside one GEMM vertex")
@@ -114,6 +116,8 @@ def main():
         cfg = cfg.with_(cap_bytes=int(args.cap_gb * 1e9), cap_frac=0.0)
     if args.materialize_scores:
         cfg = cfg.with_(tile=cfg.head_dim)
+    if args.host_inputs:
+        cfg = cfg.with_(weights_resident=False, x_resident=False)
     train = bool(args.train) if args.train >= 0 else cfg.name == "c5"
     t0 = time.perf_counter()
     distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
