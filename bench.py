@@ -71,6 +71,9 @@ def main():
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
     ap.add_argument("--evict-ahead-mb", type=int, default=-1,
                     help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/32 of the cap")
+    ap.add_argument("--checkpoint", action="store_true",
+                    help="fine-tuning step with activation checkpointing: the reverse pass of a layer forms that "
+                         "layer's forward tensors again instead of reading saved ones")
     ap.add_argument("--materialize-scores", action="store_true",
                     help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
                          "sets the tile to the head dimension (one head per column tile)")
@@ -150,7 +153,8 @@ def main():
         order = None
         if args.order == "level":
             tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train,
-                                                        k_split=args.k_split, materialize_scores=args.materialize_scores))
+                                                        k_split=args.k_split, materialize_scores=args.materialize_scores,
+                                                        checkpoint=args.checkpoint))
             order = H.level_major_order(tg)
             B.tn_taskgraph_destroy(tg)
         cap = c.cap_bytes or 0  # only the fine-tuning workload uses it, and that one states its cap in bytes
@@ -160,7 +164,7 @@ def main():
                                      next_fit=args.next_fit if args.next_fit >= 0 else None)
         return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                             lora_rank=16 if train else 0, train=train, progress=note, k_split=args.k_split,
-                            materialize_scores=args.materialize_scores)
+                            materialize_scores=args.materialize_scores, checkpoint=args.checkpoint)
 
     note("inputs generated")
     s = session(cfg)
@@ -217,7 +221,7 @@ def main():
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "materialize_scores": bool(args.materialize_scores), "memgraph_vertices": int(st.n_vertices),
+                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "materialize_scores": bool(args.materialize_scores), "checkpoint": bool(args.checkpoint), "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "loads": int(st.n_load),
                    "offload_GB": st.offload_bytes / 1e9, "load_GB": st.load_bytes / 1e9, "mem_edges": int(st.n_mem_edges)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",

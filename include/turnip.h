@@ -241,6 +241,12 @@ typedef struct {
    * SOFTMAX_APPLY per score tile, and O_i = sum_j P_ij V_j as one GEMM -- instead of the fused
    * ATTN_BLOCK / ATTN_COMBINE vertices.  attn_block is ignored. */
   int32_t materialize_scores;
+  /* != 0 (needs train != 0): activation checkpointing, the setting of the paper's fine-tuning
+   * experiment (Section 8).  The forward pass keeps only each layer's input for the reverse pass;
+   * the reverse pass of a layer is preceded by that layer's forward vertices over again (all but
+   * the second half of the feed-forward block, which nothing reads), as vertices of their own.
+   * Results are bit for bit those of train without it. */
+  int32_t checkpoint;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -59,7 +59,8 @@ class tn_llama_config(C.Structure):
                                           "dtype", "tile", "attn_block")] + \
                [("eps", C.c_float), ("rope_base", C.c_float), ("weights_residency", C.c_int32),
                 ("x_residency", C.c_int32), ("kv_outputs", C.c_int32), ("weights_transposed", C.c_int32),
-                ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32), ("materialize_scores", C.c_int32)]
+                ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32), ("materialize_scores", C.c_int32),
+                ("checkpoint", C.c_int32)]
 
 
 class tn_llama_binding(C.Structure):

@@ -483,6 +483,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.train && gw != c.tile) return fail(TN_ERR_SHAPE, "train needs head_dim <= tile (one column tile per head group)");
   if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
   if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
+  if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
   if (c.materialize_scores && (c.tile != c.head_dim || c.train || c.kv_outputs))
     return fail(TN_ERR_INVALID, "materialize_scores needs tile == head_dim and neither train nor kv_outputs");
 
@@ -510,13 +511,163 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     std::vector<tn_vid> rstd1, rstd2, tq, tv;
   };
   std::vector<std::vector<Saved>> saved(c.train ? c.layers : 0, std::vector<Saved>(c.batch));
+  // with checkpointing only the input of each layer is kept; the rest is formed again in the reverse pass
+  std::vector<std::vector<Grid>> layer_in(c.checkpoint ? c.layers : 0, std::vector<Grid>(c.batch));
   struct LayerInputs {
     Grid wq, wk, wv, wo, w1, w3, w2;
-    std::vector<tn_vid> g1, g2, aq, bq, av, bv;
+    std::vector<tn_vid> g1, g2, aq, bq, av, bv, aqT, bqT, avT, bvT;
   };
   std::vector<LayerInputs> lin(c.train ? c.layers : 0);
   const int32_t rk = c.lora_rank;
   const Range rkr{0, rk};
+
+  // One layer, one sequence, stripe by stripe.  `sv`: where to note what the reverse pass reads
+  // (null: nothing is noted).  `tail`: whether the layer's output is formed (second half of the
+  // feed-forward block and the residual); a pass that only restores saved values stops before it.
+  auto forward_layer = [&](int l, const LayerInputs& w, int b, Grid& xb, Saved* sv, bool tail) {
+    const Grid &wq = w.wq, &wk = w.wk, &wv = w.wv, &wo = w.wo, &w1 = w.w1, &w3 = w.w3, &w2 = w.w2;
+    const std::vector<tn_vid>&g1 = w.g1, &g2 = w.g2, &aqT = w.aqT, &bqT = w.bqT, &avT = w.avT, &bvT = w.bvT;
+    if (sv) {
+      sv->xin = xb;
+      for (Grid* gp : {&sv->a, &sv->q, &sv->k, &sv->v, &sv->h1, &sv->gate, &sv->up}) gp->assign(t.rows.size(), {});
+      for (auto* vp : {&sv->rstd1, &sv->rstd2, &sv->tq, &sv->tv}) vp->assign(t.rows.size(), -1);
+    }
+    Grid kk(t.rows.size()), vv(t.rows.size());  // K, V of the stripes done so far
+    for (size_t s = 0; s < stripes.size(); ++s) {
+      std::vector<size_t> rt;  // row tiles of this stripe
+      for (size_t i = 0; i < t.rows.size(); ++i)
+        if (t.rows[i].a >= stripes[s].a && t.rows[i].a < stripes[s].b) rt.push_back(i);
+      Grid q(t.rows.size());
+      for (size_t i : rt) {
+        const int32_t m = t.rows[i].len();
+        tn_vid st1 = -1, tq = -1, tv = -1;
+        auto a = t.rmsnorm(xb[i], g1, m, &st1);
+        if (rk > 0) {  // the low-rank activations a Aq and a Av
+          tq = t.gemm_list(a, aqT, m, rk, false, true);
+          tv = t.gemm_list(a, avT, m, rk, false, true);
+        }
+        for (size_t j = 0; j < nd; ++j) {
+          const int32_t n = t.dcols[j].len();
+          tn_vid qj = t.gemm(a, wq, j, m, n), vj = t.gemm(a, wv, j, m, n, c.v_transposed != 0);
+          if (rk > 0) {
+            qj = t.add(qj, t.gemm_list({tq}, {bqT[j]}, m, n, false, true), m, n);
+            const bool vt = c.v_transposed != 0;
+            vj = t.op(TN_OP_ADD, tn_op_params{}, {vj, t.gemm_list({tv}, {bvT[j]}, m, n, false, true, vt)},
+                      vt ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
+          }
+          q[i].push_back(t.rope(qj, t.rows[i].a, t.dcols[j].a, m, n));
+          kk[i].push_back(t.rope(t.gemm(a, wk, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
+          vv[i].push_back(vj);
+          if (sv && j + 1 == nd) {
+            sv->a[i] = a; sv->q[i] = q[i]; sv->k[i] = kk[i]; sv->v[i] = vv[i];
+            sv->rstd1[i] = st1; sv->tq[i] = tq; sv->tv[i] = tv;
+          }
+          if (c.kv_outputs) {
+            Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
+            for (int which = 0; which < 2; ++which) {
+              tn_vid id = which ? vv[i][j] : kk[i][j];
+              tg->v[id].output_index = (int32_t)tg->outputs.size();
+              tg->outputs.push_back(id);
+              tg->bindings.push_back({id, which ? TN_T_V : TN_T_K, l, rr.a, rr.b, t.dcols[j].a, t.dcols[j].b,
+                                      (which && c.v_transposed) ? 1 : 0});
+            }
+          }
+        }
+      }
+      // attention of this stripe against stripes 0..s, one partial per pair, per head group
+      Grid o(t.rows.size(), std::vector<tn_vid>(nd, -1));
+      if (c.materialize_scores) {
+        // scores and probabilities as tensors: per head (= column tile) and row tile i the score
+        // tiles against the row tiles 0..i, the softmax over them in two portions, and P V
+        const float scale = 1.0f / std::sqrt((float)c.head_dim);
+        for (size_t i : rt)
+          for (size_t h = 0; h < nd; ++h) {
+            const int32_t m = t.rows[i].len();
+            std::vector<tn_vid> sc, pv;
+            for (size_t j = 0; j <= i; ++j) {
+              tn_op_params p{};
+              p.nk = 1;
+              p.trans_b = 1;
+              sc.push_back(t.op(TN_OP_GEMM, p, {q[i][h], kk[j][h]}, {c.dtype, m, t.rows[j].len()}));
+            }
+            tn_op_params ps{};
+            ps.scale = scale;
+            ps.causal = 1;
+            ps.q_pos0 = t.rows[i].a;
+            ps.k_pos0 = 0;
+            const tn_vid st = t.op(TN_OP_SOFTMAX_STAT, ps, sc, {TN_F32, m, 2});
+            for (size_t j = 0; j <= i; ++j) {
+              ps.k_pos0 = t.rows[j].a;
+              pv.push_back(t.op(TN_OP_SOFTMAX_APPLY, ps, {sc[j], st}, {c.dtype, m, t.rows[j].len()}));
+            }
+            tn_op_params pg{};
+            pg.nk = (int32_t)(i + 1);
+            pg.trans_b = c.v_transposed ? 1 : 0;
+            for (size_t j = 0; j <= i; ++j) pv.push_back(vv[j][h]);
+            o[i][h] = t.op(TN_OP_GEMM, pg, std::move(pv), {c.dtype, m, t.dcols[h].len()});
+          }
+      }
+      for (int32_t gi = 0; gi < (c.materialize_scores ? 0 : n_groups); ++gi) {
+        std::vector<tn_vid> parts;
+        for (size_t s2 = 0; s2 <= s; ++s2) {
+          std::vector<size_t> kt;
+          for (size_t i = 0; i < t.rows.size(); ++i)
+            if (t.rows[i].a >= stripes[s2].a && t.rows[i].a < stripes[s2].b) kt.push_back(i);
+          std::vector<tn_vid> in;
+          for (size_t i : rt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[i][gi * ctg + cc]);
+          for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kk[i][gi * ctg + cc]);
+          for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(vv[i][gi * ctg + cc]);
+          tn_op_params p{};
+          p.n_q_tiles = (int32_t)rt.size();
+          p.n_kv_tiles = (int32_t)kt.size();
+          p.n_col_tiles = ctg;
+          p.head_dim = c.head_dim;
+          p.q_pos0 = stripes[s].a;
+          p.k_pos0 = stripes[s2].a;
+          p.causal = (s2 == s);
+          p.v_trans = c.v_transposed ? 1 : 0;
+          p.scale = 1.0f / std::sqrt((float)c.head_dim);
+          parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, stripes[s].len(), gw + 2 * hpg}));
+        }
+        for (size_t i : rt)
+          for (int32_t cc = 0; cc < ctg; ++cc) {
+            tn_op_params p{};
+            p.row0 = t.rows[i].a - stripes[s].a;
+            p.col0 = cc * c.tile;
+            p.head_dim = c.head_dim;
+            p.hpg = hpg;
+            o[i][gi * ctg + cc] = t.op(TN_OP_ATTN_COMBINE, p, parts,
+                                      {c.dtype, t.rows[i].len(), t.dcols[gi * ctg + cc].len()});
+          }
+      }
+      // output projection, residual, feed-forward, residual -- row tile by row tile
+      for (size_t i : rt) {
+        const int32_t m = t.rows[i].len();
+        std::vector<tn_vid> h(nd);
+        for (size_t j = 0; j < nd; ++j) {
+          const int32_t n = t.dcols[j].len();
+          h[j] = t.op(TN_OP_ADD, tn_op_params{}, {xb[i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
+        }
+        tn_vid st2 = -1;
+        auto bn = t.rmsnorm(h, g2, m, &st2);
+        std::vector<tn_vid> act(nf), gates(nf), ups(nf);
+        for (size_t j = 0; j < nf; ++j) {
+          const int32_t n = t.fcols[j].len();
+          tn_vid gate = t.gemm(bn, w1, j, m, n), up = t.gemm(bn, w3, j, m, n);
+          gates[j] = gate;
+          ups[j] = up;
+          if (tail) act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {gate, up}, {c.dtype, m, n});
+        }
+        if (sv) {
+          sv->h1[i] = h; sv->gate[i] = gates; sv->up[i] = ups; sv->rstd2[i] = st2;
+        }
+        for (size_t j = 0; tail && j < nd; ++j) {
+          const int32_t n = t.dcols[j].len();
+          xb[i][j] = t.op(TN_OP_ADD, tn_op_params{}, {h[j], t.gemm(act, w2, j, m, n)}, {c.dtype, m, n});
+        }
+      }
+    }
+  };
 
   for (int l = 0; l < c.layers; ++l) {
     Grid wq = t.weight(TN_T_WQ, l, t.dcols, t.dcols), wk = t.weight(TN_T_WK, l, t.dcols, t.dcols);
@@ -542,152 +693,11 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
       bqT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {bq[j]}, {c.dtype, n, rk}));
       bvT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {bv[j]}, {c.dtype, n, rk}));
     }
-    if (c.train) lin[l] = {wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv};
-
+    const LayerInputs w{wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv, aqT, bqT, avT, bvT};
+    if (c.train) lin[l] = w;
     for (int b = 0; b < c.batch; ++b) {
-      if (c.train) {
-        Saved& sv = saved[l][b];
-        sv.xin = x[b];
-        for (Grid* gp : {&sv.a, &sv.q, &sv.k, &sv.v, &sv.h1, &sv.gate, &sv.up}) gp->assign(t.rows.size(), {});
-        for (auto* vp : {&sv.rstd1, &sv.rstd2, &sv.tq, &sv.tv}) vp->assign(t.rows.size(), -1);
-      }
-      Grid kk(t.rows.size()), vv(t.rows.size());  // K, V of the stripes done so far
-      for (size_t s = 0; s < stripes.size(); ++s) {
-        std::vector<size_t> rt;  // row tiles of this stripe
-        for (size_t i = 0; i < t.rows.size(); ++i)
-          if (t.rows[i].a >= stripes[s].a && t.rows[i].a < stripes[s].b) rt.push_back(i);
-        Grid q(t.rows.size());
-        for (size_t i : rt) {
-          const int32_t m = t.rows[i].len();
-          tn_vid st1 = -1, tq = -1, tv = -1;
-          auto a = t.rmsnorm(x[b][i], g1, m, &st1);
-          if (rk > 0) {  // the low-rank activations a Aq and a Av
-            tq = t.gemm_list(a, aqT, m, rk, false, true);
-            tv = t.gemm_list(a, avT, m, rk, false, true);
-          }
-          for (size_t j = 0; j < nd; ++j) {
-            const int32_t n = t.dcols[j].len();
-            tn_vid qj = t.gemm(a, wq, j, m, n), vj = t.gemm(a, wv, j, m, n, c.v_transposed != 0);
-            if (rk > 0) {
-              qj = t.add(qj, t.gemm_list({tq}, {bqT[j]}, m, n, false, true), m, n);
-              const bool vt = c.v_transposed != 0;
-              vj = t.op(TN_OP_ADD, tn_op_params{}, {vj, t.gemm_list({tv}, {bvT[j]}, m, n, false, true, vt)},
-                        vt ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n});
-            }
-            q[i].push_back(t.rope(qj, t.rows[i].a, t.dcols[j].a, m, n));
-            kk[i].push_back(t.rope(t.gemm(a, wk, j, m, n), t.rows[i].a, t.dcols[j].a, m, n));
-            vv[i].push_back(vj);
-            if (c.train && j + 1 == nd) {
-              Saved& sv = saved[l][b];
-              sv.a[i] = a; sv.q[i] = q[i]; sv.k[i] = kk[i]; sv.v[i] = vv[i];
-              sv.rstd1[i] = st1; sv.tq[i] = tq; sv.tv[i] = tv;
-            }
-            if (c.kv_outputs) {
-              Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
-              for (int which = 0; which < 2; ++which) {
-                tn_vid id = which ? vv[i][j] : kk[i][j];
-                tg->v[id].output_index = (int32_t)tg->outputs.size();
-                tg->outputs.push_back(id);
-                tg->bindings.push_back({id, which ? TN_T_V : TN_T_K, l, rr.a, rr.b, t.dcols[j].a, t.dcols[j].b,
-                                        (which && c.v_transposed) ? 1 : 0});
-              }
-            }
-          }
-        }
-        // attention of this stripe against stripes 0..s, one partial per pair, per head group
-        Grid o(t.rows.size(), std::vector<tn_vid>(nd, -1));
-        if (c.materialize_scores) {
-          // scores and probabilities as tensors: per head (= column tile) and row tile i the score
-          // tiles against the row tiles 0..i, the softmax over them in two portions, and P V
-          const float scale = 1.0f / std::sqrt((float)c.head_dim);
-          for (size_t i : rt)
-            for (size_t h = 0; h < nd; ++h) {
-              const int32_t m = t.rows[i].len();
-              std::vector<tn_vid> sc, pv;
-              for (size_t j = 0; j <= i; ++j) {
-                tn_op_params p{};
-                p.nk = 1;
-                p.trans_b = 1;
-                sc.push_back(t.op(TN_OP_GEMM, p, {q[i][h], kk[j][h]}, {c.dtype, m, t.rows[j].len()}));
-              }
-              tn_op_params ps{};
-              ps.scale = scale;
-              ps.causal = 1;
-              ps.q_pos0 = t.rows[i].a;
-              ps.k_pos0 = 0;
-              const tn_vid st = t.op(TN_OP_SOFTMAX_STAT, ps, sc, {TN_F32, m, 2});
-              for (size_t j = 0; j <= i; ++j) {
-                ps.k_pos0 = t.rows[j].a;
-                pv.push_back(t.op(TN_OP_SOFTMAX_APPLY, ps, {sc[j], st}, {c.dtype, m, t.rows[j].len()}));
-              }
-              tn_op_params pg{};
-              pg.nk = (int32_t)(i + 1);
-              pg.trans_b = c.v_transposed ? 1 : 0;
-              for (size_t j = 0; j <= i; ++j) pv.push_back(vv[j][h]);
-              o[i][h] = t.op(TN_OP_GEMM, pg, std::move(pv), {c.dtype, m, t.dcols[h].len()});
-            }
-        }
-        for (int32_t gi = 0; gi < (c.materialize_scores ? 0 : n_groups); ++gi) {
-          std::vector<tn_vid> parts;
-          for (size_t s2 = 0; s2 <= s; ++s2) {
-            std::vector<size_t> kt;
-            for (size_t i = 0; i < t.rows.size(); ++i)
-              if (t.rows[i].a >= stripes[s2].a && t.rows[i].a < stripes[s2].b) kt.push_back(i);
-            std::vector<tn_vid> in;
-            for (size_t i : rt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[i][gi * ctg + cc]);
-            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kk[i][gi * ctg + cc]);
-            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(vv[i][gi * ctg + cc]);
-            tn_op_params p{};
-            p.n_q_tiles = (int32_t)rt.size();
-            p.n_kv_tiles = (int32_t)kt.size();
-            p.n_col_tiles = ctg;
-            p.head_dim = c.head_dim;
-            p.q_pos0 = stripes[s].a;
-            p.k_pos0 = stripes[s2].a;
-            p.causal = (s2 == s);
-            p.v_trans = c.v_transposed ? 1 : 0;
-            p.scale = 1.0f / std::sqrt((float)c.head_dim);
-            parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, stripes[s].len(), gw + 2 * hpg}));
-          }
-          for (size_t i : rt)
-            for (int32_t cc = 0; cc < ctg; ++cc) {
-              tn_op_params p{};
-              p.row0 = t.rows[i].a - stripes[s].a;
-              p.col0 = cc * c.tile;
-              p.head_dim = c.head_dim;
-              p.hpg = hpg;
-              o[i][gi * ctg + cc] = t.op(TN_OP_ATTN_COMBINE, p, parts,
-                                        {c.dtype, t.rows[i].len(), t.dcols[gi * ctg + cc].len()});
-            }
-        }
-        // output projection, residual, feed-forward, residual -- row tile by row tile
-        for (size_t i : rt) {
-          const int32_t m = t.rows[i].len();
-          std::vector<tn_vid> h(nd);
-          for (size_t j = 0; j < nd; ++j) {
-            const int32_t n = t.dcols[j].len();
-            h[j] = t.op(TN_OP_ADD, tn_op_params{}, {x[b][i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
-          }
-          tn_vid st2 = -1;
-          auto bn = t.rmsnorm(h, g2, m, &st2);
-          std::vector<tn_vid> act(nf), gates(nf), ups(nf);
-          for (size_t j = 0; j < nf; ++j) {
-            const int32_t n = t.fcols[j].len();
-            tn_vid gate = t.gemm(bn, w1, j, m, n), up = t.gemm(bn, w3, j, m, n);
-            gates[j] = gate;
-            ups[j] = up;
-            act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {gate, up}, {c.dtype, m, n});
-          }
-          if (c.train) {
-            Saved& sv = saved[l][b];
-            sv.h1[i] = h; sv.gate[i] = gates; sv.up[i] = ups; sv.rstd2[i] = st2;
-          }
-          for (size_t j = 0; j < nd; ++j) {
-            const int32_t n = t.dcols[j].len();
-            x[b][i][j] = t.op(TN_OP_ADD, tn_op_params{}, {h[j], t.gemm(act, w2, j, m, n)}, {c.dtype, m, n});
-          }
-        }
-      }
+      if (c.checkpoint) layer_in[l][b] = x[b];
+      forward_layer(l, w, b, x[b], c.train && !c.checkpoint ? &saved[l][b] : nullptr, true);
     }
   }
   for (int b = 0; b < c.batch; ++b)
@@ -713,6 +723,11 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     }
     for (int l = c.layers - 1; l >= 0; --l) {
       const LayerInputs& w = lin[l];
+      if (c.checkpoint)  // form what the reverse pass reads of this layer again, from the layer's input
+        for (int b = 0; b < c.batch; ++b) {
+          Grid xin = layer_in[l][b];
+          forward_layer(l, w, b, xin, &saved[l][b], false);
+        }
       // base weights as [in, out] tiles: the forward pass's own if it uses that layout
       const bool own = c.weights_transposed != 0;
       Grid wqn = own ? t.natural(TN_T_WQ, l, t.dcols, t.dcols) : w.wq, wkn = own ? t.natural(TN_T_WK, l, t.dcols, t.dcols) : w.wk;

@@ -28,7 +28,8 @@ EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "or
 
 def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
                         v_transposed: bool = True, lora_rank: int = 0, train: bool = False,
-                        k_split: int = 0, materialize_scores: bool = False) -> B.tn_llama_config:
+                        k_split: int = 0, materialize_scores: bool = False,
+                        checkpoint: bool = False) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -38,7 +39,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
         weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
         lora_rank=int(lora_rank), train=int(train), k_split=int(k_split),
-        materialize_scores=int(materialize_scores))
+        materialize_scores=int(materialize_scores), checkpoint=int(checkpoint))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -204,14 +205,15 @@ class GpuSession:
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
-                 materialize_scores: bool = False):
+                 materialize_scores: bool = False, checkpoint: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
         self.torch = torch
         self.cfg = cfg
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
-                                                       lora_rank, train, k_split, materialize_scores))
+                                                       lora_rank, train, k_split, materialize_scores,
+                                                       checkpoint))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

@@ -1,0 +1,115 @@
+"""Activation checkpointing of the fine-tuning step (the setting of the paper's fine-tuning
+experiment, Section 8): the forward pass keeps only the input of each layer, the reverse pass of a
+layer is preceded by that layer's forward vertices over again.  CPU tests: which forward tensors
+the reverse pass still reads, that every output is the same expression of the inputs as without
+checkpointing (so the deterministic kernels must give the same bits), the smaller uncapped peak,
+and the compiled memgraphs under the cap against the oracle's checkers."""
+import pytest
+
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import config
+
+from util import check_all, oracle_memgraph, task_preds
+
+RANK = 8
+
+
+def _graph(cfg, checkpoint):
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint))
+    try:
+        return H.export_taskgraph(tg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
+def _expressions(e):
+    """Per output binding the expression tree of its vertex, as a nested hash: an input is its
+    binding (tensor, piece), an op its kind, parameters, shape and operands' expressions."""
+    where = {b[0]: b[1:] for b in e["bindings"]}
+    memo = {}
+    for v in range(len(e["kind"])):  # ids are topological
+        if e["kind"][v] == "input":
+            memo[v] = hash(("input",) + where[v])
+        else:
+            memo[v] = hash((e["kind"][v], tuple(sorted(e["params"][v].items())), e["shape"][v], e["dtype"][v],
+                            tuple(memo[u] for u in e["inputs"][v])))
+    return {where[v]: memo[v] for v in e["outputs"]}
+
+
+@pytest.mark.parametrize("name", ["c1", "batch2_f32", "ragged_bf16"])
+def test_every_output_is_the_same_expression_with_and_without_checkpointing(name):
+    cfg = config(name)
+    plain, ck = _graph(cfg, False), _graph(cfg, True)
+    assert len(ck["kind"]) > len(plain["kind"])
+    a, b = _expressions(plain), _expressions(ck)
+    assert a.keys() == b.keys() and len(a) == len(plain["outputs"])
+    assert a == b
+
+
+def test_a_changed_operand_changes_the_expression():
+    """The comparison above can fail: swapping two operands of one vertex of the reverse pass shows."""
+    e = _graph(config("c1"), True)
+    before = _expressions(e)
+    v = max(i for i, k in enumerate(e["kind"]) if k == "silu_mul_bwd")
+    e["inputs"][v] = [e["inputs"][v][0], e["inputs"][v][2], e["inputs"][v][1]]
+    assert _expressions(e) != before
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_the_reverse_pass_reads_only_layer_inputs_of_the_forward_pass(name):
+    cfg = config(name).with_(layers=3)
+    for checkpoint in (False, True):
+        e = _graph(cfg, checkpoint)
+        first_probe = min(b[0] for b in e["bindings"] if b[1] == "probe")
+        kinds = set()
+        used = set()
+        for v in range(first_probe, len(e["kind"])):
+            for u in e["inputs"][v]:
+                used.add(u)
+                if u < first_probe and e["kind"][u] != "input":
+                    kinds.add(e["kind"][u])
+        if checkpoint:
+            # outputs of a layer (the residual add) and the transposed adapter tiles, nothing else
+            assert kinds <= {"add", "transpose"}, kinds
+        else:
+            assert {"gemm", "rope", "rms_apply", "rms_stat"} <= kinds
+        # nothing is computed in vain
+        outs = set(e["outputs"])
+        every = set(u for ins in e["inputs"] for u in ins)
+        assert all(v in every or v in outs for v in range(len(e["kind"])))
+
+
+def test_checkpointing_lowers_the_peak_when_activations_dominate():
+    cfg = config("c1").with_(layers=6, seq=512)
+    peaks = []
+    for checkpoint in (False, True):
+        tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint))
+        try:
+            peaks.append(H.uncapped_peak(tg))
+        finally:
+            B.tn_taskgraph_destroy(tg)
+    assert peaks[1] < 0.7 * peaks[0], peaks
+
+
+def test_checkpoint_without_train_is_refused():
+    with pytest.raises(B.TurnipError):
+        B.tn_build_llama(H.llama_config_struct(config("c1"), checkpoint=True))
+
+
+@pytest.mark.parametrize("name", ["c1", "batch2_f32", "ragged_bf16"])
+def test_checkpointed_memgraph_under_the_cap_is_correct_in_every_sampled_order(name):
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=True))
+    try:
+        cap = H.cap_for(cfg, tg)
+        for opts in (None, H.bench_compile_opts(cap, True)):
+            mg = B.tn_compile(tg, None, cap, opts)
+            try:
+                st = B.tn_memgraph_stats(mg)
+                assert st.n_offload > 0 and st.high_water <= cap
+                check_all(task_preds(tg), oracle_memgraph(mg), n_random=12, seed=5)
+            finally:
+                B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)

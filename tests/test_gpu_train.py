@@ -55,3 +55,34 @@ def test_adapter_gradients_match_the_oracle_under_the_cap(name, b_std, tol):
             np.testing.assert_array_equal(o2[k], out[k])
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("name,tol", [("c1", 1e-4), ("batch2_f32", 1e-4), ("ragged_bf16", 4e-2)])
+def test_checkpointed_step_gives_the_same_bits_as_the_saved_activation_step(name, tol):
+    """Activation checkpointing (Section 8, the fine-tuning experiment's setting): the layer's
+    forward vertices run a second time before its reverse pass.  The kernels are deterministic, so
+    every output must carry the bits of the step that saved its activations, and with them the
+    oracle's gradients within the tolerance."""
+    cfg, s, y_ref, g_ref = _case(name, 0.02)
+    try:
+        want, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
+    finally:
+        s.close()
+    cfg, s, _, _ = _case(name, 0.02, checkpoint=True)
+    try:
+        print(f"[case] {name} checkpointed: cap {s.cap}, {s.stats.n_vertices} vertices, {s.stats.n_offload} offloads, "
+              f"{s.stats.n_reload} reloads", flush=True)
+        for seed in range(4):
+            print(f"[case] {name} checkpointed order_seed {seed}", flush=True)
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, max_delay_us=(0, 50)[seed % 2],
+                                            max_batch=(1, 0)[seed // 2]))
+            assert rep.n_vertices == s.stats.n_vertices
+            assert out.keys() == want.keys()
+            for k in want:
+                np.testing.assert_array_equal(out[k], want[k])
+        assert R.rel_err(_f64(cfg, out["dx"]), g_ref["x"]) < tol
+        for l in range(cfg.layers):
+            for k in ("aq", "bq", "av", "bv"):
+                assert R.rel_err(_f64(cfg, out[f"d{k}.{l}"]), g_ref[f"{k}.{l}"]) < tol
+    finally:
+        s.close()
