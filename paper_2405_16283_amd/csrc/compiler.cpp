@@ -339,7 +339,8 @@ struct Compiler {
   // evict more than the allocation at hand needs (tn_compile_opts::evict_ahead_bytes)
   void evict_ahead(const std::vector<int64_t>& pinned) {
     if (!opt.evict_ahead_bytes) return;
-    constexpr int64_t kFarAhead = 30000;  // vertices of the serial order
+    // only what is not needed for a long while: a sixteenth of the serial order, 30000 vertices at most
+    const int64_t kFarAhead = std::min<int64_t>(30000, n / 16);
     uint64_t freed = 0;
     std::vector<int64_t> victims;
     for (auto c = by_use.rbegin(); c != by_use.rend() && freed < opt.evict_ahead_bytes; ++c) {
