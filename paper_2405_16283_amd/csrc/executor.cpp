@@ -975,6 +975,25 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       }
       n_ready_k -= (int64_t)same.size();
       const VInfo lead = ex->groups[gi];
+      // The workgroups of a launch run in the order of its vertices, and those of one XCD (one L2)
+      // take a contiguous run of them.  Arrange the tile products so that vertices next to each
+      // other share operands both ways -- blocks of two A row panels by four B column panels --
+      // instead of one A panel against every B panel of the launch.
+      if (lead.cls == LC_GEMM_BF16_NT256 && same.size() >= 16) {
+        auto a0 = [&](int64_t m) { return mg.v[m].operands[0]; };
+        auto b0 = [&](int64_t m) { return mg.v[m].operands[mg.v[m].p.nk]; };
+        std::vector<int64_t> bs;
+        for (int64_t m : same) bs.push_back(b0(m));
+        std::sort(bs.begin(), bs.end());
+        bs.erase(std::unique(bs.begin(), bs.end()), bs.end());
+        auto rank_b = [&](int64_t m) { return (int64_t)(std::lower_bound(bs.begin(), bs.end(), b0(m)) - bs.begin()); };
+        std::stable_sort(same.begin(), same.end(), [&](int64_t x, int64_t y) {
+          const int64_t bx = rank_b(x), by = rank_b(y);
+          if (bx / 4 != by / 4) return bx / 4 < by / 4;
+          if (a0(x) != a0(y)) return a0(x) < a0(y);
+          return bx < by;
+        });
+      }
       batch.n = (int32_t)same.size();
       batch.base = (uint32_t)ex->info[same[0]].desc;
       for (int64_t m : same) batch.base = std::min(batch.base, (uint32_t)ex->info[m].desc);
