@@ -753,6 +753,21 @@ __device__ __forceinline__ void xcd_remap(int& bx, int& by) {
   bx = v - by * gx;
 }
 
+// The same idea for kernels whose workgroups of one vertex share operands (the query blocks of an
+// attention head all read that head's keys and values): vertex by goes to XCD by % 8 as a whole,
+// and vertices that differ in cost (blocks on and off the diagonal) stay spread over the XCDs.
+__device__ __forceinline__ void xcd_remap_rows(int& bx, int& by) {
+  const int gx = gridDim.x, full = (int)(gridDim.y / 8) * 8;
+  bx = blockIdx.x;
+  by = blockIdx.y;
+  if (by >= full) return;  // the last, incomplete group of eight vertices stays as launched
+  const int n = bx + gx * by;
+  const int slot = n >> 3;
+  const int grp = slot / gx;  // vertices 8 grp .. 8 grp + 7; which XCD takes which rotates with grp, so that a
+  by = grp * 8 + ((n + grp) & 7);  // cost pattern with period 8 in the launch order does not pile up on one XCD
+  bx = slot - grp * gx;
+}
+
 // NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two
 // per SIMD, so that one wavefront's MFMAs fill the time the other spends issuing its loads).
 // MFMA with the accumulator held in the accumulation registers.  Left to itself the compiler
@@ -1117,8 +1132,10 @@ constexpr int kAttnBwdChunk = 64;                          // rows of the other 
 constexpr int attn_bwd_lds(int hd) { return 2 * 3 * kAttnBwdChunk * hd * 2 + 2 * 2 * kAttnBwdChunk * 4; }
 template <int HD, int mode>
 __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.at(blockIdx.y)];
-  if ((int)blockIdx.x >= d.nblocks) return;
+  int bx, by;
+  xcd_remap_rows(bx, by);
+  const OpDesc& d = t.descs[b.at(by)];
+  if (bx >= d.nblocks) return;
   constexpr int CH = kAttnBwdChunk;  // rows of the other side per round
   constexpr int CPR = HD / 8;        // 16-byte pieces per row of a [CH][HD] chunk
   constexpr int ABYTES = CH * HD * 2, STAGE = 3 * ABYTES;  // K | V | K^T (or Q | dO | Q^T or dO^T): equal sizes
@@ -1137,7 +1154,7 @@ __global__ void __launch_bounds__(kAttnBwdThreads) attn_bwd_bf16_kernel(DeviceTa
   void* const* Tt = St + nq;        // transposed grid (modes 1..3)
   const int my_rows = mode <= 1 ? q_rows : kv_rows;
   const int rblocks = (my_rows + kAttnBwdRows - 1) / kAttnBwdRows;
-  const int h = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
+  const int h = bx / rblocks, rb = bx % rblocks;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
   const int myrow = rb * kAttnBwdRows + w * 32 + l32;  // this lane's query (modes 0, 1) or key (modes 2, 3)
   const bool valid = myrow < my_rows;
@@ -1405,8 +1422,10 @@ constexpr float kLazy = 8.f;  // see the rescaling step of attn_bf16_kernel
 
 template <int HD>
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch b) {
-  const OpDesc& d = t.descs[b.at(blockIdx.y)];
-  if ((int)blockIdx.x >= d.nblocks) return;
+  int bx, by;
+  xcd_remap_rows(bx, by);
+  const OpDesc& d = t.descs[b.at(by)];
+  if (bx >= d.nblocks) return;
   constexpr int KC = 64;                   // keys per iteration
   constexpr int CPR = HD / 8;              // 16-byte chunks per K row
   constexpr int KBYTES = KC * HD * 2, BUF = 2 * KBYTES;  // K chunk, then V^T chunk [HD][KC]
@@ -1416,7 +1435,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
   const int tq = ax[0], tk = ax[1], tc = ax[2], q_rows = ax[3], kv_rows = ax[4];
   const int nc = d.p.n_col_tiles, gw = nc * tc, hpg = gw / HD;
   const int qblocks = (q_rows + 127) / 128;
-  const int h = blockIdx.x / qblocks, qb = blockIdx.x % qblocks;
+  const int h = bx / qblocks, qb = bx % qblocks;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
   void* const* Qp = t.ptrs + d.ptr0;
   void* const* Kp = Qp + d.p.n_q_tiles * nc;
