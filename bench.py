@@ -77,6 +77,10 @@ def main():
     ap.add_argument("--materialize-scores", action="store_true",
                     help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
                          "sets the tile to the head dimension (one head per column tile)")
+    ap.add_argument("--host-outputs", type=int, default=-1,
+                    help="1: marked outputs are stored to pinned host memory inside the timed step; 0: they are copied to a "
+                         "buffer in GPU memory outside the capped device buffer.  Default: 0 when the inputs are device-resident "
+                         "(the step begins and ends in HBM), 1 when weights are streamed from the host")
     ap.add_argument("--host-inputs", action="store_true",
                     help="weights and x start in pinned host memory and are loaded under the cap (c2 keeps them on the GPU)")
     ap.add_argument("--k-split", type=int, default=0,
@@ -149,7 +153,10 @@ def main():
         return reps
 
     t0 = time.perf_counter()
-    def session(c, pressed=False):
+    # where the marked outputs go: GPU memory when the step also starts there, else pinned host memory
+    device_outputs = (cfg.weights_resident and cfg.x_resident) if args.host_outputs < 0 else not args.host_outputs
+
+    def session(c, pressed=False, device_outputs=False):
         order = None
         if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
             tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train,
@@ -170,10 +177,11 @@ def main():
                                      next_fit=args.next_fit if args.next_fit >= 0 else None, pressed=pressed)
         return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                             lora_rank=16 if train else 0, train=train, progress=note, k_split=args.k_split,
-                            materialize_scores=args.materialize_scores, checkpoint=args.checkpoint)
+                            materialize_scores=args.materialize_scores, checkpoint=args.checkpoint,
+                            device_outputs=device_outputs)
 
     note("inputs generated")
-    s = session(cfg)
+    s = session(cfg, device_outputs=device_outputs)
     t_compile = time.perf_counter() - t0
     note(f"compiled and executor created: {int(s.stats.n_vertices)} memgraph vertices, {int(s.stats.n_offload)} offloads, "
          f"{int(s.stats.n_load)} loads")
@@ -194,6 +202,14 @@ def main():
                           transfer_depth=args.transfer_depth))
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs(only=["y"])["y"]
+    # the same step with the outputs stored to pinned host memory (the rate that includes the host link)
+    ms_host_out = None
+    if device_outputs:
+        sh = session(cfg, device_outputs=False)
+        rh = timed(sh, max(3, args.steps // 4), 1, opts)
+        ms_host_out = 1e3 * sum(dt for dt, _ in rh) / len(rh)
+        assert np.array_equal(sh.outputs(only=["y"])["y"], y)
+        sh.close()
     st = s.stats
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
     gemm_ms = sum(r.gemm_ms for _, r in reps)
@@ -226,6 +242,7 @@ def main():
                                f"tile {cfg.tile}, attention block {cfg.attn_block}",
                    "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
                    "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
+                   "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
                    "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
                    "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "materialize_scores": bool(args.materialize_scores), "checkpoint": bool(args.checkpoint), "memgraph_vertices": int(st.n_vertices),
                    "offloads": int(st.n_offload), "reloads": int(st.n_reload), "loads": int(st.n_load),
@@ -237,6 +254,8 @@ def main():
                      "flops_per_launch": gemm_flops / max(1, gemm_launches)},
         "extra": {
             "ms_per_step_without_event_pairs": ms_plain,
+            "ms_per_step_with_outputs_stored_to_host": ms_host_out,
+            "tokens_per_s_with_outputs_stored_to_host": cfg.tokens / (ms_host_out * 1e-3) if ms_host_out else None,
             "tokens_per_s_without_event_pairs": cfg.tokens / (ms_plain * 1e-3),
             "whole_run_tflops": total_flops / (ms * 1e-3) / 1e12,
             "whole_run_frac_of_mfma_peak": total_flops / (ms * 1e-3) / 1e12 / peak,

@@ -164,6 +164,7 @@ struct tn_executor {
   std::vector<int> prof_family;
   // host buffers already found to be GPU-addressable pinned memory (start, end)
   std::vector<std::pair<const char*, const char*>> pinned_ranges;
+  std::vector<std::pair<const char*, const char*>> device_ranges;  // callers' buffers in GPU memory
   bool arena_device_visible = false;
 };
 
@@ -429,16 +430,35 @@ void arena_free(tn_executor& ex, uint64_t off) {
   arena_index_add(ex, it->first, it->second.size);
 }
 
-// True if [p, p+bytes) is pinned host memory that kernels can address.  Ranges found once are
-// remembered, so that a repeated call with the same buffers costs a few comparisons.
-bool device_visible_host(tn_executor& ex, const void* p, uint64_t bytes) {
+// True if [p, p+bytes) is memory that kernels can address: pinned host memory, or memory of the
+// GPU itself (a caller's buffer for results that stay on the GPU; *on_device is then set).
+// Ranges found once are remembered, so that a repeated call with the same buffers costs a few
+// comparisons.
+bool device_visible_host(tn_executor& ex, const void* p, uint64_t bytes, bool* on_device = nullptr) {
   const char* a = (const char*)p;
+  for (auto& r : ex.device_ranges)
+    if (a >= r.first && a + bytes <= r.second) {
+      if (on_device) *on_device = true;
+      return true;
+    }
   for (auto& r : ex.pinned_ranges)
     if (a >= r.first && a + bytes <= r.second) return true;
   hipPointerAttribute_t at{};
   if (hipPointerGetAttributes(&at, p) != hipSuccess) {
     (void)hipGetLastError();  // pageable memory is reported as an error: not ours to keep
     return false;
+  }
+  if (at.type == hipMemoryTypeDevice) {
+    void* base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange((hipDeviceptr_t*)&base, &size, (hipDeviceptr_t)p) != hipSuccess || !base ||
+        a < (const char*)base || a + bytes > (const char*)base + size) {
+      (void)hipGetLastError();
+      return false;
+    }
+    ex.device_ranges.emplace_back((const char*)base, (const char*)base + size);
+    if (on_device) *on_device = true;
+    return true;
   }
   if (at.type != hipMemoryTypeHost || !at.devicePointer) return false;
   void* base = nullptr;
@@ -640,16 +660,18 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       return fail(TN_ERR_INVALID, "no host buffer for output %d", x.output_index);
   }
   bool use_copy_kernel = opt.copy_engine != TN_COPY_MEMCPY;
-  if (use_copy_kernel) {
+  bool any_on_device = false;  // a caller's buffer lies in GPU memory: hipMemcpyAsync is told to find the direction itself
+  {
     bool ok = ex->arena_device_visible || mg.stats.n_offload == 0;
     for (int64_t m = 0; m < nv && ok; ++m) {
       const MVertex& x = mg.v[m];
-      if (x.kind == TN_MG_LOAD) ok = device_visible_host(*ex, host_inputs[x.src], x.bytes);
-      else if (x.kind == TN_MG_STORE) ok = device_visible_host(*ex, host_outputs[x.output_index], x.bytes);
+      if (x.kind == TN_MG_LOAD) ok = device_visible_host(*ex, host_inputs[x.src], x.bytes, &any_on_device);
+      else if (x.kind == TN_MG_STORE) ok = device_visible_host(*ex, host_outputs[x.output_index], x.bytes, &any_on_device);
     }
-    if (!ok && opt.copy_engine == TN_COPY_KERNEL)
+    if (!ok) any_on_device = true;  // not every buffer was looked at (pageable memory ends the scan)
+    if (use_copy_kernel && !ok && opt.copy_engine == TN_COPY_KERNEL)
       return fail(TN_ERR_INVALID, "copy_engine KERNEL needs every host buffer to be GPU-addressable pinned memory");
-    use_copy_kernel = ok;
+    use_copy_kernel = use_copy_kernel && ok;
   }
   ex->remaining = ex->indeg;
   std::vector<int64_t> rem_enq(ex->indeg);           // dependencies not yet enqueued (kernels) or completed
@@ -803,6 +825,14 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       tv.clear();
       copies.n = 0;
       copies.total_blocks = 0;
+      // a group whose copies all stay inside GPU memory is not bound by the host link: it gets a
+      // launch as wide as the chip instead of the few workgroups that keep the link busy
+      bool inside_gpu = any_on_device;
+      auto on_gpu = [&](const void* p) {
+        for (auto& r : ex->device_ranges)
+          if ((const char*)p >= r.first && (const char*)p < r.second) return true;
+        return false;
+      };
       hipError_t e = hipSuccess;
       while (n_ready_x[dir] > 0 && (int)tv.size() < max_xfer && e == hipSuccess) {
         int64_t m;
@@ -818,13 +848,17 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         if (x.kind == TN_MG_LOAD) {
           src = host_inputs[x.src];
           dst = ex->dbase + x.offset;
+          inside_gpu = inside_gpu && on_gpu(src);
         } else if (x.kind == TN_MG_RELOAD) {
           src = ex->arena + ex->arena_off[x.operands[0]];
           dst = ex->dbase + x.offset;
+          inside_gpu = false;
         } else if (x.kind == TN_MG_STORE) {
           src = ex->dbase + mg.v[x.operands[0]].offset;
           dst = host_outputs[x.output_index];
+          inside_gpu = inside_gpu && on_gpu(dst);
         } else {  // offload
+          inside_gpu = false;
           uint64_t off;
           if (!ex->arena || !arena_alloc(*ex, x.bytes, &off)) {
             if (!tv.empty() || !xq[1].empty()) break;  // let the copies already queued (and later reloads) free slots
@@ -844,7 +878,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
           copies.it[copies.n++] = {src, dst, (uint32_t)x.bytes, (uint32_t)copies.total_blocks};
           copies.total_blocks += (int32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes);
         } else {
-          e = hipMemcpyAsync(dst, src, x.bytes, dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
+          e = hipMemcpyAsync(dst, src, x.bytes,
+                             any_on_device ? hipMemcpyDefault : dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
           if (e != hipSuccess) break;
         }
         if (in_order) {
@@ -871,7 +906,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         if (prof_event(&a) && prof_event(&b2)) xg.prof = (int)prof_used - 2;
       }
       if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
-      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, opt.copy_workgroups, sl.stream);
+      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, inside_gpu ? kDeviceCopyWorkgroups : opt.copy_workgroups, sl.stream);
       if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof + 1], sl.stream);
       if (e == hipSuccess) e = hipEventRecord(xg.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }

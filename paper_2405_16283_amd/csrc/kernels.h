@@ -83,6 +83,7 @@ constexpr int kCopyThreads = 1024;
 constexpr int kCopyLoads = 2;  // 16-byte loads in flight per lane
 constexpr uint32_t kCopyBlockBytes = kCopyLoads * 16 * kCopyThreads;  // bytes one workgroup moves per step: 32 KiB
 constexpr int kDefaultCopyWorkgroups = 8;
+constexpr int kDeviceCopyWorkgroups = 512;  // copies that stay inside GPU memory: two per compute unit
 struct CopyItem {
   const void* src;
   void* dst;

@@ -218,7 +218,7 @@ class GpuSession:
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
-                 materialize_scores: bool = False, checkpoint: bool = False):
+                 materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -272,7 +272,9 @@ class GpuSession:
         for (r, c) in self.out_shapes:
             self.out_offs.append(total)
             total += (r * c * es + 255) // 256 * 256
-        self.out_slab = torch.empty(max(total, 256), dtype=torch.uint8).pin_memory()
+        # results in pinned host memory, or (device_outputs) in GPU memory outside the capped buffer
+        self.out_slab = (torch.empty(max(total, 256), dtype=torch.uint8, device="cuda:0") if device_outputs
+                         else torch.empty(max(total, 256), dtype=torch.uint8).pin_memory())
         self.out_ptrs = B.ptr_array([self.out_slab.data_ptr() + o for o in self.out_offs])
         # device memory and streams
         self.dev = torch.empty(self.cap, dtype=torch.uint8, device="cuda:0")
@@ -303,7 +305,7 @@ class GpuSession:
         tiles; `only` restricts the result to the named tensors."""
         cfg = self.cfg
         out: Dict[str, np.ndarray] = {}
-        slab = self.out_slab.numpy()
+        slab = self.out_slab.cpu().numpy()
         es = np.dtype(self.elem).itemsize
         for i, v in enumerate(self.out_vids):
             _, name, r0, r1, c0, c1, tr = self.out_bind[v]

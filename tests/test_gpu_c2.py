@@ -30,7 +30,7 @@ def bench_opts(**kw):
 def test_c2_bench_configuration_matches_the_oracle_everywhere(c2):
     cfg, full, y_oracle = c2
     print("[case] c2 full size, bench configuration", flush=True)
-    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS)
+    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS, device_outputs=True)  # as bench.py runs it
     try:
         out, rep = s.run(bench_opts())
         y = bf16_bits_to_f32(out["y"]).astype(np.float64)

@@ -1,0 +1,41 @@
+"""Results that stay on the GPU: the output buffers handed to tn_execute lie in GPU memory outside
+the capped device buffer, so the store vertices are copies inside GPU memory.  The bits must be
+those of the run that stores to pinned host memory, with either copy engine, and the oracle's."""
+import numpy as np
+import pytest
+
+from oracle import llama_ref as R
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import bf16_bits_to_f32, config, make_llama_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,tol", [("c1", 1e-4), ("ragged_bf16", 2e-2)])
+def test_outputs_in_gpu_memory_carry_the_same_bits(name, tol):
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 0)
+    tg = T.build_llama_taskgraph(cfg)
+    ref = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, R.widen(cfg, full))), cfg.tokens, cfg.d_model)
+    s = H.GpuSession(cfg, full, kv_outputs=True)
+    try:
+        want, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=64))
+    finally:
+        s.close()
+    s = H.GpuSession(cfg, full, kv_outputs=True, device_outputs=True)
+    try:
+        assert s.out_slab.is_cuda and s.stats.n_offload > 0
+        for engine in (B.TN_COPY_AUTO, B.TN_COPY_KERNEL, B.TN_COPY_MEMCPY):
+            for seed in (0, 1):
+                print(f"[case] {name} device outputs, copy engine {engine}, order_seed {seed}", flush=True)
+                out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, copy_engine=engine,
+                                                max_delay_us=50 * seed))
+                assert rep.n_vertices == s.stats.n_vertices and out.keys() == want.keys()
+                for k in want:
+                    np.testing.assert_array_equal(out[k], want[k])
+        y = (bf16_bits_to_f32(out["y"]) if cfg.dtype == "bf16" else out["y"]).astype(np.float64)
+        assert R.rel_err(y, ref) < tol
+    finally:
+        s.close()
