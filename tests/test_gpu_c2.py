@@ -54,10 +54,11 @@ def test_c2_streamed_under_forty_percent_cap_gives_the_same_bits(c2):
     print("[case] c2 streamed, cap = 40 % of the uncapped peak", flush=True)
     tg = B.tn_build_llama(H.llama_config_struct(capped))
     cap = H.cap_for(capped, tg)
+    order = H.level_major_order(tg)
     B.tn_taskgraph_destroy(tg)
-    # the compile options and stream count of the benchmark's capped run
+    # the serial order, compile options and stream count of the benchmark's capped run
     s = H.GpuSession(capped, full, cap=cap, compile_opts=H.bench_compile_opts(cap, False, pressed=True),
-                     n_compute=H.BENCH_COMPUTE_STREAMS)
+                     n_compute=H.BENCH_COMPUTE_STREAMS, order=order)
     try:
         assert s.stats.n_offload > 0 and s.stats.n_load > 0
         out, rep = s.run(bench_opts())
