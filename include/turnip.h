@@ -430,7 +430,8 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
                              tn_executor** out);
 void tn_executor_destroy(tn_executor* ex);
 
-/* Copies every TN_DEVICE input from host_inputs[vid] to its compiled location and waits.  Must
+/* Copies every TN_DEVICE input from host_inputs[vid] (host memory, or GPU memory outside the
+ * device buffer) to its compiled location and waits.  Must
  * precede each tn_execute of a graph that has such inputs (their locations are reused once they
  * are dead).  host_inputs has one entry per taskgraph vertex; entries of non-inputs are ignored. */
 tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inputs);

@@ -628,7 +628,8 @@ tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inpu
     const MVertex& x = mg.v[m];
     if (x.kind != TN_MG_INPUT) continue;
     if (!host_inputs[m]) return fail(TN_ERR_INVALID, "no host buffer for device-resident input %lld", (long long)m);
-    TN_HIP(hipMemcpyAsync(ex->dbase + x.offset, host_inputs[m], x.bytes, hipMemcpyHostToDevice, s));
+    // the source may be host memory or (a tensor another kernel left there) GPU memory: let the runtime tell
+    TN_HIP(hipMemcpyAsync(ex->dbase + x.offset, host_inputs[m], x.bytes, hipMemcpyDefault, s));
   }
   TN_HIP(hipStreamSynchronize(s));
   return TN_OK;

@@ -218,7 +218,8 @@ class GpuSession:
                  kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
-                 materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False):
+                 materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
+                 device_inputs: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -261,6 +262,9 @@ class GpuSession:
             else:
                 np.copyto(dst.reshape(r1 - r0, c1 - c0), tile)
         say("input tiles cut into pinned memory")
+        if device_inputs:  # the inputs as another kernel would have left them: in GPU memory outside the capped buffer
+            self.in_slab = self.in_slab.to("cuda:0")
+            torch.cuda.synchronize()
         self.in_ptrs = [0] * self.n_task
         base = self.in_slab.data_ptr()
         for v, off in offs.items():

@@ -1,6 +1,7 @@
-"""Results that stay on the GPU: the output buffers handed to tn_execute lie in GPU memory outside
-the capped device buffer, so the store vertices are copies inside GPU memory.  The bits must be
-those of the run that stores to pinned host memory, with either copy engine, and the oracle's."""
+"""Results that stay on the GPU, and inputs that are already there: the buffers handed to
+tn_execute and tn_executor_place_inputs lie in GPU memory outside the capped device buffer, so
+the store and load vertices are copies inside GPU memory.  The bits must be those of the run that
+goes through pinned host memory, with either copy engine, and the oracle's."""
 import numpy as np
 import pytest
 
@@ -37,5 +38,30 @@ def test_outputs_in_gpu_memory_carry_the_same_bits(name, tol):
                     np.testing.assert_array_equal(out[k], want[k])
         y = (bf16_bits_to_f32(out["y"]) if cfg.dtype == "bf16" else out["y"]).astype(np.float64)
         assert R.rel_err(y, ref) < tol
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("resident", [False, True])
+def test_inputs_in_gpu_memory_carry_the_same_bits(resident):
+    """resident=False: every input is a load vertex reading GPU memory; True: the inputs are placed
+    by tn_executor_place_inputs from GPU memory."""
+    cfg = config("ragged_bf16").with_(weights_resident=resident, x_resident=resident)
+    full = make_llama_inputs(cfg, 0)
+    cap = 64 << 20 if resident else None  # resident inputs alone exceed the workload's own 40 % cap
+    s = H.GpuSession(cfg, full, cap=cap)
+    try:
+        want, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=64))
+    finally:
+        s.close()
+    s = H.GpuSession(cfg, full, cap=cap, device_inputs=True, device_outputs=True)
+    try:
+        assert s.in_slab.is_cuda and s.out_slab.is_cuda
+        assert (s.stats.n_load == 0) == resident
+        for engine in (B.TN_COPY_AUTO, B.TN_COPY_MEMCPY):
+            print(f"[case] ragged_bf16 inputs in GPU memory, resident {resident}, copy engine {engine}", flush=True)
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=3, copy_engine=engine))
+            assert rep.n_vertices == s.stats.n_vertices
+            np.testing.assert_array_equal(out["y"], want["y"])
     finally:
         s.close()
