@@ -86,7 +86,8 @@ class MemGraph:
 # 1. Algorithms 1 and 2, uniform slots
 # =============================================================================================
 
-def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_slots: int) -> MemGraph:
+def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_slots: int,
+                           sums: Sequence[int] = ()) -> MemGraph:
     """BuildMemgraph (Algorithm 1) with simMalloc / simMallocForceReld / simMallocOffld
     (Algorithm 2) for tensors that take exactly one slot each.
 
@@ -95,8 +96,17 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
     other vertex (Section 4's example counts two input tensors among GPU 1's seven tensors).
     Returned locations are (slot, 1).  Raises CapTooSmall when some vertex's inputs and output
     cannot be co-resident.
+
+    sums: taskgraph vertices that add up their operands by increments into a write-locked output
+    (Section 8, resources).  Such a vertex asks for no slot of its own when its turn comes: its
+    output is allocated and cleared ("zero") when its first operand has been produced, every
+    operand is added by an "increment" placed right after the operand's producer, and the vertex
+    itself becomes the "join" that takes the slot over.  The slot cannot be evicted while
+    increments are outstanding (it holds a partial sum that only they may touch).
     """
     n = len(preds)
+    sums = set(sums)
+    assert all(preds[s] and len(set(preds[s])) == len(preds[s]) for s in sums)
     pos = {v: i for i, v in enumerate(V)}
     assert len(pos) == n and all(pos[u] < pos[v] for v in range(n) for u in preds[v])
     mg = MemGraph(n_task=n, cap=n_slots)
@@ -108,7 +118,13 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
     # taskgraph consumer lists; `name[t]` is what tensor t is currently called (t itself or its
     # newest reload vertex): the "rename all instances" of simMallocOffld, applied only to the
     # accesses that have not been simulated yet ("future" accesses, Section 6 last paragraph).
-    cons_pos = [sorted(pos[w] for w in range(n) if v in preds[w]) for v in range(n)]
+    # (a sum consumes an operand right after the operand is produced, not at its own position)
+    cons_pos = [sorted(pos[w] for w in range(n) if v in preds[w] and w not in sums) for v in range(n)]
+    sums_of = [[w for w in sorted(sums, key=lambda x: pos[x]) if v in preds[w]] for v in range(n)]
+    acc: Dict[int, int] = {}   # sum -> its "zero" vertex
+    incs: Dict[int, List[int]] = {s: [] for s in sums}
+    open_acc: set = set()      # accumulators whose join has not run
+    post: List[List[int]] = [[] for _ in range(n)]  # what follows V[i] at once: clears, increments, their offloads
     name = list(range(n))
     readers: Dict[int, List[int]] = {v: [] for v in range(n)}  # per memgraph vertex with a slot: who read it so far
     owner: List[Optional[int]] = [None] * n_slots  # memgraph vertex now in the slot
@@ -117,6 +133,7 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
     added_by_malloc: Dict[int, List[Tuple[int, int, str]]] = {}
     pre: List[List[int]] = [[] for _ in range(n)]  # offload/reload vertices placed just before V[i]
     execHzn, allocHzn = 0, 0
+    sink: List[Optional[List[int]]] = [None]  # where evictions are noted instead of pre[execHzn], if set
 
     def add_edge(a, b, k):
         e = (a, b, k)
@@ -162,10 +179,13 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
         "run" yet holds no data, so it cannot be offloaded; Algorithm 1 does not say what to do
         when only such slots are left)."""
         nonlocal allocHzn
-        if allocHzn - 1 <= execHzn:
-            return False
-        allocHzn -= 1
-        v = V[allocHzn]
+        while True:
+            if allocHzn - 1 <= execHzn:
+                return False
+            allocHzn -= 1
+            v = V[allocHzn]
+            if v not in sums:  # a sum holds no reservation of its own: look further back
+                break
         owner[mg.loc[v][0]] = None
         mg.loc[v] = None
         for e in added_by_malloc.pop(v):
@@ -193,7 +213,7 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
         add_edge(vp, off, "data")
         add_edge(off, rel, "data")
         readers[vp].append(off)  # the offload reads the slot; it precedes v in the order
-        pre[execHzn].append(off)
+        (sink[0] if sink[0] is not None else pre[execHzn]).append(off)
         # simMalloc on the vacated slot adds offload -> v and (earlier consumers of v') -> v
         simFree(vp)
         name[t] = rel
@@ -211,11 +231,54 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
         return simMallocOffld(v, pinned)
 
     def produced(m: int) -> bool:
-        return m >= n or pos[m] < execHzn
+        return (m >= n and m not in open_acc) or (m < n and pos[m] < execHzn)
+
+    def increment(s: int, u: int, i_u: int):
+        """u = V[i_u] has just run: add it to the sum s, clearing s's output first if u is the first."""
+        sink[0] = post[i_u]
+        if s not in acc:
+            z = mg.add_vertex("zero", s, None, [])
+            readers[z] = []
+            acc[s] = z
+            open_acc.add(z)
+            if simMalloc(z) == -1:
+                simMallocOffld(z, {name[u]})
+            post[i_u].append(z)
+        z = acc[s]
+        i = mg.add_vertex("increment", s, None, [name[u], z])
+        add_edge(name[u], i, "data")
+        add_edge(z, i, "data")
+        readers[name[u]].append(i)
+        readers[z].append(i)
+        incs[s].append(i)
+        post[i_u].append(i)
+        sink[0] = None
 
     while execHzn < n:
-        if allocHzn < n and simMalloc(V[allocHzn]) != -1:
+        if allocHzn < n and V[allocHzn] in sums:
+            allocHzn += 1  # a sum's output is allocated with its first increment
+        elif allocHzn < n and simMalloc(V[allocHzn]) != -1:
             allocHzn += 1  # successfully allocated space for a future result
+        elif V[execHzn] in sums:
+            # the join: every operand has been added; the cleared-and-summed slot is now s's
+            s = V[execHzn]
+            z = acc[s]
+            slot = mg.loc[z][0]
+            mg.kind[s] = "join"
+            mg.loc[s] = mg.loc[z]
+            mg.operands[s] = [z]
+            for i in incs[s]:
+                add_edge(i, s, "data")
+            add_edge(z, s, "data")
+            readers[z].append(s)
+            readers[s] = readers[z]  # whoever takes the slot later waits for all of them and for s's readers
+            owner[slot] = s
+            open_acc.discard(z)
+            execHzn += 1
+            for w in sums_of[s]:
+                increment(w, s, execHzn - 1)
+            if sums_of[s] and next_use(s) > n:  # read by sums only, and they have taken it; a final result stays
+                simFree(s)
         elif allocHzn == execHzn:
             v = V[allocHzn]
             pinned = {name[u] for u in preds[v] if name[u] not in Evicted} | {v}
@@ -238,13 +301,16 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
                 mg.operands[v].append(name[u])
                 readers[name[u]].append(v)
             execHzn += 1
-            for u in dict.fromkeys(deps):
-                if next_use(u) > n:
+            for w in sums_of[v]:
+                increment(w, v, execHzn - 1)
+            for u in dict.fromkeys(list(deps) + ([v] if sums_of[v] else [])):
+                if next_use(u) > n and name[u] not in Evicted and mg.loc[name[u]] is not None \
+                        and owner[mg.loc[name[u]][0]] == name[u]:
                     simFree(name[u])
     for i, v in enumerate(V):
         offs = [m for m in pre[i] if mg.kind[m] == "offload"]
         rels = [m for m in pre[i] if mg.kind[m] == "reload"]
-        mg.order.extend(offs + rels + [v])
+        mg.order.extend(offs + rels + [v] + post[i])
     # a reload that was created at eviction time but never needed afterwards (the tensor is a
     # final result that now lives in host memory) has no location and never runs: leave it out
     if Evicted:
