@@ -195,11 +195,11 @@ def main():
     reps = timed(s, args.steps, args.warmup, opts)
     ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
     # unprofiled steps, to show what the event pairs around every launch cost
-    plain = timed(s, max(1, min(3, args.steps), args.steps // 4), 1 if args.steps > 1 else 0, B.tn_exec_opts(policy=policy, max_batch=args.max_batch,
-                                                                max_transfers=args.max_transfers,
-                                                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth,
-                                                                copy_engine=engine, copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
-                          transfer_depth=args.transfer_depth))
+    plain_opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, max_transfers=args.max_transfers,
+                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
+                                copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
+                                transfer_depth=args.transfer_depth)
+    plain = timed(s, max(1, min(3, args.steps), args.steps // 4), 1 if args.steps > 1 else 0, plain_opts)
     ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
     y = s.outputs(only=["y"])["y"]
     # the same step with the outputs stored to pinned host memory (the rate that includes the host link)
