@@ -15,6 +15,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <array>
 #include <chrono>
 #include <cmath>
 #include <cstring>
@@ -810,7 +811,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   std::deque<XGroup> xq[2];  // copy groups in flight, host to device and device to host
   int xring[2] = {0, 0};
   const int xdepth = std::max(1, std::min<int>(opt.transfer_depth > 0 ? opt.transfer_depth : 3, kMaxQueueDepth));
-  std::vector<int64_t> same, xverts;
+  std::vector<int64_t> same, xverts, sort_b;
+  std::vector<std::array<int64_t, 4>> sort_keys;
   std::vector<hipEvent_t> waited;
 
   while (completed < nv && status == TN_OK) {
@@ -1016,19 +1018,21 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       // other share operands both ways -- blocks of two A row panels by four B column panels --
       // instead of one A panel against every B panel of the launch.
       if (lead.cls == LC_GEMM_BF16_NT256 && same.size() >= 16) {
-        auto a0 = [&](int64_t m) { return mg.v[m].operands[0]; };
         auto b0 = [&](int64_t m) { return mg.v[m].operands[mg.v[m].p.nk]; };
-        std::vector<int64_t> bs;
+        std::vector<int64_t>& bs = sort_b;
+        bs.clear();
         for (int64_t m : same) bs.push_back(b0(m));
         std::sort(bs.begin(), bs.end());
         bs.erase(std::unique(bs.begin(), bs.end()), bs.end());
-        auto rank_b = [&](int64_t m) { return (int64_t)(std::lower_bound(bs.begin(), bs.end(), b0(m)) - bs.begin()); };
-        std::stable_sort(same.begin(), same.end(), [&](int64_t x, int64_t y) {
-          const int64_t bx = rank_b(x), by = rank_b(y);
-          if (bx / 4 != by / 4) return bx / 4 < by / 4;
-          if (a0(x) != a0(y)) return a0(x) < a0(y);
-          return bx < by;
-        });
+        sort_keys.clear();  // (block of four B panels, A panel, B panel, position in the policy's order)
+        for (size_t k = 0; k < same.size(); ++k) {
+          const int64_t rb = (int64_t)(std::lower_bound(bs.begin(), bs.end(), b0(same[k])) - bs.begin());
+          sort_keys.push_back({rb / 4, mg.v[same[k]].operands[0], rb, (int64_t)k});
+        }
+        std::sort(sort_keys.begin(), sort_keys.end());
+        sort_b.resize(same.size());
+        for (size_t k = 0; k < same.size(); ++k) sort_b[k] = same[(size_t)sort_keys[k][3]];
+        same.swap(sort_b);
       }
       batch.n = (int32_t)same.size();
       batch.base = (uint32_t)ex->info[same[0]].desc;
