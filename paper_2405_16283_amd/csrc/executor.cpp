@@ -837,7 +837,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
         return false;
       };
       hipError_t e = hipSuccess;
-      while (n_ready_x[dir] > 0 && (int)tv.size() < max_xfer && e == hipSuccess) {
+      // (copies inside GPU memory need no pipelining against the host link: one group takes all that fit)
+      while (n_ready_x[dir] > 0 && (int)tv.size() < (inside_gpu && use_copy_kernel ? kMaxCopies : max_xfer) && e == hipSuccess) {
         int64_t m;
         if (in_order) {  // the next transfer of this direction in the serial order, or none
           m = serial[serial_next[1 + dir]];
