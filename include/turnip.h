@@ -440,7 +440,8 @@ tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inpu
  * vertices (pinned memory recommended); host_outputs[i] receives marked output i.  An entry of
  * either array may instead point into memory of the executor's GPU outside its device buffer (a
  * result the next step consumes on the GPU, an input another kernel left there): that transfer is
- * then a copy inside GPU memory, on the same streams.  Synchronous:
+ * then a copy inside GPU memory, on the same streams; a buffer that overlaps the executor's device
+ * buffer is TN_ERR_INVALID.  Synchronous:
  * returns after every vertex has completed.  Makes no hipMalloc/hipFree/hipHostMalloc call.
  * opts NULL = FIFO, no delays; report may be NULL.  Calls on one executor must not overlap. */
 tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,

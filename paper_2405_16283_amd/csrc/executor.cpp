@@ -660,6 +660,12 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       return fail(TN_ERR_INVALID, "no host buffer for input %d", (int)x.src);
     if (x.kind == TN_MG_STORE && (!host_outputs || !host_outputs[x.output_index]))
       return fail(TN_ERR_INVALID, "no host buffer for output %d", x.output_index);
+    // a caller's buffer in GPU memory must not lie inside the buffer the memgraph's locations refer to
+    const char* cb = x.kind == TN_MG_LOAD ? (const char*)host_inputs[x.src]
+                     : x.kind == TN_MG_STORE ? (const char*)host_outputs[x.output_index] : nullptr;
+    if (cb && cb < ex->dbase + mg.cap && cb + x.bytes > ex->dbase)
+      return fail(TN_ERR_INVALID, "buffer of %s %d overlaps the executor's device buffer",
+                  x.kind == TN_MG_LOAD ? "input" : "output", x.kind == TN_MG_LOAD ? (int)x.src : x.output_index);
   }
   bool use_copy_kernel = opt.copy_engine != TN_COPY_MEMCPY;
   bool any_on_device = false;  // a caller's buffer lies in GPU memory: hipMemcpyAsync is told to find the direction itself

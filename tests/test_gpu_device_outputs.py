@@ -65,3 +65,20 @@ def test_inputs_in_gpu_memory_carry_the_same_bits(resident):
             np.testing.assert_array_equal(out["y"], want["y"])
     finally:
         s.close()
+
+
+def test_an_output_buffer_inside_the_device_buffer_is_refused():
+    """The host-side check turns the mistake into an error before anything is launched."""
+    cfg = config("c1")
+    full = make_llama_inputs(cfg, 0)
+    s = H.GpuSession(cfg, full, device_outputs=True)
+    try:
+        bad = list(s.out_ptrs)
+        bad[0] = s.dev.data_ptr() + 256  # inside the capped buffer the memgraph's locations refer to
+        s.place_inputs()
+        with pytest.raises(B.TurnipError, match="overlaps"):
+            B.tn_execute(s.ex, s.in_ptrs, B.ptr_array(bad), None)
+        out, rep = s.run()  # the executor is still usable
+        assert rep.n_vertices == s.stats.n_vertices
+    finally:
+        s.close()
