@@ -177,6 +177,15 @@ namespace {
     if (e_ != hipSuccess) return fail(TN_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
+// (query, key) pairs of an attention block that the causal mask lets through: the work its
+// products are accounted with (the masked part of a block on the diagonal is not work)
+double visible_pairs(int q_rows, int kv_rows, const tn_op_params& p) {
+  if (!p.causal) return (double)q_rows * kv_rows;
+  double n = 0;
+  for (int q = 0; q < q_rows; ++q) n += std::min<int64_t>(kv_rows, std::max<int64_t>(0, (int64_t)p.q_pos0 + q - p.k_pos0 + 1));
+  return n;
+}
+
 tn_status build_tables(tn_executor& ex) {
   const MemGraph& mg = *ex.mg;
   const int64_t nv = (int64_t)mg.v.size();
@@ -282,7 +291,7 @@ tn_status build_tables(tn_executor& ex) {
         vi.cls = (d.dtype == TN_BF16 && x.p.v_trans && tc % hd == 0 && tk % 64 == 0 && kv_rows % 8 == 0 && x.p.scale > 0.f)
                      ? LC_ATTN_BF16 : LC_ATTN_F32;
         vi.head_dim = (int16_t)hd;
-        vi.flops = 4.0 * q_rows * kv_rows * (double)(nc * tc);
+        vi.flops = 4.0 * visible_pairs(q_rows, kv_rows, x.p) * (double)(nc * tc);
         break;
       }
       case TN_OP_ATTN_COMBINE:
@@ -360,7 +369,7 @@ tn_status build_tables(tn_executor& ex) {
                   tk % 64 == 0 && q_rows % 8 == 0 && kv_rows % 8 == 0 && q_rows >= 8 && kv_rows >= 8)
                      ? (int8_t)(LC_ATTN_BWD_BF16 + x.p.mode) : (int8_t)LC_ATTN_BWD;
         vi.head_dim = (int16_t)hd;
-        vi.flops = (x.p.mode == 3 ? 4.0 : 6.0) * q_rows * kv_rows * (double)(nc * tc);
+        vi.flops = (x.p.mode == 3 ? 4.0 : 6.0) * visible_pairs(q_rows, kv_rows, x.p) * (double)(nc * tc);
         break;
       }
       default: return fail(TN_ERR_INVALID, "vertex %lld has an unknown kind", (long long)m);
