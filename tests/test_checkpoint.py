@@ -113,3 +113,24 @@ def test_checkpointed_memgraph_under_the_cap_is_correct_in_every_sampled_order(n
                 B.tn_memgraph_destroy(mg)
     finally:
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_forward_memgraph_with_a_quarter_of_the_cap_kept_free_is_correct(name):
+    """The compile options of the benchmark's run under 40 % of the peak (evictions free a quarter
+    of the cap beyond their need, next fit, bounded run-ahead), in the tiler's and in the
+    level-by-level serial order."""
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg))
+    try:
+        cap = H.cap_for(cfg, tg)
+        for order in (None, H.level_major_order(tg)):
+            mg = B.tn_compile(tg, order, cap, H.bench_compile_opts(cap, False, pressed=True))
+            try:
+                st = B.tn_memgraph_stats(mg)
+                assert st.high_water <= cap and st.n_offload + st.n_drop > 0
+                check_all(task_preds(tg), oracle_memgraph(mg), n_random=12, seed=7)
+            finally:
+                B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
