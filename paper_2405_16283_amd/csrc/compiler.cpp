@@ -412,9 +412,6 @@ struct Compiler {
         }
       }
       const bool shortcut = found;
-#ifdef TN_COMPILE_DEBUG
-      { static long n_short = 0, n_full = 0; (shortcut ? n_short : n_full)++; if (((n_short + n_full) % 5000) == 0) fprintf(stderr, "shortcut %ld full %ld size %llu by_use %zu blocks %zu\n", n_short, n_full, (unsigned long long)size, by_use.size(), blocks.size()); }
-#endif
       for (auto i = blocks.begin(); i != blocks.end() && !shortcut; ++i) {
         uint64_t total = 0, ev_bytes = 0;
         int64_t min_use = LLONG_MAX;
