@@ -86,3 +86,26 @@ def test_checkpointed_step_gives_the_same_bits_as_the_saved_activation_step(name
                 assert R.rel_err(_f64(cfg, out[f"d{k}.{l}"]), g_ref[f"{k}.{l}"]) < tol
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("name,tol,checkpoint", [("c1", 1e-4, False), ("c1", 1e-4, True), ("ragged_bf16", 4e-2, True)])
+def test_fine_tuning_step_with_k_split_projections(name, tol, checkpoint):
+    """The tiler's options together: projections of the forward pass as partial products joined by
+    sums (two per sum, so the order of the increments cannot matter), with and without
+    checkpointing; gradients against the oracle, a second dispatch order bit for bit."""
+    cfg, s, y_ref, g_ref = _case(name, 0.02, k_split=2, checkpoint=checkpoint)
+    try:
+        print(f"[case] {name} k_split 2 checkpoint {checkpoint}: {s.stats.n_increment} increments, {s.stats.n_offload} offloads", flush=True)
+        assert s.stats.n_increment > 0 and s.stats.n_offload > 0
+        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=1, max_delay_us=50))
+        assert rep.n_vertices == s.stats.n_vertices
+        assert R.rel_err(_f64(cfg, out["y"]), y_ref) < tol
+        assert R.rel_err(_f64(cfg, out["dx"]), g_ref["x"]) < tol
+        for l in range(cfg.layers):
+            for k in ("aq", "bq", "av", "bv"):
+                assert R.rel_err(_f64(cfg, out[f"d{k}.{l}"]), g_ref[f"{k}.{l}"]) < tol
+        o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
+        for k in out:
+            np.testing.assert_array_equal(o2[k], out[k])
+    finally:
+        s.close()
