@@ -81,3 +81,27 @@ def test_c2_shape_with_materialized_scores():
         np.testing.assert_array_equal(o2["y"], out["y"])
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_materialized_scores_together_with_k_split_projections(name):
+    """Both tiler options at once (two partial products per sum: the order of the increments cannot
+    matter): the oracle's result within the tolerance, five dispatch orders bit for bit."""
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 0)
+    tg = T.build_llama_taskgraph(cfg, k_split=2, materialize_scores=True)
+    y_oracle = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, R.widen(cfg, full))), cfg.tokens, cfg.d_model)
+    s = H.GpuSession(cfg, full, materialize_scores=True, k_split=2)
+    try:
+        print(f"[case] {name} materialised scores + k_split 2: {s.stats.n_increment} increments, {s.stats.n_offload} offloads", flush=True)
+        assert s.stats.n_increment > 0 and s.stats.n_offload > 0
+        ref, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
+        assert rep.n_vertices == s.stats.n_vertices
+        assert R.rel_err(_f64(cfg, ref["y"]), y_oracle) < TOL[cfg.dtype]
+        for seed in range(5):
+            print(f"[case] {name} materialised + k_split order_seed {seed}", flush=True)
+            out, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, max_delay_us=(0, 100)[seed % 2],
+                                          max_batch=(0, 2)[seed % 2]))
+            np.testing.assert_array_equal(out["y"], ref["y"])
+    finally:
+        s.close()

@@ -114,3 +114,31 @@ def test_materialized_memgraph_under_the_cap_is_correct_in_every_sampled_order(n
     finally:
         B.tn_memgraph_destroy(mg)
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_materialized_scores_together_with_k_split_projections(name):
+    """Both tiler options at once: the library's taskgraph evaluated by the oracle equals the
+    oracle's own, and its memgraph under the cap passes the checks."""
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, weights_transposed=False, v_transposed=False, materialize_scores=True,
+                                                k_split=2))
+    try:
+        otg = oracle_taskgraph(tg)
+        mine = T.build_llama_taskgraph(cfg, k_split=2, materialize_scores=True)
+        for k in ("gemm", "sum", "softmax_stat", "softmax_apply"):
+            assert otg.kind.count(k) == mine.kind.count(k) > 0
+        y_lib = T.assemble_outputs(otg, T.evaluate(otg, T.cut_inputs(otg, w)), cfg.tokens, cfg.d_model)
+        y_own = T.assemble_outputs(mine, T.evaluate(mine, T.cut_inputs(mine, w)), cfg.tokens, cfg.d_model)
+        np.testing.assert_array_equal(y_lib, y_own)
+        cap = H.cap_for(cfg, tg)
+        mg = B.tn_compile(tg, None, cap)
+        try:
+            st = B.tn_memgraph_stats(mg)
+            assert st.n_increment > 0 and st.n_offload > 0 and st.high_water <= cap
+            check_all(task_preds(tg), oracle_memgraph(mg), n_random=8, seed=2)
+        finally:
+            B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
