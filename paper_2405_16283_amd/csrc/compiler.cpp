@@ -488,24 +488,50 @@ struct Compiler {
     return p;
   }
 
+  // brings evicted tensor u back: a reload of what its offload holds (a fresh load after a drop),
+  // placed with `pinned` kept where it is; the new vertex joins the transfers of the current step
+  tn_status bring_back(tn_vid u, const std::vector<int64_t>& pinned) {
+    const int64_t ev = evicted_by[u];
+    const int64_t r = new_vertex(mg.v[ev].kind == TN_MG_DROP ? TN_MG_LOAD : TN_MG_RELOAD, u);
+    mg.v[r].operands = {ev};
+    add_edge(ev, r, TN_EDGE_DATA, false);
+    tn_status s = sim_malloc_offld(r, pinned);
+    if (s != TN_OK) return s;
+    name[u] = r;
+    use_insert(u);
+    evicted_by[u] = -1;
+    step_pre.push_back(r);
+    return TN_OK;
+  }
+
   // tensor u, just produced, is added to the output of sum vertex s
   tn_status increment(tn_vid s, tn_vid u) {
-    const std::vector<int64_t> pinned{name[u]};
     // the output is allocated like any other, ahead of the execution if memory allows; if the
     // run-ahead has not come this far, now is the latest moment (the entries between are outputs
     // of other sums that u is the first operand of)
     while (allocHzn <= apos_acc[s]) {
-      tn_status st = sim_malloc_offld(entry_vertex(allocHzn), pinned);
+      tn_status st = sim_malloc_offld(entry_vertex(allocHzn), name[u] >= 0 ? std::vector<int64_t>{name[u]} : std::vector<int64_t>{});
       if (st != TN_OK) return st;
       ++allocHzn;
     }
+    // Emptying the memory against fragmentation spares nothing that holds data, u included: it
+    // comes back next to the output it is added to (outputs of unfinished sums never move).  If the
+    // two do not fit together, the cap is too small for this sum.
+    if (name[u] < 0) {
+      tn_status st = bring_back(u, {});
+      if (st != TN_OK)
+        return st != TN_ERR_CAP_TOO_SMALL ? st : fail(TN_ERR_CAP_TOO_SMALL,
+                    "adding vertex %d to the sum %d needs the two (%llu bytes each) co-resident next to the outputs of "
+                    "unfinished sums; cap %llu is too small", (int)u, (int)s,
+                    (unsigned long long)aligned(tensor_bytes(tg.v[u].desc)), (unsigned long long)cap);
+    }
+    for (int64_t o : step_pre) mg.order.push_back(o);  // what made room comes first
+    step_pre.clear();
     if (!zero_placed[s]) {
       const int64_t z0 = acc_of[s];
       zero_placed[s] = 1;
       if (counted_ahead[z0]) lookahead_bytes -= vbytes(z0);
       counted_ahead[z0] = 0;
-      for (int64_t o : step_pre) mg.order.push_back(o);  // what made room for it comes first
-      step_pre.clear();
       mg.order.push_back(z0);
     }
     const int64_t z = acc_of[s];
@@ -543,17 +569,9 @@ struct Compiler {
       again = false;
       for (tn_vid u : tv.in) {
         if (name[u] >= 0) continue;
-        const int64_t ev = evicted_by[u];
-        const int64_t r = new_vertex(mg.v[ev].kind == TN_MG_DROP ? TN_MG_LOAD : TN_MG_RELOAD, u);
-        mg.v[r].operands = {ev};
-        add_edge(ev, r, TN_EDGE_DATA, false);
         const int64_t compactions = mg.stats.n_compactions;
-        tn_status s = sim_malloc_offld(r, pinned_for(v));
+        tn_status s = bring_back(u, pinned_for(v));
         if (s != TN_OK) return s;
-        name[u] = r;
-        use_insert(u);
-        evicted_by[u] = -1;
-        step_pre.push_back(r);
         if (mg.stats.n_compactions != compactions) again = true;
       }
     }
