@@ -416,14 +416,19 @@ typedef struct {
   double gemm_flops, attn_flops;
   double ewise_bytes;
   double kernel_busy_ms; /* union of kernel intervals over all compute streams */
-  double idle_frac;      /* 1 - kernel_busy_ms / span of device activity */
+  double idle_frac;      /* 1 - kernel_busy_ms / (first kernel start .. last kernel end): gaps between kernels only */
+  double idle_frac_wall; /* 1 - kernel_busy_ms / wall_ms: the share of the run during which no kernel ran
+                            (Section 5: the GPU "sits idle"), leading loads and trailing stores included */
+  int64_t untimed_launches; /* profile != 0: launches beyond the executor's pool of timing events (65536 per
+                               run), left out of the *_ms fields */
 } tn_exec_report;
 
 /* device_base: device memory of at least the memgraph's cap bytes, 256-byte aligned; borrowed
  * for the executor's lifetime.  pinned_arena: pinned host memory for offloaded tensors, or NULL
  * to let the library allocate arena_bytes itself (arena_bytes 0 = the memgraph's safe bound).
  * Streams are hipStream_t values created by the caller at default priority; n_compute >= 1.
- * Creation allocates the descriptor tables the kernels read; nothing is allocated later. */
+ * Creation allocates the operand tables the kernels read (GPU memory plus a pinned host image)
+ * and every event a run can need; nothing is allocated or created later. */
 tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t device_bytes,
                              void* pinned_arena, uint64_t arena_bytes, void* const* compute_streams,
                              int32_t n_compute, void* h2d_stream, void* d2h_stream,

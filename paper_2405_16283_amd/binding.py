@@ -108,7 +108,8 @@ class tn_exec_report(C.Structure):
                 ("h2d_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("gemm_launches", C.c_int64), ("attn_launches", C.c_int64), ("ewise_launches", C.c_int64),
                 ("gemm_flops", C.c_double), ("attn_flops", C.c_double), ("ewise_bytes", C.c_double),
-                ("kernel_busy_ms", C.c_double), ("idle_frac", C.c_double)]
+                ("kernel_busy_ms", C.c_double), ("idle_frac", C.c_double), ("idle_frac_wall", C.c_double),
+                ("untimed_launches", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

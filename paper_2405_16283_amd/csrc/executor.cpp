@@ -32,6 +32,7 @@ namespace {
 
 using Clock = std::chrono::steady_clock;
 constexpr int kMaxQueueDepth = 8;  // groups in flight per compute stream, at most
+constexpr int64_t kMaxProfEvents = (1 << 17) + 1;  // timing events per executor: 65536 timed launches per run
 
 struct VInfo {
   int8_t cls = -1;  // LaunchClass, or -1 for non-kernel vertices
@@ -143,11 +144,12 @@ struct tn_executor {
   hipEvent_t xevents[2][kMaxQueueDepth] = {};    // per copy direction: ring of completion events
   std::vector<std::deque<Group>> cqueue;         // per compute stream: groups in flight, oldest first
   std::vector<int64_t> pred_start, pred;         // CSR of predecessors
-  // device tables
-  OpDesc* d_descs = nullptr;
-  void** d_ptrs = nullptr;
-  int32_t* d_aux = nullptr;
-  double* d_theta = nullptr;
+  // The operand tables the kernels read, as one image: descriptors, operand addresses, auxiliary
+  // integers, rotary angles, each section 256-byte aligned.  h_image is pinned host memory (the
+  // source of every upload), d_image the copy in GPU memory that tn_execute's kernels read.
+  char* h_image = nullptr;
+  char* d_image = nullptr;
+  size_t image_bytes = 0, image_off[4] = {0, 0, 0, 0};
   DeviceTables tables{};
   std::vector<VInfo> info;
   // dependency structure (CSR of successors)
@@ -184,6 +186,12 @@ double visible_pairs(int q_rows, int kv_rows, const tn_op_params& p) {
   double n = 0;
   for (int q = 0; q < q_rows; ++q) n += std::min<int64_t>(kv_rows, std::max<int64_t>(0, (int64_t)p.q_pos0 + q - p.k_pos0 + 1));
   return n;
+}
+
+// the table pointers for a copy of the image that starts at `base`
+DeviceTables tables_at(const tn_executor& ex, const char* base) {
+  return {(const OpDesc*)(base + ex.image_off[0]), (void* const*)(base + ex.image_off[1]),
+          (const int32_t*)(base + ex.image_off[2]), (const double*)(base + ex.image_off[3])};
 }
 
 tn_status build_tables(tn_executor& ex) {
@@ -379,18 +387,21 @@ tn_status build_tables(tn_executor& ex) {
     vi.desc = (int32_t)descs.size();
     descs.push_back(d);
   }
-  auto upload = [&](const void* src, size_t bytes, void** dst) -> tn_status {
-    if (bytes == 0) bytes = 16;
-    TN_HIP(hipMalloc(dst, bytes));
-    if (src) TN_HIP(hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice));
-    return TN_OK;
-  };
-  tn_status s;
-  if ((s = upload(descs.empty() ? nullptr : descs.data(), descs.size() * sizeof(OpDesc), (void**)&ex.d_descs)) != TN_OK) return s;
-  if ((s = upload(ptrs.empty() ? nullptr : ptrs.data(), ptrs.size() * sizeof(void*), (void**)&ex.d_ptrs)) != TN_OK) return s;
-  if ((s = upload(aux.empty() ? nullptr : aux.data(), aux.size() * 4, (void**)&ex.d_aux)) != TN_OK) return s;
-  if ((s = upload(theta.empty() ? nullptr : theta.data(), theta.size() * 8, (void**)&ex.d_theta)) != TN_OK) return s;
-  ex.tables = {ex.d_descs, ex.d_ptrs, ex.d_aux, ex.d_theta};
+  const size_t sizes[4] = {descs.size() * sizeof(OpDesc), ptrs.size() * sizeof(void*), aux.size() * 4, theta.size() * 8};
+  const void* src[4] = {descs.data(), ptrs.data(), aux.data(), theta.data()};
+  size_t at = 0;
+  for (int k = 0; k < 4; ++k) {
+    ex.image_off[k] = at;
+    at += (std::max<size_t>(sizes[k], 16) + 255) / 256 * 256;
+  }
+  ex.image_bytes = at;
+  TN_HIP(hipHostMalloc((void**)&ex.h_image, at, hipHostMallocDefault));
+  memset(ex.h_image, 0, at);
+  for (int k = 0; k < 4; ++k)
+    if (sizes[k]) memcpy(ex.h_image + ex.image_off[k], src[k], sizes[k]);
+  TN_HIP(hipMalloc((void**)&ex.d_image, at));
+  TN_HIP(hipMemcpy(ex.d_image, ex.h_image, at, hipMemcpyHostToDevice));
+  ex.tables = tables_at(ex, ex.d_image);
   return TN_OK;
 }
 
@@ -581,6 +592,21 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
       if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)));
     }
   ex->arena_off.assign(nv, -1);
+  {
+    // Timing events for profiled runs: a pair per launch, and a launch carries at least one kernel
+    // or transfer vertex.  Made here so that a run creates nothing (Section 5: no allocation calls
+    // while the memgraph executes).
+    int64_t n_work = 0;
+    for (const auto& x : mg->v) n_work += x.kind != TN_MG_INPUT && x.kind != TN_MG_DROP && x.kind != TN_MG_JOIN;
+    const int64_t pool = std::min<int64_t>(2 * n_work + 1, kMaxProfEvents);
+    ex->prof_events.reserve(pool);
+    for (int64_t k = 0; k < pool; ++k) {
+      hipEvent_t ev;
+      hipError_t e = hipEventCreate(&ev);
+      if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e)));
+      ex->prof_events.push_back(ev);
+    }
+  }
   tn_status s = build_tables(*ex);
   if (s != TN_OK) return bail(s);
   {
@@ -621,10 +647,8 @@ void tn_executor_destroy(tn_executor* ex) {
   for (auto& ring : ex->xevents)
     for (auto e : ring)
       if (e) (void)hipEventDestroy(e);
-  if (ex->d_descs) (void)hipFree(ex->d_descs);
-  if (ex->d_ptrs) (void)hipFree(ex->d_ptrs);
-  if (ex->d_aux) (void)hipFree(ex->d_aux);
-  if (ex->d_theta) (void)hipFree(ex->d_theta);
+  if (ex->d_image) (void)hipFree(ex->d_image);
+  if (ex->h_image) (void)hipHostFree(ex->h_image);
   if (ex->own_arena && ex->arena) (void)hipHostFree(ex->arena);
   delete ex;
 }
@@ -645,10 +669,9 @@ tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inpu
   return TN_OK;
 }
 
-tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
-                     const tn_exec_opts* opts_in, tn_exec_report* report) {
-  if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
-  if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
+// The engine behind tn_execute: `tables` says where the kernels of this run find their operand tables.
+static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                              const tn_exec_opts* opts_in, tn_exec_report* report, const DeviceTables& tables) {
   const MemGraph& mg = *ex->mg;
   const int64_t nv = (int64_t)mg.v.size();
   tn_exec_opts opt{};
@@ -745,13 +768,15 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   hipEvent_t prof_base = nullptr;
   tn_status status = TN_OK;
 
-  auto prof_event = [&](hipEvent_t* e) -> bool {
-    if (prof_used == ex->prof_events.size()) {
-      hipEvent_t ne;
-      if (hipEventCreate(&ne) != hipSuccess) return false;
-      ex->prof_events.push_back(ne);
+  // timing events come from the pool made at creation; a run with more launches than the pool
+  // covers leaves the rest untimed (counted in the report) rather than create events while it runs
+  auto prof_pair = [&](int* first) -> bool {
+    if (prof_used + 2 > ex->prof_events.size()) {
+      ++rep.untimed_launches;
+      return false;
     }
-    *e = ex->prof_events[prof_used++];
+    *first = (int)prof_used;
+    prof_used += 2;
     return true;
   };
 
@@ -816,7 +841,7 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   };
 
   if (opt.profile) {
-    if (!prof_event(&prof_base) || hipEventRecord(prof_base, ex->slots[0].stream) != hipSuccess)
+    if (ex->prof_events.empty() || hipEventRecord(prof_base = ex->prof_events[prof_used++], ex->slots[0].stream) != hipSuccess)
       return fail(TN_ERR_HIP, "cannot record the profiling base event");
     ex->prof_family.clear();
   }
@@ -918,12 +943,9 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       XGroup xg;
       xg.done = ex->xevents[dir][xring[dir]];
       xring[dir] = (xring[dir] + 1) % kMaxQueueDepth;
-      if (e == hipSuccess && opt.profile) {
-        hipEvent_t a, b2;
-        // the start stamp goes after whatever the stream still carries; the group's copies are
-        // queued behind it
-        if (prof_event(&a) && prof_event(&b2)) xg.prof = (int)prof_used - 2;
-      }
+      // the start stamp goes after whatever the stream still carries; the group's copies are
+      // queued behind it
+      if (e == hipSuccess && opt.profile) (void)prof_pair(&xg.prof);
       if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
       if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, inside_gpu ? kDeviceCopyWorkgroups : opt.copy_workgroups, sl.stream);
       if (xg.prof >= 0) xg.done = ex->prof_events[xg.prof + 1];
@@ -1079,14 +1101,8 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       grp.family = family_of(lead.cls);
       grp.done = ex->cevents[si][ring_next[si]];
       ring_next[si] = (ring_next[si] + 1) % kMaxQueueDepth;
-      if (e == hipSuccess && opt.profile) {
-        hipEvent_t a, b;
-        if (prof_event(&a) && prof_event(&b)) {
-          grp.prof = (int)prof_used - 2;
-          e = hipEventRecord(a, stream);
-        }
-      }
-      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, ex->tables, batch, max_blocks, stream);
+      if (e == hipSuccess && opt.profile && prof_pair(&grp.prof)) e = hipEventRecord(ex->prof_events[grp.prof], stream);
+      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, tables, batch, max_blocks, stream);
       // a timed launch completes with its second stamp: one event record less between two kernels
       if (grp.prof >= 0) grp.done = ex->prof_events[grp.prof + 1];
       if (e == hipSuccess) e = hipEventRecord(grp.done, stream);
@@ -1210,10 +1226,18 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
       rep.kernel_busy_ms += hi - lo;
       const double span = std::max<double>(last - first, 1e-9);
       rep.idle_frac = 1.0 - rep.kernel_busy_ms / span;
+      rep.idle_frac_wall = std::max(0.0, 1.0 - rep.kernel_busy_ms / std::max(rep.wall_ms, 1e-9));
     }
   }
   if (report) *report = rep;
   return status;
+}
+
+tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                     const tn_exec_opts* opts, tn_exec_report* report) {
+  if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
+  if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
+  return run_memgraph(ex, host_inputs, host_outputs, opts, report, ex->tables);
 }
 
 int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap) {
