@@ -1,18 +1,29 @@
 """Benchmark of the hot path: build taskgraph -> compile memgraph under the GPU-memory cap ->
 event-driven execution on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--subs LIST|none]
 
-One "step" is one execution of the whole memgraph of the workload (all vertex kinds, all
-transfers the memgraph contains) on one batch of seeded synthetic input; inputs that the
-workload declares device-resident are placed in HBM before the timed region.  Prints ONE JSON
-line: tokens/s under the cap, plus the roofline of the dominant kernel (bf16 MFMA tile GEMM),
-measured with HIP events on the streams the kernels run on, and the CPU oracle timed on a
-bounded sample as a baseline.
+One "step" is one execution of the whole memgraph of a workload (all vertex kinds, all transfers
+the memgraph contains) on one batch of seeded synthetic input; inputs that a workload declares
+device-resident are placed in HBM before the timed region, everything else crosses the host link
+inside it.  Prints ONE JSON line.
+
+Without --workload the line's `value` is the largest configuration that fits one GPU, c4 (80
+layers of the 65B shape, 48 GB cap, about 130 GB of weights streamed from pinned host memory per
+step), timed for exactly K steps after W warm-up steps, and the line carries, as sub-records with
+a few steps each: c2 (one 7B layer, everything in HBM: the clean measurement of the tile kernels
+against the MFMA roofline), c2 under 40 % of its uncapped peak with all inputs on the host (the
+offload path under pressure), c3 (32 layers, 16 GB cap) and c5 (fine-tuning step, 32 GB cap).
+Every record reports tokens/s, the memgraph's offload/reload/load counts, host-link GB/s per
+direction against the link's peak (64 GB/s per direction by specification, and the rate measured on
+this box with one large pinned copy), the tile GEMM and attention kernels in TFLOP/s against the
+dense bf16 MFMA peak (HIP event pairs on the launching streams), and the share of wall time with no
+kernel running.  The CPU oracle is timed on a bounded sample of the headline workload as a baseline.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -23,7 +34,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA (256 CUs x 4096 flop/clk x 2.4 GHz)
 PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
 HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
+
+# steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)
+SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
 
 
 def cpu_baseline(cfg, full, budget_tokens):
@@ -50,12 +65,34 @@ def cpu_baseline(cfg, full, budget_tokens):
                       f"all {cfg.layers} layer(s), {dt:.1f} s"}, y
 
 
+def measure_link(torch, mib=256, reps=3):
+    """GB/s of one large copy between pinned host memory and HBM, each direction on its own."""
+    n = mib << 20
+    h = torch.empty(n, dtype=torch.uint8).pin_memory()
+    d = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    out = {}
+    for name, (dst, src) in (("h2d", (d, h)), ("d2h", (h, d))):
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        out[name] = reps * n / (time.perf_counter() - t) / 1e9
+    del h, d
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="",
+                    help="time this workload alone (c1..c5, c2_capped40, or a parity shape); default: c4 as the "
+                         "headline plus the sub-records of --subs")
+    ap.add_argument("--subs", default="",
+                    help="comma-separated sub-records, or 'none'; default c2,c2_capped40,c3,c5 when --workload is not given")
     ap.add_argument("--streams", type=int, default=0, help="compute streams; default: harness.BENCH_COMPUTE_STREAMS")
     ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
@@ -63,14 +100,13 @@ def main():
     ap.add_argument("--queue-depth", type=int, default=3)
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order", "in_order"])
     ap.add_argument("--max-delay-us", type=int, default=0, help="inject a pseudo-random delay of up to this many microseconds into every transfer group")
-    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample; 0 = skip")
-    ap.add_argument("--capped", action="store_true",
-                    help="add a run with everything streamed from the host under 40 %% of the uncapped peak (offload path)")
-    ap.add_argument("--no-capped", action="store_true", help=argparse.SUPPRESS)  # the default now
+    ap.add_argument("--cpu-tokens", type=int, default=-1,
+                    help="tokens of the CPU-oracle sample; 0 = skip; default: 4096 for one layer, 64 for deep workloads")
+    ap.add_argument("--capped", action="store_true", help=argparse.SUPPRESS)  # now a sub-record: --subs c2_capped40
     ap.add_argument("--order", default="tiler", choices=["tiler", "level"],
                     help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
     ap.add_argument("--evict-ahead-mb", type=int, default=-1,
-                    help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/32 of the cap")
+                    help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/8 of the cap")
     ap.add_argument("--checkpoint", action="store_true",
                     help="fine-tuning step with activation checkpointing: the reverse pass of a layer forms that "
                          "layer's forward tensors again instead of reading saved ones")
@@ -87,7 +123,7 @@ def main():
                     help="cut every projection along K into this many partial products joined by a sum vertex (increments "
                          "into a write-locked output); 0 = the whole K range inside one GEMM vertex")
     ap.add_argument("--lookahead-mb", type=int, default=-1,
-                    help="compile option max_lookahead_bytes in MiB; default unbounded, for the fine-tuning step a quarter of the cap")
+                    help="compile option max_lookahead_bytes in MiB; default unbounded, for the fine-tuning step half of the cap")
     ap.add_argument("--next-fit", type=int, default=-1, help="compile option next_fit; default 0, for the fine-tuning step 1")
     ap.add_argument("--cap-gb", type=float, default=0.0, help="GPU-memory cap in GB instead of the workload's own")
     ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
@@ -116,29 +152,25 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     t_begin = time.perf_counter()
-    cfg = config(args.workload)
-    if args.layers > 0:
-        cfg = cfg.with_(layers=args.layers)
-    if args.cap_gb > 0:
-        cfg = cfg.with_(cap_bytes=int(args.cap_gb * 1e9), cap_frac=0.0)
-    if args.materialize_scores:
-        cfg = cfg.with_(tile=cfg.head_dim)
-    if args.host_inputs:
-        cfg = cfg.with_(weights_resident=False, x_resident=False)
-    train = bool(args.train) if args.train >= 0 else cfg.name == "c5"
-    t0 = time.perf_counter()
-    distinct = args.distinct_layers if args.distinct_layers >= 0 else (0 if cfg.layers <= 8 else 4)
-    kv_outputs = bool(args.kv_outputs) if args.kv_outputs >= 0 else (cfg.layers > 1 and not cfg.weights_resident)
-    full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
-    if train:
-        kv_outputs = False
-        full.update(make_lora_inputs(cfg, 0, rank=16, b_std=0.0))
-    t_gen = time.perf_counter() - t0
 
     def note(msg):
         print(f"[bench {time.perf_counter() - t_begin:7.1f}s] {msg}", file=sys.stderr, flush=True)
 
-    def timed(session, steps, warmup, opts):
+    link = measure_link(torch)
+    note(f"host link measured with one 256 MiB pinned copy per direction: {link['h2d']:.1f} GB/s to the GPU, "
+         f"{link['d2h']:.1f} GB/s back")
+
+    policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
+              "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
+    engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
+
+    def exec_opts(profile):
+        return B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=profile, max_transfers=args.max_transfers,
+                              max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
+                              copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
+                              transfer_depth=args.transfer_depth)
+
+    def timed(session, steps, warmup, opts, label):
         reps = []
         for i in range(warmup + steps):
             session.place_inputs()  # device-resident inputs go to HBM outside the timed region
@@ -147,164 +179,230 @@ def main():
             rep = session.execute(opts)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t
-            note(f"step {i + 1} of {warmup + steps}: {dt * 1e3:.1f} ms")
+            note(f"{label}: step {i + 1} of {warmup + steps}: {dt * 1e3:.1f} ms")
             if i >= warmup:
                 reps.append((dt, rep))
         return reps
 
-    t0 = time.perf_counter()
-    # where the marked outputs go: GPU memory when the step also starts there, else pinned host memory
-    device_outputs = (cfg.weights_resident and cfg.x_resident) if args.host_outputs < 0 else not args.host_outputs
+    def run_case(name, steps, warmup, headline):
+        """One workload: inputs, taskgraph, memgraph, executor, `warmup` untimed and `steps` timed
+        steps.  Returns (record, cfg, full inputs, y)."""
+        capped40 = name == "c2_capped40"
+        cfg = config("c2" if capped40 else name)
+        pressed = level = False
+        if capped40:
+            # everything streamed from the host, the cap at 40 % of the uncapped peak; level-by-level
+            # serial order, so that every weight tile is loaded once per step
+            cfg = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
+            pressed = level = True
+        if headline:  # the shape-changing flags apply to the workload named on the command line only
+            if args.layers > 0:
+                cfg = cfg.with_(layers=args.layers)
+            if args.cap_gb > 0:
+                cfg = cfg.with_(cap_bytes=int(args.cap_gb * 1e9), cap_frac=0.0)
+            if args.materialize_scores:
+                cfg = cfg.with_(tile=cfg.head_dim)
+            if args.host_inputs:
+                cfg = cfg.with_(weights_resident=False, x_resident=False)
+            level = level or args.order == "level"
+        materialize = headline and args.materialize_scores
+        checkpoint = headline and args.checkpoint
+        k_split = args.k_split if headline else 0
+        train = bool(args.train) if (headline and args.train >= 0) else cfg.name == "c5"
+        t0 = time.perf_counter()
+        distinct = args.distinct_layers if (headline and args.distinct_layers >= 0) else (0 if cfg.layers <= 8 else 4)
+        kv_outputs = (bool(args.kv_outputs) if (headline and args.kv_outputs >= 0)
+                      else (cfg.layers > 1 and not cfg.weights_resident))
+        full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
+        if train:
+            kv_outputs = False
+            full.update(make_lora_inputs(cfg, 0, rank=16, b_std=0.0))
+        t_gen = time.perf_counter() - t0
+        note(f"{name}: inputs generated")
+        # where the marked outputs go: GPU memory when the step also starts there, else pinned host memory
+        device_outputs = ((cfg.weights_resident and cfg.x_resident) if (not headline or args.host_outputs < 0)
+                          else not args.host_outputs)
 
-    def session(c, pressed=False, device_outputs=False, level=False):
-        order = None
-        if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
-            tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train,
-                                                        k_split=args.k_split, materialize_scores=args.materialize_scores,
-                                                        checkpoint=args.checkpoint))
-            c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
-            B.tn_taskgraph_destroy(tg)
-        if args.order == "level" or level:
-            tg = B.tn_build_llama(H.llama_config_struct(c, kv_outputs, lora_rank=16 if train else 0, train=train,
-                                                        k_split=args.k_split, materialize_scores=args.materialize_scores,
-                                                        checkpoint=args.checkpoint))
-            order = H.level_major_order(tg)
-            B.tn_taskgraph_destroy(tg)
-        cap = c.cap_bytes or 0  # only the fine-tuning workload uses it, and that one states its cap in bytes
-        copts = H.bench_compile_opts(cap, train,
-                                     lookahead=args.lookahead_mb << 20 if args.lookahead_mb >= 0 else None,
-                                     evict_ahead=args.evict_ahead_mb << 20 if args.evict_ahead_mb >= 0 else None,
-                                     next_fit=args.next_fit if args.next_fit >= 0 else None, pressed=pressed)
-        return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
-                            lora_rank=16 if train else 0, train=train, progress=note, k_split=args.k_split,
-                            materialize_scores=args.materialize_scores, checkpoint=args.checkpoint,
-                            device_outputs=device_outputs)
+        def session(c, device_outputs):
+            order = None
+            struct = lambda cc: H.llama_config_struct(cc, kv_outputs, lora_rank=16 if train else 0, train=train,
+                                                      k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint)
+            if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
+                tg = B.tn_build_llama(struct(c))
+                c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
+                B.tn_taskgraph_destroy(tg)
+            if level:
+                tg = B.tn_build_llama(struct(c))
+                order = B.tn_taskgraph_level_order(tg)
+                B.tn_taskgraph_destroy(tg)
+            cap = c.cap_bytes or 0
+            hl = headline
+            copts = H.bench_compile_opts(cap, train,
+                                         lookahead=args.lookahead_mb << 20 if (hl and args.lookahead_mb >= 0) else None,
+                                         evict_ahead=args.evict_ahead_mb << 20 if (hl and args.evict_ahead_mb >= 0) else None,
+                                         next_fit=args.next_fit if (hl and args.next_fit >= 0) else None, pressed=pressed)
+            return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
+                                lora_rank=16 if train else 0, train=train, progress=lambda m: note(f"{name}: {m}"),
+                                k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
+                                device_outputs=device_outputs)
 
-    note("inputs generated")
-    s = session(cfg, device_outputs=device_outputs)
-    t_compile = time.perf_counter() - t0
-    note(f"compiled and executor created: {int(s.stats.n_vertices)} memgraph vertices, {int(s.stats.n_offload)} offloads, "
-         f"{int(s.stats.n_load)} loads")
-    policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
-              "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
-    engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
-    opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=1, max_transfers=args.max_transfers,
-                          max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
-                          copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
-                          transfer_depth=args.transfer_depth)
-    reps = timed(s, args.steps, args.warmup, opts)
-    ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
-    # unprofiled steps, to show what the event pairs around every launch cost
-    plain_opts = B.tn_exec_opts(policy=policy, max_batch=args.max_batch, max_transfers=args.max_transfers,
-                                max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
-                                copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
-                                transfer_depth=args.transfer_depth)
-    plain = timed(s, max(1, min(3, args.steps), args.steps // 4), 1 if args.steps > 1 else 0, plain_opts)
-    ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
-    y = s.outputs(only=["y"])["y"]
-    # the same step with the outputs stored to pinned host memory (the rate that includes the host link)
-    ms_host_out = None
-    if device_outputs:
-        sh = session(cfg, device_outputs=False)
-        rh = timed(sh, max(3, args.steps // 4), 1, opts)
-        ms_host_out = 1e3 * sum(dt for dt, _ in rh) / len(rh)
-        assert np.array_equal(sh.outputs(only=["y"])["y"], y)
-        sh.close()
-    st = s.stats
-    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
-    gemm_ms = sum(r.gemm_ms for _, r in reps)
-    gemm_launches = sum(r.gemm_launches for _, r in reps)
-    gemm_flops = sum(r.gemm_flops for _, r in reps)
-    attn_ms = sum(r.attn_ms for _, r in reps)
-    attn_flops = sum(r.attn_flops for _, r in reps)
-    ew_ms = sum(r.ewise_ms for _, r in reps)
-    ew_bytes = sum(r.ewise_bytes for _, r in reps)
-    rep0 = reps[-1][1]
-    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    total_flops = rep0.gemm_flops + rep0.attn_flops
-    # HBM bytes per GEMM launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE
-    # and WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel calibration)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"{cfg.name}_gemm_traffic.txt")
-    if os.path.exists(tpath):
-        kv = dict(l.split() for l in open(tpath) if l.strip() and not l.startswith("#"))
-        traffic = 1024.0 * (float(kv["fetch_kib_per_launch"]) / float(kv["fetch_scale"])
-                            + float(kv["write_kib_per_launch"]) / float(kv["write_scale"]))
-    line = {
-        "metric": "tokens/s under GPU-RAM cap", "value": cfg.tokens / (ms * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.layers}-layer LLaMA-shaped "
-                               + ("fine-tuning step (rank-16 adapters on q and v, forward + backward)" if train else "prefill")
-                               + f", d {cfg.d_model}, "
-                               f"{cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, batch {cfg.batch}, "
-                               f"tile {cfg.tile}, attention block {cfg.attn_block}",
-                   "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
-                   "gpu_cap_bytes": s.cap, "weights": "device-resident" if cfg.weights_resident else "streamed from pinned host",
-                   "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
-                   "compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
-                   "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth, "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "serial_order": args.order, "k_split": args.k_split, "materialize_scores": bool(args.materialize_scores), "checkpoint": bool(args.checkpoint), "memgraph_vertices": int(st.n_vertices),
-                   "offloads": int(st.n_offload), "reloads": int(st.n_reload), "loads": int(st.n_load),
-                   "offload_GB": st.offload_bytes / 1e9, "load_GB": st.load_bytes / 1e9, "mem_edges": int(st.n_mem_edges)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": traffic,
-                     "avg_launch_ms": gemm_ms / max(1, gemm_launches),
-                     "flops_per_launch": gemm_flops / max(1, gemm_launches)},
-        "extra": {
+        t0 = time.perf_counter()
+        s = session(cfg, device_outputs)
+        t_compile = time.perf_counter() - t0
+        st = s.stats
+        note(f"{name}: compiled and executor created: {int(st.n_vertices)} memgraph vertices, {int(st.n_offload)} offloads, "
+             f"{int(st.n_load)} loads")
+        reps = timed(s, steps, warmup, exec_opts(1), name)
+        ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
+        # unprofiled steps, to show what the event pairs around every launch cost (short steps only)
+        ms_plain = None
+        if ms < 200:
+            plain = timed(s, max(1, min(3, steps), steps // 4), 1 if steps > 1 else 0, exec_opts(0), name + " (no event pairs)")
+            ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
+        y = s.outputs(only=["y"])["y"]
+        # the same step with the outputs stored to pinned host memory (the rate that includes the host link)
+        ms_host_out = None
+        if device_outputs:
+            sh = session(cfg, False)
+            rh = timed(sh, max(3, steps // 4), 1, exec_opts(1), name + " (outputs to host)")
+            ms_host_out = 1e3 * sum(dt for dt, _ in rh) / len(rh)
+            assert np.array_equal(sh.outputs(only=["y"])["y"], y)
+            sh.close()
+        peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+        n = len(reps)
+        tot = lambda f: sum(getattr(r, f) for _, r in reps)
+        gemm_ms, gemm_launches, gemm_flops = tot("gemm_ms"), tot("gemm_launches"), tot("gemm_flops")
+        attn_ms, attn_flops = tot("attn_ms"), tot("attn_flops")
+        ew_ms, ew_bytes = tot("ewise_ms"), tot("ewise_bytes")
+        busy_ms = tot("kernel_busy_ms") / n
+        h2d_bytes, d2h_bytes = tot("h2d_bytes") / n, tot("d2h_bytes") / n
+        h2d_ms, d2h_ms = tot("h2d_ms") / n, tot("d2h_ms") / n
+        rep0 = reps[-1][1]
+        gemm_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+        attn_tf = attn_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None
+        ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None
+        total_flops = (gemm_flops + attn_flops) / n
+        h2d_gbs, d2h_gbs = h2d_bytes / (ms * 1e-3) / 1e9, d2h_bytes / (ms * 1e-3) / 1e9
+        workload = (f"{name}: {cfg.layers}-layer LLaMA-shaped "
+                    + ("fine-tuning step (rank-16 adapters on q and v, forward + backward)" if train else "prefill")
+                    + f", d {cfg.d_model}, {cfg.n_heads}x{cfg.head_dim} heads, ffn {cfg.ffn}, seq {cfg.seq}, "
+                      f"batch {cfg.batch}, tile {cfg.tile}, attention block {cfg.attn_block}, "
+                    + ("weights and x device-resident" if cfg.weights_resident else "weights and x streamed from pinned host memory")
+                    + f", GPU-memory cap {s.cap / 1e9:.3f} GB"
+                    + (" (40 % of the uncapped peak)" if capped40 else ""))
+        rec = {
+            "workload": workload, "tokens": cfg.tokens, "steps": steps, "warmup": warmup,
+            "ms_per_step": ms, "tokens_per_s": cfg.tokens / (ms * 1e-3),
+            "gpu_cap_bytes": s.cap, "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
+            "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
+            "serial_order": "level" if level else "tiler",
+            "memgraph": {"vertices": int(st.n_vertices), "offloads": int(st.n_offload), "reloads": int(st.n_reload),
+                         "loads": int(st.n_load), "drops": int(st.n_drop), "stores": int(st.n_store),
+                         "mem_edges": int(st.n_mem_edges), "offload_GB": st.offload_bytes / 1e9,
+                         "load_GB": st.load_bytes / 1e9, "store_GB": st.store_bytes / 1e9},
+            "host_link": {
+                "h2d_GB_per_step": h2d_bytes / 1e9, "d2h_GB_per_step": d2h_bytes / 1e9,
+                "h2d_GBs_over_wall": h2d_gbs, "d2h_GBs_over_wall": d2h_gbs,
+                "h2d_frac_of_spec_peak": h2d_gbs / HOST_LINK_GBS, "d2h_frac_of_spec_peak": d2h_gbs / HOST_LINK_GBS,
+                "h2d_frac_of_measured_peak": h2d_gbs / link["h2d"], "d2h_frac_of_measured_peak": d2h_gbs / link["d2h"],
+                "h2d_GBs_while_copying": h2d_bytes / (h2d_ms * 1e-3) / 1e9 if h2d_ms > 0 else None,
+                "d2h_GBs_while_copying": d2h_bytes / (d2h_ms * 1e-3) / 1e9 if d2h_ms > 0 else None,
+                "spec_peak_GBs": HOST_LINK_GBS, "measured_peak_GBs": {"h2d": link["h2d"], "d2h": link["d2h"]}},
+            "mfma": {"gemm_tflops": gemm_tf, "gemm_frac_of_peak": gemm_tf / peak,
+                     "gemm_avg_launch_ms": gemm_ms / max(1, gemm_launches), "gemm_launches_per_step": gemm_launches / n,
+                     "gemm_flops_per_launch": gemm_flops / max(1, gemm_launches),
+                     "attention_tflops": attn_tf, "attention_frac_of_peak": attn_tf / peak if attn_tf else None,
+                     "whole_run_tflops": total_flops / (ms * 1e-3) / 1e12,
+                     "whole_run_frac_of_peak": total_flops / (ms * 1e-3) / 1e12 / peak, "peak_tflops": peak},
+            "elementwise_GBs": ew_gbs, "elementwise_frac_of_hbm_peak": ew_gbs / PEAK_HBM_GBS if ew_gbs else None,
+            # share of the step's wall time during which no kernel ran (Section 5: the GPU "sits idle")
+            "gpu_idle_frac": max(0.0, 1.0 - busy_ms / ms),
+            "gpu_idle_frac_between_first_and_last_kernel": rep0.idle_frac,
+            "kernel_busy_ms": busy_ms, "gemm_ms": gemm_ms / n, "attn_ms": attn_ms / n, "ewise_ms": ew_ms / n,
+            "h2d_busy_ms": h2d_ms, "d2h_busy_ms": d2h_ms,
+            "kernel_launches_per_step": int(rep0.n_kernel_launches), "launches_per_step": int(rep0.n_launches),
+            "untimed_launches": int(rep0.untimed_launches),
             "ms_per_step_without_event_pairs": ms_plain,
             "ms_per_step_with_outputs_stored_to_host": ms_host_out,
-            "tokens_per_s_with_outputs_stored_to_host": cfg.tokens / (ms_host_out * 1e-3) if ms_host_out else None,
-            "tokens_per_s_without_event_pairs": cfg.tokens / (ms_plain * 1e-3),
-            "whole_run_tflops": total_flops / (ms * 1e-3) / 1e12,
-            "whole_run_frac_of_mfma_peak": total_flops / (ms * 1e-3) / 1e12 / peak,
-            "attention_tflops": attn_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None,
-            "elementwise_GBs": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
-            "kernel_launches_per_step": int(rep0.n_kernel_launches),
-            "gpu_idle_frac": rep0.idle_frac,
-            "kernel_busy_ms": rep0.kernel_busy_ms, "gemm_ms": rep0.gemm_ms, "attn_ms": rep0.attn_ms,
-            "ewise_ms": rep0.ewise_ms, "h2d_ms": rep0.h2d_ms, "d2h_ms": rep0.d2h_ms,
-            "h2d_GBs_while_copying": rep0.h2d_bytes / (rep0.h2d_ms * 1e-3) / 1e9 if rep0.h2d_ms > 0 else None,
-            "d2h_GBs_while_copying": rep0.d2h_bytes / (rep0.d2h_ms * 1e-3) / 1e9 if rep0.d2h_ms > 0 else None,
-            "launches_per_step": int(rep0.n_launches),
-            "d2h_GBs_over_wall": rep0.d2h_bytes / (ms * 1e-3) / 1e9,
-            "h2d_GBs_over_wall": rep0.h2d_bytes / (ms * 1e-3) / 1e9,
             "input_generation_s": t_gen, "build_and_compile_s": t_compile,
-        },
-    }
-    s.close()
-
-    # the same shape with everything streamed from the host and the cap at 40 % of the uncapped
-    # peak, so that the offload/reload path carries real traffic
-    if args.capped and cfg.cap_bytes:
-        cfg2 = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
-        # level-by-level serial order: every weight tile is loaded once per step, where the tiler's
-        # stripe-by-stripe order loads the feed-forward weights once per row tile
-        s2 = session(cfg2, pressed=True, level=True)
-        r2 = timed(s2, max(3, args.steps // 4), 1, opts)
-        ms2 = 1e3 * sum(dt for dt, _ in r2) / len(r2)
-        rr = r2[-1][1]
-        y2 = s2.outputs(only=["y"])["y"]
-        line["capped40"] = {
-            "gpu_cap_bytes": s2.cap, "serial_order": "level", "ms_per_step": ms2, "tokens_per_s": cfg.tokens / (ms2 * 1e-3),
-            "offloads": int(s2.stats.n_offload), "reloads": int(s2.stats.n_reload), "loads": int(s2.stats.n_load),
-            "h2d_GBs_over_wall": rr.h2d_bytes / (ms2 * 1e-3) / 1e9, "d2h_GBs_over_wall": rr.d2h_bytes / (ms2 * 1e-3) / 1e9,
-            "h2d_frac_of_link": rr.h2d_bytes / (ms2 * 1e-3) / 1e9 / HOST_LINK_GBS,
-            "gpu_idle_frac": rr.idle_frac, "identical_to_uncapped_run": bool(np.array_equal(y, y2)),
+            "exec": {"compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
+                     "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth,
+                     "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "k_split": k_split,
+                     "materialize_scores": bool(materialize), "checkpoint": bool(checkpoint)},
         }
-        s2.close()
+        s.close()
+        del s
+        # give the device buffer and the pinned slabs back before the next workload asks for its own
+        gc.collect()
+        torch.cuda.empty_cache()
+        if hasattr(torch._C, "_host_emptyCache"):
+            torch._C._host_emptyCache()
+        return rec, cfg, full, y
 
-    if args.cpu_tokens > 0:
+    head_name = args.workload or "c4"
+    subs = [] if args.workload else ["c2", "c2_capped40", "c3", "c5"]
+    if args.subs:
+        subs = [] if args.subs == "none" else [x for x in args.subs.split(",") if x]
+    if args.capped and "c2_capped40" not in subs:
+        subs.append("c2_capped40")
+
+    rec, cfg, full, y = run_case(head_name, args.steps, args.warmup, headline=True)
+    gemm_kernel = "gemm_bf16_nt256_kernel" if cfg.dtype == "bf16" else "gemm_generic_kernel"
+    config_keys = ("workload", "gpu_cap_bytes", "distinct_layers", "kv_outputs", "outputs", "serial_order", "memgraph", "exec")
+    top_keys = config_keys + ("host_link", "mfma", "gpu_idle_frac", "tokens_per_s", "ms_per_step", "steps", "warmup")
+    line = {
+        "metric": "tokens/s under GPU-RAM cap", "value": rec["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {k: rec[k] for k in config_keys},
+        # The dominant kernel (by kernel time) of the timed steps: the bf16 tile GEMM, in situ -- its launches
+        # are as large as the loads that have arrived allow.  `traffic` (HBM bytes per launch from the
+        # profiler's counters) is not measured by this run; the recorded figure is kept with the profiles.
+        "roofline": {"bound": "mfma", "kernel": gemm_kernel, "achieved": rec["mfma"]["gemm_tflops"],
+                     "peak": rec["mfma"]["peak_tflops"], "unit": "TFLOP/s", "frac": rec["mfma"]["gemm_frac_of_peak"],
+                     "traffic": None, "avg_launch_ms": rec["mfma"]["gemm_avg_launch_ms"],
+                     "flops_per_launch": rec["mfma"]["gemm_flops_per_launch"],
+                     "attention_tflops": rec["mfma"]["attention_tflops"],
+                     "attention_frac": rec["mfma"]["attention_frac_of_peak"],
+                     # what bounds the whole step of a weight-streaming workload: bytes over the host link
+                     "host_link": {"bound": "host link, host to GPU", "achieved": rec["host_link"]["h2d_GBs_over_wall"],
+                                   "peak": HOST_LINK_GBS, "unit": "GB/s", "frac": rec["host_link"]["h2d_frac_of_spec_peak"],
+                                   "measured_peak": link["h2d"],
+                                   "frac_of_measured_peak": rec["host_link"]["h2d_frac_of_measured_peak"]}},
+        "host_link": rec["host_link"], "mfma": rec["mfma"],
+        "gpu_idle_frac": rec["gpu_idle_frac"],
+        "extra": {k: rec[k] for k in rec if k not in top_keys},
+    }
+
+    cpu_tokens = args.cpu_tokens if args.cpu_tokens >= 0 else (4096 if cfg.layers <= 2 else 64)
+    if cpu_tokens > 0:
         from oracle import llama_ref as R
-        n = min(args.cpu_tokens, cfg.seq)
+        n = min(cpu_tokens, cfg.seq)
+        note(f"CPU oracle on the first {n} tokens of {head_name}")
         base, y_cpu = cpu_baseline(cfg, full, n)
         line["cpu_baseline"] = base
-        yy = (bf16_bits_to_f32(y) if cfg.dtype == "bf16" else y).astype(np.float64)
-        rows = np.concatenate([np.arange(b * cfg.seq, b * cfg.seq + n) for b in range(cfg.batch)])
-        line["extra"]["rel_err_vs_untiled_oracle_on_cpu_sample"] = R.rel_err(yy[rows], y_cpu)
+        if cfg.layers <= 2:  # deeper stacks: two correct bf16 pipelines drift apart; the parity tests hold the bar layer by layer
+            yy = (bf16_bits_to_f32(y) if cfg.dtype == "bf16" else y).astype(np.float64)
+            rows = np.concatenate([np.arange(b * cfg.seq, b * cfg.seq + n) for b in range(cfg.batch)])
+            line["extra"]["rel_err_vs_untiled_oracle_on_cpu_sample"] = R.rel_err(yy[rows], y_cpu)
+        del y_cpu
     else:
         line["cpu_baseline"] = None
+    del full, y
+
+    y_c2 = None
+    for sub in subs:
+        if sub == head_name:
+            continue
+        k, w = SUB_STEPS.get(sub, (3, 1))
+        srec, scfg, sfull, sy = run_case(sub, k, w, headline=False)
+        if sub == "c2":
+            y_c2 = sy
+        elif sub == "c2_capped40" and y_c2 is not None:
+            srec["identical_to_the_uncapped_c2_run"] = bool(np.array_equal(sy, y_c2))
+        line.setdefault("sub_records", {})[sub] = srec
+        del sfull, sy
     print(json.dumps(line))
 
 

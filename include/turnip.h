@@ -206,6 +206,15 @@ tn_status tn_taskgraph_vertex(const tn_taskgraph* tg, tn_vid v, tn_tg_vertex* ou
 /* Copies up to cap operand ids of v into out; returns the operand count (or a negative status). */
 int32_t tn_taskgraph_inputs(const tn_taskgraph* tg, tn_vid v, tn_vid* out, int32_t cap);
 
+/* A serial order V for tn_compile that runs the graph level by level (Section 6 takes V as given;
+ * Section 8, item 3 shows how much the choice matters to an executor that must follow it): the
+ * level of a kernel vertex is one more than the highest level among its operands that are kernel
+ * vertices (1 if it reads inputs only); an input comes just before the first level that reads it;
+ * vertices of one level keep their numbering.  Vertices of one kind end up next to each other, so
+ * launches can be grouped, and every weight tile of a layer is loaded once per pass instead of once
+ * per row stripe.  out receives all vertex ids; cap = room in out, at least the vertex count. */
+tn_status tn_taskgraph_level_order(const tn_taskgraph* tg, tn_vid* out, int64_t cap);
+
 /* A tiled LLaMA-style decoder forward pass as a taskgraph (the paper's workload, Section 8;
  * the decomposition into tiles is this library's, since the paper leaves taskgraph production
  * to an outside framework, Section 4 second paragraph). */

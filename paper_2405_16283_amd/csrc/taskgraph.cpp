@@ -453,6 +453,35 @@ int32_t tn_taskgraph_inputs(const tn_taskgraph* tg, tn_vid v, tn_vid* out, int32
   return (int32_t)in.size();
 }
 
+tn_status tn_taskgraph_level_order(const tn_taskgraph* tg, tn_vid* out, int64_t cap) {
+  if (!tg || !out) return fail(TN_ERR_INVALID, "NULL argument");
+  const int64_t n = (int64_t)tg->v.size();
+  if (cap < n) return fail(TN_ERR_INVALID, "room for %lld vertex ids, the graph has %lld", (long long)cap, (long long)n);
+  // keys in half levels: an operation of level l has key 2l, an input read first at level l key 2l - 1
+  std::vector<int64_t> key(n, 0);
+  for (int64_t v = 0; v < n; ++v) {
+    const Vertex& x = tg->v[v];
+    if (x.kind == TN_OP_INPUT) continue;
+    int64_t lv = 0;
+    for (tn_vid u : x.in)
+      if (tg->v[u].kind != TN_OP_INPUT) lv = std::max(lv, key[u] / 2);
+    key[v] = 2 * (lv + 1);
+  }
+  for (int64_t v = 0; v < n; ++v) {
+    const Vertex& x = tg->v[v];
+    if (x.kind == TN_OP_INPUT) continue;
+    for (tn_vid u : x.in)
+      if (tg->v[u].kind == TN_OP_INPUT && (key[u] == 0 || key[v] - 1 < key[u])) key[u] = key[v] - 1;
+  }
+  for (int64_t v = 0; v < n; ++v)
+    if (tg->v[v].kind == TN_OP_INPUT && key[v] == 0) key[v] = 1;  // an input nobody reads: before the first level
+  std::vector<tn_vid> order(n);
+  for (int64_t v = 0; v < n; ++v) order[v] = (tn_vid)v;
+  std::stable_sort(order.begin(), order.end(), [&](tn_vid a, tn_vid b) { return key[a] < key[b]; });
+  std::copy(order.begin(), order.end(), out);
+  return TN_OK;
+}
+
 int64_t tn_taskgraph_num_bindings(const tn_taskgraph* tg) { return tg ? (int64_t)tg->bindings.size() : TN_ERR_INVALID; }
 
 tn_status tn_taskgraph_binding(const tn_taskgraph* tg, int64_t i, tn_llama_binding* out) {

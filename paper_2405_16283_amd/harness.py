@@ -127,31 +127,6 @@ def output_vertices(tg):
     return vids, shapes, bind
 
 
-def level_major_order(tg) -> List[int]:
-    """A serial order V that runs the graph level by level: an operation's level is one more than
-    the highest level among its operands, an input sits just before the first level that reads
-    it, and vertices of one level keep their numbering.  Same-kind vertices end up next to each
-    other, which is what an executor that must follow V needs in order to group launches."""
-    n = B.tn_taskgraph_num_vertices(tg)
-    level = [0.0] * n
-    first_use = [None] * n
-    is_input = [False] * n
-    for v in range(n):
-        x = B.tn_taskgraph_vertex(tg, v)
-        if x.n_inputs == 0:
-            is_input[v] = True
-            continue
-        ins = B.tn_taskgraph_inputs(tg, v)
-        level[v] = 1.0 + max((level[u] for u in ins if not is_input[u]), default=0.0)
-        for u in ins:
-            if is_input[u] and (first_use[u] is None or level[v] < first_use[u]):
-                first_use[u] = level[v]
-    for v in range(n):
-        if is_input[v]:
-            level[v] = (first_use[v] if first_use[v] is not None else 1.0) - 0.5
-    return sorted(range(n), key=lambda v: (level[v], v))
-
-
 def uncapped_peak(tg) -> int:
     """Peak bytes of the serial run with unlimited memory and no run-ahead allocation."""
     opts = B.tn_compile_opts(max_lookahead_bytes=0, drop_clean_inputs=1)

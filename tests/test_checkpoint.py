@@ -124,7 +124,7 @@ def test_forward_memgraph_with_a_quarter_of_the_cap_kept_free_is_correct(name):
     tg = B.tn_build_llama(H.llama_config_struct(cfg))
     try:
         cap = H.cap_for(cfg, tg)
-        for order in (None, H.level_major_order(tg)):
+        for order in (None, B.tn_taskgraph_level_order(tg)):
             mg = B.tn_compile(tg, order, cap, H.bench_compile_opts(cap, False, pressed=True))
             try:
                 st = B.tn_memgraph_stats(mg)

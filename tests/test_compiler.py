@@ -406,3 +406,42 @@ def test_two_vertex_chain_may_become_offload_reload(tmp_path):
         B.tn_memgraph_destroy(mg)
     finally:
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name,kw", [("c1", {}), ("ragged_bf16", dict(lora_rank=8, train=True)), ("batch2_f32", dict(k_split=2))])
+def test_level_order_runs_the_graph_level_by_level_and_compiles(name, kw):
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, **kw))
+    try:
+        order = B.tn_taskgraph_level_order(tg)
+        preds = task_preds(tg)
+        n = len(preds)
+        assert sorted(order) == list(range(n))
+        pos = {v: i for i, v in enumerate(order)}
+        assert all(pos[u] < pos[v] for v in range(n) for u in preds[v])
+        # levels worked out here from the definition: longest chain of kernel vertices ending at v
+        level = [0] * n
+        for v in range(n):
+            if preds[v]:
+                level[v] = 1 + max((level[u] for u in preds[v] if preds[u]), default=0)
+        ops = [v for v in order if preds[v]]
+        assert all(level[a] <= level[b] for a, b in zip(ops, ops[1:]))
+        assert all(a < b for a, b in zip(ops, ops[1:]) if level[a] == level[b]), "a level keeps its numbering"
+        for v in order:  # an input sits directly before the first level that reads it
+            if not preds[v]:
+                first = min((level[w] for w in range(n) if v in preds[w]), default=1)
+                later_ops = [level[w] for w in order[pos[v]:] if preds[w]]
+                earlier_ops = [level[w] for w in order[:pos[v]] if preds[w]]
+                assert (not later_ops or later_ops[0] == first) and (not earlier_ops or earlier_ops[-1] < first)
+        # (outputs of unfinished sums cannot move, and a level opens all of its sums at once: more room there)
+        cap = H.cap_for(cfg, tg) * (2 if kw.get("k_split") else 1)
+        mg = B.tn_compile(tg, order, cap, None)
+        try:
+            check_all(preds, oracle_memgraph(mg), n_random=10, seed=2)
+        finally:
+            B.tn_memgraph_destroy(mg)
+        with pytest.raises(B.TurnipError):
+            buf = (ctypes.c_int32 * 4)()
+            B._check(B.lib().tn_taskgraph_level_order(tg, buf, 4))
+    finally:
+        B.tn_taskgraph_destroy(tg)

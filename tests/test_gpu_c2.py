@@ -54,7 +54,7 @@ def test_c2_streamed_under_forty_percent_cap_gives_the_same_bits(c2):
     print("[case] c2 streamed, cap = 40 % of the uncapped peak", flush=True)
     tg = B.tn_build_llama(H.llama_config_struct(capped))
     cap = H.cap_for(capped, tg)
-    order = H.level_major_order(tg)
+    order = B.tn_taskgraph_level_order(tg)
     B.tn_taskgraph_destroy(tg)
     # the serial order, compile options and stream count of the benchmark's capped run
     s = H.GpuSession(capped, full, cap=cap, compile_opts=H.bench_compile_opts(cap, False, pressed=True),
