@@ -461,6 +461,24 @@ tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inpu
 tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
                      const tn_exec_opts* opts, tn_exec_report* report);
 
+/* For callers that cannot allocate while they run -- a serving loop that keeps one executor per
+ * compiled memgraph and must not grow GPU memory per executor, a harness that forbids hipMalloc
+ * after start-up, code whose surroundings are being captured into a HIP graph.  Same contract and
+ * same results as tn_execute, bit for bit, but the kernels read their operand tables (descriptors,
+ * operand addresses, tile sizes, rotary angles: what tn_executor_create puts into GPU memory of its
+ * own) from a region of 8 MiB that is part of the loaded library on every GPU: the call copies the
+ * executor's pinned table image there (one asynchronous copy on the first compute stream, awaited
+ * before anything is launched) and runs.  It calls no hipMalloc, hipFree, hipHostMalloc or
+ * hipEventCreate, nor anything else that allocates GPU or pinned memory.
+ *   - A memgraph whose tables exceed 8 MiB (about 25 000 kernel vertices of the LLaMA graphs) is
+ *     refused with TN_ERR_INVALID; tn_last_error() names both sizes.
+ *   - All calls on one GPU share the one region, which keeps the last call's tables; every call
+ *     rewrites all of what its own kernels read, so nothing needs clearing.  Calls that overlap
+ *     in time on the same GPU (from several threads or executors) race on it: serialise them.
+ *     tn_execute does not use the region and may overlap with it. */
+tn_status tn_execute_static(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                            const tn_exec_opts* opts, tn_exec_report* report);
+
 /* Launch order of the last run: copies up to cap memgraph vertex ids in the order the loop
  * launched them; returns the count. */
 int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap);

@@ -148,6 +148,8 @@ SIGNATURES = {
     "tn_executor_destroy": (None, [_P]),
     "tn_executor_place_inputs": (C.c_int32, [_P, C.POINTER(_P)]),
     "tn_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(tn_exec_opts), C.POINTER(tn_exec_report)]),
+    "tn_execute_static": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(tn_exec_opts),
+                                      C.POINTER(tn_exec_report)]),
     "tn_executor_last_order": (C.c_int64, [_P, C.POINTER(C.c_int64), C.c_int64]),
 }
 
@@ -351,6 +353,14 @@ def tn_execute(ex, host_inputs: Sequence[int], host_outputs: Sequence[int],
     rep = tn_exec_report()
     _check(lib().tn_execute(ex, _ptr_array(host_inputs), _ptr_array(host_outputs),
                             C.byref(opts) if opts is not None else None, C.byref(rep)))
+    return rep
+
+
+def tn_execute_static(ex, host_inputs: Sequence[int], host_outputs: Sequence[int],
+                      opts: Optional[tn_exec_opts] = None) -> tn_exec_report:
+    rep = tn_exec_report()
+    _check(lib().tn_execute_static(ex, _ptr_array(host_inputs), _ptr_array(host_outputs),
+                                   C.byref(opts) if opts is not None else None, C.byref(rep)))
     return rep
 
 

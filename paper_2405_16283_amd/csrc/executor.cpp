@@ -669,7 +669,8 @@ tn_status tn_executor_place_inputs(tn_executor* ex, const void* const* host_inpu
   return TN_OK;
 }
 
-// The engine behind tn_execute: `tables` says where the kernels of this run find their operand tables.
+// The engine behind tn_execute and tn_execute_static: `tables` says where the kernels of this run
+// find their operand tables.
 static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
                               const tn_exec_opts* opts_in, tn_exec_report* report, const DeviceTables& tables) {
   const MemGraph& mg = *ex->mg;
@@ -1238,6 +1239,29 @@ tn_status tn_execute(tn_executor* ex, const void* const* host_inputs, void* cons
   if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
   if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
   return run_memgraph(ex, host_inputs, host_outputs, opts, report, ex->tables);
+}
+
+tn_status tn_execute_static(tn_executor* ex, const void* const* host_inputs, void* const* host_outputs,
+                            const tn_exec_opts* opts, tn_exec_report* report) {
+  if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
+  if (ex->poisoned) return fail(TN_ERR_HIP, "executor is poisoned by an earlier HIP error");
+  if (ex->image_bytes > kStaticTableBytes)
+    return fail(TN_ERR_INVALID, "the operand tables of this memgraph take %llu bytes; the static table region holds %llu",
+                (unsigned long long)ex->image_bytes, (unsigned long long)kStaticTableBytes);
+  char* region = nullptr;
+  hipError_t e = static_table_region((void**)&region);
+  if (e != hipSuccess) return fail(TN_ERR_HIP, "address of the static table region: %s", hipGetErrorString(e));
+  // The region keeps whatever the last call on this GPU left there; this call's kernels read only
+  // [0, image_bytes), all of which is written here, and nothing else has to start from zero.  The
+  // upload is complete before the first kernel is enqueued on any stream.
+  hipStream_t s0 = ex->slots[0].stream;
+  e = hipMemcpyAsync(region, ex->h_image, ex->image_bytes, hipMemcpyHostToDevice, s0);
+  if (e == hipSuccess) e = hipStreamSynchronize(s0);
+  if (e != hipSuccess) {
+    ex->poisoned = true;
+    return fail(TN_ERR_HIP, "upload of the operand tables: %s", hipGetErrorString(e));
+  }
+  return run_memgraph(ex, host_inputs, host_outputs, opts, report, tables_at(*ex, region));
 }
 
 int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap) {

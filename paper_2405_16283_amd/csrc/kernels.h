@@ -98,6 +98,13 @@ struct CopyBatch {
 // max_workgroups <= 0 selects kDefaultCopyWorkgroups
 hipError_t launch_copies(const CopyBatch& b, int max_workgroups, hipStream_t stream);
 
+// A region of GPU memory that exists from the moment the library is loaded until the process ends,
+// for callers that want the operand tables of a run somewhere nobody has to allocate.  Each GPU
+// holds its own copy of the region at its own address; *ptr receives the address on the current
+// device (looked up once per device).  Contents are whatever the last user left there.
+constexpr size_t kStaticTableBytes = 8u << 20;
+hipError_t static_table_region(void** ptr);
+
 // Workgroups a vertex needs in the given class (host side, used to fill OpDesc::nblocks).
 int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux);
 

@@ -9,6 +9,7 @@
 #include "kernels.h"
 
 #include <climits>
+#include <mutex>
 #include <type_traits>
 
 namespace tn {
@@ -1696,6 +1697,30 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
     }
     default: return 0;
   }
+}
+
+// The static table region (kernels.h).  In host code the array's name is only a handle for
+// hipGetSymbolAddress; every use of the memory goes through the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kStaticTableBytes];
+
+hipError_t static_table_region(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* region_of[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!region_of[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    region_of[dev] = p;
+  }
+  *ptr = region_of[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_copies(const CopyBatch& b, int max_workgroups, hipStream_t s) {

@@ -270,6 +270,9 @@ class GpuSession:
     def execute(self, opts: Optional[B.tn_exec_opts] = None) -> B.tn_exec_report:
         return B.tn_execute(self.ex, self.in_ptrs, self.out_ptrs, opts)
 
+    def execute_static(self, opts: Optional[B.tn_exec_opts] = None) -> B.tn_exec_report:
+        return B.tn_execute_static(self.ex, self.in_ptrs, self.out_ptrs, opts)
+
     def run(self, opts: Optional[B.tn_exec_opts] = None, poison: bool = True,
             only: Optional[Sequence[str]] = None):
         """place inputs, execute, and return ({"y": array, ["k.l", "v.l": arrays]}, report)."""
