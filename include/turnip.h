@@ -256,6 +256,13 @@ typedef struct {
    * the second half of the feed-forward block, which nothing reads), as vertices of their own.
    * Results are bit for bit those of train without it. */
   int32_t checkpoint;
+  /* != 0: the hidden state after every layer but the last (whose output is y) is a marked output
+   * too, bound as TN_T_H of that layer: what a check layer by layer, or a probe, reads. */
+  int32_t hidden_outputs;
+  /* n > 1: kv_outputs and hidden_outputs apply only to the layers l with l mod n == 0 or n - 1, and to
+   * the last two layers -- pairs of neighbouring layers through the depth of the stack, so that
+   * a layer's input and output can both be read back without storing every layer.  0 or 1: all. */
+  int32_t output_layer_stride;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */
@@ -263,7 +270,8 @@ enum {
   TN_T_X = 0, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2,
   TN_T_Y, TN_T_K, TN_T_V,
   TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE,          /* adapter matrices and the probe (inputs)      */
-  TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX            /* their gradients and that of x (outputs)      */
+  TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX,           /* their gradients and that of x (outputs)      */
+  TN_T_H                                                     /* hidden state after a layer (hidden_outputs)  */
 };
 typedef struct {
   tn_vid vid;

@@ -81,6 +81,52 @@ def decoder_layer(x, w, layer: int, n_heads: int, head_dim: int, eps: float, bas
     return y
 
 
+def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim: int, eps: float, base: float,
+                       k_ctx=None, v_ctx=None, store=None):
+    """One decoder layer for a sample of the rows of one sequence.
+
+    Every step of the layer works row by row except attention, in which the row at position p reads
+    the keys and values of positions 0..p.  h_rows [n, d] are the layer's input rows at `positions`.
+    k_ctx, v_ctx [n_ctx, d]: the keys (after the rotation) and values of positions 0..n_ctx-1 as the
+    run under test stored them, so that a late row can be checked without running the whole sequence;
+    None: the rows are positions 0..n-1 and their own keys and values are all there is to attend to
+    (a causal prefix).  store: the rounding applied wherever the tiled execution stores a tensor (every
+    taskgraph tensor is rounded to its storage type; attention partials and statistics are not);
+    None: exact.  Returns (output rows, key rows after the rotation, value rows).
+    """
+    st = store if store is not None else (lambda z: z)
+    h = np.asarray(h_rows, dtype=np.float64)
+    positions = np.asarray(positions)
+    n = h.shape[0]
+    a = st(rmsnorm(h, w[f"g1.{layer}"], eps))
+    q, k, v = st(a @ w[f"wq.{layer}"]), st(a @ w[f"wk.{layer}"]), st(a @ w[f"wv.{layer}"])
+    for hh in range(n_heads):
+        sl = slice(hh * head_dim, (hh + 1) * head_dim)
+        q[:, sl] = rope(q[:, sl], positions, base)
+        k[:, sl] = rope(k[:, sl], positions, base)
+    q, k = st(q), st(k)
+    if k_ctx is None:
+        assert np.array_equal(positions, np.arange(n)), "without a context the rows must be a prefix"
+        kc, vc = k, v
+    else:
+        kc, vc = np.asarray(k_ctx, dtype=np.float64), np.asarray(v_ctx, dtype=np.float64)
+    o = np.empty_like(q)
+    for r in range(n):
+        p = int(positions[r])
+        for hh in range(n_heads):
+            sl = slice(hh * head_dim, (hh + 1) * head_dim)
+            s = (kc[:p + 1, sl] @ q[r, sl]) / np.sqrt(head_dim)
+            e = np.exp(s - np.max(s))
+            o[r, sl] = (e / np.sum(e)) @ vc[:p + 1, sl]
+    o = st(o)
+    h1 = st(h + st(o @ w[f"wo.{layer}"]))
+    b = st(rmsnorm(h1, w[f"g2.{layer}"], eps))
+    gate, up = st(b @ w[f"w1.{layer}"]), st(b @ w[f"w3.{layer}"])
+    act = st(silu(gate) * up)
+    y = st(h1 + st(act @ w[f"w2.{layer}"]))
+    return y, k, v
+
+
 def forward(cfg, inputs_f64, n_tokens_prefix=None):
     """All layers, all sequences of the batch.  inputs_f64: name -> float64 array (full tensors).
 

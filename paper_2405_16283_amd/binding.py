@@ -21,7 +21,7 @@ TN_HOST, TN_DEVICE = 0, 1
  TN_OP_ATTN_COMBINE, TN_OP_SILU_MUL, TN_OP_ADD, TN_OP_SILU_MUL_BWD, TN_OP_RMS_BWD_STAT, TN_OP_RMS_BWD_APPLY,
  TN_OP_ATTN_BWD, TN_OP_TRANSPOSE, TN_OP_SUM, TN_OP_ZERO, TN_OP_SUM_INTO, TN_OP_SOFTMAX_STAT, TN_OP_SOFTMAX_APPLY) = range(19)
 (TN_T_X, TN_T_WQ, TN_T_WK, TN_T_WV, TN_T_WO, TN_T_W1, TN_T_W3, TN_T_W2, TN_T_G1, TN_T_G2, TN_T_Y, TN_T_K, TN_T_V,
- TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE, TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX) = range(23)
+ TN_T_AQ, TN_T_BQ, TN_T_AV, TN_T_BV, TN_T_PROBE, TN_T_DAQ, TN_T_DBQ, TN_T_DAV, TN_T_DBV, TN_T_DX, TN_T_H) = range(24)
 (TN_MG_INPUT, TN_MG_LOAD, TN_MG_OP, TN_MG_OFFLOAD, TN_MG_RELOAD, TN_MG_DROP, TN_MG_STORE, TN_MG_JOIN) = range(8)
 TN_EDGE_DATA, TN_EDGE_MEM, TN_EDGE_ORDER = 0, 1, 2
 TN_POLICY_FIFO, TN_POLICY_LIFO, TN_POLICY_RANDOM, TN_POLICY_BY_ORDER, TN_POLICY_IN_ORDER = 0, 1, 2, 3, 4
@@ -60,7 +60,8 @@ class tn_llama_config(C.Structure):
                [("eps", C.c_float), ("rope_base", C.c_float), ("weights_residency", C.c_int32),
                 ("x_residency", C.c_int32), ("kv_outputs", C.c_int32), ("weights_transposed", C.c_int32),
                 ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32), ("materialize_scores", C.c_int32),
-                ("checkpoint", C.c_int32)]
+                ("checkpoint", C.c_int32), ("hidden_outputs", C.c_int32),
+                ("output_layer_stride", C.c_int32)]
 
 
 class tn_llama_binding(C.Structure):

@@ -512,6 +512,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.train && gw != c.tile) return fail(TN_ERR_SHAPE, "train needs head_dim <= tile (one column tile per head group)");
   if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
   if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
+  if (c.output_layer_stride < 0) return fail(TN_ERR_INVALID, "output_layer_stride must not be negative");
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
   if (c.materialize_scores && (c.tile != c.head_dim || c.train || c.kv_outputs))
     return fail(TN_ERR_INVALID, "materialize_scores needs tile == head_dim and neither train nor kv_outputs");
@@ -549,6 +550,12 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   std::vector<LayerInputs> lin(c.train ? c.layers : 0);
   const int32_t rk = c.lora_rank;
   const Range rkr{0, rk};
+
+  // which layers' K/V (kv_outputs) and hidden states (hidden_outputs) are outputs
+  auto layer_is_output = [&](int l) {
+    const int n = c.output_layer_stride;
+    return n <= 1 || l % n == 0 || l % n == n - 1 || l + 2 >= c.layers;
+  };
 
   // One layer, one sequence, stripe by stripe.  `sv`: where to note what the reverse pass reads
   // (null: nothing is noted).  `tail`: whether the layer's output is formed (second half of the
@@ -591,7 +598,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
             sv->a[i] = a; sv->q[i] = q[i]; sv->k[i] = kk[i]; sv->v[i] = vv[i];
             sv->rstd1[i] = st1; sv->tq[i] = tq; sv->tv[i] = tv;
           }
-          if (c.kv_outputs) {
+          if (c.kv_outputs && layer_is_output(l)) {
             Range rr{b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b};
             for (int which = 0; which < 2; ++which) {
               tn_vid id = which ? vv[i][j] : kk[i][j];
@@ -727,6 +734,10 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     for (int b = 0; b < c.batch; ++b) {
       if (c.checkpoint) layer_in[l][b] = x[b];
       forward_layer(l, w, b, x[b], c.train && !c.checkpoint ? &saved[l][b] : nullptr, true);
+      if (c.hidden_outputs && layer_is_output(l) && l + 1 < c.layers)  // (the last layer's output is y)
+        for (size_t i = 0; i < t.rows.size(); ++i)
+          for (size_t j = 0; j < nd; ++j)
+            t.mark_output(x[b][i][j], TN_T_H, l, {b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b}, t.dcols[j]);
     }
   }
   for (int b = 0; b < c.batch; ++b)

@@ -13,8 +13,8 @@ _TENSOR_NAMES = {B.TN_T_X: "x", B.TN_T_WQ: "wq", B.TN_T_WK: "wk", B.TN_T_WV: "wv
                  B.TN_T_W1: "w1", B.TN_T_W3: "w3", B.TN_T_W2: "w2", B.TN_T_G1: "g1", B.TN_T_G2: "g2",
                  B.TN_T_Y: "y", B.TN_T_K: "k", B.TN_T_V: "v", B.TN_T_AQ: "aq", B.TN_T_BQ: "bq", B.TN_T_AV: "av",
                  B.TN_T_BV: "bv", B.TN_T_PROBE: "probe", B.TN_T_DAQ: "daq", B.TN_T_DBQ: "dbq", B.TN_T_DAV: "dav",
-                 B.TN_T_DBV: "dbv", B.TN_T_DX: "dx"}
-OUTPUT_TENSORS = ("y", "k", "v", "daq", "dbq", "dav", "dbv", "dx")
+                 B.TN_T_DBV: "dbv", B.TN_T_DX: "dx", B.TN_T_H: "h"}
+OUTPUT_TENSORS = ("y", "k", "v", "daq", "dbq", "dav", "dbv", "dx", "h")
 OP_NAMES = {B.TN_OP_INPUT: "input", B.TN_OP_GEMM: "gemm", B.TN_OP_RMS_STAT: "rms_stat",
             B.TN_OP_RMS_APPLY: "rms_apply", B.TN_OP_ROPE: "rope", B.TN_OP_ATTN_BLOCK: "attn_block",
             B.TN_OP_ATTN_COMBINE: "attn_combine", B.TN_OP_SILU_MUL: "silu_mul", B.TN_OP_ADD: "add",
@@ -29,7 +29,8 @@ EDGE_NAMES = {B.TN_EDGE_DATA: "data", B.TN_EDGE_MEM: "mem", B.TN_EDGE_ORDER: "or
 def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool = True,
                         v_transposed: bool = True, lora_rank: int = 0, train: bool = False,
                         k_split: int = 0, materialize_scores: bool = False,
-                        checkpoint: bool = False) -> B.tn_llama_config:
+                        checkpoint: bool = False, hidden_outputs: bool = False,
+                        output_layer_stride: int = 0) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -39,7 +40,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         x_residency=B.TN_DEVICE if cfg.x_resident else B.TN_HOST, kv_outputs=int(kv_outputs),
         weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
         lora_rank=int(lora_rank), train=int(train), k_split=int(k_split),
-        materialize_scores=int(materialize_scores), checkpoint=int(checkpoint))
+        materialize_scores=int(materialize_scores), checkpoint=int(checkpoint),
+        hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -194,7 +196,7 @@ class GpuSession:
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
                  materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
-                 device_inputs: bool = False):
+                 device_inputs: bool = False, hidden_outputs: bool = False, output_layer_stride: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -202,7 +204,7 @@ class GpuSession:
         self.cfg = cfg
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
                                                        lora_rank, train, k_split, materialize_scores,
-                                                       checkpoint))
+                                                       checkpoint, hidden_outputs, output_layer_stride))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

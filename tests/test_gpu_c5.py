@@ -24,6 +24,8 @@ from paper_2405_16283_amd import binding as B
 from paper_2405_16283_amd import harness as H
 from workloads import bf16_bits_to_f32, config, make_llama_inputs, make_lora_inputs
 
+from util import check_layer_rows
+
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 RANK = 16
 NOISE_FACTOR = 1.5  # see test_gpu_deep: distance to the exact result, relative to the bf16 oracle's own
@@ -80,7 +82,10 @@ def test_full_step_in_the_benchmark_configuration():
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     full.update(make_lora_inputs(cfg, 0, rank=RANK, b_std=0.0))
     print(f"[c5] inputs generated {time.time() - t0:.1f}s", flush=True)
+    stride = 8  # hidden states of pairs of neighbouring layers through the depth of the stack are outputs
+    probe = [0] + [l for l in range(stride, cfg.layers - 1, stride)] + [last]
     s = H.GpuSession(cfg, full, lora_rank=RANK, train=True, compile_opts=H.bench_compile_opts(cfg.cap_bytes, True), n_compute=H.BENCH_COMPUTE_STREAMS,
+                     hidden_outputs=True, output_layer_stride=stride,
                      progress=lambda m: print(f"[c5] {m} {time.time() - t0:.1f}s", flush=True))
     st = s.stats
     print(f"[c5] compiled and placed {time.time() - t0:.1f}s: {st.n_vertices} vertices, {st.n_load} loads "
@@ -88,6 +93,7 @@ def test_full_step_in_the_benchmark_configuration():
     try:
         assert st.n_offload > 0 and st.high_water <= cfg.cap_bytes
         names = ["y", "dx", "daq.0", "dbq.0", "dav.0", "dbv.0", f"daq.{last}", f"dbq.{last}", f"dav.{last}", f"dbv.{last}"]
+        names += [f"h.{l}" for l in probe if l != last] + [f"h.{l - 1}" for l in probe if l > 0]
         opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
         out, rep = s.run(opts, only=names)
         print(f"[c5] executed in {rep.wall_ms:.1f} ms ({cfg.tokens / rep.wall_ms * 1e3:.0f} tokens/s), "
@@ -114,6 +120,14 @@ def test_full_step_in_the_benchmark_configuration():
                         wide[id(a)] = R.widen_array(a)
                     w[k] = wide[id(a)]
             return w
+
+        # Forward pass layer by layer at the one-layer tolerance (B = 0: the adapters add nothing to it):
+        # the GPU's own input rows of a layer, the first 32 positions of the first and the last sequence,
+        # through one oracle layer with the storage rounding of the tiled execution
+        for l in probe:
+            for b in (0, cfg.batch - 1):
+                check_layer_rows(cfg, full, out, l, b, np.arange(32), 2e-2, False, "[c5]", wide)
+        print(f"[c5] layers {probe} checked one by one {time.time() - t0:.1f}s", flush=True)
 
         def rms_err(a, b):
             return float(np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2)))

@@ -22,6 +22,8 @@ from paper_2405_16283_amd import binding as B
 from paper_2405_16283_amd import harness as H
 from workloads import bf16_bits_to_f32, config, make_llama_inputs
 
+from util import check_layer_rows
+
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
 # Through {cfg.layers} layers a bf16 pipeline drifts from the exact result by far more than the one-layer
@@ -37,18 +39,22 @@ def _f64(a):
     return bf16_bits_to_f32(a).astype(np.float64)
 
 
-@pytest.mark.parametrize("name,PREFIX,distinct,kv", [("c3", 256, 4, True), ("c4", 16, 2, False)])
-def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, kv):
+@pytest.mark.parametrize("name,PREFIX,distinct,stride", [("c3", 256, 4, 8), ("c4", 16, 2, 20)])
+def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stride):
+    kv = True
     cfg = config(name)
     last = cfg.layers - 1
     t0 = time.time()
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     print(f"[{name}] inputs generated {time.time() - t0:.1f}s", flush=True)
-    s = H.GpuSession(cfg, full, kv_outputs=kv)
+    # K/V and the hidden state of pairs of neighbouring layers through the depth of the stack are outputs
+    s = H.GpuSession(cfg, full, kv_outputs=kv, hidden_outputs=True, output_layer_stride=stride)
+    probe = [0] + [l for l in range(stride, cfg.layers - 1, stride)] + [last]  # layers checked one by one
     print(f"[{name}] compiled and placed {time.time() - t0:.1f}s: {s.stats.n_vertices} vertices, "
           f"{s.stats.n_load} loads, {s.stats.n_offload} offloads, {s.stats.n_store} stores", flush=True)
     try:
-        names = ["y", "k.0", "v.0", f"k.{last}", f"v.{last}"] if kv else ["y"]
+        names = ["y"] + [f"{t}.{l}" for l in probe for t in ("k", "v")] + [f"h.{l}" for l in probe if l != last] \
+            + [f"h.{l - 1}" for l in probe if l > 0]
         opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
         out, rep = s.run(opts, only=names)
         print(f"[{name}] executed in {rep.wall_ms:.1f} ms ({cfg.tokens / rep.wall_ms * 1e3:.0f} tokens/s), "
@@ -78,6 +84,15 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, kv):
                 err = R.rel_err(_f64(out[tensor][:PREFIX]), ref)
                 print(f"[{name}] {tensor} prefix rel err {err:.3e}", flush=True)
                 assert err < 2e-2
+
+        # Layer by layer at the one-layer tolerance: the GPU's own input rows of a layer through one
+        # oracle layer (storage rounding as in the tiled execution); late rows attend to the GPU's
+        # stored keys and values of that layer, which are held to the same bar on those rows
+        rng = np.random.default_rng(11)
+        rows = np.unique(np.concatenate([np.arange(8), rng.integers(8, cfg.seq - 8, size=8), np.arange(cfg.seq - 8, cfg.seq)]))
+        for l in probe:
+            check_layer_rows(cfg, full, out, l, 0, rows, 2e-2, True, f"[{name}]", wide)
+        print(f"[{name}] layers {probe} checked one by one {time.time() - t0:.1f}s", flush=True)
 
         # the whole stack on the prefix: exact (float64, untiled), and tiled with the GPU path's
         # rounding points

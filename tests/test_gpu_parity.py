@@ -9,7 +9,7 @@ from paper_2405_16283_amd import binding as B
 from paper_2405_16283_amd import harness as H
 from workloads import bf16_bits_to_f32, config, make_llama_inputs
 
-from util import oracle_taskgraph
+from util import check_layer_rows, oracle_taskgraph
 
 pytestmark = pytest.mark.gpu
 
@@ -236,3 +236,23 @@ def test_generic_taskgraph_through_the_abi():
         B.tn_executor_destroy(ex)
         B.tn_memgraph_destroy(mg)
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name,stride", [("ragged_bf16", 0), ("c1", 0), ("batch2_f32", 0)])
+def test_every_layer_alone_against_the_oracle(name, stride):
+    """The check used on the deep workloads, on shapes where everything else is checked too: each
+    layer's input rows as the GPU produced them through one oracle layer, the GPU's stored keys and
+    values as the context of late rows."""
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 2)
+    s = H.GpuSession(cfg, full, kv_outputs=True, hidden_outputs=True, output_layer_stride=stride)
+    try:
+        print(f"[case] per-layer check {name}", flush=True)
+        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=9, queue_depth=2))
+        rows = np.array(sorted({0, 1, 5, cfg.seq // 2, cfg.seq - 2, cfg.seq - 1}))
+        for layer in range(cfg.layers):
+            for b in range(cfg.batch):
+                check_layer_rows(cfg, full, out, layer, b, rows, TOL[cfg.dtype], True, name)
+                check_layer_rows(cfg, full, out, layer, b, np.arange(8), TOL[cfg.dtype], False, name)
+    finally:
+        s.close()

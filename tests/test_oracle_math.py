@@ -172,3 +172,39 @@ def test_input_generator_is_counter_based_and_normal():
     # bf16 rounding: nearest, ties to even
     f = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7], dtype=np.float32)
     np.testing.assert_array_equal(bf16_bits_to_f32(to_bf16_bits(f)), [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7])
+
+
+def test_layer_on_sampled_rows_is_the_layer():
+    """decoder_layer_rows is pinned to decoder_layer: all rows as a prefix, a sample of rows with the
+    full run's keys and values as context, and -- with storage rounding -- to the tiled interpreter,
+    whose rounding points it repeats."""
+    from oracle import tiled as T
+    cfg = config("ragged_bf16")
+    w = R.widen(cfg, make_llama_inputs(cfg, 5))
+    x = w["x"][:cfg.seq]
+    args = (cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
+    y, k, v = R.decoder_layer(x, w, 1, *args, return_kv=True)
+    # every row, no context given
+    y2, k2, v2 = R.decoder_layer_rows(x, np.arange(cfg.seq), w, 1, *args)
+    for a, b in ((y2, y), (k2, k), (v2, v)):
+        np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-12)
+    # a few rows, early and late, against the full run's keys and values
+    rows = np.array([0, 1, 77, 200, cfg.seq - 1])
+    y3, k3, v3 = R.decoder_layer_rows(x[rows], rows, w, 1, *args, k_ctx=k, v_ctx=v)
+    for a, b in ((y3, y[rows]), (k3, k[rows]), (v3, v[rows])):
+        np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-12)
+    # a wrong position, a context from another layer, a swapped context must all show
+    bad, _, _ = R.decoder_layer_rows(x[rows], rows + 1, w, 1, *args, k_ctx=k, v_ctx=v)
+    assert R.rel_err(bad[2:], y[rows][2:]) > 1e-3
+    _, k0, v0 = R.decoder_layer(x, w, 0, *args, return_kv=True)
+    assert R.rel_err(R.decoder_layer_rows(x[rows], rows, w, 1, *args, k_ctx=k0, v_ctx=v0)[0][2:], y[rows][2:]) > 1e-3
+    assert R.rel_err(R.decoder_layer_rows(x[rows], rows, w, 1, *args, k_ctx=v, v_ctx=k)[0][2:], y[rows][2:]) > 1e-3
+    # with the storage rounding of the tiled execution: one layer of the tiled interpreter
+    one = cfg.with_(layers=1)
+    tg = T.build_llama_taskgraph(one)
+    w1 = {n: a for n, a in w.items() if n == "x" or n.endswith(".0")}
+    y_tiled = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w1)), one.tokens, one.d_model)
+    y_rows, _, _ = R.decoder_layer_rows(x, np.arange(cfg.seq), w, 0, *args, store=lambda z: T.round_store(z, "bf16"))
+    # blocked and unblocked softmax differ in the last bits of float64, which moves a rounding now and then
+    assert np.mean(y_rows != y_tiled) < 2e-3 and R.rel_err(y_rows, y_tiled) < 2.0 ** -7
+    assert R.rel_err(y_rows, R.decoder_layer(x, w, 0, *args)) > 1e-4  # the rounding is really applied

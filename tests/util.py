@@ -61,3 +61,45 @@ def check_all(preds, mg: M.MemGraph, n_random=20, seed=0, exhaustive=False):
         assert r["results"] == ref["results"]
         count += 1
     return count, ref
+
+
+def check_layer_rows(cfg, full, out, layer, seq_index, rows, tol, use_context, label="", wide_cache=None):
+    """One layer of a deep stack held to the one-layer tolerance: the GPU run's own input rows of
+    `layer` (x, or its hidden state after layer - 1) go through one oracle layer with the tiled
+    execution's storage rounding, and the GPU's output rows of that layer (hidden state after it,
+    or y) must agree within `tol`.  use_context: late rows attend to the GPU's stored keys and values
+    of that layer, which are themselves held to `tol` on the sampled rows; otherwise `rows` must be
+    a prefix 0..n-1.  `out` maps "h.l", "k.l", "v.l", "y" to the GPU's full tensors (storage type)."""
+    from oracle import llama_ref as R
+    from workloads import bf16_bits_to_f32
+
+    def f64(a):
+        return (bf16_bits_to_f32(a) if a.dtype == np.uint16 else a).astype(np.float64)
+
+    base = seq_index * cfg.seq
+    rows = np.asarray(rows)
+    src = full["x"] if layer == 0 else out[f"h.{layer - 1}"]
+    dst = out["y"] if layer == cfg.layers - 1 else out[f"h.{layer}"]
+    wide_cache = {} if wide_cache is None else wide_cache  # layers that share their arrays share the float64 copy
+    w = {}
+    for k, a in full.items():
+        if k.endswith(f".{layer}") and k.split(".")[0] in ("wq", "wk", "wv", "wo", "w1", "w2", "w3", "g1", "g2"):
+            if id(a) not in wide_cache:
+                wide_cache[id(a)] = R.widen_array(a)
+            w[k] = wide_cache[id(a)]
+    store = (lambda z: T.round_store(z, cfg.dtype))
+    kc = vc = None
+    if use_context:
+        kc = f64(out[f"k.{layer}"][base:base + cfg.seq])
+        vc = f64(out[f"v.{layer}"][base:base + cfg.seq])
+    y, k, v = R.decoder_layer_rows(f64(src[base + rows]), rows, w, layer, cfg.n_heads, cfg.head_dim, cfg.eps,
+                                   cfg.rope_base, k_ctx=kc, v_ctx=vc, store=store)
+    errs = {"h": R.rel_err(f64(dst[base + rows]), y)}
+    if use_context:
+        errs["k"] = R.rel_err(kc[rows], k)
+        errs["v"] = R.rel_err(vc[rows], v)
+    print(f"{label} layer {layer}, sequence {seq_index}, {len(rows)} rows up to position {int(rows.max())}: "
+          + ", ".join(f"{n} {e:.3e}" for n, e in errs.items()), flush=True)
+    for n, e in errs.items():
+        assert e < tol, (label, layer, n, e)
+    return errs
