@@ -28,7 +28,7 @@ def _oracle(cfg, full, tg_handle=None):
     return y_tiled, R.forward(cfg, w)
 
 
-@pytest.mark.parametrize("name", ["c1", "ragged_f32", "batch2_f32", "ragged_bf16"])
+@pytest.mark.parametrize("name", ["c1", "ragged_f32", "batch2_f32", "ragged_bf16", "mid_bf16"])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_forward_matches_oracle_under_the_cap(name, seed):
     cfg = config(name)
@@ -51,7 +51,7 @@ def test_forward_matches_oracle_under_the_cap(name, seed):
         s.close()
 
 
-@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16", "mid_bf16"])
 def test_twenty_dispatch_orders_and_transfer_delays_give_identical_bits(name):
     """Any dependency-respecting order must produce the same output (Introduction); the vertex
     kernels have a fixed summation order, so 'same' means bit for bit."""
@@ -238,18 +238,18 @@ def test_generic_taskgraph_through_the_abi():
         B.tn_taskgraph_destroy(tg)
 
 
-@pytest.mark.parametrize("name,stride", [("ragged_bf16", 0), ("c1", 0), ("batch2_f32", 0)])
-def test_every_layer_alone_against_the_oracle(name, stride):
+@pytest.mark.parametrize("name,layers", [("ragged_bf16", 2), ("c1", 2), ("batch2_f32", 1), ("mid_bf16", 3)])
+def test_every_layer_alone_against_the_oracle(name, layers):
     """The check used on the deep workloads, on shapes where everything else is checked too: each
     layer's input rows as the GPU produced them through one oracle layer, the GPU's stored keys and
     values as the context of late rows."""
-    cfg = config(name)
+    cfg = config(name).with_(layers=layers)
     full = make_llama_inputs(cfg, 2)
-    s = H.GpuSession(cfg, full, kv_outputs=True, hidden_outputs=True, output_layer_stride=stride)
+    s = H.GpuSession(cfg, full, kv_outputs=True, hidden_outputs=True)
     try:
         print(f"[case] per-layer check {name}", flush=True)
         out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=9, queue_depth=2))
-        rows = np.array(sorted({0, 1, 5, cfg.seq // 2, cfg.seq - 2, cfg.seq - 1}))
+        rows = np.array(sorted({0, 1, 5, cfg.seq // 2, cfg.seq // 2 + 1, cfg.seq - 34, cfg.seq - 2, cfg.seq - 1}))
         for layer in range(cfg.layers):
             for b in range(cfg.batch):
                 check_layer_rows(cfg, full, out, layer, b, rows, TOL[cfg.dtype], True, name)

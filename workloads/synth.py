@@ -69,6 +69,11 @@ CONFIGS: Dict[str, LlamaConfig] = {
                               0, 0.40, False, False),
     "ragged_bf16": LlamaConfig("ragged_bf16", 2, 256, 2, 128, 432, 320, 1, "bf16", 128, 256,
                                0, 0.40, False, False),
+    # mid-size bf16 shape whose tiles (384, last ones 288) are cut by the 256x256 MFMA GEMM kernel into
+    # blocks with ragged rows and columns, and whose attention blocks (768 = two row tiles, then 672)
+    # go through the MFMA attention kernel with head size 128
+    "mid_bf16": LlamaConfig("mid_bf16", 1, 1152, 9, 128, 1440, 1440, 1, "bf16", 384, 768,
+                            0, 0.40, False, False),
     "batch2_f32": LlamaConfig("batch2_f32", 1, 128, 2, 64, 176, 128, 2, "f32", 64, 64,
                               0, 0.50, False, False),
 }
