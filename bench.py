@@ -37,6 +37,13 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 
+# Transfer groups per workload where the defaults (32 copies per group, 8 copy workgroups) are not the best
+# measured choice.  c4 is bound by the host link: its copy launches compete for compute units with tile
+# products that hold a unit for 250 us each, so fewer, larger copy launches with more workgroups keep
+# the link busier (2.66 -> 2.51 s per step, 48.7 -> 51.6 GB/s); on the compute-bound c3 and c5 the same
+# setting costs 3-6 %.
+TRANSFERS = {"c4": (128, 16)}
+
 # steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)
 SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
 
@@ -164,10 +171,12 @@ def main():
               "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
     engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
 
-    def exec_opts(profile):
-        return B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=profile, max_transfers=args.max_transfers,
+    def exec_opts(profile, name=""):
+        mt, cw = TRANSFERS.get(name, (0, 0))
+        return B.tn_exec_opts(policy=policy, max_batch=args.max_batch, profile=profile,
+                              max_transfers=args.max_transfers or mt,
                               max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
-                              copy_workgroups=args.copy_workgroups, max_delay_us=args.max_delay_us, delay_seed=7,
+                              copy_workgroups=args.copy_workgroups or cw, max_delay_us=args.max_delay_us, delay_seed=7,
                               transfer_depth=args.transfer_depth)
 
     def timed(session, steps, warmup, opts, label):
@@ -252,19 +261,19 @@ def main():
         st = s.stats
         note(f"{name}: compiled and executor created: {int(st.n_vertices)} memgraph vertices, {int(st.n_offload)} offloads, "
              f"{int(st.n_load)} loads")
-        reps = timed(s, steps, warmup, exec_opts(1), name)
+        reps = timed(s, steps, warmup, exec_opts(1, name), name)
         ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
         # unprofiled steps, to show what the event pairs around every launch cost (short steps only)
         ms_plain = None
         if ms < 200:
-            plain = timed(s, max(1, min(3, steps), steps // 4), 1 if steps > 1 else 0, exec_opts(0), name + " (no event pairs)")
+            plain = timed(s, max(1, min(3, steps), steps // 4), 1 if steps > 1 else 0, exec_opts(0, name), name + " (no event pairs)")
             ms_plain = 1e3 * sum(dt for dt, _ in plain) / len(plain)
         y = s.outputs(only=["y"])["y"]
         # the same step with the outputs stored to pinned host memory (the rate that includes the host link)
         ms_host_out = None
         if device_outputs:
             sh = session(cfg, False)
-            rh = timed(sh, max(3, steps // 4), 1, exec_opts(1), name + " (outputs to host)")
+            rh = timed(sh, max(3, steps // 4), 1, exec_opts(1, name), name + " (outputs to host)")
             ms_host_out = 1e3 * sum(dt for dt, _ in rh) / len(rh)
             assert np.array_equal(sh.outputs(only=["y"])["y"], y)
             sh.close()
@@ -327,7 +336,9 @@ def main():
             "input_generation_s": t_gen, "build_and_compile_s": t_compile,
             "exec": {"compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
                      "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth,
-                     "copy_engine": args.copy_engine, "max_delay_us": args.max_delay_us, "k_split": k_split,
+                     "copy_engine": args.copy_engine, "max_transfers": args.max_transfers or TRANSFERS.get(name, (0, 0))[0] or 32,
+                     "copy_workgroups": args.copy_workgroups or TRANSFERS.get(name, (0, 0))[1] or 8,
+                     "max_delay_us": args.max_delay_us, "k_split": k_split,
                      "materialize_scores": bool(materialize), "checkpoint": bool(checkpoint)},
         }
         s.close()
