@@ -74,7 +74,7 @@ enum {
   TN_OP_RMS_BWD_APPLY = 11, /* dy, x, stat, dot, gain[, residual gradient] -> gradient of x            */
   TN_OP_ATTN_BWD = 12,      /* Q, K, V, dO tiles[, statistics][, transposed tiles] -> statistics, dQ, dK or dV (mode) */
   TN_OP_TRANSPOSE = 13,     /* X [rows, cols] -> X^T [cols, rows]                                      */
-  /* Section 8 (resources): a sum of n tensors is run as n increment kernels into an output
+  /* Appendix A (resources): a sum of n tensors is run as n increment kernels into an output
    * protected by a write lock.  P_0..P_{n-1}, all of the output's shape and type -> their sum.  In
    * the memgraph the vertex becomes TN_OP_ZERO, one TN_OP_SUM_INTO per operand and TN_MG_JOIN; the
    * increments run in whatever order their operands arrive, and each rounds the output to its
@@ -83,7 +83,7 @@ enum {
   TN_OP_ZERO = 15,          /* memgraph only: () -> zeros, the start of a sum's output               */
   TN_OP_SUM_INTO = 16,      /* memgraph only: P, accumulator -> accumulator += P, in place           */
   /* Softmax "in portions" over materialised attention scores (Introduction, second paragraph;
-   * Section 8, kernel list): the score tiles S_0..S_{n-1} of one row block, left to right
+   * Appendix A, hand-written kernels): the score tiles S_0..S_{n-1} of one row block, left to right
    * -> fp32 [rows, 2]: per row the maximum m of scale * s over the visible entries, then
    * l = sum exp(scale * s - m) over them.  Entry (r, c), c counted across the tiles, is visible
    * unless causal != 0 and k_pos0 + c > q_pos0 + r. */
@@ -241,7 +241,7 @@ typedef struct {
   int32_t train;
   /* > 1: every projection of the forward pass is cut along K into k_split partial products
    * (contiguous runs of ceil(nk / k_split) K tiles, one GEMM vertex each) joined by a TN_OP_SUM
-   * vertex -- the k-split + sum-into form of a matrix product (Section 8, resources).  0 or 1:
+   * vertex -- the k-split + sum-into form of a matrix product (Appendix A, resources).  0 or 1:
    * the whole K range inside one GEMM vertex. */
   int32_t k_split;
   /* != 0 (needs tile == head_dim, so that a column tile is one head, and train == 0): attention

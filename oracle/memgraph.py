@@ -24,7 +24,7 @@ Memgraph vertex kinds: "input" (tensor already in GPU memory at start), "load" (
 of an input), "op" (kernel call), "offload", "reload", "drop" (eviction of a tensor whose host
 copy is still valid: no bytes move), "store" (GPU -> host copy of a wanted result).
 
-A taskgraph vertex that sums n tensors takes the form Section 8 (resources) gives a reduction: an
+A taskgraph vertex that sums n tensors takes the form Appendix A (resources) gives a reduction: an
 output that several kernels increment under a write lock.  Its memgraph vertices are "zero" (the
 output is given its location and cleared; memory dependencies of the location point here),
 one "increment" per operand (operands: the tensor added, then the "zero" vertex; it owns no
@@ -98,7 +98,7 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
     cannot be co-resident.
 
     sums: taskgraph vertices that add up their operands by increments into a write-locked output
-    (Section 8, resources).  Such a vertex asks for no slot of its own when its turn comes: its
+    (Appendix A, resources).  Such a vertex asks for no slot of its own when its turn comes: its
     output is allocated and cleared ("zero") when its first operand has been produced, every
     operand is added by an "increment" placed right after the operand's producer, and the vertex
     itself becomes the "join" that takes the slot over.  The slot cannot be evicted while
@@ -254,59 +254,79 @@ def build_memgraph_uniform(preds: Sequence[Sequence[int]], V: Sequence[int], n_s
         post[i_u].append(i)
         sink[0] = None
 
+    def reserve_ahead() -> bool:
+        """The allocation horizon moves on by one vertex if that takes no eviction."""
+        nonlocal allocHzn
+        if allocHzn >= n:
+            return False
+        if V[allocHzn] in sums:  # a sum's output is placed with its first increment, not here
+            allocHzn += 1
+            return True
+        if simMalloc(V[allocHzn]) != -1:  # an open slot: the location of a result that does not exist yet
+            allocHzn += 1
+            return True
+        return False
+
+    def join_sum(s: int):
+        """Every operand of s has been added: the cleared-and-summed slot is now s's."""
+        nonlocal execHzn
+        z = acc[s]
+        slot = mg.loc[z][0]
+        mg.kind[s] = "join"
+        mg.loc[s] = mg.loc[z]
+        mg.operands[s] = [z]
+        for i in incs[s]:
+            add_edge(i, s, "data")
+        add_edge(z, s, "data")
+        readers[z].append(s)
+        readers[s] = readers[z]  # whoever takes the slot later waits for all of them and for s's readers
+        owner[slot] = s
+        open_acc.discard(z)
+        execHzn += 1
+        for w in sums_of[s]:
+            increment(w, s, execHzn - 1)
+        if sums_of[s] and next_use(s) > n:  # read by sums only, and they have taken it; a final result stays
+            simFree(s)
+
+    def run_next(v: int):
+        """The execution horizon passes v, whose output already has its slot."""
+        nonlocal execHzn
+        deps = list(preds[v])
+        # Algorithm 1 reloads, frees and adds the data edge dependency by dependency.  Freeing
+        # inside that loop would let a later dependency's reload land in the slot just
+        # vacated by an earlier dependency of the same vertex, which orders v before its own
+        # input; Section 7 puts all reloads "just before v", so: reload all, then add the
+        # data edges, then free.
+        for u in deps:
+            if name[u] in Evicted:
+                pinned = {name[w] for w in deps if name[w] not in Evicted} | {v}
+                simMallocForceReld(name[u], pinned)
+        for u in deps:
+            add_edge(name[u], v, "data")
+            mg.operands[v].append(name[u])
+            readers[name[u]].append(v)
+        execHzn += 1
+        for w in sums_of[v]:
+            increment(w, v, execHzn - 1)
+        for u in dict.fromkeys(list(deps) + ([v] if sums_of[v] else [])):
+            if next_use(u) > n and name[u] not in Evicted and mg.loc[name[u]] is not None \
+                    and owner[mg.loc[name[u]][0]] == name[u]:
+                simFree(name[u])
+
+    # Algorithm 1: run ahead with allocations while slots are open; otherwise the vertex at the
+    # execution horizon runs -- after an eviction on its behalf if it is the very vertex that
+    # could not be placed
     while execHzn < n:
-        if allocHzn < n and V[allocHzn] in sums:
-            allocHzn += 1  # a sum's output is allocated with its first increment
-        elif allocHzn < n and simMalloc(V[allocHzn]) != -1:
-            allocHzn += 1  # successfully allocated space for a future result
-        elif V[execHzn] in sums:
-            # the join: every operand has been added; the cleared-and-summed slot is now s's
-            s = V[execHzn]
-            z = acc[s]
-            slot = mg.loc[z][0]
-            mg.kind[s] = "join"
-            mg.loc[s] = mg.loc[z]
-            mg.operands[s] = [z]
-            for i in incs[s]:
-                add_edge(i, s, "data")
-            add_edge(z, s, "data")
-            readers[z].append(s)
-            readers[s] = readers[z]  # whoever takes the slot later waits for all of them and for s's readers
-            owner[slot] = s
-            open_acc.discard(z)
-            execHzn += 1
-            for w in sums_of[s]:
-                increment(w, s, execHzn - 1)
-            if sums_of[s] and next_use(s) > n:  # read by sums only, and they have taken it; a final result stays
-                simFree(s)
+        if reserve_ahead():
+            continue
+        v = V[execHzn]
+        if v in sums:
+            join_sum(v)
         elif allocHzn == execHzn:
-            v = V[allocHzn]
-            pinned = {name[u] for u in preds[v] if name[u] not in Evicted} | {v}
-            simMallocOffld(v, pinned)
+            simMallocOffld(v, {name[u] for u in preds[v] if name[u] not in Evicted} | {v})
             allocHzn += 1
         else:
-            v = V[execHzn]
-            deps = list(preds[v])
-            # Algorithm 1 reloads, frees and adds the data edge dependency by dependency.  Freeing
-            # inside that loop would let a later dependency's reload land in the slot just
-            # vacated by an earlier dependency of the same vertex, which orders v before its own
-            # input; Section 7 puts all reloads "just before v", so: reload all, then add the
-            # data edges, then free.
-            for u in deps:
-                if name[u] in Evicted:
-                    pinned = {name[w] for w in deps if name[w] not in Evicted} | {v}
-                    simMallocForceReld(name[u], pinned)
-            for u in deps:
-                add_edge(name[u], v, "data")
-                mg.operands[v].append(name[u])
-                readers[name[u]].append(v)
-            execHzn += 1
-            for w in sums_of[v]:
-                increment(w, v, execHzn - 1)
-            for u in dict.fromkeys(list(deps) + ([v] if sums_of[v] else [])):
-                if next_use(u) > n and name[u] not in Evicted and mg.loc[name[u]] is not None \
-                        and owner[mg.loc[name[u]][0]] == name[u]:
-                    simFree(name[u])
+            run_next(v)
     for i, v in enumerate(V):
         offs = [m for m in pre[i] if mg.kind[m] == "offload"]
         rels = [m for m in pre[i] if mg.kind[m] == "reload"]

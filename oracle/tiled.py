@@ -32,10 +32,10 @@ Vertex kinds (inputs -> output):
                                                         is visible unless causal and k_pos0 + c > q_pos0 + r, c counted
                                                         across the tiles.  With softmax_apply this is the softmax "in
                                                         portions" of materialised attention scores (Introduction,
-                                                        second paragraph; Section 8, item 1 of the kernel list)
+                                                        second paragraph; Appendix A, hand-written kernels)
   softmax_apply S, stat                              -> exp(scale * s - m) / l where visible, else 0; k_pos0 is the
                                                         position of this tile's first column
-  sum           p_0..p_{n-1}                         -> their sum, formed the way Section 8 (resources) describes a
+  sum           p_0..p_{n-1}                         -> their sum, formed the way Appendix A (resources) describes a
                                                         reduction: an output that starts at zero and receives the
                                                         n operands as n increments, each increment rounding the
                                                         output to its storage type.  The increments hold a write

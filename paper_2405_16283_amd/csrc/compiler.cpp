@@ -13,7 +13,7 @@
 // a byte-addressed first-fit allocator over [0, cap), an interval map of the last dead occupant
 // of every byte, and victim *windows* of adjacent blocks.
 //
-// Section 8 (resources): a vertex that sums n tensors runs as n increment kernels into an output
+// Appendix A (resources): a vertex that sums n tensors runs as n increment kernels into an output
 // protected by a write lock.  Here the output gets its location when the first operand has been
 // produced (a vertex that clears it; the memory dependencies of the location point there), every
 // operand is added by an increment vertex placed right after its producer -- so a partial product

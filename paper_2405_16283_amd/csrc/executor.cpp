@@ -781,7 +781,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
     return true;
   };
 
-  // Section 8 (resources): the output of a sum is protected by a write lock; an increment takes
+  // Appendix A (resources): the output of a sum is protected by a write lock; an increment takes
   // it when it is launched and gives it back when it has completed, and increments that find it
   // taken wait here, outside the ready lists
   std::vector<char> lock_busy(nv, 0);

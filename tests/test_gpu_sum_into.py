@@ -1,4 +1,4 @@
-"""GPU parity of the k-split + sum-into form of the projections (Section 8, resources): partial
+"""GPU parity of the k-split + sum-into form of the projections (Appendix A, resources): partial
 products over runs of K tiles, added by increment kernels into a write-locked output, in whatever
 order they arrive.  Each increment rounds the output to its storage type, so dispatch orders agree
 with the oracle and with each other within the tolerance, not bit for bit; with two partial

@@ -1,4 +1,4 @@
-"""The oracle's own BuildMemgraph with sum vertices (Section 8, resources: a reduction as
+"""The oracle's own BuildMemgraph with sum vertices (Appendix A, resources: a reduction as
 increments into a write-locked output): uniform slots, random graphs in which some vertices are
 sums, every slot count from roomy down to the smallest that compiles.  Each result must pass the
 three structural requirements of Section 6 and run correctly on the address-level memory model in

@@ -1,4 +1,4 @@
-"""Sum vertices: a reduction run as increments into a write-locked output (Section 8, resources),
+"""Sum vertices: a reduction run as increments into a write-locked output (Appendix A, resources),
 and the k-split form of the projections built on it.  CPU tests: the oracle's definition against
 plain sums and error bounds, the library's tiler against the oracle's, and the compiled memgraphs
 (clear, increments in any order, join) against the oracle's checkers and address-level simulator."""
