@@ -263,6 +263,14 @@ typedef struct {
    * the last two layers -- pairs of neighbouring layers through the depth of the stack, so that
    * a layer's input and output can both be read back without storing every layer.  0 or 1: all. */
   int32_t output_layer_stride;
+  /* > 0 (needs batch == 1, train == 0, materialize_scores == 0): after the prefill of `seq` positions,
+   * this many decode steps, fixed beforehand (Section 9, limitations: a memgraph compiled for a given
+   * number of generated tokens).  Step u runs the single row at position seq + u through all layers
+   * against the cached keys and values: the prefill's tiles, plus one single-row tile per generated
+   * position, so the attention block over the generated positions grows by a tile per step.  The
+   * row's embedding is an input, bound as row seq + u of x (there is no vocabulary to sample from);
+   * its result is row seq + u of y.  kv_outputs / hidden_outputs cover the decode rows too. */
+  int32_t decode_steps;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -82,7 +82,7 @@ def decoder_layer(x, w, layer: int, n_heads: int, head_dim: int, eps: float, bas
 
 
 def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim: int, eps: float, base: float,
-                       k_ctx=None, v_ctx=None, store=None):
+                       k_ctx=None, v_ctx=None, store=None, own_follow_ctx=False):
     """One decoder layer for a sample of the rows of one sequence.
 
     Every step of the layer works row by row except attention, in which the row at position p reads
@@ -92,7 +92,10 @@ def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim:
     None: the rows are positions 0..n-1 and their own keys and values are all there is to attend to
     (a causal prefix).  store: the rounding applied wherever the tiled execution stores a tensor (every
     taskgraph tensor is rounded to its storage type; attention partials and statistics are not);
-    None: exact.  Returns (output rows, key rows after the rotation, value rows).
+    None: exact.  own_follow_ctx: the context holds positions 0..n_ctx-1 and the rows given are the
+    positions n_ctx..n_ctx+n-1 that follow it, so each row attends to the context and to the given rows
+    up to itself (a decode step: the cache, then the new row).  Returns (output rows, key rows after the
+    rotation, value rows).
     """
     st = store if store is not None else (lambda z: z)
     h = np.asarray(h_rows, dtype=np.float64)
@@ -110,6 +113,9 @@ def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim:
         kc, vc = k, v
     else:
         kc, vc = np.asarray(k_ctx, dtype=np.float64), np.asarray(v_ctx, dtype=np.float64)
+        if own_follow_ctx:
+            assert np.array_equal(positions, kc.shape[0] + np.arange(n)), "the rows must follow the context"
+            kc, vc = np.concatenate([kc, k]), np.concatenate([vc, v])
     o = np.empty_like(q)
     for r in range(n):
         p = int(positions[r])
@@ -134,14 +140,46 @@ def forward(cfg, inputs_f64, n_tokens_prefix=None):
     prefill's rows [0, r) equal the model run on the first r tokens).
     """
     out = []
+    n = cfg.seq + getattr(cfg, "decode_steps", 0)  # positions per sequence
     for b in range(cfg.batch):
-        x = inputs_f64["x"][b * cfg.seq:(b + 1) * cfg.seq]
+        x = inputs_f64["x"][b * n:(b + 1) * n]
         if n_tokens_prefix is not None:
             x = x[:n_tokens_prefix]
         for l in range(cfg.layers):
             x = decoder_layer(x, inputs_f64, l, cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
         out.append(x)
     return np.concatenate(out, axis=0)
+
+
+def decode(cfg, inputs_f64, store=None):
+    """Prefill of the first cfg.seq positions of the one sequence, then cfg.decode_steps steps of one
+    position each (Section 9, limitations: generation with the number of steps fixed beforehand).
+
+    A step takes the embedding of its position (row seq + u of x: there is no vocabulary here, so the
+    row is given rather than sampled), and runs it through every layer against that layer's cache:
+    the keys and values of all earlier positions, to which the step appends its own.  Returns
+    (y [seq + steps, d], k, v) with k[l], v[l] [seq + steps, d] the caches at the end.  store: as in
+    decoder_layer_rows.  Since attention is causal, y equals forward() on all seq + steps positions.
+    """
+    assert cfg.batch == 1
+    P, N = cfg.seq, cfg.decode_steps
+    args = (cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
+    x = np.asarray(inputs_f64["x"], dtype=np.float64)
+    h = x[:P]
+    kc, vc = [], []
+    for l in range(cfg.layers):
+        h, k, v = decoder_layer_rows(h, np.arange(P), inputs_f64, l, *args, store=store)
+        kc.append(k)
+        vc.append(v)
+    ys = [h]
+    for u in range(N):
+        r = x[P + u:P + u + 1]
+        for l in range(cfg.layers):
+            r, k, v = decoder_layer_rows(r, [P + u], inputs_f64, l, *args, k_ctx=kc[l], v_ctx=vc[l], store=store,
+                                         own_follow_ctx=True)
+            kc[l], vc[l] = np.concatenate([kc[l], k]), np.concatenate([vc[l], v])
+        ys.append(r)
+    return np.concatenate(ys), kc, vc
 
 
 def widen_array(a: np.ndarray) -> np.ndarray:

@@ -277,6 +277,12 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
     never straddle sequences.  Attention runs per (sequence, head group, q block, kv block <= q
     block) with one partial per pair and one combine per output tile; blocks above the diagonal
     are never created.  A head group is the set of heads covering max(tile, head_dim) columns.
+
+    cfg.decode_steps > 0 (one sequence): after the prefill of cfg.seq positions, that many steps of one
+    row each (Section 9, limitations: the number of generated tokens is fixed when the graph is
+    built).  A step's key and value rows are single-row tiles that join the layer's cache; its
+    attention is one block per prefill block plus one block over the single-row tiles so far.  The
+    step's embedding is row seq + u of the input "x", its result row seq + u of "y".
     """
     tg = TaskGraph()
     dt, t, d, f, hd = cfg.dtype, cfg.tile, cfg.d_model, cfg.ffn, cfg.head_dim
@@ -386,17 +392,23 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
                                          col0=ci * t, rows=m, cols=n_, head_dim=hd, hpg=hpg)
         return o
 
+    steps = getattr(cfg, "decode_steps", 0)
+    assert steps == 0 or (cfg.batch == 1 and not materialize_scores)
+    weights, cache = [], []  # per layer: the weight grids, and the prefill's K (rotated) and V grids
     for l in range(cfg.layers):
         w = {k: input_tiles(f"{k}.{l}", dcols, dcols) for k in ("wq", "wk", "wv", "wo")}
         w["w1"] = input_tiles(f"w1.{l}", dcols, fcols)
         w["w3"] = input_tiles(f"w3.{l}", dcols, fcols)
         w["w2"] = input_tiles(f"w2.{l}", fcols, dcols)
         g1, g2 = gain_tiles(f"g1.{l}", dcols), gain_tiles(f"g2.{l}", dcols)
+        weights.append((w, g1, g2))
         for b in range(cfg.batch):
             x = xs[b]
             a = rmsnorm(x, g1, dcols)
             q, k, v = gemm(a, w["wq"], dcols), gemm(a, w["wk"], dcols), gemm(a, w["wv"], dcols)
-            o = attention(roped(q), roped(k), v)
+            k = roped(k)
+            cache.append((k, v))
+            o = attention(roped(q), k, v)
             h1 = ewise("add", x, gemm(o, w["wo"], dcols))
             bn = rmsnorm(h1, g2, dcols)
             act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
@@ -407,6 +419,46 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
                 tg.outputs.append(vtx)
                 tg.binding[vtx] = ("y", b * cfg.seq + rows[i][0], b * cfg.seq + rows[i][1],
                                    dcols[j][0], dcols[j][1])
+
+    # decode steps: position P + u, one row, through every layer against the layer's cache
+    P = cfg.seq
+    new_k = [[] for _ in range(cfg.layers)]  # per layer: one line of single-row tiles per step so far
+    new_v = [[] for _ in range(cfg.layers)]
+    for u in range(steps):
+        pos = P + u
+        x = input_tiles("x", [(pos, pos + 1)], dcols)
+        for l in range(cfg.layers):
+            w, g1, g2 = weights[l]
+            pk, pv = cache[l]
+            a = rmsnorm(x, g1, dcols)
+            q, k, v = gemm(a, w["wq"], dcols), gemm(a, w["wk"], dcols), gemm(a, w["wv"], dcols)
+            turn = lambda line: [tg.add("rope", [xv], tg.shape[xv], dt, pos0=pos, col0=dcols[j][0] % hd, head_dim=hd,
+                                        base=cfg.rope_base) for j, xv in enumerate(line)]
+            q, k = turn(q[0]), turn(k[0])
+            new_k[l].append(k)
+            new_v[l].append(v[0])
+            o = [None] * len(dcols)
+            for g in range(d // gw):
+                cts = list(range(g * ctg, (g + 1) * ctg))
+                common = dict(n_q_tiles=1, n_col_tiles=ctg, head_dim=hd, q_pos0=pos, causal=0, scale=1.0 / np.sqrt(hd))
+                parts = []
+                for bj, (k0, _) in enumerate(blocks):  # the prefill's blocks: all of their positions are earlier
+                    kj = tiles_of_block[bj]
+                    ins = [q[c] for c in cts] + [pk[r][c] for r in kj for c in cts] + [pv[r][c] for r in kj for c in cts]
+                    parts.append(tg.add("attn_block", ins, (1, gw + 2 * hpg), "f32", n_kv_tiles=len(kj), k_pos0=k0, **common))
+                ins = ([q[c] for c in cts] + [line[c] for line in new_k[l] for c in cts]
+                       + [line[c] for line in new_v[l] for c in cts])
+                parts.append(tg.add("attn_block", ins, (1, gw + 2 * hpg), "f32", n_kv_tiles=u + 1, k_pos0=P, **common))
+                for ci, c in enumerate(cts):
+                    n_ = dcols[c][1] - dcols[c][0]
+                    o[c] = tg.add("attn_combine", parts, (1, n_), dt, row0=0, col0=ci * t, rows=1, cols=n_, head_dim=hd, hpg=hpg)
+            h1 = ewise("add", x, gemm([o], w["wo"], dcols))
+            bn = rmsnorm(h1, g2, dcols)
+            act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
+            x = ewise("add", h1, gemm(act, w["w2"], dcols))
+        for j, vtx in enumerate(x[0]):
+            tg.outputs.append(vtx)
+            tg.binding[vtx] = ("y", pos, pos + 1, dcols[j][0], dcols[j][1])
     return tg
 
 

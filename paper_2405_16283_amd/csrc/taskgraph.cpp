@@ -513,6 +513,9 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.train && c.kv_outputs) return fail(TN_ERR_INVALID, "train and kv_outputs do not go together");
   if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
   if (c.output_layer_stride < 0) return fail(TN_ERR_INVALID, "output_layer_stride must not be negative");
+  if (c.decode_steps < 0) return fail(TN_ERR_INVALID, "decode_steps must not be negative");
+  if (c.decode_steps > 0 && (c.train || c.materialize_scores || c.batch != 1 || c.lora_rank > 0))
+    return fail(TN_ERR_INVALID, "decode_steps needs one sequence, and none of train, lora_rank, materialize_scores");
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
   if (c.materialize_scores && (c.tile != c.head_dim || c.train || c.kv_outputs))
     return fail(TN_ERR_INVALID, "materialize_scores needs tile == head_dim and neither train nor kv_outputs");
@@ -547,7 +550,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     Grid wq, wk, wv, wo, w1, w3, w2;
     std::vector<tn_vid> g1, g2, aq, bq, av, bv, aqT, bqT, avT, bvT;
   };
-  std::vector<LayerInputs> lin(c.train ? c.layers : 0);
+  std::vector<LayerInputs> lin(c.train || c.decode_steps ? c.layers : 0);
+  std::vector<Grid> kcache(c.decode_steps ? c.layers : 0), vcache(c.decode_steps ? c.layers : 0);  // K, V of the prefill
   const int32_t rk = c.lora_rank;
   const Range rkr{0, rk};
 
@@ -703,6 +707,10 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         }
       }
     }
+    if (c.decode_steps) {
+      kcache[l] = kk;
+      vcache[l] = vv;
+    }
   };
 
   for (int l = 0; l < c.layers; ++l) {
@@ -730,7 +738,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
       bvT.push_back(t.op(TN_OP_TRANSPOSE, tn_op_params{}, {bv[j]}, {c.dtype, n, rk}));
     }
     const LayerInputs w{wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv, aqT, bqT, avT, bvT};
-    if (c.train) lin[l] = w;
+    if (c.train || c.decode_steps) lin[l] = w;
     for (int b = 0; b < c.batch; ++b) {
       if (c.checkpoint) layer_in[l][b] = x[b];
       forward_layer(l, w, b, x[b], c.train && !c.checkpoint ? &saved[l][b] : nullptr, true);
@@ -749,6 +757,93 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         tg->bindings.push_back({id, TN_T_Y, -1, b * c.seq + t.rows[i].a, b * c.seq + t.rows[i].b,
                                 t.dcols[j].a, t.dcols[j].b, 0});
       }
+  // ---- decode steps, known in number beforehand (Section 9, limitations: the memgraph is compiled
+  // for a fixed number of generated tokens).  Step u runs the one row at position seq + u through
+  // every layer; its keys and values join the cache as single-row tiles, so the attention block over
+  // the generated positions grows by one tile per step, while the blocks over the prefill's stripes
+  // read the prefill's tiles.  The row's embedding is an input (there is no vocabulary here), bound
+  // as row seq + u of x; its output is row seq + u of y.
+  if (c.decode_steps > 0) {
+    const int32_t P = c.seq;
+    std::vector<std::vector<std::vector<tn_vid>>> kdec(c.layers), vdec(c.layers);  // [layer][step][column tile]
+    const float scale = 1.0f / std::sqrt((float)c.head_dim);
+    for (int u = 0; u < c.decode_steps; ++u) {
+      const Range rr{P + u, P + u + 1};
+      std::vector<tn_vid> xr(nd);
+      for (size_t j = 0; j < nd; ++j) xr[j] = t.input(1, t.dcols[j].len(), c.x_residency, TN_T_X, -1, rr, t.dcols[j]);
+      for (int l = 0; l < c.layers; ++l) {
+        const LayerInputs& w = lin[l];
+        auto a = t.rmsnorm(xr, w.g1, 1);
+        std::vector<tn_vid> q(nd), kr(nd), vr(nd);
+        for (size_t j = 0; j < nd; ++j) {
+          const int32_t n = t.dcols[j].len();
+          q[j] = t.rope(t.gemm(a, w.wq, j, 1, n), P + u, t.dcols[j].a, 1, n);
+          kr[j] = t.rope(t.gemm(a, w.wk, j, 1, n), P + u, t.dcols[j].a, 1, n);
+          vr[j] = t.gemm(a, w.wv, j, 1, n, c.v_transposed != 0);
+          if (c.kv_outputs && layer_is_output(l)) {
+            t.mark_output(kr[j], TN_T_K, l, rr, t.dcols[j]);
+            t.mark_output(vr[j], TN_T_V, l, rr, t.dcols[j]);
+            if (c.v_transposed) tg->bindings.back().transposed = 1;
+          }
+        }
+        kdec[l].push_back(kr);
+        vdec[l].push_back(vr);
+        std::vector<tn_vid> o(nd);
+        for (int32_t gi = 0; gi < n_groups; ++gi) {
+          std::vector<tn_vid> parts;
+          tn_op_params p{};
+          p.n_q_tiles = 1;
+          p.n_col_tiles = ctg;
+          p.head_dim = c.head_dim;
+          p.q_pos0 = P + u;
+          p.causal = 0;  // every cached position lies before the row's own
+          p.v_trans = c.v_transposed ? 1 : 0;
+          p.scale = scale;
+          for (size_t s2 = 0; s2 < stripes.size(); ++s2) {  // the prefill's stripes
+            std::vector<size_t> kt;
+            for (size_t i = 0; i < t.rows.size(); ++i)
+              if (t.rows[i].a >= stripes[s2].a && t.rows[i].a < stripes[s2].b) kt.push_back(i);
+            std::vector<tn_vid> in;
+            for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[gi * ctg + cc]);
+            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kcache[l][i][gi * ctg + cc]);
+            for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(vcache[l][i][gi * ctg + cc]);
+            p.n_kv_tiles = (int32_t)kt.size();
+            p.k_pos0 = stripes[s2].a;
+            parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, 1, gw + 2 * hpg}));
+          }
+          {  // the generated positions so far, this row's included: one single-row tile each
+            std::vector<tn_vid> in;
+            for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[gi * ctg + cc]);
+            for (int v = 0; v <= u; ++v) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kdec[l][v][gi * ctg + cc]);
+            for (int v = 0; v <= u; ++v) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(vdec[l][v][gi * ctg + cc]);
+            p.n_kv_tiles = u + 1;
+            p.k_pos0 = P;
+            parts.push_back(t.op(TN_OP_ATTN_BLOCK, p, std::move(in), {TN_F32, 1, gw + 2 * hpg}));
+          }
+          for (int32_t cc = 0; cc < ctg; ++cc) {
+            tn_op_params pc{};
+            pc.row0 = 0;
+            pc.col0 = cc * c.tile;
+            pc.head_dim = c.head_dim;
+            pc.hpg = hpg;
+            o[gi * ctg + cc] = t.op(TN_OP_ATTN_COMBINE, pc, parts, {c.dtype, 1, t.dcols[gi * ctg + cc].len()});
+          }
+        }
+        std::vector<tn_vid> h(nd);
+        for (size_t j = 0; j < nd; ++j) h[j] = t.add(xr[j], t.gemm(o, w.wo, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
+        auto bn = t.rmsnorm(h, w.g2, 1);
+        std::vector<tn_vid> act(nf);
+        for (size_t j = 0; j < nf; ++j) {
+          const int32_t n = t.fcols[j].len();
+          act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {t.gemm(bn, w.w1, j, 1, n), t.gemm(bn, w.w3, j, 1, n)}, {c.dtype, 1, n});
+        }
+        for (size_t j = 0; j < nd; ++j) xr[j] = t.add(h[j], t.gemm(act, w.w2, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
+        if (c.hidden_outputs && layer_is_output(l) && l + 1 < c.layers)
+          for (size_t j = 0; j < nd; ++j) t.mark_output(xr[j], TN_T_H, l, rr, t.dcols[j]);
+      }
+      for (size_t j = 0; j < nd; ++j) t.mark_output(xr[j], TN_T_Y, -1, rr, t.dcols[j]);
+    }
+  }
   if (c.train) {
     // ---- reverse pass for L = sum(y * probe): dL/dy is the probe itself ------------------------
     const size_t nr = t.rows.size();

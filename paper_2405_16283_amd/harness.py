@@ -41,7 +41,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         weights_transposed=int(weights_transposed), v_transposed=int(v_transposed),
         lora_rank=int(lora_rank), train=int(train), k_split=int(k_split),
         materialize_scores=int(materialize_scores), checkpoint=int(checkpoint),
-        hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride))
+        hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride),
+        decode_steps=int(getattr(cfg, "decode_steps", 0)))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:

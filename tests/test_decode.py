@@ -1,0 +1,90 @@
+"""The decode taskgraph and its memgraph on the CPU (Section 9, limitations: the number of generated
+tokens is fixed when the graph is compiled): the library's tiler against the oracle's tiler and
+against the oracle's row-by-row decode, and the compiled memgraph under the cap against the
+checkers of Section 6."""
+import numpy as np
+import pytest
+
+from oracle import llama_ref as R
+from oracle import tiled as T
+from paper_2405_16283_amd import binding as B
+from paper_2405_16283_amd import harness as H
+from workloads import config, make_llama_inputs
+
+from util import assemble_named, check_all, oracle_memgraph, oracle_taskgraph, task_preds
+
+
+@pytest.mark.parametrize("name", ["decode_f32", "decode_bf16"])
+def test_oracle_decode_graph_is_the_row_by_row_decode(name):
+    """The oracle's tiler + interpreter (blocked attention over prefill blocks and single-row tiles)
+    against decode(): exact arithmetic in float32 storage up to its rounding, and with bf16 storage
+    the same rounding points (a blocked softmax moves a rounding now and then)."""
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    tg = T.build_llama_taskgraph(cfg)
+    y = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
+    y_rows, _, _ = R.decode(cfg, w, store=lambda z: T.round_store(z, cfg.dtype))
+    y_exact = R.forward(cfg, w)
+    P = cfg.seq
+    if cfg.dtype == "f32":
+        assert R.rel_err(y, y_rows) < 1e-6 and R.rel_err(y[P:], y_exact[P:]) < 1e-5
+    else:
+        assert R.rel_err(y, y_rows) < 2.0 ** -6 and np.mean(y != y_rows) < 0.02
+        assert R.rel_err(y[P:], y_exact[P:]) < 2e-2
+    # the attention blocks of step u: one per prefill block and one over u + 1 single-row tiles
+    blocks = -(-cfg.seq // cfg.attn_block)
+    groups = cfg.d_model // max(cfg.tile, cfg.head_dim)
+    single = [v for v, k in enumerate(tg.kind) if k == "attn_block" and tg.shape[tg.inputs[v][-1]][0] == 1]
+    assert len(single) == cfg.decode_steps * cfg.layers * groups
+    assert sorted({tg.params[v]["n_kv_tiles"] for v in single}) == list(range(1, cfg.decode_steps + 1))
+    one_row = [v for v, k in enumerate(tg.kind) if k == "attn_block" and tg.shape[v][0] == 1]
+    assert len(one_row) == (blocks + 1) * len(single)
+
+
+@pytest.mark.parametrize("name", ["decode_f32", "decode_bf16"])
+@pytest.mark.parametrize("natural", [True, False])
+def test_library_decode_taskgraph_and_memgraph(name, natural):
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 1))
+    mine = T.build_llama_taskgraph(cfg)
+    y_own = T.assemble_outputs(mine, T.evaluate(mine, T.cut_inputs(mine, w)), cfg.tokens, cfg.d_model)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, kv_outputs=True, weights_transposed=not natural, v_transposed=not natural))
+    try:
+        otg = oracle_taskgraph(tg)
+        assert len(otg.kind) == len(mine.kind)
+        vals = T.evaluate(otg, T.cut_inputs(otg, w))
+        y_lib = assemble_named(otg, vals, "y", cfg.tokens, cfg.d_model)
+        if natural:
+            np.testing.assert_array_equal(y_lib, y_own)
+        else:  # transposed operands change the summation order of float64 products, hence a rounding now and then
+            assert R.rel_err(y_lib, y_own) < (2.0 ** -6 if cfg.dtype == "bf16" else 1e-6)
+        # K/V outputs cover every position, decode rows included
+        seen = {}
+        for v, nm, r0, r1, c0, c1, tr in H.bindings(tg):
+            if nm.startswith(("k.", "v.")) and otg.kind[v] != "input":
+                seen.setdefault(nm, np.zeros((cfg.tokens, cfg.d_model), dtype=bool))[r0:r1, c0:c1] = True
+        assert len(seen) == 2 * cfg.layers and all(m.all() for m in seen.values())
+
+        cap = H.cap_for(cfg, tg)
+        mg = B.tn_compile(tg, None, cap)
+        try:
+            st = B.tn_memgraph_stats(mg)
+            assert st.n_offload > 0 and st.high_water <= cap
+            omg = oracle_memgraph(mg)
+            check_all(task_preds(tg), omg, n_random=6, seed=3)
+            e = H.export_memgraph(mg)
+            kv = {v for v, nm, *_ in H.bindings(tg) if nm.startswith(("k.", "v."))}
+            assert any(e["kind"][v] in ("reload", "load") and e["src"][v] in kv for v in range(len(e["kind"])))
+        finally:
+            B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
+def test_decode_options_that_do_not_go_together_are_refused():
+    cfg = config("decode_f32")
+    for bad in (dict(train=True, lora_rank=4), dict(materialize_scores=True), dict(lora_rank=4)):
+        with pytest.raises(B.TurnipError):
+            B.tn_build_llama(H.llama_config_struct(cfg, **bad))
+    with pytest.raises(B.TurnipError):
+        B.tn_build_llama(H.llama_config_struct(cfg.with_(batch=2)))

@@ -208,3 +208,34 @@ def test_layer_on_sampled_rows_is_the_layer():
     # blocked and unblocked softmax differ in the last bits of float64, which moves a rounding now and then
     assert np.mean(y_rows != y_tiled) < 2e-3 and R.rel_err(y_rows, y_tiled) < 2.0 ** -7
     assert R.rel_err(y_rows, R.decoder_layer(x, w, 0, *args)) > 1e-4  # the rounding is really applied
+
+
+def test_decode_steps_give_the_rows_of_the_whole_sequence():
+    """decode() (prefill, then one row at a time against a cache that grows) is pinned by causality:
+    its rows are those of the plain layer-by-layer forward pass over all positions at once, and its
+    caches are that pass's keys and values.  A step that skips its own key, reads a stale cache or
+    sits at the wrong position must show."""
+    cfg = config("decode_f32")
+    w = R.widen(cfg, make_llama_inputs(cfg, 2))
+    assert w["x"].shape[0] == cfg.seq + cfg.decode_steps
+    y, kc, vc = R.decode(cfg, w)
+    ref = R.forward(cfg, w)  # decoder_layer on all seq + steps positions
+    assert ref.shape == y.shape == (cfg.seq + cfg.decode_steps, cfg.d_model)
+    np.testing.assert_allclose(y, ref, rtol=1e-10, atol=1e-11)
+    h = w["x"]
+    args = (cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
+    for l in range(cfg.layers):
+        h, k, v = R.decoder_layer(h, w, l, *args, return_kv=True)
+        np.testing.assert_allclose(kc[l], k, rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(vc[l], v, rtol=1e-10, atol=1e-11)
+    # the decode rows really depend on the cache and on their own position
+    P = cfg.seq
+    row = w["x"][P + 3:P + 4]
+    _, k0, v0 = R.decoder_layer(w["x"], w, 0, *args, return_kv=True)
+    good = R.decoder_layer(w["x"][:P + 4], w, 0, *args)[-1:]
+    ok, _, _ = R.decoder_layer_rows(row, [P + 3], w, 0, *args, k_ctx=k0[:P + 3], v_ctx=v0[:P + 3], own_follow_ctx=True)
+    np.testing.assert_allclose(ok, good, rtol=1e-10, atol=1e-11)
+    stale, _, _ = R.decoder_layer_rows(row, [P + 2], w, 0, *args, k_ctx=k0[:P + 2], v_ctx=v0[:P + 2], own_follow_ctx=True)
+    assert R.rel_err(stale, good) > 1e-4
+    no_own, _, _ = R.decoder_layer_rows(row, [P + 3], w, 0, *args, k_ctx=k0[:P + 3], v_ctx=v0[:P + 3])
+    assert R.rel_err(no_own, good) > 1e-4

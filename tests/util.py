@@ -34,6 +34,17 @@ def oracle_taskgraph(tg_handle) -> T.TaskGraph:
     return tg
 
 
+def assemble_named(tg: T.TaskGraph, values, name: str, rows: int, cols: int) -> np.ndarray:
+    """The output tensor `name` of an interpreted graph (a library graph may have several outputs, some
+    of them stored transposed), put together from its tiles; NaN where no tile lies."""
+    a = np.full((rows, cols), np.nan)
+    for v in tg.outputs:
+        b = tg.binding[v]
+        if b[0] == name:
+            a[b[1]:b[2], b[3]:b[4]] = values[v].T if len(b) > 5 and b[5] else values[v]
+    return a
+
+
 def task_preds(tg_handle):
     n = B.tn_taskgraph_num_vertices(tg_handle)
     return [B.tn_taskgraph_inputs(tg_handle, v) if B.tn_taskgraph_vertex(tg_handle, v).n_inputs else []

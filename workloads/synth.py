@@ -36,10 +36,16 @@ class LlamaConfig:
     x_resident: bool  # same for the input embeddings
     eps: float = 1e-6
     rope_base: float = 10000.0
+    decode_steps: int = 0  # single-row steps after the prefill of `seq` positions (one sequence only)
+
+    @property
+    def total_seq(self) -> int:
+        """Positions per sequence: the prefill's plus the decode steps'."""
+        return self.seq + self.decode_steps
 
     @property
     def tokens(self) -> int:
-        return self.seq * self.batch
+        return self.total_seq * self.batch
 
     @property
     def elem_bytes(self) -> int:
@@ -74,6 +80,12 @@ CONFIGS: Dict[str, LlamaConfig] = {
     # go through the MFMA attention kernel with head size 128
     "mid_bf16": LlamaConfig("mid_bf16", 1, 1152, 9, 128, 1440, 1440, 1, "bf16", 384, 768,
                             0, 0.40, False, False),
+    # prefill, then decode steps fixed in number: each step's keys and values join the cache as
+    # single-row tiles (prefill lengths that leave ragged last tiles and, for bf16, two stripes)
+    "decode_f32": LlamaConfig("decode_f32", 2, 256, 4, 64, 688, 120, 1, "f32", 64, 64,
+                              0, 0.40, False, False, decode_steps=8),
+    "decode_bf16": LlamaConfig("decode_bf16", 2, 256, 2, 128, 432, 320, 1, "bf16", 128, 256,
+                               0, 0.40, False, False, decode_steps=9),
     "batch2_f32": LlamaConfig("batch2_f32", 1, 128, 2, 64, 176, 128, 2, "f32", 64, 64,
                               0, 0.50, False, False),
 }
