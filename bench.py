@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--workload", default="",
                     help="time this workload alone (c1..c5, c2_capped40, or a parity shape); default: c4 as the "
                          "headline plus the sub-records of --subs")
+    ap.add_argument("--launch-trace", default="",
+                    help="write the timed launches of the headline workload's last step (family, vertices, workgroups or "
+                         "bytes, start and end in ms) to this .npy file")
     ap.add_argument("--subs", default="",
                     help="comma-separated sub-records, or 'none'; default c2,c2_capped40,c3,c5 when --workload is not given")
     ap.add_argument("--streams", type=int, default=0, help="compute streams; default: harness.BENCH_COMPUTE_STREAMS")
@@ -263,6 +266,8 @@ def main():
              f"{int(st.n_load)} loads")
         reps = timed(s, steps, warmup, exec_opts(1, name), name)
         ms = 1e3 * sum(dt for dt, _ in reps) / len(reps)
+        if headline and args.launch_trace:
+            np.save(args.launch_trace, B.tn_executor_last_launches(s.ex))
         # unprofiled steps, to show what the event pairs around every launch cost (short steps only)
         ms_plain = None
         if ms < 200:

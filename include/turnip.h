@@ -499,6 +499,22 @@ tn_status tn_execute_static(tn_executor* ex, const void* const* host_inputs, voi
  * launched them; returns the count. */
 int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap);
 
+/* One timed launch of the last run (Section 5: what the engine launched when, for judging how well a
+ * memgraph keeps the GPU and the link busy).  family: 0 tile products, 1 attention kernels, 2 everything
+ * else on the compute streams, 3 a group of host -> GPU copies, 4 a group of GPU -> host copies.
+ * work: workgroups of a kernel launch, bytes of a copy group.  Times in ms from the run's first stamp,
+ * taken by HIP events on the stream of the launch. */
+typedef struct {
+  int32_t family, n_vertices;
+  int64_t work;
+  float start_ms, end_ms;
+} tn_launch_record;
+
+/* The timed launches of the last tn_execute / tn_execute_static with opts.profile != 0, in launch order
+ * (none if the run was not profiled).  Copies up to cap records to out (out may be NULL); returns how
+ * many there are, or a negative tn_status.  The records live in memory set aside at creation. */
+int64_t tn_executor_last_launches(const tn_executor* ex, tn_launch_record* out, int64_t cap);
+
 #ifdef __cplusplus
 }
 #endif

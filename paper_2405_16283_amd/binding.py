@@ -101,6 +101,11 @@ class tn_exec_opts(C.Structure):
                 ("copy_workgroups", C.c_int32)]
 
 
+class tn_launch_record(C.Structure):
+    _fields_ = [("family", C.c_int32), ("n_vertices", C.c_int32), ("work", C.c_int64),
+                ("start_ms", C.c_float), ("end_ms", C.c_float)]
+
+
 class tn_exec_report(C.Structure):
     _fields_ = [("wall_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64),
                 ("n_vertices", C.c_int64), ("n_launches", C.c_int64), ("n_kernel_launches", C.c_int64),
@@ -152,6 +157,7 @@ SIGNATURES = {
     "tn_execute_static": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(tn_exec_opts),
                                       C.POINTER(tn_exec_report)]),
     "tn_executor_last_order": (C.c_int64, [_P, C.POINTER(C.c_int64), C.c_int64]),
+    "tn_executor_last_launches": (C.c_int64, [_P, C.POINTER(tn_launch_record), C.c_int64]),
 }
 
 _lib: Optional[C.CDLL] = None
@@ -363,6 +369,18 @@ def tn_execute_static(ex, host_inputs: Sequence[int], host_outputs: Sequence[int
     _check(lib().tn_execute_static(ex, _ptr_array(host_inputs), _ptr_array(host_outputs),
                                    C.byref(opts) if opts is not None else None, C.byref(rep)))
     return rep
+
+
+def tn_executor_last_launches(ex):
+    """The timed launches of the last profiled run as a structured numpy array
+    (family, n_vertices, work, start_ms, end_ms)."""
+    import numpy as np
+    n = lib().tn_executor_last_launches(ex, None, 0)
+    _check(min(n, 0))
+    buf = (tn_launch_record * max(1, n))()
+    k = lib().tn_executor_last_launches(ex, buf, n)
+    dt = np.dtype([("family", "<i4"), ("n_vertices", "<i4"), ("work", "<i8"), ("start_ms", "<f4"), ("end_ms", "<f4")])
+    return np.frombuffer(buf, dtype=dt, count=max(0, k)).copy()
 
 
 def tn_executor_last_order(ex, n: int) -> List[int]:

@@ -164,7 +164,9 @@ struct tn_executor {
   std::map<uint64_t, ArenaBlock> arena_map;
   std::map<uint64_t, std::set<uint64_t>> arena_free;  // size -> offsets of the free blocks of that size
   std::vector<hipEvent_t> prof_events;
-  std::vector<int> prof_family;
+  struct ProfRec { int32_t family, prof, n_vertices; int64_t work; };  // one timed launch of the last run
+  std::vector<ProfRec> prof_recs;
+  std::vector<tn_launch_record> launch_log;  // the same with its times, filled when the run ends
   // host buffers already found to be GPU-addressable pinned memory (start, end)
   std::vector<std::pair<const char*, const char*>> pinned_ranges;
   std::vector<std::pair<const char*, const char*>> device_ranges;  // callers' buffers in GPU memory
@@ -606,6 +608,8 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
       if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e)));
       ex->prof_events.push_back(ev);
     }
+    ex->prof_recs.reserve((size_t)pool / 2);
+    ex->launch_log.reserve((size_t)pool / 2);
   }
   tn_status s = build_tables(*ex);
   if (s != TN_OK) return bail(s);
@@ -844,7 +848,8 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
   if (opt.profile) {
     if (ex->prof_events.empty() || hipEventRecord(prof_base = ex->prof_events[prof_used++], ex->slots[0].stream) != hipSuccess)
       return fail(TN_ERR_HIP, "cannot record the profiling base event");
-    ex->prof_family.clear();
+    ex->prof_recs.clear();
+    ex->launch_log.clear();
   }
   const auto t_start = Clock::now();
   Batch batch;
@@ -953,8 +958,9 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       if (e == hipSuccess) e = hipEventRecord(xg.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }
       if (xg.prof >= 0) {
-        ex->prof_family.push_back(3 + dir);
-        ex->prof_family.push_back(xg.prof);
+        int64_t moved = 0;
+        for (int64_t m : tv) moved += (int64_t)mg.v[m].bytes;
+        ex->prof_recs.push_back({3 + dir, xg.prof, (int32_t)tv.size(), moved});
       }
       xg.verts = tv;
       xq[dir].push_back(std::move(xg));
@@ -1077,11 +1083,13 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       batch.base = (uint32_t)ex->info[same[0]].desc;
       for (int64_t m : same) batch.base = std::min(batch.base, (uint32_t)ex->info[m].desc);
       int32_t max_blocks = 0;
+      int64_t n_blocks = 0;
       double flops = 0, bytes = 0;
       for (int k = 0; k < batch.n; ++k) {
         const VInfo& v = ex->info[same[k]];
         batch.idx[k] = (uint16_t)(v.desc - batch.base);
         max_blocks = std::max(max_blocks, v.nblocks);
+        n_blocks += v.nblocks;
         flops += v.flops;
         bytes += v.bytes;
       }
@@ -1125,7 +1133,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       if (grp.family == 0) { ++rep.gemm_launches; rep.gemm_flops += flops; }
       else if (grp.family == 1) { ++rep.attn_launches; rep.attn_flops += flops; }
       else { ++rep.ewise_launches; rep.ewise_bytes += bytes; }
-      if (grp.prof >= 0) ex->prof_family.push_back(grp.family), ex->prof_family.push_back(grp.prof);
+      if (grp.prof >= 0) ex->prof_recs.push_back({grp.family, grp.prof, batch.n, n_blocks});
       grp.verts = same;
       ex->cqueue[si].push_back(std::move(grp));
       progressed = true;
@@ -1202,12 +1210,13 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
   if (status == TN_OK && opt.profile) {
     // device time per family and the union of kernel intervals
     std::vector<std::pair<float, float>> iv;
-    for (size_t k = 0; k + 1 < ex->prof_family.size(); k += 2) {
-      const int fam = ex->prof_family[k], p = ex->prof_family[k + 1];
+    for (const auto& r : ex->prof_recs) {
+      const int fam = r.family, p = r.prof;
       float t0 = 0, t1 = 0;
       if (hipEventElapsedTime(&t0, prof_base, ex->prof_events[p]) != hipSuccess ||
           hipEventElapsedTime(&t1, prof_base, ex->prof_events[p + 1]) != hipSuccess)
         continue;
+      ex->launch_log.push_back({r.family, r.n_vertices, r.work, t0, t1});
       if (fam >= 3) {  // transfers: time per direction, not part of the kernel-busy union
         (fam == 3 ? rep.h2d_ms : rep.d2h_ms) += t1 - t0;
         continue;
@@ -1268,6 +1277,13 @@ int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap)
   if (!ex) return TN_ERR_INVALID;
   const int64_t n = (int64_t)ex->last_order.size();
   for (int64_t i = 0; i < n && i < cap; ++i) out[i] = ex->last_order[i];
+  return n;
+}
+
+int64_t tn_executor_last_launches(const tn_executor* ex, tn_launch_record* out, int64_t cap) {
+  if (!ex) return fail(TN_ERR_INVALID, "NULL executor");
+  const int64_t n = (int64_t)ex->launch_log.size();
+  for (int64_t i = 0; out && i < cap && i < n; ++i) out[i] = ex->launch_log[(size_t)i];
   return n;
 }
 

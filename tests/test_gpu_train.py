@@ -29,7 +29,8 @@ def _case(name, b_std, **session):
 
 
 @pytest.mark.parametrize("name,b_std,tol", [("c1", 0.02, 1e-4), ("c1", 0.0, 1e-4), ("ragged_f32", 0.02, 1e-4),
-                                            ("batch2_f32", 0.02, 1e-4), ("ragged_bf16", 0.02, 4e-2)])
+                                            ("batch2_f32", 0.02, 1e-4), ("ragged_bf16", 0.02, 4e-2),
+                                            ("mid_bf16", 0.02, 4e-2)])
 def test_adapter_gradients_match_the_oracle_under_the_cap(name, b_std, tol):
     cfg, s, y_ref, g_ref = _case(name, b_std)
     try:
@@ -53,6 +54,31 @@ def test_adapter_gradients_match_the_oracle_under_the_cap(name, b_std, tol):
         o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
         for k in out:
             np.testing.assert_array_equal(o2[k], out[k])
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("name", ["ragged_bf16", "mid_bf16"])
+def test_twenty_dispatch_orders_of_the_fine_tuning_step_give_identical_bits(name):
+    """The reverse pass through the MFMA kernels (attention statistics, dQ, dK, dV at head size 128; on
+    mid_bf16 also the 256x256 tile products with ragged blocks and transposed operands) under the
+    cap: any dependency-respecting order, group size, queue depth and transfer delay gives the same
+    bits in y, dx and every adapter gradient."""
+    cfg, s, y_ref, g_ref = _case(name, 0.02)
+    try:
+        assert s.stats.n_offload > 0
+        ref, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1))
+        assert R.rel_err(_f64(cfg, ref["y"]), y_ref) < 4e-2 and R.rel_err(_f64(cfg, ref["dx"]), g_ref["x"]) < 4e-2
+        orders = set()
+        for seed in range(20):
+            delay, batch, depth = (0, 50, 500)[seed % 3], (1, 4, 0)[(seed // 3) % 3], (1, 3, 8)[(seed // 2) % 3]
+            print(f"[case] {name} train order_seed {seed} delay {delay} batch {batch} depth {depth}", flush=True)
+            out, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, delay_seed=100 + seed,
+                                          max_delay_us=delay, max_batch=batch, queue_depth=depth))
+            for k in ref:
+                np.testing.assert_array_equal(out[k], ref[k])
+            orders.add(tuple(s.last_order()))
+        assert len(orders) >= 15
     finally:
         s.close()
 
