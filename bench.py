@@ -37,12 +37,15 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 
-# Transfer groups per workload where the defaults (32 copies per group, 8 copy workgroups) are not the best
-# measured choice.  c4 is bound by the host link: its copy launches compete for compute units with tile
-# products that hold a unit for 250 us each, so fewer, larger copy launches with more workgroups keep
-# the link busier (2.66 -> 2.51 s per step, 48.7 -> 51.6 GB/s); on the compute-bound c3 and c5 the same
-# setting costs 3-6 %.
+# Executor options per workload where the defaults (32 copies per group, 8 copy workgroups, small groups of
+# tile products cut into 128x128 tiles) are not the best measured choice.  c4 is bound by the host link: its
+# copy launches compete for compute units with tile products that hold a unit for 250 us each, so fewer,
+# larger copy launches with more workgroups keep the link busier (55.9 GB/s host to GPU while copying
+# against 51 with the defaults); on the compute-bound c3 the same setting costs 20 %.  On c5 the small groups
+# of tile products appear while the link is the bottleneck (the reverse pass waits for reloads), and spread
+# over all compute units they slow the copy kernel more than they gain (1.34 against 1.30 s per step).
 TRANSFERS = {"c4": (128, 16)}
+SMALL_GEMM_TILES = {"c5": -1}
 
 # steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)
 SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
@@ -136,9 +139,12 @@ def main():
                     help="compile option max_lookahead_bytes in MiB; default unbounded, for the fine-tuning step half of the cap")
     ap.add_argument("--next-fit", type=int, default=-1, help="compile option next_fit; default 0, for the fine-tuning step 1")
     ap.add_argument("--cap-gb", type=float, default=0.0, help="GPU-memory cap in GB instead of the workload's own")
-    ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel"])
+    ap.add_argument("--copy-engine", default="auto", choices=["auto", "memcpy", "kernel", "kernel_in"])
     ap.add_argument("--copy-workgroups", type=int, default=0)
     ap.add_argument("--transfer-depth", type=int, default=0)
+    ap.add_argument("--d2h-workgroups", type=int, default=0)
+    ap.add_argument("--small-gemm-tiles", type=int, default=0,
+                    help="executor option small_gemm_tiles: 0 = default (128), negative = always 256x256 tiles")
     ap.add_argument("--train", type=int, default=-1,
                     help="1: fine-tuning step (adapters of rank 16 on q and v, probe loss, reverse pass); default: only for c5")
     ap.add_argument("--layers", type=int, default=0, help="run the workload's shape with this many layers instead of its own")
@@ -172,7 +178,7 @@ def main():
 
     policy = {"fifo": B.TN_POLICY_FIFO, "lifo": B.TN_POLICY_LIFO, "random": B.TN_POLICY_RANDOM,
               "by_order": B.TN_POLICY_BY_ORDER, "in_order": B.TN_POLICY_IN_ORDER}[args.policy]
-    engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL}[args.copy_engine]
+    engine = {"auto": B.TN_COPY_AUTO, "memcpy": B.TN_COPY_MEMCPY, "kernel": B.TN_COPY_KERNEL, "kernel_in": B.TN_COPY_KERNEL_IN}[args.copy_engine]
 
     def exec_opts(profile, name=""):
         mt, cw = TRANSFERS.get(name, (0, 0))
@@ -180,7 +186,8 @@ def main():
                               max_transfers=args.max_transfers or mt,
                               max_gemm_inflight=args.max_gemm_inflight, queue_depth=args.queue_depth, copy_engine=engine,
                               copy_workgroups=args.copy_workgroups or cw, max_delay_us=args.max_delay_us, delay_seed=7,
-                              transfer_depth=args.transfer_depth)
+                              transfer_depth=args.transfer_depth, small_gemm_tiles=args.small_gemm_tiles or SMALL_GEMM_TILES.get(name, 0),
+                              d2h_workgroups=args.d2h_workgroups)
 
     def timed(session, steps, warmup, opts, label):
         reps = []
@@ -343,6 +350,7 @@ def main():
                      "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth,
                      "copy_engine": args.copy_engine, "max_transfers": args.max_transfers or TRANSFERS.get(name, (0, 0))[0] or 32,
                      "copy_workgroups": args.copy_workgroups or TRANSFERS.get(name, (0, 0))[1] or 8,
+                     "small_gemm_tiles": args.small_gemm_tiles or SMALL_GEMM_TILES.get(name, 0) or 128,
                      "max_delay_us": args.max_delay_us, "k_split": k_split,
                      "materialize_scores": bool(materialize), "checkpoint": bool(checkpoint)},
         }

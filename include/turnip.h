@@ -406,8 +406,15 @@ enum { TN_POLICY_FIFO = 0, TN_POLICY_LIFO = 1, TN_POLICY_RANDOM = 2, TN_POLICY_B
 /* How transfers are carried out.  MEMCPY: one hipMemcpyAsync per tensor on the copy streams.
  * KERNEL: one grouped copy kernel per group of ready transfers, on the same streams; needs every
  * host buffer to be pinned memory the GPU can address (hipHostMalloc), else TN_ERR_INVALID.
- * AUTO: KERNEL when all host buffers of the call qualify, otherwise MEMCPY. */
-enum { TN_COPY_AUTO = 0, TN_COPY_MEMCPY = 1, TN_COPY_KERNEL = 2 };
+ * KERNEL_IN: the copy kernel for host -> GPU groups only.  GPU -> host copies go to the chip's copy
+ * engines: the tensors of a group are first gathered, by a copy inside GPU memory, into a staging
+ * slot (8 slots of 16 MiB of GPU memory that tn_executor_create allocates beside the caller's
+ * buffer) and leave with one hipMemcpyAsync per run of adjacent places in host memory: the offloads
+ * of a group get adjacent arena slots; stores are merged where the caller's buffers follow one
+ * another without a gap.  (Stores to host memory from a kernel are accepted slowly by
+ * the link and hold up the memory traffic of the kernels that run beside them.)
+ * AUTO: KERNEL_IN when all host buffers of the call qualify, otherwise MEMCPY. */
+enum { TN_COPY_AUTO = 0, TN_COPY_MEMCPY = 1, TN_COPY_KERNEL = 2, TN_COPY_KERNEL_IN = 3 };
 
 typedef struct {
   int32_t policy;        /* which ready vertex the loop takes first */
@@ -427,6 +434,10 @@ typedef struct {
                               while the host has not yet seen the previous one complete */
   int32_t copy_workgroups; /* TN_COPY_KERNEL: workgroups of a copy launch (each walks over 32 KiB pieces of the
                               group's tensors); 0 = default (8) */
+  int32_t d2h_workgroups;  /* TN_COPY_KERNEL: workgroups of a GPU -> host copy launch; 0 = copy_workgroups */
+  int32_t small_gemm_tiles; /* a group of bf16 tile products with at most this many 256x256 output tiles is launched
+                               with 128x128 tiles per workgroup instead (four times the workgroups, the same bits);
+                               0 = default (128), negative = never */
 } tn_exec_opts;
 
 typedef struct {
@@ -507,6 +518,7 @@ int64_t tn_executor_last_order(const tn_executor* ex, int64_t* out, int64_t cap)
 typedef struct {
   int32_t family, n_vertices;
   int64_t work;
+  double amount; /* algorithmic flops of a launch of family 0 or 1, algorithmic bytes of the others */
   float start_ms, end_ms;
 } tn_launch_record;
 

@@ -26,6 +26,7 @@ TN_HOST, TN_DEVICE = 0, 1
 TN_EDGE_DATA, TN_EDGE_MEM, TN_EDGE_ORDER = 0, 1, 2
 TN_POLICY_FIFO, TN_POLICY_LIFO, TN_POLICY_RANDOM, TN_POLICY_BY_ORDER, TN_POLICY_IN_ORDER = 0, 1, 2, 3, 4
 TN_COPY_AUTO, TN_COPY_MEMCPY, TN_COPY_KERNEL = 0, 1, 2
+TN_COPY_KERNEL_IN = 3
 UINT64_MAX = (1 << 64) - 1
 
 
@@ -98,11 +99,11 @@ class tn_exec_opts(C.Structure):
                 ("max_delay_us", C.c_uint32), ("max_batch", C.c_int32), ("profile", C.c_int32),
                 ("max_transfers", C.c_int32), ("copy_engine", C.c_int32),
                 ("max_gemm_inflight", C.c_int32), ("queue_depth", C.c_int32), ("transfer_depth", C.c_int32),
-                ("copy_workgroups", C.c_int32)]
+                ("copy_workgroups", C.c_int32), ("d2h_workgroups", C.c_int32), ("small_gemm_tiles", C.c_int32)]
 
 
 class tn_launch_record(C.Structure):
-    _fields_ = [("family", C.c_int32), ("n_vertices", C.c_int32), ("work", C.c_int64),
+    _fields_ = [("family", C.c_int32), ("n_vertices", C.c_int32), ("work", C.c_int64), ("amount", C.c_double),
                 ("start_ms", C.c_float), ("end_ms", C.c_float)]
 
 
@@ -373,13 +374,14 @@ def tn_execute_static(ex, host_inputs: Sequence[int], host_outputs: Sequence[int
 
 def tn_executor_last_launches(ex):
     """The timed launches of the last profiled run as a structured numpy array
-    (family, n_vertices, work, start_ms, end_ms)."""
+    (family, n_vertices, work, amount, start_ms, end_ms)."""
     import numpy as np
     n = lib().tn_executor_last_launches(ex, None, 0)
     _check(min(n, 0))
     buf = (tn_launch_record * max(1, n))()
     k = lib().tn_executor_last_launches(ex, buf, n)
-    dt = np.dtype([("family", "<i4"), ("n_vertices", "<i4"), ("work", "<i8"), ("start_ms", "<f4"), ("end_ms", "<f4")])
+    dt = np.dtype([("family", "<i4"), ("n_vertices", "<i4"), ("work", "<i8"), ("amount", "<f8"), ("start_ms", "<f4"),
+                   ("end_ms", "<f4")])
     return np.frombuffer(buf, dtype=dt, count=max(0, k)).copy()
 
 

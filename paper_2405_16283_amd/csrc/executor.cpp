@@ -56,6 +56,12 @@ struct Slot {  // one stream and the group it carries
   double flops = 0, bytes = 0;
 };
 
+constexpr int64_t kSmallGemmTiles = 128;
+// Offloads moved by the chip's copy engines (TN_COPY_KERNEL_IN) are first gathered, by a copy inside GPU
+// memory, into one of these staging slots, so that a whole group leaves with a single large copy.
+constexpr uint64_t kStageBytes = 16ull << 20;
+constexpr int kStageGatherWorkgroups = 64;  // see the launch of tile products in run_memgraph
+
 struct Group {  // one grouped kernel launch in flight on a compute stream
   std::vector<int64_t> verts;
   hipEvent_t done = nullptr;
@@ -136,6 +142,7 @@ struct tn_executor {
   char* dbase = nullptr;
   uint64_t dbytes = 0;
   char* arena = nullptr;
+  char* stage = nullptr;  // kMaxQueueDepth staging slots of kStageBytes in GPU memory, for GPU -> host copies
   uint64_t arena_bytes = 0;
   bool own_arena = false, poisoned = false;
   int n_compute = 0;
@@ -164,7 +171,7 @@ struct tn_executor {
   std::map<uint64_t, ArenaBlock> arena_map;
   std::map<uint64_t, std::set<uint64_t>> arena_free;  // size -> offsets of the free blocks of that size
   std::vector<hipEvent_t> prof_events;
-  struct ProfRec { int32_t family, prof, n_vertices; int64_t work; };  // one timed launch of the last run
+  struct ProfRec { int32_t family, prof, n_vertices; int64_t work; double amount; };  // one timed launch of the last run
   std::vector<ProfRec> prof_recs;
   std::vector<tn_launch_record> launch_log;  // the same with its times, filled when the run ends
   // host buffers already found to be GPU-addressable pinned memory (start, end)
@@ -432,6 +439,24 @@ bool arena_alloc(tn_executor& ex, uint64_t size, uint64_t* off) {
   return true;
 }
 
+// Largest free block: what a run of adjacent slots can take at most.
+uint64_t arena_largest_free(const tn_executor& ex) { return ex.arena_free.empty() ? 0 : ex.arena_free.rbegin()->first; }
+
+// Adjacent slots for n tensors (sizes rounded up to 256 bytes), each of which can be freed on its own.
+bool arena_alloc_run(tn_executor& ex, const uint64_t* sizes, int n, uint64_t* first) {
+  uint64_t total = 0;
+  for (int i = 0; i < n; ++i) total += (sizes[i] + 255) / 256 * 256;
+  if (!arena_alloc(ex, total, first)) return false;
+  ex.arena_map.erase(*first);
+  uint64_t at = *first;
+  for (int i = 0; i < n; ++i) {
+    const uint64_t sz = (sizes[i] + 255) / 256 * 256;
+    ex.arena_map[at] = {sz, true};
+    at += sz;
+  }
+  return true;
+}
+
 void arena_free(tn_executor& ex, uint64_t off) {
   auto it = ex.arena_map.find(off);
   it->second.used = false;
@@ -557,6 +582,10 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
     ex->own_arena = true;
   }
   if (ex->arena && ex->arena_bytes) ex->arena_device_visible = device_visible_host(*ex, ex->arena, ex->arena_bytes);
+  if (mg->stats.n_offload + mg->stats.n_store > 0) {
+    hipError_t e = hipMalloc((void**)&ex->stage, kStageBytes * kMaxQueueDepth);
+    if (e != hipSuccess) return bail(fail(TN_ERR_HIP, "hipMalloc of the offload staging slots: %s", hipGetErrorString(e)));
+  }
   // dependency structure
   const int64_t nv = (int64_t)mg->v.size();
   ex->indeg.assign(nv, 0);
@@ -654,6 +683,7 @@ void tn_executor_destroy(tn_executor* ex) {
   if (ex->d_image) (void)hipFree(ex->d_image);
   if (ex->h_image) (void)hipHostFree(ex->h_image);
   if (ex->own_arena && ex->arena) (void)hipHostFree(ex->arena);
+  if (ex->stage) (void)hipFree(ex->stage);
   delete ex;
 }
 
@@ -704,7 +734,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       return fail(TN_ERR_INVALID, "buffer of %s %d overlaps the executor's device buffer",
                   x.kind == TN_MG_LOAD ? "input" : "output", x.kind == TN_MG_LOAD ? (int)x.src : x.output_index);
   }
-  bool use_copy_kernel = opt.copy_engine != TN_COPY_MEMCPY;
+  bool kernel_copies = opt.copy_engine != TN_COPY_MEMCPY;
   bool any_on_device = false;  // a caller's buffer lies in GPU memory: hipMemcpyAsync is told to find the direction itself
   {
     bool ok = ex->arena_device_visible || mg.stats.n_offload == 0;
@@ -714,9 +744,9 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       else if (x.kind == TN_MG_STORE) ok = device_visible_host(*ex, host_outputs[x.output_index], x.bytes, &any_on_device);
     }
     if (!ok) any_on_device = true;  // not every buffer was looked at (pageable memory ends the scan)
-    if (use_copy_kernel && !ok && opt.copy_engine == TN_COPY_KERNEL)
+    if (kernel_copies && !ok && (opt.copy_engine == TN_COPY_KERNEL || opt.copy_engine == TN_COPY_KERNEL_IN))
       return fail(TN_ERR_INVALID, "copy_engine KERNEL needs every host buffer to be GPU-addressable pinned memory");
-    use_copy_kernel = use_copy_kernel && ok;
+    kernel_copies = kernel_copies && ok;
   }
   ex->remaining = ex->indeg;
   std::vector<int64_t> rem_enq(ex->indeg);           // dependencies not yet enqueued (kernels) or completed
@@ -857,7 +887,8 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
   std::deque<XGroup> xq[2];  // copy groups in flight, host to device and device to host
   int xring[2] = {0, 0};
   const int xdepth = std::max(1, std::min<int>(opt.transfer_depth > 0 ? opt.transfer_depth : 3, kMaxQueueDepth));
-  std::vector<int64_t> same, xverts, sort_b;
+  std::vector<int64_t> same, xverts, sort_b, stage_verts;
+  std::vector<uint64_t> stage_sizes, stage_run;
   std::vector<std::array<int64_t, 4>> sort_keys;
   std::vector<hipEvent_t> waited;
 
@@ -883,6 +914,19 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
         return false;
       };
       hipError_t e = hipSuccess;
+      // GPU -> host copies can be left to the copy engines of the chip while host -> GPU copies stay with the
+      // copy kernel (TN_COPY_KERNEL_IN); copies into a caller's buffer in GPU memory stay with the kernel
+      const bool use_copy_kernel = kernel_copies && !(dir == 1 && (opt.copy_engine == TN_COPY_KERNEL_IN || opt.copy_engine == TN_COPY_AUTO) && !any_on_device);
+      // ... and then the offloads of a group are gathered into a staging slot and leave as one copy
+      const bool staged = dir == 1 && kernel_copies && !use_copy_kernel && ex->stage;
+      char* const slot = staged ? ex->stage + (uint64_t)xring[1] * kStageBytes : nullptr;
+      uint64_t stage_used = 0;
+      stage_verts.clear();
+      stage_sizes.clear();
+      // copies handed to the runtime one by one are enqueued as the group is put together: their start stamp
+      // has to go first (given back below if the group stays empty)
+      int early_prof = -1;
+      if (!use_copy_kernel && opt.profile && prof_pair(&early_prof)) e = hipEventRecord(ex->prof_events[early_prof], sl.stream);
       // (copies inside GPU memory need no pipelining against the host link: one group takes all that fit)
       while (n_ready_x[dir] > 0 && (int)tv.size() < (inside_gpu && use_copy_kernel ? kMaxCopies : max_xfer) && e == hipSuccess) {
         int64_t m;
@@ -903,10 +947,41 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
           src = ex->arena + ex->arena_off[x.operands[0]];
           dst = ex->dbase + x.offset;
           inside_gpu = false;
-        } else if (x.kind == TN_MG_STORE) {
+        } else if (x.kind == TN_MG_STORE && !(staged && x.bytes <= kStageBytes)) {
           src = ex->dbase + mg.v[x.operands[0]].offset;
           dst = host_outputs[x.output_index];
           inside_gpu = inside_gpu && on_gpu(dst);
+        } else if (x.kind == TN_MG_STORE) {  // store by way of the staging slot
+          const uint64_t need = (x.bytes + 255) / 256 * 256;
+          if (stage_used + need > kStageBytes || copies.n >= kMaxCopies) break;
+          copies.it[copies.n++] = {ex->dbase + mg.v[x.operands[0]].offset, slot + stage_used, (uint32_t)x.bytes,
+                                   (uint32_t)copies.total_blocks};
+          copies.total_blocks += (int32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes);
+          stage_used += need;
+          stage_verts.push_back(m);
+          stage_sizes.push_back(x.bytes);
+          src = dst = nullptr;  // moved after the loop
+        } else if (staged && ex->arena && x.bytes <= kStageBytes) {  // offload by way of the staging slot
+          inside_gpu = false;
+          const uint64_t need = (x.bytes + 255) / 256 * 256;
+          if (stage_used + need > kStageBytes || copies.n >= kMaxCopies) break;  // the slot is full: the rest goes with the next group
+          if (arena_largest_free(*ex) < stage_used + need) {
+            if (!tv.empty() || !xq[1].empty()) break;  // what is queued (and later reloads) will free slots
+            if (!xq[0].empty() || n_ready_x[0] > 0) break;
+            status = fail(TN_ERR_ARENA, "pinned host arena of %llu bytes is exhausted (offload of %llu bytes)",
+                          (unsigned long long)ex->arena_bytes, (unsigned long long)x.bytes);
+            break;
+          }
+          copies.it[copies.n++] = {ex->dbase + mg.v[x.operands[0]].offset, slot + stage_used, (uint32_t)x.bytes,
+                                   (uint32_t)copies.total_blocks};
+          copies.total_blocks += (int32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes);
+          stage_used += need;
+          stage_verts.push_back(m);
+          stage_sizes.push_back(x.bytes);
+          arena_used += need;
+          rep.arena_high_water = std::max(rep.arena_high_water, arena_used);
+          ++rep.n_offload;
+          src = dst = nullptr;  // moved after the loop
         } else {  // offload
           inside_gpu = false;
           uint64_t off;
@@ -927,7 +1002,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
         if (use_copy_kernel) {
           copies.it[copies.n++] = {src, dst, (uint32_t)x.bytes, (uint32_t)copies.total_blocks};
           copies.total_blocks += (int32_t)((x.bytes + kCopyBlockBytes - 1) / kCopyBlockBytes);
-        } else {
+        } else if (src) {
           e = hipMemcpyAsync(dst, src, x.bytes,
                              any_on_device ? hipMemcpyDefault : dir == 0 ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, sl.stream);
           if (e != hipSuccess) break;
@@ -945,22 +1020,68 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
         ex->last_order.push_back(m);
       }
       if (status != TN_OK) break;
-      if (tv.empty() && e == hipSuccess) continue;
+      if (tv.empty() && e == hipSuccess) {
+        if (early_prof >= 0) prof_used -= 2;
+        continue;
+      }
       XGroup xg;
       xg.done = ex->xevents[dir][xring[dir]];
       xring[dir] = (xring[dir] + 1) % kMaxQueueDepth;
       // the start stamp goes after whatever the stream still carries; the group's copies are
       // queued behind it
-      if (e == hipSuccess && opt.profile) (void)prof_pair(&xg.prof);
-      if (e == hipSuccess && xg.prof >= 0) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
-      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, inside_gpu ? kDeviceCopyWorkgroups : opt.copy_workgroups, sl.stream);
+      if (early_prof >= 0) xg.prof = early_prof;
+      else if (e == hipSuccess && opt.profile && prof_pair(&xg.prof)) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
+      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, inside_gpu ? kDeviceCopyWorkgroups : (dir == 1 && opt.d2h_workgroups > 0) ? opt.d2h_workgroups : opt.copy_workgroups, sl.stream);
+      if (e == hipSuccess && !stage_verts.empty()) {
+        // adjacent arena slots for the gathered offloads (the largest free block was checked to suffice, and
+        // nothing has taken from the arena since), the gather inside GPU memory, then one copy to the host per
+        // run of tensors whose places in host memory follow one another as their places in the slot do
+        stage_run.clear();
+        for (size_t k = 0; k < stage_verts.size(); ++k)
+          if (mg.v[stage_verts[k]].kind == TN_MG_OFFLOAD) stage_run.push_back(stage_sizes[k]);
+        uint64_t at = 0;
+        if (!stage_run.empty() && !arena_alloc_run(*ex, stage_run.data(), (int)stage_run.size(), &at)) {
+          status = fail(TN_ERR_ARENA, "pinned host arena: no run of adjacent slots for %zu offloads", stage_run.size());
+          break;
+        }
+        e = launch_copies(copies, kStageGatherWorkgroups, sl.stream);
+        // A run may cross the padding behind a tensor (sizes are rounded up to 256 bytes in the slot) only where
+        // that padding is the library's own, in the arena: bytes between two of the caller's buffers are not ours.
+        char* run_dst = nullptr;
+        uint64_t run_src = 0, run_bytes = 0, run_pad = 0, in_slot = 0;
+        bool pad_is_ours = true;
+        auto flush = [&]() {
+          if (run_bytes) e = hipMemcpyAsync(run_dst, slot + run_src, run_bytes - run_pad, hipMemcpyDeviceToHost, sl.stream);
+          run_bytes = 0;
+        };
+        for (size_t k = 0; k < stage_verts.size() && e == hipSuccess; ++k) {
+          const MVertex& x = mg.v[stage_verts[k]];
+          const uint64_t sz = (stage_sizes[k] + 255) / 256 * 256;
+          char* dst;
+          if (x.kind == TN_MG_OFFLOAD) {
+            ex->arena_off[stage_verts[k]] = (int64_t)at;
+            dst = ex->arena + at;
+            at += sz;
+          } else {
+            dst = (char*)host_outputs[x.output_index];
+          }
+          if (run_bytes && !(dst == run_dst + run_bytes && (run_pad == 0 || pad_is_ours))) flush();
+          if (e != hipSuccess) break;
+          if (!run_bytes) { run_dst = dst; run_src = in_slot; }
+          run_bytes += sz;
+          run_pad = sz - stage_sizes[k];
+          pad_is_ours = x.kind == TN_MG_OFFLOAD;
+          in_slot += sz;
+        }
+        if (e == hipSuccess) flush();
+      }
       if (xg.prof >= 0) xg.done = ex->prof_events[xg.prof + 1];
       if (e == hipSuccess) e = hipEventRecord(xg.done, sl.stream);
       if (e != hipSuccess) { hip_fail("transfer", e); break; }
       if (xg.prof >= 0) {
         int64_t moved = 0;
         for (int64_t m : tv) moved += (int64_t)mg.v[m].bytes;
-        ex->prof_recs.push_back({3 + dir, xg.prof, (int32_t)tv.size(), moved});
+        ex->prof_recs.push_back({3 + dir, xg.prof, (int32_t)tv.size(), moved, (double)moved});
       }
       xg.verts = tv;
       xq[dir].push_back(std::move(xg));
@@ -1111,7 +1232,16 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       grp.done = ex->cevents[si][ring_next[si]];
       ring_next[si] = (ring_next[si] + 1) % kMaxQueueDepth;
       if (e == hipSuccess && opt.profile && prof_pair(&grp.prof)) e = hipEventRecord(ex->prof_events[grp.prof], stream);
-      if (e == hipSuccess) e = launch_batch(lead.cls, lead.dtype, lead.head_dim, tables, batch, max_blocks, stream);
+      // A group of tile products with at most kSmallGemmTiles 256x256 tiles leaves CUs without work for as long
+      // as one tile takes; cut into 128x128 tiles (at most four per 256x256 tile, two workgroups per CU) it is
+      // spread over four times as many workgroups that all run at once.  The bits do not depend on the form.
+      int launch_cls = lead.cls;
+      if (lead.cls == LC_GEMM_BF16_NT256 && n_blocks <= (opt.small_gemm_tiles > 0 ? opt.small_gemm_tiles : opt.small_gemm_tiles < 0 ? 0 : kSmallGemmTiles)) {
+        launch_cls = LC_GEMM_BF16_NT256_SMALL;
+        max_blocks *= 4;
+        n_blocks *= 4;
+      }
+      if (e == hipSuccess) e = launch_batch(launch_cls, lead.dtype, lead.head_dim, tables, batch, max_blocks, stream);
       // a timed launch completes with its second stamp: one event record less between two kernels
       if (grp.prof >= 0) grp.done = ex->prof_events[grp.prof + 1];
       if (e == hipSuccess) e = hipEventRecord(grp.done, stream);
@@ -1133,7 +1263,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       if (grp.family == 0) { ++rep.gemm_launches; rep.gemm_flops += flops; }
       else if (grp.family == 1) { ++rep.attn_launches; rep.attn_flops += flops; }
       else { ++rep.ewise_launches; rep.ewise_bytes += bytes; }
-      if (grp.prof >= 0) ex->prof_recs.push_back({grp.family, grp.prof, batch.n, n_blocks});
+      if (grp.prof >= 0) ex->prof_recs.push_back({grp.family, grp.prof, batch.n, n_blocks, grp.family == 2 ? bytes : flops});
       grp.verts = same;
       ex->cqueue[si].push_back(std::move(grp));
       progressed = true;
@@ -1216,7 +1346,7 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       if (hipEventElapsedTime(&t0, prof_base, ex->prof_events[p]) != hipSuccess ||
           hipEventElapsedTime(&t1, prof_base, ex->prof_events[p + 1]) != hipSuccess)
         continue;
-      ex->launch_log.push_back({r.family, r.n_vertices, r.work, t0, t1});
+      ex->launch_log.push_back({r.family, r.n_vertices, r.work, r.amount, t0, t1});
       if (fam >= 3) {  // transfers: time per direction, not part of the kernel-busy union
         (fam == 3 ? rep.h2d_ms : rep.d2h_ms) += t1 - t0;
         continue;

@@ -52,7 +52,10 @@ enum LaunchClass {
   LC_ZERO,           // clears a tensor: the start of a sum's output
   LC_SOFTMAX_STAT,   // row maximum and sum of exponentials over the score tiles of a row block
   LC_SOFTMAX_APPLY,  // probabilities of one score tile
-  LC_COUNT
+  LC_COUNT,
+  // Not a class of its own for grouping: the form in which a group of LC_GEMM_BF16_NT256 vertices is
+  // launched when it has too few 256x256 tiles to give every CU one (128x128 tiles, same bits).
+  LC_GEMM_BF16_NT256_SMALL
 };
 
 // Vertices per launch.  The list travels in the kernel arguments (4 KiB at most), as 16-bit

@@ -708,10 +708,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(DeviceTables t, Batch
 #ifndef TN_GEMM_WAVES
 #define TN_GEMM_WAVES 8
 #endif
-constexpr int G2_M = 256, G2_N = 256, G2_K = 32, G2_STAGES = 4;
-constexpr int G2_OPER_BYTES = G2_M * G2_K * 2;               // one operand of one stage: 16 KiB
-constexpr int G2_STAGE_BYTES = 2 * G2_OPER_BYTES;            // A then B
-constexpr int G2_LDS_BYTES = G2_STAGES * G2_STAGE_BYTES;     // 128 KiB
+constexpr int G2_K = 32, G2_STAGES = 4;
+// LDS of a workgroup with a tile of bm rows and as many columns: per stage bm x 32 of A, then of B
+constexpr int g2_lds_bytes(int bm) { return G2_STAGES * 2 * bm * G2_K * 2; }  // 128 KiB for 256, 64 KiB for 128
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -795,28 +794,36 @@ __device__ __forceinline__ void mfma_acc_drain() {
 #ifndef TN_GEMM_STAGGER
 #define TN_GEMM_STAGGER(w) (((w) >> 2) & 1)  // wavefronts w and w + 4 share a SIMD
 #endif
-template <int NW>
-__global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
-  constexpr int TJ = 16 / NW;             // 32-column MFMA tiles per wavefront (TI = 4 row tiles)
-  constexpr int NLD = 16 / NW;            // load instructions per thread, operand and step
+// NW wavefronts in two rows; each holds TI x TJ accumulator tiles of 32x32, so the workgroup's output
+// tile is 64 TI rows by as many columns: (8, 4) is the 256x256 tile, (4, 2) a 128x128 tile with half
+// the LDS and a quarter of the registers, two workgroups per CU, for launches too small to give every
+// CU a 256x256 tile.  Every output element sums its products in the same order of K in all forms (the
+// same MFMA, the same sequence of 16-deep slabs), so the forms agree bit for bit.
+template <int NW, int TI>
+__global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kernel(DeviceTables t, Batch b) {
   constexpr int WNS = NW / 2;             // wavefronts along N
+  constexpr int BM = 64 * TI, BN = BM;    // output tile of the workgroup
+  constexpr int TJ = 2 * TI / WNS;        // 32-column MFMA tiles per wavefront
+  constexpr int NLD = 4 * TI / NW;        // load instructions per thread, operand and step
+  constexpr int OPER_BYTES = BM * G2_K * 2, STAGE_BYTES = 2 * OPER_BYTES;
+  static_assert(TJ >= 1 && NLD >= 1 && BN == 32 * TJ * WNS, "tile shape");
   int bx, by;
   xcd_remap(bx, by);
   const OpDesc& d = t.descs[b.at(by)];
-  if (bx >= d.nblocks) return;
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int M = d.rows, N = d.cols, nk = d.p.nk;
+  const int tn_ = (N + BN - 1) / BN;
+  if (bx >= ((M + BM - 1) / BM) * tn_) return;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
   const void* const* ptrA = t.ptrs + d.ptr0;  // A_0.., then nk entries later B_0..
   const int* ksz = t.aux + d.aux0;
   bf16_t* const Cp = (bf16_t*)d.out;
-  const int tn_ = (N + G2_N - 1) / G2_N;
-  const int m0 = (bx / tn_) * G2_M, n0 = (bx % tn_) * G2_N;
+  const int m0 = (bx / tn_) * BM, n0 = (bx % tn_) * BN;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w / WNS, wn = w % WNS;
   const int l32 = lane & 31, g = lane >> 5;
 
-  f32x16 acc[4][TJ];
+  f32x16 acc[TI][TJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
@@ -852,13 +859,13 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
   const uint32_t lds0 = (uint32_t)(size_t)(lptr_t)lds;
   const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + w * 1024);
   auto issue = [&](int stage) {  // loads of the K step (kt, k0) into `stage`, then advance
-    const uint32_t dstA = ldsw + stage * G2_STAGE_BYTES;
+    const uint32_t dstA = ldsw + stage * STAGE_BYTES;
     const bf16_t* a = A + k0;
     const bf16_t* bq = B + k0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       load_lds16_so(a, offA[i], dstA + i * 1024 * NW);
-      load_lds16_so(bq, offB[i], dstA + G2_OPER_BYTES + i * 1024 * NW);
+      load_lds16_so(bq, offB[i], dstA + OPER_BYTES + i * 1024 * NW);
     }
     k0 += G2_K;
     if (k0 >= K && kt + 1 < nk) {
@@ -876,38 +883,41 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
 
   // fragment addresses inside a stage: row-major chunks, swizzled as above
   const int sw = (l32 >> 2) & 3;
-  const int fragA = ((wm * 128 + l32) * 4) * 16, fragB = G2_OPER_BYTES + ((wn * 32 * TJ + l32) * 4) * 16;
+  const int fragA = ((wm * 32 * TI + l32) * 4) * 16, fragB = OPER_BYTES + ((wn * 32 * TJ + l32) * 4) * 16;
   const int c0 = ((0 + g) ^ sw) * 16, c1 = ((2 + g) ^ sw) * 16;
 
   for (int s = 0; s < G2_STAGES - 1 && s < nsteps; ++s) issue(s);
   // Each step covers two MFMA slabs of 16 along K, held in the register sets (xa, xb) and
-  // (ya, yb).  While the eight MFMAs of one slab run, the fragments of the next slab are read,
+  // (ya, yb).  While the MFMAs of one slab run, the fragments of the next slab are read,
   // one LDS read after each MFMA: a wavefront can issue a short instruction in the shadow of
   // its own MFMA, so the reads cost no matrix-unit time, and both register sets keep their role
   // from step to step (no copies).  The second slab of a step is multiplied after the barrier
   // of the next step.
-  bf16x8 xa[4], xb[TJ], ya[4], yb[TJ];
+  bf16x8 xa[TI], xb[TJ], ya[TI], yb[TJ];
   const bool loads_first = __builtin_amdgcn_readfirstlane(TN_GEMM_STAGGER(w)) != 0;
 #define TN_READ_SLAB(DA, DB, COL)                                                                      \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) DA[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + COL);  \
+  _Pragma("unroll") for (int i = 0; i < TI; ++i) DA[i] = *(const bf16x8*)(st_ + fragA + i * 2048 + COL); \
   _Pragma("unroll") for (int j = 0; j < TJ; ++j) DB[j] = *(const bf16x8*)(st_ + fragB + j * 2048 + COL);
 #define TN_MFMA_SLAB(SA, SB)                                  \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i)               \
+  _Pragma("unroll") for (int i = 0; i < TI; ++i)              \
   _Pragma("unroll") for (int j = 0; j < TJ; ++j) mfma_acc(acc[i][j], SA[i], SB[j]);
   // one MFMA, then one LDS read, for as many reads as a slab has; the remaining MFMAs follow
 #define TN_INTERLEAVE()                                                          \
-  _Pragma("unroll") for (int q = 0; q < 4 + TJ; ++q) {                           \
+  _Pragma("unroll") for (int q = 0; q < (TI + TJ < TI * TJ ? TI + TJ : TI * TJ); ++q) { \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                           \
   }                                                                              \
-  __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ - (4 + TJ), 0);
+  if constexpr (TI * TJ > TI + TJ) __builtin_amdgcn_sched_group_barrier(0x008, TI * TJ - (TI + TJ), 0);
+  // stage s must have landed: at most the loads of the next two steps may still be in flight
+  // (2 NLD load instructions per thread and step)
+  constexpr int W2 = NLD == 4 ? 0x4F70 : 0x0F78, W1 = NLD == 4 ? 0x0F78 : 0x0F74;  // vmcnt(16 | 8), vmcnt(8 | 4)
+  static_assert(NLD == 2 || NLD == 4, "the wait counts above are written for 4 or 8 loads per step");
   for (int s = 0; s < nsteps; ++s) {
-    // stage s must have landed: at most the loads of the next two steps may still be in flight
-    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(NW == 4 ? 0x4F70 : 0x0F78);       // vmcnt(16 | 8)
-    else if (s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(NW == 4 ? 0x0F78 : 0x0F74);  // vmcnt(8 | 4)
+    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(W2);
+    else if (s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(W1);
     else __builtin_amdgcn_s_waitcnt(0x0F70);                                         // vmcnt(0)
     __syncthreads();
-    const char* st_ = lds + (s % G2_STAGES) * G2_STAGE_BYTES;
+    const char* st_ = lds + (s % G2_STAGES) * STAGE_BYTES;
     const bool more = s + G2_STAGES - 1 < nsteps;
     // Issuing a load stalls a wavefront for as long as the address path is busy with the loads
     // of the others, so the two wavefronts of a SIMD issue theirs at different points of a step.
@@ -936,7 +946,7 @@ __global__ void __launch_bounds__(64 * NW, 1) gemm_bf16_nt256_kernel(DeviceTable
 #undef TN_INTERLEAVE
   mfma_acc_drain();
 
-  store_c_tiles<4, TJ>(acc, Cp, M, N, m0 + wm * 128, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
+  store_c_tiles<TI, TJ>(acc, Cp, M, N, m0 + wm * 32 * TI, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1661,7 +1671,7 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
   switch (cls) {
     case LC_GEMM_F32: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
     case LC_GEMM_BF16_NT: return cdiv(d.rows, GB_M) * cdiv(d.cols, GB_N);
-    case LC_GEMM_BF16_NT256: return cdiv(d.rows, G2_M) * cdiv(d.cols, G2_N);
+    case LC_GEMM_BF16_NT256: return cdiv(d.rows, 256) * cdiv(d.cols, 256);
     case LC_RMS_STAT: return cdiv(d.rows, 4);
     case LC_RMS_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ROPE:
@@ -1744,10 +1754,17 @@ hipError_t launch_batch(int cls, int dtype, int head_dim, const DeviceTables& t,
     case LC_GEMM_F32: TN_LAUNCH_T(gemm_generic_kernel); break;
     case LC_GEMM_BF16_NT: hipLaunchKernelGGL(gemm_bf16_nt_kernel, grid, wg, 0, s, t, b); break;
     case LC_GEMM_BF16_NT256: {
-      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel<TN_GEMM_WAVES>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel<TN_GEMM_WAVES, 4>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, g2_lds_bytes(256));
       if (attr != hipSuccess) return attr;
-      hipLaunchKernelGGL(gemm_bf16_nt256_kernel<TN_GEMM_WAVES>, grid, dim3(64 * TN_GEMM_WAVES), G2_LDS_BYTES, s, t, b);
+      hipLaunchKernelGGL((gemm_bf16_nt256_kernel<TN_GEMM_WAVES, 4>), grid, dim3(64 * TN_GEMM_WAVES), g2_lds_bytes(256), s, t, b);
+      break;
+    }
+    case LC_GEMM_BF16_NT256_SMALL: {
+      static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_bf16_nt256_kernel<4, 2>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, g2_lds_bytes(128));
+      if (attr != hipSuccess) return attr;
+      hipLaunchKernelGGL((gemm_bf16_nt256_kernel<4, 2>), grid, dim3(256), g2_lds_bytes(128), s, t, b);
       break;
     }
     case LC_RMS_STAT: TN_LAUNCH_T(rms_stat_kernel); break;

@@ -28,7 +28,7 @@ def test_outputs_in_gpu_memory_carry_the_same_bits(name, tol):
     s = H.GpuSession(cfg, full, kv_outputs=True, device_outputs=True)
     try:
         assert s.out_slab.is_cuda and s.stats.n_offload > 0
-        for engine in (B.TN_COPY_AUTO, B.TN_COPY_KERNEL, B.TN_COPY_MEMCPY):
+        for engine in (B.TN_COPY_AUTO, B.TN_COPY_KERNEL, B.TN_COPY_MEMCPY, B.TN_COPY_KERNEL_IN):
             for seed in (0, 1):
                 print(f"[case] {name} device outputs, copy engine {engine}, order_seed {seed}", flush=True)
                 out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, copy_engine=engine,

@@ -158,8 +158,8 @@ def test_kv_outputs_match_the_oracle():
         s.close()
 
 
-@pytest.mark.parametrize("engine", [B.TN_COPY_MEMCPY, B.TN_COPY_KERNEL])
-def test_both_copy_engines_give_identical_bits(engine):
+@pytest.mark.parametrize("engine", [B.TN_COPY_MEMCPY, B.TN_COPY_KERNEL, B.TN_COPY_KERNEL_IN])
+def test_all_copy_engines_give_identical_bits(engine):
     cfg = config("ragged_bf16")
     s = H.GpuSession(cfg, make_llama_inputs(cfg, 0))
     try:
@@ -167,6 +167,33 @@ def test_both_copy_engines_give_identical_bits(engine):
         out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=3, copy_engine=engine, max_transfers=5))
         np.testing.assert_array_equal(out["y"], ref["y"])
         assert rep.n_offload == s.stats.n_offload > 0
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "mid_bf16", "decode_bf16"])
+def test_offloads_gathered_in_staging_slots_give_identical_bits(name):
+    """TN_COPY_KERNEL_IN: the offloads of a group are gathered into a staging slot in GPU memory and leave
+    with one copy into adjacent arena slots, from where each tensor is reloaded on its own; stores go
+    one by one.  Group sizes from one tensor to as many as fit, orders, delays and depths perturbed; K/V
+    outputs (stores) mixed in."""
+    cfg = config(name)
+    s = H.GpuSession(cfg, make_llama_inputs(cfg, 0), kv_outputs=True)
+    try:
+        assert s.stats.n_offload > 0
+        ref, rep0 = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, copy_engine=B.TN_COPY_KERNEL))
+        for seed in range(12):
+            mt, depth, td = (1, 3, 32, 128)[seed % 4], (1, 3, 8)[seed % 3], (1, 3, 8)[(seed // 2) % 3]
+            print(f"[case] {name} staged offloads, order_seed {seed}, max_transfers {mt}, queue_depth {depth}, "
+                  f"transfer_depth {td}", flush=True)
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, copy_engine=B.TN_COPY_KERNEL_IN,
+                                            max_transfers=mt, queue_depth=depth, transfer_depth=td,
+                                            max_delay_us=(0, 100)[seed % 2], delay_seed=seed))
+            assert rep.n_offload == s.stats.n_offload and rep.n_reload == s.stats.n_reload
+            assert rep.d2h_bytes == rep0.d2h_bytes and rep.h2d_bytes == rep0.h2d_bytes
+            assert rep.arena_high_water <= s.stats.host_arena_bytes
+            for k in ref:
+                np.testing.assert_array_equal(out[k], ref[k])
     finally:
         s.close()
 
