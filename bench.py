@@ -109,7 +109,7 @@ def main():
     ap.add_argument("--streams", type=int, default=0, help="compute streams; default: harness.BENCH_COMPUTE_STREAMS")
     ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
-    ap.add_argument("--max-gemm-inflight", type=int, default=2)
+    ap.add_argument("--max-gemm-inflight", type=int, default=1)
     ap.add_argument("--queue-depth", type=int, default=3)
     ap.add_argument("--policy", default="by_order", choices=["fifo", "lifo", "random", "by_order", "in_order"])
     ap.add_argument("--max-delay-us", type=int, default=0, help="inject a pseudo-random delay of up to this many microseconds into every transfer group")

@@ -154,10 +154,11 @@ def bench_compile_opts(cap_bytes: int, train: bool, lookahead=None, evict_ahead=
     A forward pass reserves memory as far ahead of the execution as memory allows: weights stream in
     early and nothing else competes.  The fine-tuning step keeps saved activations for the reverse
     pass, and reservations made without bound push those out only to fetch them back (measured on
-    the 32-layer workload: 75 GB of loads instead of 26 GB).  There the run-ahead is bounded by half
-    of the cap, every eviction frees an eighth of the cap beyond what it needs, and the allocator
-    walks through memory (next fit) instead of refilling the lowest hole (measured, same workload:
-    1.39 s per step; with a quarter and 1/32 of the cap 1.45-1.49 s).
+    the 32-layer workload: 75 GB of loads instead of 26 GB).  There the run-ahead is bounded by 3/8
+    of the cap, every eviction frees 1/32 of the cap beyond what it needs, and the allocator walks
+    through memory (next fit) instead of refilling the lowest hole (measured, same workload, with
+    GPU -> host copies on the copy engines: 1.20 s per step and 17.7 GB offloaded; with a half and an
+    eighth of the cap 1.25 s and 19.9 GB; without next fit 1.98 s).
 
     `pressed`: a forward pass under a cap far below its working set, where weights are loaded again
     and again.  The victim with the furthest next use is then the tile the running kernel reads, and
@@ -171,9 +172,9 @@ def bench_compile_opts(cap_bytes: int, train: bool, lookahead=None, evict_ahead=
         evict_ahead = cap_bytes // 4 if evict_ahead is None else evict_ahead
         next_fit = 1 if next_fit is None else next_fit
     if lookahead is None:
-        lookahead = cap_bytes // 2 if train else (1 << 64) - 1
+        lookahead = cap_bytes // 8 * 3 if train else (1 << 64) - 1
     if evict_ahead is None:
-        evict_ahead = cap_bytes // 8 if train else 0
+        evict_ahead = cap_bytes // 32 if train else 0
     if next_fit is None:
         next_fit = int(train)
     return B.tn_compile_opts(max_lookahead_bytes=lookahead, drop_clean_inputs=1, evict_ahead_bytes=evict_ahead,

@@ -28,7 +28,7 @@ def c2():
 
 
 def bench_opts(**kw):
-    return B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3, **kw)
+    return B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3, **kw)
 
 
 def test_c2_bench_configuration_matches_the_oracle_everywhere(c2):

@@ -55,7 +55,7 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
     try:
         names = ["y"] + [f"{t}.{l}" for l in probe for t in ("k", "v")] + [f"h.{l}" for l in probe if l != last] \
             + [f"h.{l - 1}" for l in probe if l > 0]
-        opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
+        opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3)
         if name == "c4":  # the launch configuration the benchmark times this workload in
             opts.max_transfers, opts.copy_workgroups = 128, 16
         out, rep = s.run(opts, only=names)

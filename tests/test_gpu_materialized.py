@@ -65,7 +65,7 @@ def test_c2_shape_with_materialized_scores():
     s = H.GpuSession(cfg, full, materialize_scores=True, n_compute=H.BENCH_COMPUTE_STREAMS)
     try:
         st = s.stats
-        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3))
+        out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3))
         y = _f64(cfg, out["y"])
 
         def rms_err(a, b):

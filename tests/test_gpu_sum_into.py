@@ -79,7 +79,7 @@ def test_c2_with_k_split_two_matches_the_oracle():
     print("[case] c2 full size, k_split 2, bench configuration", flush=True)
     s = H.GpuSession(cfg, full, k_split=2, n_compute=H.BENCH_COMPUTE_STREAMS)
     try:
-        opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=2, queue_depth=3)
+        opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3)
         out, rep = s.run(opts)
         y = _f64(cfg, out["y"])
 
