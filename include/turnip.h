@@ -463,8 +463,9 @@ typedef struct {
  * for the executor's lifetime.  pinned_arena: pinned host memory for offloaded tensors, or NULL
  * to let the library allocate arena_bytes itself (arena_bytes 0 = the memgraph's safe bound).
  * Streams are hipStream_t values created by the caller at default priority; n_compute >= 1.
- * Creation allocates the operand tables the kernels read (GPU memory plus a pinned host image)
- * and every event a run can need; nothing is allocated or created later. */
+ * Creation allocates the operand tables the kernels read (GPU memory plus a pinned host image),
+ * the staging slots of GPU -> host copies (8 x 16 MiB of GPU memory, see TN_COPY_KERNEL_IN) and
+ * every event a run can need; nothing is allocated or created later. */
 tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t device_bytes,
                              void* pinned_arena, uint64_t arena_bytes, void* const* compute_streams,
                              int32_t n_compute, void* h2d_stream, void* d2h_stream,
