@@ -116,8 +116,11 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=-1,
                     help="tokens of the CPU-oracle sample; 0 = skip; default: 4096 for one layer, 64 for deep workloads")
     ap.add_argument("--capped", action="store_true", help=argparse.SUPPRESS)  # now a sub-record: --subs c2_capped40
-    ap.add_argument("--order", default="tiler", choices=["tiler", "level"],
-                    help="serial order given to the compiler: the tiler's (stripe by stripe) or level by level")
+    ap.add_argument("--order", default="", choices=["", "tiler", "level", "clustered"],
+                    help="serial order given to the compiler (default: the workload's own, harness.BENCH_ORDER, else the "
+                         "tiler's): the tiler's (stripe by stripe), level by level, or level by "
+                         "level with reductions next to their operands and the vertices of a level ordered by the weight "
+                         "tile they read (tn_taskgraph_clustered_order)")
     ap.add_argument("--evict-ahead-mb", type=int, default=-1,
                     help="compile option evict_ahead_bytes in MiB; default 0, for the fine-tuning step 1/8 of the cap")
     ap.add_argument("--checkpoint", action="store_true",
@@ -208,12 +211,13 @@ def main():
         steps.  Returns (record, cfg, full inputs, y)."""
         capped40 = name == "c2_capped40"
         cfg = config("c2" if capped40 else name)
-        pressed = level = False
+        pressed = False
         if capped40:
-            # everything streamed from the host, the cap at 40 % of the uncapped peak; level-by-level
-            # serial order, so that every weight tile is loaded once per step
+            # everything streamed from the host, the cap at 40 % of the uncapped peak; clustered serial
+            # order, so that every weight tile is loaded once per step and reductions follow their operands
             cfg = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
-            pressed = level = True
+            pressed = True
+        level = H.BENCH_ORDER.get(name, "")
         if headline:  # the shape-changing flags apply to the workload named on the command line only
             if args.layers > 0:
                 cfg = cfg.with_(layers=args.layers)
@@ -223,7 +227,8 @@ def main():
                 cfg = cfg.with_(tile=cfg.head_dim)
             if args.host_inputs:
                 cfg = cfg.with_(weights_resident=False, x_resident=False)
-            level = level or args.order == "level"
+            if args.order:
+                level = "" if args.order == "tiler" else args.order
         materialize = headline and args.materialize_scores
         checkpoint = headline and args.checkpoint
         k_split = args.k_split if headline else 0
@@ -252,7 +257,7 @@ def main():
                 B.tn_taskgraph_destroy(tg)
             if level:
                 tg = B.tn_build_llama(struct(c))
-                order = B.tn_taskgraph_level_order(tg)
+                order = (B.tn_taskgraph_clustered_order if level == "clustered" else B.tn_taskgraph_level_order)(tg)
                 B.tn_taskgraph_destroy(tg)
             cap = c.cap_bytes or 0
             hl = headline
@@ -316,7 +321,7 @@ def main():
             "ms_per_step": ms, "tokens_per_s": cfg.tokens / (ms * 1e-3),
             "gpu_cap_bytes": s.cap, "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
             "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
-            "serial_order": "level" if level else "tiler",
+            "serial_order": level or "tiler",
             "memgraph": {"vertices": int(st.n_vertices), "offloads": int(st.n_offload), "reloads": int(st.n_reload),
                          "loads": int(st.n_load), "drops": int(st.n_drop), "stores": int(st.n_store),
                          "mem_edges": int(st.n_mem_edges), "offload_GB": st.offload_bytes / 1e9,

@@ -215,6 +215,18 @@ int32_t tn_taskgraph_inputs(const tn_taskgraph* tg, tn_vid v, tn_vid* out, int32
  * per row stripe.  out receives all vertex ids; cap = room in out, at least the vertex count. */
 tn_status tn_taskgraph_level_order(const tn_taskgraph* tg, tn_vid* out, int64_t cap);
 
+/* A serial order V for caps far below the working set (Section 6 takes V as given and notes that the
+ * quality of the memgraph depends on it): level by level as above, with two changes that keep the live
+ * set small.  (1) A kernel vertex whose kernel operands all lie one level below it and are read by
+ * nothing but vertices with the very same operand list (the combine of attention partials, the product
+ * of the two gated projections, a sum of partial products, a rotation of a projection) is placed, with
+ * those vertices, right after its operands, and the operands of one such group are placed together:
+ * the operands die at once instead of waiting for the whole level.  (2) Within a level, vertices and
+ * such groups are ordered by the first input they read, then by their numbering, so that everything
+ * that reads one weight tile is adjacent and the tile is needed for one stretch of the order only.  An
+ * input comes right before its first reader.  out receives all vertex ids; cap as above. */
+tn_status tn_taskgraph_clustered_order(const tn_taskgraph* tg, tn_vid* out, int64_t cap);
+
 /* A tiled LLaMA-style decoder forward pass as a taskgraph (the paper's workload, Section 8;
  * the decomposition into tiles is this library's, since the paper leaves taskgraph production
  * to an outside framework, Section 4 second paragraph). */

@@ -137,6 +137,7 @@ SIGNATURES = {
     "tn_taskgraph_vertex": (C.c_int32, [_P, C.c_int32, C.POINTER(tn_tg_vertex)]),
     "tn_taskgraph_inputs": (C.c_int32, [_P, C.c_int32, C.POINTER(C.c_int32), C.c_int32]),
     "tn_taskgraph_level_order": (C.c_int32, [_P, C.POINTER(C.c_int32), C.c_int64]),
+    "tn_taskgraph_clustered_order": (C.c_int32, [_P, C.POINTER(C.c_int32), C.c_int64]),
     "tn_build_llama": (C.c_int32, [C.POINTER(tn_llama_config), C.POINTER(_P)]),
     "tn_taskgraph_num_bindings": (C.c_int64, [_P]),
     "tn_taskgraph_binding": (C.c_int32, [_P, C.c_int64, C.POINTER(tn_llama_binding)]),
@@ -261,6 +262,13 @@ def tn_taskgraph_level_order(tg) -> List[int]:
     n = tn_taskgraph_num_vertices(tg)
     buf = (C.c_int32 * max(1, n))()
     _check(lib().tn_taskgraph_level_order(tg, buf, n))
+    return list(buf[:n])
+
+
+def tn_taskgraph_clustered_order(tg) -> List[int]:
+    n = tn_taskgraph_num_vertices(tg)
+    buf = (C.c_int32 * max(1, n))()
+    _check(lib().tn_taskgraph_clustered_order(tg, buf, n))
     return list(buf[:n])
 
 

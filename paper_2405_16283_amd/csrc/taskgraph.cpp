@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <limits>
 
 #include "graph.h"
 
@@ -479,6 +480,113 @@ tn_status tn_taskgraph_level_order(const tn_taskgraph* tg, tn_vid* out, int64_t 
   for (int64_t v = 0; v < n; ++v) order[v] = (tn_vid)v;
   std::stable_sort(order.begin(), order.end(), [&](tn_vid a, tn_vid b) { return key[a] < key[b]; });
   std::copy(order.begin(), order.end(), out);
+  return TN_OK;
+}
+
+tn_status tn_taskgraph_clustered_order(const tn_taskgraph* tg, tn_vid* out, int64_t cap) {
+  if (!tg || !out) return fail(TN_ERR_INVALID, "NULL argument");
+  const int64_t n = (int64_t)tg->v.size();
+  if (cap < n) return fail(TN_ERR_INVALID, "room for %lld vertex ids, the graph has %lld", (long long)cap, (long long)n);
+  auto is_input = [&](tn_vid u) { return tg->v[u].kind == TN_OP_INPUT; };
+  std::vector<int64_t> lv(n, 0);  // level of a kernel vertex as in the level order; 0 for inputs
+  std::vector<std::vector<tn_vid>> readers(n);
+  for (int64_t v = 0; v < n; ++v) {
+    if (is_input((tn_vid)v)) continue;
+    int64_t l = 0;
+    for (tn_vid u : tg->v[v].in) {
+      if (!is_input(u)) l = std::max(l, lv[u]);
+      if (readers[u].empty() || readers[u].back() != (tn_vid)v) readers[u].push_back((tn_vid)v);
+    }
+    lv[v] = l + 1;
+  }
+  // Reductions: kernel vertices whose kernel operands all lie one level below and are read by nothing but
+  // vertices with this very operand list.  Such a vertex, the vertices that share its operand list and the
+  // operands form a cluster that is placed as a whole at the operands' level: operands, then the reductions.
+  std::vector<int64_t> cluster(n, -1), role(n, 0);
+  std::vector<std::vector<tn_vid>> members;
+  for (int64_t c = 0; c < n; ++c) {
+    const Vertex& x = tg->v[c];
+    if (x.kind == TN_OP_INPUT || cluster[c] >= 0) continue;
+    bool ok = false;
+    for (tn_vid u : x.in)
+      if (!is_input(u)) ok = true;
+    for (tn_vid u : x.in) {
+      if (!ok) break;
+      if (is_input(u)) continue;
+      if (lv[u] != lv[c] - 1 || cluster[u] >= 0) ok = false;
+      for (tn_vid w : readers[u])
+        if (ok && (cluster[w] >= 0 || tg->v[w].in != x.in)) ok = false;
+    }
+    if (!ok) continue;
+    const int64_t id = (int64_t)members.size();
+    members.emplace_back();
+    for (tn_vid u : x.in)
+      if (!is_input(u) && cluster[u] < 0) {
+        cluster[u] = id;
+        members[id].push_back(u);
+      }
+    tn_vid first_op = x.in[0];
+    for (tn_vid u : x.in)
+      if (!is_input(u)) { first_op = u; break; }
+    for (tn_vid w : readers[first_op]) {  // every kernel operand has the same readers
+      cluster[w] = id;
+      role[w] = 1;
+      members[id].push_back(w);
+    }
+  }
+  // Units (clusters and single vertices) of one level are ordered by the first input any of their vertices
+  // reads -- so that the units that read one weight tile follow one another and the tile is needed once --
+  // and then by their numbering.
+  auto first_input = [&](tn_vid v) {
+    int64_t k = std::numeric_limits<int64_t>::max();
+    for (tn_vid u : tg->v[v].in)
+      if (is_input(u)) k = std::min<int64_t>(k, u);
+    return k;
+  };
+  struct Unit { int64_t level, input, first; int64_t cluster; tn_vid v; };
+  std::vector<Unit> units;
+  for (int64_t v = 0; v < n; ++v)
+    if (!is_input((tn_vid)v) && cluster[v] < 0) units.push_back({lv[v], first_input((tn_vid)v), v, -1, (tn_vid)v});
+  for (size_t id = 0; id < members.size(); ++id) {
+    Unit u{0, std::numeric_limits<int64_t>::max(), std::numeric_limits<int64_t>::max(), (int64_t)id, -1};
+    for (tn_vid v : members[id]) {
+      if (role[v] == 0) u.level = lv[v];
+      u.input = std::min(u.input, first_input(v));
+      u.first = std::min<int64_t>(u.first, v);
+    }
+    units.push_back(u);
+  }
+  std::sort(units.begin(), units.end(), [](const Unit& a, const Unit& b) {
+    if (a.level != b.level) return a.level < b.level;
+    if (a.input != b.input) return a.input < b.input;
+    return a.first < b.first;
+  });
+  // inputs go right before their first reader; inputs nobody reads come first
+  std::vector<char> placed(n, 0);
+  int64_t at = 0;
+  for (int64_t v = 0; v < n; ++v)
+    if (is_input((tn_vid)v) && readers[v].empty()) {
+      out[at++] = (tn_vid)v;
+      placed[v] = 1;
+    }
+  auto emit = [&](tn_vid v) {
+    for (tn_vid u : tg->v[v].in)
+      if (is_input(u) && !placed[u]) {
+        out[at++] = u;
+        placed[u] = 1;
+      }
+    out[at++] = v;
+  };
+  for (const Unit& u : units) {
+    if (u.cluster < 0) {
+      emit(u.v);
+      continue;
+    }
+    std::vector<tn_vid> ms = members[(size_t)u.cluster];
+    std::stable_sort(ms.begin(), ms.end(), [&](tn_vid a, tn_vid b) { return role[a] != role[b] ? role[a] < role[b] : a < b; });
+    for (tn_vid v : ms) emit(v);
+  }
+  if (at != n) return fail(TN_ERR_INVALID, "internal: %lld of %lld vertices ordered", (long long)at, (long long)n);
   return TN_OK;
 }
 

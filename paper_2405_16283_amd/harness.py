@@ -181,6 +181,14 @@ def bench_compile_opts(cap_bytes: int, train: bool, lookahead=None, evict_ahead=
                              next_fit=next_fit)
 
 
+# The serial order V the benchmark compiles each workload for, where it is not the tiler's own (stripe by
+# stripe).  c3: level by level, so that the launches of a kind gather a whole layer's tiles (412-419 -> 396 ms
+# per step; on the link-bound c4 and on the fine-tuning step, where a level keeps far more alive, the
+# tiler's order measures better).  c2 under 40 % of its peak: with the reductions next to their operands
+# and a level walked weight tile by weight tile nothing has to leave the GPU at all (30.4 -> 11.8 ms).
+BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered"}
+
+
 def cap_for(cfg, tg) -> int:
     """The workload's GPU-memory cap in bytes."""
     if cfg.cap_bytes:
@@ -194,7 +202,7 @@ class GpuSession:
 
     def __init__(self, cfg, full_inputs: Dict[str, np.ndarray], cap: Optional[int] = None,
                  compile_opts: Optional[B.tn_compile_opts] = None, n_compute: int = 4,
-                 kv_outputs: bool = False, order: Optional[Sequence[int]] = None,
+                 kv_outputs: bool = False, order=None,
                  weights_transposed: bool = True, arena_bytes: int = 0, v_transposed: bool = True,
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
                  materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
@@ -210,6 +218,9 @@ class GpuSession:
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")
+        if isinstance(order, str):  # a serial order of the library's by name; None or "tiler": the tiler's own
+            order = {"tiler": lambda tg: None, "level": B.tn_taskgraph_level_order,
+                     "clustered": B.tn_taskgraph_clustered_order}[order](self.tg)
         self.mg = B.tn_compile(self.tg, order, self.cap, compile_opts)
         self.stats = B.tn_memgraph_stats(self.mg)
         say("memgraph compiled")

@@ -445,3 +445,64 @@ def test_level_order_runs_the_graph_level_by_level_and_compiles(name, kw):
             B._check(B.lib().tn_taskgraph_level_order(tg, buf, 4))
     finally:
         B.tn_taskgraph_destroy(tg)
+
+
+@pytest.mark.parametrize("name,kw", [("c1", {}), ("ragged_bf16", {}), ("batch2_f32", {}), ("ragged_f32", {"k_split": 2}),
+                                     ("c1", {"train": True, "lora_rank": 4}), ("decode_f32", {})])
+def test_clustered_order_keeps_reductions_next_to_their_operands_and_compiles(name, kw):
+    """tn_taskgraph_clustered_order: a valid order; every combine directly behind its partials (and the
+    partials of one combine together), every SiLU-mul directly behind its two products; an input right
+    before its first reader; vertices of a level that read inputs ordered by the first input they read;
+    the memgraph compiled for it under the cap passes the checks of Section 6 and moves no more bytes to
+    the host than the one compiled for the level order."""
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, **kw))
+    try:
+        order = B.tn_taskgraph_clustered_order(tg)
+        preds = task_preds(tg)
+        n = len(preds)
+        assert sorted(order) == list(range(n))
+        pos = {v: i for i, v in enumerate(order)}
+        assert all(pos[u] < pos[v] for v in range(n) for u in preds[v])
+        kinds = [B.tn_taskgraph_vertex(tg, v).kind for v in range(n)]
+        readers = [[] for _ in range(n)]
+        for v in range(n):
+            for u in dict.fromkeys(preds[v]):
+                readers[u].append(v)
+        ops_only = [v for v in order if preds[v]]
+        opos = {v: i for i, v in enumerate(ops_only)}  # positions among the kernel vertices alone
+        seen = 0
+        for v in range(n):
+            if kinds[v] not in (B.TN_OP_ATTN_COMBINE, B.TN_OP_SILU_MUL):
+                continue
+            group = sorted(w for w in range(n) if preds[w] == preds[v])  # the vertices with this operand list
+            if v != group[0] or any(not preds[u] for u in preds[v]) or any(set(readers[u]) != set(group) for u in preds[v]):
+                continue
+            if any(kinds[u] == B.TN_OP_SUM for u in preds[v]):
+                continue  # the operands are reductions themselves (placed with their own operands): no chains
+            block = sorted(opos[u] for u in set(preds[v])) + sorted(opos[w] for w in group)
+            assert block == list(range(block[0], block[0] + len(block))), (v, block)  # one uninterrupted run
+            assert max(opos[u] for u in preds[v]) < min(opos[w] for w in group)
+            seen += 1
+        assert seen > 0
+        for v in range(n):  # an input sits right before its first reader (other inputs of that reader may lie between)
+            if not preds[v] and readers[v]:
+                first = min(readers[v], key=pos.get)
+                assert all(not preds[w] for w in order[pos[v] + 1:pos[first]])
+        cap = H.cap_for(cfg, tg) * (2 if kw.get("k_split") else 1)
+        mg = B.tn_compile(tg, order, cap, None)
+        mg_level = B.tn_compile(tg, B.tn_taskgraph_level_order(tg), cap, None)
+        try:
+            check_all(preds, oracle_memgraph(mg), n_random=10, seed=2)
+            st, st_level = B.tn_memgraph_stats(mg), B.tn_memgraph_stats(mg_level)
+            assert st.offload_bytes <= st_level.offload_bytes
+            print(f"{name} {kw}: offloaded {st.offload_bytes} against {st_level.offload_bytes} bytes in level order; "
+                  f"loaded {st.load_bytes} against {st_level.load_bytes}")
+        finally:
+            B.tn_memgraph_destroy(mg)
+            B.tn_memgraph_destroy(mg_level)
+        with pytest.raises(B.TurnipError):
+            buf = (ctypes.c_int32 * 4)()
+            B._check(B.lib().tn_taskgraph_clustered_order(tg, buf, 4))
+    finally:
+        B.tn_taskgraph_destroy(tg)

@@ -48,7 +48,8 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     print(f"[{name}] inputs generated {time.time() - t0:.1f}s", flush=True)
     # K/V and the hidden state of pairs of neighbouring layers through the depth of the stack are outputs
-    s = H.GpuSession(cfg, full, kv_outputs=kv, hidden_outputs=True, output_layer_stride=stride)
+    s = H.GpuSession(cfg, full, kv_outputs=kv, hidden_outputs=True, output_layer_stride=stride,
+                     order=H.BENCH_ORDER.get(name))  # the serial order the benchmark compiles this workload for
     probe = [0] + [l for l in range(stride, cfg.layers - 1, stride)] + [last]  # layers checked one by one
     print(f"[{name}] compiled and placed {time.time() - t0:.1f}s: {s.stats.n_vertices} vertices, "
           f"{s.stats.n_load} loads, {s.stats.n_offload} offloads, {s.stats.n_store} stores", flush=True)
