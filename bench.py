@@ -48,7 +48,7 @@ TRANSFERS = {"c4": (128, 16)}
 SMALL_GEMM_TILES = {"c5": -1}
 
 # steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)
-SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
+SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c2_capped25": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
 
 
 def cpu_baseline(cfg, full, budget_tokens):
@@ -99,13 +99,13 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="",
-                    help="time this workload alone (c1..c5, c2_capped40, or a parity shape); default: c4 as the "
+                    help="time this workload alone (c1..c5, c2_capped40, c2_capped25, or a parity shape); default: c4 as the "
                          "headline plus the sub-records of --subs")
     ap.add_argument("--launch-trace", default="",
                     help="write the timed launches of the headline workload's last step (family, vertices, workgroups or "
                          "bytes, start and end in ms) to this .npy file")
     ap.add_argument("--subs", default="",
-                    help="comma-separated sub-records, or 'none'; default c2,c2_capped40,c3,c5 when --workload is not given")
+                    help="comma-separated sub-records, or 'none'; default c2,c2_capped40,c2_capped25,c3,c5 when --workload is not given")
     ap.add_argument("--streams", type=int, default=0, help="compute streams; default: harness.BENCH_COMPUTE_STREAMS")
     ap.add_argument("--max-batch", type=int, default=1920)
     ap.add_argument("--max-transfers", type=int, default=0)
@@ -209,13 +209,15 @@ def main():
     def run_case(name, steps, warmup, headline):
         """One workload: inputs, taskgraph, memgraph, executor, `warmup` untimed and `steps` timed
         steps.  Returns (record, cfg, full inputs, y)."""
-        capped40 = name == "c2_capped40"
+        capped40 = name.startswith("c2_capped")  # c2_capped40, c2_capped25: the cap as a percentage of the uncapped peak
         cfg = config("c2" if capped40 else name)
         pressed = False
         if capped40:
-            # everything streamed from the host, the cap at 40 % of the uncapped peak; clustered serial
+            # everything streamed from the host, the cap a fraction of the uncapped peak; clustered serial
             # order, so that every weight tile is loaded once per step and reductions follow their operands
-            cfg = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
+            # (at 40 % nothing has to be offloaded then; at 25 % activations are)
+            cfg = cfg.with_(cap_bytes=0, cap_frac=int(name[len("c2_capped"):]) / 100.0, weights_resident=False,
+                            x_resident=False)
             pressed = True
         level = H.BENCH_ORDER.get(name, "")
         if headline:  # the shape-changing flags apply to the workload named on the command line only
@@ -315,7 +317,7 @@ def main():
                       f"batch {cfg.batch}, tile {cfg.tile}, attention block {cfg.attn_block}, "
                     + ("weights and x device-resident" if cfg.weights_resident else "weights and x streamed from pinned host memory")
                     + f", GPU-memory cap {s.cap / 1e9:.3f} GB"
-                    + (" (40 % of the uncapped peak)" if capped40 else ""))
+                    + (f" ({name[len('c2_capped'):]} % of the uncapped peak)" if capped40 else ""))
         rec = {
             "workload": workload, "tokens": cfg.tokens, "steps": steps, "warmup": warmup,
             "ms_per_step": ms, "tokens_per_s": cfg.tokens / (ms * 1e-3),
@@ -369,7 +371,7 @@ def main():
         return rec, cfg, full, y
 
     head_name = args.workload or "c4"
-    subs = [] if args.workload else ["c2", "c2_capped40", "c3", "c5"]
+    subs = [] if args.workload else ["c2", "c2_capped40", "c2_capped25", "c3", "c5"]
     if args.subs:
         subs = [] if args.subs == "none" else [x for x in args.subs.split(",") if x]
     if args.capped and "c2_capped40" not in subs:
@@ -428,7 +430,7 @@ def main():
         srec, scfg, sfull, sy = run_case(sub, k, w, headline=False)
         if sub == "c2":
             y_c2 = sy
-        elif sub == "c2_capped40" and y_c2 is not None:
+        elif sub.startswith("c2_capped") and y_c2 is not None:
             srec["identical_to_the_uncapped_c2_run"] = bool(np.array_equal(sy, y_c2))
         line.setdefault("sub_records", {})[sub] = srec
         del sfull, sy

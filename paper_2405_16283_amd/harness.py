@@ -186,7 +186,7 @@ def bench_compile_opts(cap_bytes: int, train: bool, lookahead=None, evict_ahead=
 # per step; on the link-bound c4 and on the fine-tuning step, where a level keeps far more alive, the
 # tiler's order measures better).  c2 under 40 % of its peak: with the reductions next to their operands
 # and a level walked weight tile by weight tile nothing has to leave the GPU at all (30.4 -> 11.8 ms).
-BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered"}
+BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered", "c2_capped25": "clustered"}
 
 
 def cap_for(cfg, tg) -> int:

@@ -68,23 +68,28 @@ def test_c2_other_seeds_match_the_oracle_everywhere(seed):
         s.close()
 
 
-def test_c2_streamed_under_forty_percent_cap_gives_the_same_bits(c2):
+@pytest.mark.parametrize("percent,order", [(40, "clustered"), (25, "clustered"), (40, "level")])
+def test_c2_streamed_under_a_fraction_of_its_peak_gives_the_same_bits(c2, percent, order):
+    """The benchmark's capped runs of the one-layer workload (everything streamed from the host; cap 40 % and
+    25 % of the uncapped peak, clustered serial order) and the level order at 40 %, which offloads: the
+    oracle's result at the one-layer bar, and the bits of the uncapped run."""
     cfg, full, y_oracle = c2
-    capped = cfg.with_(cap_bytes=0, cap_frac=0.40, weights_resident=False, x_resident=False)
-    print("[case] c2 streamed, cap = 40 % of the uncapped peak", flush=True)
+    capped = cfg.with_(cap_bytes=0, cap_frac=percent / 100.0, weights_resident=False, x_resident=False)
+    print(f"[case] c2 streamed, cap = {percent} % of the uncapped peak, serial order {order}", flush=True)
     tg = B.tn_build_llama(H.llama_config_struct(capped))
     cap = H.cap_for(capped, tg)
-    order = B.tn_taskgraph_level_order(tg)
     B.tn_taskgraph_destroy(tg)
-    # the serial order, compile options and stream count of the benchmark's capped run
+    # the serial order, compile options and stream count of the benchmark's capped runs
     s = H.GpuSession(capped, full, cap=cap, compile_opts=H.bench_compile_opts(cap, False, pressed=True),
                      n_compute=H.BENCH_COMPUTE_STREAMS, order=order)
     try:
-        assert s.stats.n_offload > 0 and s.stats.n_load > 0
+        print(f"  {s.stats.n_offload} offloads, {s.stats.n_load} loads", flush=True)
+        assert s.stats.n_load > 0 and s.stats.high_water <= cap
+        assert (s.stats.n_offload > 0) == (percent == 25 or order == "level")
         out, rep = s.run(bench_opts())
         y = bf16_bits_to_f32(out["y"]).astype(np.float64)
         assert R.rel_err(y, y_oracle) < 2e-2
-        assert rep.n_offload == s.stats.n_offload and rep.arena_high_water > 0
+        assert rep.n_offload == s.stats.n_offload and (rep.arena_high_water > 0) == (s.stats.n_offload > 0)
         o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=11, max_batch=32, max_delay_us=200))
         np.testing.assert_array_equal(o2["y"], out["y"])
     finally:
