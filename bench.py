@@ -41,9 +41,10 @@ HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 # tile products cut into 128x128 tiles) are not the best measured choice.  c4 is bound by the host link: its
 # copy launches compete for compute units with tile products that hold a unit for 250 us each, so fewer,
 # larger copy launches with more workgroups keep the link busier (56.0 GB/s host to GPU while copying
-# against 51 with the defaults; 10 to 16 workgroups measure within 2 % of one another, 24 cost 5 %); on the compute-bound c3 the same setting costs 20 %.  On c5 the small groups
-# of tile products appear while the link is the bottleneck (the reverse pass waits for reloads), and spread
-# over all compute units they slow the copy kernel more than they gain (1.34 against 1.30 s per step).
+# against 51 with the defaults; 10 to 16 workgroups measure within 2 % of one another, 24 cost 5 %); on
+# the compute-bound c3 the same setting costs 20 %.  On c5 the small groups of tile products appear while
+# the link is the bottleneck (the reverse pass waits for reloads), and spread over all compute units they
+# slow the copy kernel more than they gain (1.34 against 1.30 s per step).
 TRANSFERS = {"c4": (128, 14)}
 SMALL_GEMM_TILES = {"c5": -1}
 
