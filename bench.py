@@ -127,6 +127,9 @@ def main():
     ap.add_argument("--checkpoint", action="store_true",
                     help="fine-tuning step with activation checkpointing: the reverse pass of a layer forms that "
                          "layer's forward tensors again instead of reading saved ones")
+    ap.add_argument("--attn-whole-rows", type=int, default=-1,
+                    help="1: attention of a query block as one vertex over all keys up to its own (one partial per block "
+                         "instead of one per key block); 0: one vertex per pair of blocks; default: harness.BENCH_WHOLE_ROWS")
     ap.add_argument("--materialize-scores", action="store_true",
                     help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
                          "sets the tile to the head dimension (one head per column tile)")
@@ -233,6 +236,8 @@ def main():
             if args.order:
                 level = "" if args.order == "tiler" else args.order
         materialize = headline and args.materialize_scores
+        whole_rows = (bool(args.attn_whole_rows) if (headline and args.attn_whole_rows >= 0)
+                      else H.BENCH_WHOLE_ROWS.get(name, False))
         checkpoint = headline and args.checkpoint
         k_split = args.k_split if headline else 0
         train = bool(args.train) if (headline and args.train >= 0) else cfg.name == "c5"
@@ -253,7 +258,8 @@ def main():
         def session(c, device_outputs):
             order = None
             struct = lambda cc: H.llama_config_struct(cc, kv_outputs, lora_rank=16 if train else 0, train=train,
-                                                      k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint)
+                                                      k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
+                                                      attn_whole_rows=whole_rows)
             if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
                 tg = B.tn_build_llama(struct(c))
                 c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
@@ -270,7 +276,7 @@ def main():
                                          next_fit=args.next_fit if (hl and args.next_fit >= 0) else None, pressed=pressed)
             return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                                 lora_rank=16 if train else 0, train=train, progress=lambda m: note(f"{name}: {m}"),
-                                k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
+                                k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint, attn_whole_rows=whole_rows,
                                 device_outputs=device_outputs)
 
         t0 = time.perf_counter()
@@ -324,7 +330,7 @@ def main():
             "ms_per_step": ms, "tokens_per_s": cfg.tokens / (ms * 1e-3),
             "gpu_cap_bytes": s.cap, "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
             "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
-            "serial_order": level or "tiler",
+            "serial_order": level or "tiler", "attention_vertices": "whole rows" if whole_rows else "per pair of blocks",
             "memgraph": {"vertices": int(st.n_vertices), "offloads": int(st.n_offload), "reloads": int(st.n_reload),
                          "loads": int(st.n_load), "drops": int(st.n_drop), "stores": int(st.n_store),
                          "mem_edges": int(st.n_mem_edges), "offload_GB": st.offload_bytes / 1e9,

@@ -283,6 +283,14 @@ typedef struct {
    * row's embedding is an input, bound as row seq + u of x (there is no vocabulary to sample from);
    * its result is row seq + u of y.  kv_outputs / hidden_outputs cover the decode rows too. */
   int32_t decode_steps;
+  /* != 0 (needs train == 0, materialize_scores == 0): attention of a query block as ONE vertex over all
+   * keys from position 0 to the block's own end, instead of one vertex per key block of attn_block
+   * positions (the tiling is the front end's choice, Section 4; the blocks remain what the kernel walks
+   * through).  The online softmax then runs over the whole range inside the kernel and a query block
+   * has a single partial, which the combine vertex normalises: s + 1 times less partial traffic for the
+   * block in stripe s, at the price that all earlier K/V tiles of the layer are operands of one vertex
+   * and must be resident together. */
+  int32_t attn_whole_rows;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

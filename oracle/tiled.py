@@ -261,7 +261,8 @@ def _splits(n: int, t: int) -> List[Tuple[int, int]]:
     return [(s, min(s + t, n)) for s in range(0, n, t)]
 
 
-def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = False) -> TaskGraph:
+def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = False,
+                          attn_whole_rows: bool = False) -> TaskGraph:
     """Tile the decoder of `cfg` (a workloads.LlamaConfig) into a taskgraph.
 
     k_split > 1: every projection is cut along K into that many partial products (contiguous runs
@@ -277,6 +278,10 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
     never straddle sequences.  Attention runs per (sequence, head group, q block, kv block <= q
     block) with one partial per pair and one combine per output tile; blocks above the diagonal
     are never created.  A head group is the set of heads covering max(tile, head_dim) columns.
+
+    attn_whole_rows: one attention vertex per (sequence, head group, q block) over all keys from
+    position 0 to the end of the q block (its softmax runs over the whole range at once) instead of one
+    per kv block; the combine then has a single partial to normalise.
 
     cfg.decode_steps > 0 (one sequence): after the prefill of cfg.seq positions, that many steps of one
     row each (Section 9, limitations: the number of generated tokens is fixed when the graph is
@@ -376,9 +381,10 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
             cts = list(range(g * ctg, (g + 1) * ctg))
             for bi, (q0, q1) in enumerate(blocks):
                 parts = []
-                for bj in range(bi + 1):
-                    k0 = blocks[bj][0]
-                    qi, kj = tiles_of_block[bi], tiles_of_block[bj]
+                for bj in ([bi] if attn_whole_rows else range(bi + 1)):
+                    k0 = 0 if attn_whole_rows else blocks[bj][0]
+                    qi = tiles_of_block[bi]
+                    kj = [r for b2 in range(bi + 1) for r in tiles_of_block[b2]] if attn_whole_rows else tiles_of_block[bj]
                     ins = ([q[r][c] for r in qi for c in cts] + [k[r][c] for r in kj for c in cts]
                            + [v[r][c] for r in kj for c in cts])
                     parts.append(tg.add("attn_block", ins, (q1 - q0, gw + 2 * hpg), "f32",

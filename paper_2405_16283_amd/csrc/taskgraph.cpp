@@ -622,6 +622,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.k_split < 0) return fail(TN_ERR_INVALID, "k_split must not be negative");
   if (c.output_layer_stride < 0) return fail(TN_ERR_INVALID, "output_layer_stride must not be negative");
   if (c.decode_steps < 0) return fail(TN_ERR_INVALID, "decode_steps must not be negative");
+  if (c.attn_whole_rows && (c.train || c.materialize_scores))
+    return fail(TN_ERR_INVALID, "attn_whole_rows goes with neither train nor materialize_scores");
   if (c.decode_steps > 0 && (c.train || c.materialize_scores || c.batch != 1 || c.lora_rank > 0))
     return fail(TN_ERR_INVALID, "decode_steps needs one sequence, and none of train, lora_rank, materialize_scores");
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
@@ -757,10 +759,13 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
       }
       for (int32_t gi = 0; gi < (c.materialize_scores ? 0 : n_groups); ++gi) {
         std::vector<tn_vid> parts;
-        for (size_t s2 = 0; s2 <= s; ++s2) {
+        // attn_whole_rows: one vertex per query block over all keys up to the block's own, instead of one per
+        // key block (its online softmax runs over the whole range; one partial instead of s + 1)
+        for (size_t s2 = c.attn_whole_rows ? s : 0; s2 <= s; ++s2) {
+          const int32_t k_from = c.attn_whole_rows ? 0 : stripes[s2].a;
           std::vector<size_t> kt;
           for (size_t i = 0; i < t.rows.size(); ++i)
-            if (t.rows[i].a >= stripes[s2].a && t.rows[i].a < stripes[s2].b) kt.push_back(i);
+            if (t.rows[i].a >= k_from && t.rows[i].a < stripes[s2].b) kt.push_back(i);
           std::vector<tn_vid> in;
           for (size_t i : rt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(q[i][gi * ctg + cc]);
           for (size_t i : kt) for (int32_t cc = 0; cc < ctg; ++cc) in.push_back(kk[i][gi * ctg + cc]);
@@ -771,7 +776,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           p.n_col_tiles = ctg;
           p.head_dim = c.head_dim;
           p.q_pos0 = stripes[s].a;
-          p.k_pos0 = stripes[s2].a;
+          p.k_pos0 = k_from;
           p.causal = (s2 == s);
           p.v_trans = c.v_transposed ? 1 : 0;
           p.scale = 1.0f / std::sqrt((float)c.head_dim);

@@ -88,3 +88,39 @@ def test_decode_options_that_do_not_go_together_are_refused():
             B.tn_build_llama(H.llama_config_struct(cfg, **bad))
     with pytest.raises(B.TurnipError):
         B.tn_build_llama(H.llama_config_struct(cfg.with_(batch=2)))
+
+
+# ---------------------------------------------------------------------------------------------
+# attention of a query block as one vertex over all earlier keys (tiler option attn_whole_rows)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["c1", "ragged_f32", "ragged_bf16", "batch2_f32"])
+def test_whole_row_attention_vertices(name):
+    """One attention vertex per query block over the keys 0 .. end of the block, its softmax over the whole
+    range at once: the oracle's tiler against the untiled model; the library's tiler under the oracle's
+    interpreter against the oracle's own, bit for bit; the memgraph under the cap against the checkers."""
+    cfg = config(name)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    mine = T.build_llama_taskgraph(cfg, attn_whole_rows=True)
+    blocks = -(-cfg.seq // cfg.attn_block)
+    groups = cfg.d_model // max(cfg.tile, cfg.head_dim)
+    assert mine.kind.count("attn_block") == cfg.layers * cfg.batch * groups * blocks
+    y_own = T.assemble_outputs(mine, T.evaluate(mine, T.cut_inputs(mine, w)), cfg.tokens, cfg.d_model)
+    assert R.rel_err(y_own, R.forward(cfg, w)) < (2e-6 if cfg.dtype == "f32" else 2e-2)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, weights_transposed=False, v_transposed=False, attn_whole_rows=True))
+    try:
+        otg = oracle_taskgraph(tg)
+        y_lib = T.assemble_outputs(otg, T.evaluate(otg, T.cut_inputs(otg, w)), cfg.tokens, cfg.d_model)
+        np.testing.assert_array_equal(y_lib, y_own)
+        cap = H.cap_for(cfg, tg)
+        mg = B.tn_compile(tg, None, cap)
+        try:
+            assert B.tn_memgraph_stats(mg).n_offload > 0
+            check_all(task_preds(tg), oracle_memgraph(mg), n_random=6, seed=5)
+        finally:
+            B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+    for bad in (dict(train=True, lora_rank=4), dict(materialize_scores=True)):
+        with pytest.raises(B.TurnipError):
+            B.tn_build_llama(H.llama_config_struct(cfg, attn_whole_rows=True, **bad))

@@ -308,3 +308,26 @@ def test_serial_orders_change_the_memgraph_and_not_the_bits(name):
         finally:
             s.close()
     assert len(set(moved.values())) > 1
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16", "mid_bf16"])
+def test_whole_row_attention_vertices_match_the_oracle(name):
+    """Tiler option attn_whole_rows: one attention vertex per query block over all earlier keys (the MFMA
+    kernel then walks through up to 1440 keys with the diagonal inside its last blocks) against the oracle's
+    tiling of the same kind, under the cap, and the same bits in another order."""
+    cfg = config(name)
+    full = make_llama_inputs(cfg, 0)
+    w = R.widen(cfg, full)
+    own = T.build_llama_taskgraph(cfg, attn_whole_rows=True)
+    y_tiled = T.assemble_outputs(own, T.evaluate(own, T.cut_inputs(own, w)), cfg.tokens, cfg.d_model)
+    s = H.GpuSession(cfg, full, attn_whole_rows=True)
+    try:
+        assert s.stats.n_offload > 0
+        out, _ = s.run()
+        err = R.rel_err(_as_f64(cfg, out["y"]), y_tiled)
+        print(f"[case] {name} whole-row attention: rel err {err:.3e}", flush=True)
+        assert err < TOL[cfg.dtype]
+        o2, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=3, max_batch=2, max_delay_us=100))
+        np.testing.assert_array_equal(o2["y"], out["y"])
+    finally:
+        s.close()
