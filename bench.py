@@ -47,6 +47,8 @@ HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 # slow the copy kernel more than they gain (1.34 against 1.30 s per step).
 TRANSFERS = {"c4": (128, 14)}
 SMALL_GEMM_TILES = {"c5": -1}
+# c5's sub-record is also timed with this many of its first layers checkpointed (--checkpoint --checkpoint-layers)
+MIXED_CHECKPOINT_LAYERS = 12
 
 # steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)
 SUB_STEPS = {"c2": (20, 3), "c2_capped40": (5, 1), "c2_capped25": (5, 1), "c3": (4, 1), "c5": (3, 1), "c4": (3, 1)}
@@ -130,6 +132,8 @@ def main():
     ap.add_argument("--attn-whole-rows", type=int, default=-1,
                     help="1: attention of a query block as one vertex over all keys up to its own (one partial per block "
                          "instead of one per key block); 0: one vertex per pair of blocks; default: harness.BENCH_WHOLE_ROWS")
+    ap.add_argument("--checkpoint-layers", type=int, default=0,
+                    help="with --checkpoint: only the first this many layers are recomputed, the rest keep saved activations")
     ap.add_argument("--materialize-scores", action="store_true",
                     help="attention with scores and probabilities as taskgraph tensors and the softmax in two portions; "
                          "sets the tile to the head dimension (one head per column tile)")
@@ -255,11 +259,11 @@ def main():
         device_outputs = ((cfg.weights_resident and cfg.x_resident) if (not headline or args.host_outputs < 0)
                           else not args.host_outputs)
 
-        def session(c, device_outputs):
+        def session(c, device_outputs, checkpoint=checkpoint, ck_layers=args.checkpoint_layers if checkpoint else 0):
             order = None
             struct = lambda cc: H.llama_config_struct(cc, kv_outputs, lora_rank=16 if train else 0, train=train,
                                                       k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
-                                                      attn_whole_rows=whole_rows)
+                                                      attn_whole_rows=whole_rows, checkpoint_layers=ck_layers)
             if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
                 tg = B.tn_build_llama(struct(c))
                 c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
@@ -277,7 +281,7 @@ def main():
             return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                                 lora_rank=16 if train else 0, train=train, progress=lambda m: note(f"{name}: {m}"),
                                 k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint, attn_whole_rows=whole_rows,
-                                device_outputs=device_outputs)
+                                checkpoint_layers=ck_layers, device_outputs=device_outputs)
 
         t0 = time.perf_counter()
         s = session(cfg, device_outputs)
@@ -303,6 +307,19 @@ def main():
             ms_host_out = 1e3 * sum(dt for dt, _ in rh) / len(rh)
             assert np.array_equal(sh.outputs(only=["y"])["y"], y)
             sh.close()
+        # the fine-tuning step as a sub-record: also with the first MIXED_CHECKPOINT_LAYERS layers recomputed in the
+        # reverse pass and the others' activations saved (the same outputs, bit for bit; no or hardly any offloads)
+        ms_mixed = None
+        if train and not headline and not checkpoint and cfg.layers > MIXED_CHECKPOINT_LAYERS:
+            rep_last = reps[-1][1]
+            s.close()
+            gc.collect()
+            torch.cuda.empty_cache()
+            s = session(cfg, device_outputs, checkpoint=True, ck_layers=MIXED_CHECKPOINT_LAYERS)
+            rm = timed(s, 2, 1, exec_opts(1, name), name + f" (first {MIXED_CHECKPOINT_LAYERS} layers checkpointed)")
+            ms_mixed = 1e3 * sum(dt for dt, _ in rm) / len(rm)
+            assert np.array_equal(s.outputs(only=["y"])["y"], y)
+            mixed_offload_gb = s.stats.offload_bytes / 1e9
         peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
         n = len(reps)
         tot = lambda f: sum(getattr(r, f) for _, r in reps)
@@ -359,6 +376,9 @@ def main():
             "untimed_launches": int(rep0.untimed_launches),
             "ms_per_step_without_event_pairs": ms_plain,
             "ms_per_step_with_outputs_stored_to_host": ms_host_out,
+            **({"with_the_first_layers_checkpointed": {"layers": MIXED_CHECKPOINT_LAYERS, "ms_per_step": ms_mixed,
+                                                        "tokens_per_s": cfg.tokens / (ms_mixed * 1e-3),
+                                                        "offload_GB": mixed_offload_gb}} if ms_mixed else {}),
             "input_generation_s": t_gen, "build_and_compile_s": t_compile,
             "exec": {"compute_streams": args.streams, "ready_policy": args.policy, "max_batch": args.max_batch,
                      "max_gemm_inflight": args.max_gemm_inflight, "queue_depth": args.queue_depth,

@@ -291,6 +291,12 @@ typedef struct {
    * block in stripe s, at the price that all earlier K/V tiles of the layer are operands of one vertex
    * and must be resident together. */
   int32_t attn_whole_rows;
+  /* with checkpoint != 0: only the first this many layers are checkpointed (their forward tensors are formed
+   * again in the reverse pass), the later layers keep their saved activations; 0 = every layer.  The first
+   * layers are the ones whose saved activations would wait longest for the reverse pass, i.e. the ones a cap
+   * pushes to the host: recomputing those and saving the rest trades a little arithmetic for all of the
+   * offload traffic when the rest fits. */
+  int32_t checkpoint_layers;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -627,6 +627,10 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.decode_steps > 0 && (c.train || c.materialize_scores || c.batch != 1 || c.lora_rank > 0))
     return fail(TN_ERR_INVALID, "decode_steps needs one sequence, and none of train, lora_rank, materialize_scores");
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
+  if (c.checkpoint_layers < 0 || (c.checkpoint_layers > 0 && !c.checkpoint))
+    return fail(TN_ERR_INVALID, "checkpoint_layers needs checkpoint and must not be negative");
+  // layers whose forward tensors the reverse pass forms again instead of reading saved ones
+  auto recomputed = [&](int l) { return c.checkpoint && (c.checkpoint_layers == 0 || l < c.checkpoint_layers); };
   if (c.materialize_scores && (c.tile != c.head_dim || c.train || c.kv_outputs))
     return fail(TN_ERR_INVALID, "materialize_scores needs tile == head_dim and neither train nor kv_outputs");
 
@@ -853,8 +857,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     const LayerInputs w{wq, wk, wv, wo, w1, w3, w2, g1, g2, aq, bq, av, bv, aqT, bqT, avT, bvT};
     if (c.train || c.decode_steps) lin[l] = w;
     for (int b = 0; b < c.batch; ++b) {
-      if (c.checkpoint) layer_in[l][b] = x[b];
-      forward_layer(l, w, b, x[b], c.train && !c.checkpoint ? &saved[l][b] : nullptr, true);
+      if (recomputed(l)) layer_in[l][b] = x[b];
+      forward_layer(l, w, b, x[b], c.train && !recomputed(l) ? &saved[l][b] : nullptr, true);
       if (c.hidden_outputs && layer_is_output(l) && l + 1 < c.layers)  // (the last layer's output is y)
         for (size_t i = 0; i < t.rows.size(); ++i)
           for (size_t j = 0; j < nd; ++j)
@@ -971,7 +975,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
     }
     for (int l = c.layers - 1; l >= 0; --l) {
       const LayerInputs& w = lin[l];
-      if (c.checkpoint)  // form what the reverse pass reads of this layer again, from the layer's input
+      if (recomputed(l))  // form what the reverse pass reads of this layer again, from the layer's input
         for (int b = 0; b < c.batch; ++b) {
           Grid xin = layer_in[l][b];
           forward_layer(l, w, b, xin, &saved[l][b], false);

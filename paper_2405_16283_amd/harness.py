@@ -30,7 +30,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
                         v_transposed: bool = True, lora_rank: int = 0, train: bool = False,
                         k_split: int = 0, materialize_scores: bool = False,
                         checkpoint: bool = False, hidden_outputs: bool = False,
-                        output_layer_stride: int = 0, attn_whole_rows: bool = False) -> B.tn_llama_config:
+                        output_layer_stride: int = 0, attn_whole_rows: bool = False,
+                        checkpoint_layers: int = 0) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -42,7 +43,8 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         lora_rank=int(lora_rank), train=int(train), k_split=int(k_split),
         materialize_scores=int(materialize_scores), checkpoint=int(checkpoint),
         hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride),
-        decode_steps=int(getattr(cfg, "decode_steps", 0)), attn_whole_rows=int(attn_whole_rows))
+        decode_steps=int(getattr(cfg, "decode_steps", 0)), attn_whole_rows=int(attn_whole_rows),
+        checkpoint_layers=int(checkpoint_layers))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -212,7 +214,7 @@ class GpuSession:
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
                  materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
                  device_inputs: bool = False, hidden_outputs: bool = False, output_layer_stride: int = 0,
-                 attn_whole_rows: bool = False):
+                 attn_whole_rows: bool = False, checkpoint_layers: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -221,7 +223,7 @@ class GpuSession:
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
                                                        lora_rank, train, k_split, materialize_scores,
                                                        checkpoint, hidden_outputs, output_layer_stride,
-                                                       attn_whole_rows))
+                                                       attn_whole_rows, checkpoint_layers))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

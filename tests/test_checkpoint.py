@@ -15,8 +15,9 @@ from util import check_all, oracle_memgraph, task_preds
 RANK = 8
 
 
-def _graph(cfg, checkpoint):
-    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint))
+def _graph(cfg, checkpoint, checkpoint_layers=0):
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint,
+                                                checkpoint_layers=checkpoint_layers))
     try:
         return H.export_taskgraph(tg)
     finally:
@@ -45,6 +46,31 @@ def test_every_output_is_the_same_expression_with_and_without_checkpointing(name
     a, b = _expressions(plain), _expressions(ck)
     assert a.keys() == b.keys() and len(a) == len(plain["outputs"])
     assert a == b
+
+
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16"])
+def test_checkpointing_the_first_layers_only(name):
+    """checkpoint_layers = 1 of 2 layers: the same expressions again; the graph lies between the two
+    extremes in size; the reverse pass reads saved tensors of layer 1 and only the input of layer 0;
+    the memgraph under the cap passes the checks."""
+    cfg = config(name)
+    assert cfg.layers == 2
+    plain, half, full = _graph(cfg, False), _graph(cfg, True, 1), _graph(cfg, True)
+    assert len(plain["kind"]) < len(half["kind"]) < len(full["kind"])
+    assert _expressions(half) == _expressions(plain)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=True, checkpoint_layers=1))
+    try:
+        cap = H.cap_for(cfg, tg)
+        mg = B.tn_compile(tg, None, cap, H.bench_compile_opts(cap, True))
+        try:
+            assert B.tn_memgraph_stats(mg).high_water <= cap
+            check_all(task_preds(tg), oracle_memgraph(mg), n_random=10, seed=9)
+        finally:
+            B.tn_memgraph_destroy(mg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+    with pytest.raises(B.TurnipError):  # a count without the option
+        B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint_layers=1))
 
 
 def test_a_changed_operand_changes_the_expression():
