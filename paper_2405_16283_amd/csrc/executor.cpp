@@ -1031,7 +1031,11 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
       // queued behind it
       if (early_prof >= 0) xg.prof = early_prof;
       else if (e == hipSuccess && opt.profile && prof_pair(&xg.prof)) e = hipEventRecord(ex->prof_events[xg.prof], sl.stream);
-      if (e == hipSuccess && use_copy_kernel) e = launch_copies(copies, inside_gpu ? kDeviceCopyWorkgroups : (dir == 1 && opt.d2h_workgroups > 0) ? opt.d2h_workgroups : opt.copy_workgroups, sl.stream);
+      if (e == hipSuccess && use_copy_kernel) {
+        const int wgs = inside_gpu ? kDeviceCopyWorkgroups
+                        : (dir == 1 && opt.d2h_workgroups > 0) ? opt.d2h_workgroups : opt.copy_workgroups;
+        e = launch_copies(copies, wgs, sl.stream);
+      }
       if (e == hipSuccess && !stage_verts.empty()) {
         // adjacent arena slots for the gathered offloads (the largest free block was checked to suffice, and
         // nothing has taken from the arena since), the gather inside GPU memory, then one copy to the host per
