@@ -104,10 +104,21 @@ class TaskGraph:
 def _eval_vertex(kind: str, p: dict, ins: Sequence[np.ndarray]) -> np.ndarray:
     if kind == "gemm":
         nk = p["nk"]
-        acc = None
-        for k in range(nk):
-            t = ins[k] @ (ins[nk + k].T if p.get("trans_b") else ins[nk + k])
-            acc = t if acc is None else acc + t
+
+        def product(first):  # sum over k of A_k times the operand at first + k
+            acc = None
+            for k in range(nk):
+                t = ins[k] @ (ins[first + k].T if p.get("trans_b") else ins[first + k])
+                acc = t if acc is None else acc + t
+            return acc
+
+        mode = p.get("mode", 0)
+        if mode == 1:  # the product plus one more operand of the output's shape (a residual)
+            return product(nk) + ins[2 * nk]
+        if mode == 2:  # two products from the same A tiles, gate and up: silu(gate) * up
+            gate, up = product(nk), product(2 * nk)
+            return gate / (1.0 + np.exp(-gate)) * up
+        acc = product(nk)
         return acc.T if p.get("trans_c") else acc
     if kind == "rms_stat":
         ss = sum(np.sum(x * x, axis=1, keepdims=True) for x in ins)
@@ -262,7 +273,7 @@ def _splits(n: int, t: int) -> List[Tuple[int, int]]:
 
 
 def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = False,
-                          attn_whole_rows: bool = False) -> TaskGraph:
+                          attn_whole_rows: bool = False, fuse_epilogues: int = 0) -> TaskGraph:
     """Tile the decoder of `cfg` (a workloads.LlamaConfig) into a taskgraph.
 
     k_split > 1: every projection is cut along K into that many partial products (contiguous runs
@@ -282,6 +293,11 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
     attn_whole_rows: one attention vertex per (sequence, head group, q block) over all keys from
     position 0 to the end of the q block (its softmax runs over the whole range at once) instead of one
     per kv block; the combine then has a single partial to normalise.
+
+    fuse_epilogues (needs k_split == 1): bit 0 -- the two residual additions of a layer become the last
+    operand of the products before them (gemm, mode 1); bit 1 -- the W1 and W3 products and silu * up
+    become one vertex (gemm, mode 2).  The fused vertices round to the storage type once, where the
+    separate ones round after every step.
 
     cfg.decode_steps > 0 (one sequence): after the prefill of cfg.seq positions, that many steps of one
     row each (Section 9, limitations: the number of generated tokens is fixed when the graph is
@@ -317,15 +333,23 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
             out.append(v)
         return out
 
-    def gemm(a_grid, b_grid, out_cols):
-        """a_grid [row tiles][k tiles], b_grid [k tiles][col tiles]."""
+    assert fuse_epilogues == 0 or k_split <= 1
+
+    def gemm(a_grid, b_grid, out_cols, residual=None, up_grid=None):
+        """a_grid [row tiles][k tiles], b_grid [k tiles][col tiles]; residual [row tiles][col tiles] is added
+        inside the vertex; up_grid (like b_grid) makes it the gated pair of products."""
         res = []
-        for arow in a_grid:
+        for i, arow in enumerate(a_grid):
             line = []
             m = tg.shape[arow[0]][0]
             nk = len(arow)
             per = -(-nk // max(1, k_split))
             for j, (c0, c1) in enumerate(out_cols):
+                if residual is not None or up_grid is not None:
+                    ins = list(arow) + [b_grid[k][j] for k in range(nk)]
+                    ins += [residual[i][j]] if residual is not None else [up_grid[k][j] for k in range(nk)]
+                    line.append(tg.add("gemm", ins, (m, c1 - c0), dt, nk=nk, mode=1 if residual is not None else 2))
+                    continue
                 parts = []
                 for k0 in range(0, nk, per):
                     ks = range(k0, min(k0 + per, nk))
@@ -398,6 +422,21 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
                                          col0=ci * t, rows=m, cols=n_, head_dim=hd, hpg=hpg)
         return o
 
+    def after_attention(x, o, w, g2):
+        """Output projection, residual, feed-forward, residual; returns (h1, its normalised form, the layer's result)."""
+        if fuse_epilogues & 1:
+            h1 = gemm(o, w["wo"], dcols, residual=x)
+        else:
+            h1 = ewise("add", x, gemm(o, w["wo"], dcols))
+        bn = rmsnorm(h1, g2, dcols)
+        if fuse_epilogues & 2:
+            act = gemm(bn, w["w1"], fcols, up_grid=w["w3"])
+        else:
+            act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
+        if fuse_epilogues & 1:
+            return h1, bn, gemm(act, w["w2"], dcols, residual=h1)
+        return h1, bn, ewise("add", h1, gemm(act, w["w2"], dcols))
+
     steps = getattr(cfg, "decode_steps", 0)
     assert steps == 0 or (cfg.batch == 1 and not materialize_scores)
     weights, cache = [], []  # per layer: the weight grids, and the prefill's K (rotated) and V grids
@@ -415,10 +454,7 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
             k = roped(k)
             cache.append((k, v))
             o = attention(roped(q), k, v)
-            h1 = ewise("add", x, gemm(o, w["wo"], dcols))
-            bn = rmsnorm(h1, g2, dcols)
-            act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
-            xs[b] = ewise("add", h1, gemm(act, w["w2"], dcols))
+            h1, bn, xs[b] = after_attention(x, o, w, g2)
     for b in range(cfg.batch):
         for i, line in enumerate(xs[b]):
             for j, vtx in enumerate(line):
@@ -458,10 +494,7 @@ def build_llama_taskgraph(cfg, k_split: int = 1, materialize_scores: bool = Fals
                 for ci, c in enumerate(cts):
                     n_ = dcols[c][1] - dcols[c][0]
                     o[c] = tg.add("attn_combine", parts, (1, n_), dt, row0=0, col0=ci * t, rows=1, cols=n_, head_dim=hd, hpg=hpg)
-            h1 = ewise("add", x, gemm([o], w["wo"], dcols))
-            bn = rmsnorm(h1, g2, dcols)
-            act = ewise("silu_mul", gemm(bn, w["w1"], fcols), gemm(bn, w["w3"], fcols))
-            x = ewise("add", h1, gemm(act, w["w2"], dcols))
+            h1, bn, x = after_attention(x, [o], w, g2)
         for j, vtx in enumerate(x[0]):
             tg.outputs.append(vtx)
             tg.binding[vtx] = ("y", pos, pos + 1, dcols[j][0], dcols[j][1])

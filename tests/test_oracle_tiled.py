@@ -110,6 +110,53 @@ def test_vertex_kinds_reduce_to_untiled_routines():
     np.testing.assert_allclose(c, a @ b, rtol=1e-13)
 
 
+def test_fused_gemm_modes_are_the_separate_vertices_in_one():
+    """Mode 1 (the product plus a residual operand) and mode 2 (silu(A G) * (A U)) against the routines they
+    replace: the plain product, an addition, the scipy logistic function."""
+    from scipy.special import expit
+    rng = np.random.default_rng(11)
+    a, g, u, r = rng.standard_normal((5, 10)), rng.standard_normal((10, 4)), rng.standard_normal((10, 4)), rng.standard_normal((5, 4))
+    ins = [a[:, :6], a[:, 6:], g[:6], g[6:]]
+    np.testing.assert_allclose(T._eval_vertex("gemm", dict(nk=2, mode=1), ins + [r]), a @ g + r, rtol=1e-13)
+    gate, up = a @ g, a @ u
+    got = T._eval_vertex("gemm", dict(nk=2, mode=2), ins + [u[:6], u[6:]])
+    np.testing.assert_allclose(got, gate * expit(gate) * up, rtol=1e-12)
+    # weights stored [out, in]
+    got_t = T._eval_vertex("gemm", dict(nk=2, mode=2, trans_b=1), [a[:, :6], a[:, 6:], g[:6].T, g[6:].T, u[:6].T, u[6:].T])
+    np.testing.assert_allclose(got_t, got, rtol=1e-13)
+    # separate vertices give the same numbers
+    sep = T._eval_vertex("silu_mul", {}, [T._eval_vertex("gemm", dict(nk=2), ins), T._eval_vertex("gemm", dict(nk=2), [a[:, :6], a[:, 6:], u[:6], u[6:]])])
+    np.testing.assert_allclose(got, sep, rtol=1e-13)
+
+
+@pytest.mark.parametrize("fuse", [1, 2, 3])
+def test_fused_graph_equals_the_untiled_model(monkeypatch, fuse):
+    """Without storage rounding the fused graph is the same function as the untiled layers (and so as the
+    unfused graph); with fp32 storage it stays as close as the unfused one; it has fewer vertices."""
+    cfg = config("ragged_f32")
+    w = R.widen(cfg, make_llama_inputs(cfg, 3))
+    tg = T.build_llama_taskgraph(cfg, fuse_epilogues=fuse)
+    plain = T.build_llama_taskgraph(cfg)
+    y1 = R.forward(cfg, w)
+    y2 = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
+    assert R.rel_err(y2, y1) < 2e-6
+    assert tg.kind.count("add") == (0 if fuse & 1 else plain.kind.count("add"))
+    assert tg.kind.count("silu_mul") == (0 if fuse & 2 else plain.kind.count("silu_mul"))
+    n_ffn_tiles = plain.kind.count("silu_mul")
+    assert plain.kind.count("gemm") - tg.kind.count("gemm") == (n_ffn_tiles if fuse & 2 else 0)
+    monkeypatch.setattr(T, "round_store", lambda x, dtype: np.asarray(x, dtype=np.float64))
+    y3 = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
+    assert R.rel_err(y3, y1) < 1e-12
+
+
+def test_fused_decode_steps_give_the_rows_of_the_whole_sequence():
+    cfg = config("decode_f32")
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    tg = T.build_llama_taskgraph(cfg, fuse_epilogues=3)
+    y = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
+    assert R.rel_err(y, R.forward(cfg, w)) < 2e-6
+
+
 def test_graph_sizes_match_the_workload_arithmetic():
     cfg = config("c1")
     tg = T.build_llama_taskgraph(cfg)
