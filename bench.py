@@ -132,6 +132,9 @@ def main():
     ap.add_argument("--attn-whole-rows", type=int, default=-1,
                     help="1: attention of a query block as one vertex over all keys up to its own (one partial per block "
                          "instead of one per key block); 0: one vertex per pair of blocks; default: harness.BENCH_WHOLE_ROWS")
+    ap.add_argument("--fuse-epilogues", type=int, default=-1,
+                    help="tiler option fuse_epilogues (bit 0: residual additions inside the products before them, bit 1: "
+                         "W1, W3 and silu * up as one vertex); default: harness.BENCH_FUSE for the workload")
     ap.add_argument("--checkpoint-layers", type=int, default=0,
                     help="with --checkpoint: only the first this many layers are recomputed, the rest keep saved activations")
     ap.add_argument("--materialize-scores", action="store_true",
@@ -245,6 +248,9 @@ def main():
         checkpoint = headline and args.checkpoint
         k_split = args.k_split if headline else 0
         train = bool(args.train) if (headline and args.train >= 0) else cfg.name == "c5"
+        fuse = (args.fuse_epilogues if (headline and args.fuse_epilogues >= 0) else H.BENCH_FUSE.get(name, 0))
+        if train or k_split > 1:
+            fuse = 0
         t0 = time.perf_counter()
         distinct = args.distinct_layers if (headline and args.distinct_layers >= 0) else (0 if cfg.layers <= 8 else 4)
         kv_outputs = (bool(args.kv_outputs) if (headline and args.kv_outputs >= 0)
@@ -263,7 +269,8 @@ def main():
             order = None
             struct = lambda cc: H.llama_config_struct(cc, kv_outputs, lora_rank=16 if train else 0, train=train,
                                                       k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
-                                                      attn_whole_rows=whole_rows, checkpoint_layers=ck_layers)
+                                                      attn_whole_rows=whole_rows, checkpoint_layers=ck_layers,
+                                                      fuse_epilogues=fuse)
             if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
                 tg = B.tn_build_llama(struct(c))
                 c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
@@ -281,7 +288,7 @@ def main():
             return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                                 lora_rank=16 if train else 0, train=train, progress=lambda m: note(f"{name}: {m}"),
                                 k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint, attn_whole_rows=whole_rows,
-                                checkpoint_layers=ck_layers, device_outputs=device_outputs)
+                                checkpoint_layers=ck_layers, device_outputs=device_outputs, fuse_epilogues=fuse)
 
         t0 = time.perf_counter()
         s = session(cfg, device_outputs)
@@ -348,6 +355,7 @@ def main():
             "gpu_cap_bytes": s.cap, "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
             "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
             "serial_order": level or "tiler", "attention_vertices": "whole rows" if whole_rows else "per pair of blocks",
+            "fuse_epilogues": fuse,
             "memgraph": {"vertices": int(st.n_vertices), "offloads": int(st.n_offload), "reloads": int(st.n_reload),
                          "loads": int(st.n_load), "drops": int(st.n_drop), "stores": int(st.n_store),
                          "mem_edges": int(st.n_mem_edges), "offload_GB": st.offload_bytes / 1e9,

@@ -60,7 +60,7 @@ enum { TN_HOST = 0, TN_DEVICE = 1 }; /* where an input tensor lies when executio
  * (Introduction, fourth paragraph: the output is correct no matter the execution order). */
 enum {
   TN_OP_INPUT = 0,        /* ()                       -> the tensor itself                        */
-  TN_OP_GEMM = 1,         /* A_0..A_{nk-1}, B_0..B_{nk-1} -> sum_k A_k B_k, k ascending, fp32 acc  */
+  TN_OP_GEMM = 1,         /* A_0..A_{nk-1}, B_0..B_{nk-1}[, ...] -> sum_k A_k B_k, k ascending, fp32 acc (+ mode) */
   TN_OP_RMS_STAT = 2,     /* X_0..X_{n-1} (one row block) -> fp32 [rows,1]: rsqrt(sum x^2 / d + eps) */
   TN_OP_RMS_APPLY = 3,    /* X, stat[rows,1] fp32, gain[1,cols] -> x * stat * gain                 */
   TN_OP_ROPE = 4,         /* X -> rotary embedding of interleaved pairs (2i, 2i+1)                 */
@@ -123,6 +123,12 @@ typedef struct {
  *                                       output tile = rows [row0, row0 + rows) and columns
  *                                       [col0, col0 + cols) of the merged, normalised block.
  *   GEMM         trans_a                != 0: A_k is stored transposed, [K_k, rows]
+ *   GEMM         mode                   1: one more operand follows the B tiles, R of the output's shape and
+ *                                       type; the result is sum_k A_k B_k + R, added in fp32 before the one
+ *                                       rounding.  2: nk more operands follow the B tiles, U_0..U_{nk-1}
+ *                                       shaped like them; with gate = sum_k A_k B_k and up = sum_k A_k U_k
+ *                                       (both fp32) the result is gate / (1 + exp(-gate)) * up.  Both need
+ *                                       trans_a == 0 and trans_c == 0.
  *   ROPE         mode                   != 0: the inverse rotation (which is also the rotation's gradient)
  *   SILU_MUL_BWD mode                   with s = 1/(1 + exp(-gate)): mode 0 -> dact * up * s * (1 + gate * (1 - s)),
  *                                       mode 1 -> dact * gate * s
@@ -297,6 +303,12 @@ typedef struct {
    * pushes to the host: recomputing those and saving the rest trades a little arithmetic for all of the
    * offload traffic when the rest fits. */
   int32_t checkpoint_layers;
+  /* bits (need train == 0 and k_split <= 1; which steps of a layer share a vertex is the front end's
+   * choice, Section 4): 1 -- the two residual additions of a layer become the last operand of the products
+   * before them (GEMM, mode 1), so the projection's own output tile is never stored; 2 -- the W1 and W3
+   * products and silu(gate) * up become one vertex (GEMM, mode 2), so the two [rows, ffn] intermediates
+   * never exist.  A fused vertex rounds to the storage type once. */
+  int32_t fuse_epilogues;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -255,8 +255,10 @@ tn_status build_tables(tn_executor& ex) {
           if (kk % 8) mfma = false;
           if (kk % 32) k32 = false;
         }
-        vi.cls = !mfma ? LC_GEMM_F32 : (k32 && d.rows >= 256 && d.cols >= 256) ? LC_GEMM_BF16_NT256 : LC_GEMM_BF16_NT;
-        vi.flops = 2.0 * d.rows * d.cols * K;
+        const bool big = k32 && d.rows >= 256 && d.cols >= 256;
+        // the fused forms (mode 1: + residual, mode 2: gated pair) exist in the 256-tile kernel and in the generic one
+        vi.cls = !mfma ? LC_GEMM_F32 : big ? LC_GEMM_BF16_NT256 : x.p.mode != 0 ? LC_GEMM_F32 : LC_GEMM_BF16_NT;
+        vi.flops = (x.p.mode == 2 ? 4.0 : 2.0) * d.rows * d.cols * K;
         break;
       }
       case TN_OP_RMS_STAT:

@@ -531,9 +531,17 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch
   const int m0 = (blockIdx.x / tn_) * 64, n0 = (blockIdx.x % tn_) * 64;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   float acc[4][4] = {};
+  float gate[4][4];  // mode 2: the first of the two products, while the second is formed
+  for (int pass = 0; pass < (d.p.mode == 2 ? 2 : 1); ++pass) {
+  if (pass == 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { gate[i][j] = acc[i][j]; acc[i][j] = 0.f; }
+  }
   for (int kt = 0; kt < nk; ++kt) {
     const T* A = (const T*)t.ptrs[d.ptr0 + kt];
-    const T* B = (const T*)t.ptrs[d.ptr0 + nk + kt];
+    const T* B = (const T*)t.ptrs[d.ptr0 + (1 + pass) * nk + kt];
     const int K = t.aux[d.aux0 + kt];
     for (int k0 = 0; k0 < K; k0 += 16) {
       {
@@ -572,13 +580,19 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(DeviceTables t, Batch
       __syncthreads();
     }
   }
+  }
   T* Cp = (T*)d.out;
+  const T* R = d.p.mode == 1 ? (const T*)t.ptrs[d.ptr0 + 2 * nk] : nullptr;  // the residual operand
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int r = m0 + ty * 4 + i, c = n0 + tx * 4 + j;
-      if (r < M && c < N) st(d.p.trans_c ? Cp + (size_t)c * M + r : Cp + (size_t)r * N + c, acc[i][j]);
+      if (r >= M || c >= N) continue;
+      float v = acc[i][j];
+      if (d.p.mode == 1) v += ld(R + (size_t)r * N + c);
+      if (d.p.mode == 2) v = gate[i][j] / (1.f + __expf(-gate[i][j])) * v;
+      st(d.p.trans_c ? Cp + (size_t)c * M + r : Cp + (size_t)r * N + c, v);
     }
 }
 
@@ -622,6 +636,75 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[TI][TJ], bf16_
           if (row + 3 < M) p[3 * sr] = h3;
         }
       }
+    }
+  }
+}
+
+// Accumulator tiles formed with the operands exchanged (B fragments first): acc[i][j] is then the transpose
+// of a 32x32 piece of C -- a lane holds row l32 of row group j and, per group of four registers, the four
+// consecutive columns 8*(r/4) + 4*g + r%4 of column group i.  The wavefront's piece of C (32 TJ rows by
+// 32 NT columns) goes through `stage`, LDS of its own (EpilogueStage<NT, TJ>::BYTES), as bf16 rows of a
+// padded pitch -- 8-byte writes from this layout, 16-byte reads along the rows -- so that every global
+// store instruction writes whole runs of 64 NT bytes.
+// R: a [M, N] bf16 tensor added to the product before the rounding.
+template <int NT, int TJ>
+struct EpilogueStage {
+  static constexpr int PITCH = 64 * NT + 16;  // bytes per row: the lanes of a half-wavefront write 32 rows at once
+  static constexpr int BYTES = 32 * TJ * PITCH;
+};
+template <int NT, int TJ>
+__device__ __forceinline__ void store_c_rows(const f32x16 (&acc)[NT][TJ], char* stage, bf16_t* Cp, int M, int N, int row0,
+                                             int col0, int lane, const bf16_t* R) {
+  constexpr int PITCH = EpilogueStage<NT, TJ>::PITCH;
+  const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) {
+    const int row = row0 + j * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      const f32x16 c = acc[i][j];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int cin = i * 32 + 8 * a + 4 * g;  // column inside the wavefront's piece
+        float v[4] = {c[4 * a], c[4 * a + 1], c[4 * a + 2], c[4 * a + 3]};
+        if (R != nullptr && row < M) {
+          const size_t at = (size_t)row * N + col0 + cin;
+          if ((N & 3) == 0 && col0 + cin + 3 < N) {
+            const uint2 r = *(const uint2*)(R + at);
+            v[0] += __uint_as_float(r.x << 16);
+            v[1] += __uint_as_float(r.x & 0xFFFF0000u);
+            v[2] += __uint_as_float(r.y << 16);
+            v[3] += __uint_as_float(r.y & 0xFFFF0000u);
+          } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              if (col0 + cin + k < N) v[k] += bf2f(R[at + k]);
+          }
+        }
+        uint2 o;
+        o.x = f2bf2(v[0], v[1]);
+        o.y = f2bf2(v[2], v[3]);
+        *(uint2*)(stage + (j * 32 + l32) * PITCH + cin * 2) = o;
+      }
+    }
+  }
+  // rows of the piece, 16 bytes per lane: 4 NT lanes per row
+  constexpr int LPR = 4 * NT, RPI = 64 / LPR;  // lanes per row, rows per instruction
+  const int rin = lane / LPR, cin = (lane % LPR) * 8;
+  const bool whole = (N & 7) == 0;  // rows of C are 16-byte aligned
+#pragma unroll
+  for (int q = 0; q < 32 * TJ / RPI; ++q) {
+    const int r = q * RPI + rin, row = row0 + r, col = col0 + cin;
+    const uint4 x = *(const uint4*)(stage + r * PITCH + cin * 2);
+    if (row >= M || col >= N) continue;
+    bf16_t* dst = Cp + (size_t)row * N + col;
+    if (whole && col + 7 < N) {
+      *(uint4*)dst = x;
+    } else {
+      const bf16_t* e = (const bf16_t*)&x;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (col + k < N) dst[k] = e[k];
     }
   }
 }
@@ -811,13 +894,19 @@ __global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kern
   xcd_remap(bx, by);
   const OpDesc& d = t.descs[b.at(by)];
   const int M = d.rows, N = d.cols, nk = d.p.nk;
-  const int tn_ = (N + BN - 1) / BN;
+  // Mode 2 (gate and up products, silu(gate) * up): the workgroup's BN rows of B are half gate columns and
+  // half up columns of the same BN / 2 output columns: 32 gate rows, then the 32 up rows of the same outputs,
+  // and so on, so that a wavefront's two 32-column accumulator tiles are the gate and the up of one piece.
+  const bool gated = d.p.mode == 2;
+  static_assert(TJ == 2 && TI % 2 == 0, "the gated form pairs the two accumulator tiles of a wavefront; mode 1 stores in halves");
+  const int bn_out = gated ? BN / 2 : BN;  // output columns per workgroup
+  const int tn_ = (N + bn_out - 1) / bn_out;
   if (bx >= ((M + BM - 1) / BM) * tn_) return;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const void* const* ptrA = t.ptrs + d.ptr0;  // A_0.., then nk entries later B_0..
+  const void* const* ptrA = t.ptrs + d.ptr0;  // A_0.., then nk entries later B_0.. (and nk later again the up tiles)
   const int* ksz = t.aux + d.aux0;
   bf16_t* const Cp = (bf16_t*)d.out;
-  const int m0 = (bx / tn_) * BM, n0 = (bx % tn_) * BN;
+  const int m0 = (bx / tn_) * BM, n0 = (bx % tn_) * bn_out;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w / WNS, wn = w % WNS;
   const int l32 = lane & 31, g = lane >> 5;
 
@@ -840,13 +929,16 @@ __global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kern
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
     rowA[i] = min(m0 + lrow + i * 16 * NW, M - 1);
-    rowB[i] = min(n0 + lrow + i * 16 * NW, N - 1);
+    const int rb = lrow + i * 16 * NW;  // row of the B operand in LDS; gated: columns (rb / 64) * 32 + rb % 32
+    rowB[i] = min(n0 + (gated ? (rb >> 6) * 32 + (rb & 31) : rb), N - 1);
   }
+  // gated: rows 32..63 of every 64 come from the up tiles; a wavefront's 16-row pieces lie all on one side
+  const int bsel = __builtin_amdgcn_readfirstlane(gated ? nk * (1 + ((w >> 1) & 1)) : nk);
   int nsteps = 0;
   for (int k = 0; k < nk; ++k) nsteps += ksz[k] / G2_K;
   int kt = 0, k0 = 0, K = sload_int(ksz);
   const bf16_t* A = (const bf16_t*)sload_ptr(ptrA);
-  const bf16_t* B = (const bf16_t*)sload_ptr(ptrA + nk);
+  const bf16_t* B = (const bf16_t*)sload_ptr(ptrA + bsel);
   uint32_t offA[NLD], offB[NLD];
   auto set_offsets = [&]() {
 #pragma unroll
@@ -873,7 +965,7 @@ __global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kern
       k0 = 0;
       const int Kn = sload_int(ksz + kt);
       A = (const bf16_t*)sload_ptr(ptrA + kt);
-      B = (const bf16_t*)sload_ptr(ptrA + nk + kt);
+      B = (const bf16_t*)sload_ptr(ptrA + bsel + kt);
       if (Kn != K) {
         K = Kn;
         set_offsets();
@@ -883,7 +975,15 @@ __global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kern
 
   // fragment addresses inside a stage: row-major chunks, swizzled as above
   const int sw = (l32 >> 2) & 3;
-  const int fragA = ((wm * 32 * TI + l32) * 4) * 16, fragB = OPER_BYTES + ((wn * 32 * TJ + l32) * 4) * 16;
+  // With a residual operand (mode 1) the product is formed with the operands exchanged: the first MFMA
+  // operand (TI fragments, 32 TI rows of its region per wavefront row wm) comes from B and the second (TJ
+  // fragments, wavefront column wn) from A, so an accumulator tile is a piece of C^T and a lane holds runs of
+  // four consecutive columns of one row -- 8-byte pieces of the residual's rows instead of single elements
+  // (see store_c_rows).  The sums are the same sums.  (For the plain product this form measures 2 % slower
+  // than the stores straight from the registers below, so only mode 1 takes it.)
+  const bool exch = d.p.mode == 1;
+  const int fragA = (exch ? OPER_BYTES : 0) + ((wm * 32 * TI + l32) * 4) * 16;
+  const int fragB = (exch ? 0 : OPER_BYTES) + ((wn * 32 * TJ + l32) * 4) * 16;
   const int c0 = ((0 + g) ^ sw) * 16, c1 = ((2 + g) ^ sw) * 16;
 
   for (int s = 0; s < G2_STAGES - 1 && s < nsteps; ++s) issue(s);
@@ -946,7 +1046,37 @@ __global__ void __launch_bounds__(64 * NW, TI == 2 ? 2 : 1) gemm_bf16_nt256_kern
 #undef TN_INTERLEAVE
   mfma_acc_drain();
 
-  store_c_tiles<TI, TJ>(acc, Cp, M, N, m0 + wm * 32 * TI, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
+  if (gated) {
+    f32x16 act[TI][1];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float gt = acc[i][0][r];
+        act[i][0][r] = gt / (1.f + __expf(-gt)) * acc[i][1][r];
+      }
+    store_c_tiles<TI, 1>(act, Cp, M, N, m0 + wm * 32 * TI, n0 + wn * 32, l32, g, false);
+    return;
+  }
+  if (!exch) {
+    store_c_tiles<TI, TJ>(acc, Cp, M, N, m0 + wm * 32 * TI, n0 + wn * 32 * TJ, l32, g, d.p.trans_c != 0);
+    return;
+  }
+  // exchanged: this wavefront holds rows m0 + 32 TJ wn .. and columns n0 + 32 TI wm ..; it stores them in
+  // two halves of 16 TI columns through LDS of its own, once nobody reads the last stage any more
+  static_assert(NW * EpilogueStage<TI / 2, TJ>::BYTES <= G2_STAGES * STAGE_BYTES, "the epilogue's rows fit the stages' LDS");
+  __syncthreads();
+  char* const ep = lds + w * EpilogueStage<TI / 2, TJ>::BYTES;
+  const bf16_t* R = (const bf16_t*)sload_ptr(ptrA + 2 * nk);
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    f32x16 part[TI / 2][TJ];
+#pragma unroll
+    for (int i = 0; i < TI / 2; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) part[i][j] = acc[hf * (TI / 2) + i][j];
+    store_c_rows<TI / 2, TJ>(part, ep, Cp, M, N, m0 + wn * 32 * TJ, n0 + wm * 32 * TI + hf * 16 * TI, lane, R);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1671,7 +1801,7 @@ int32_t blocks_for(int cls, const OpDesc& d, const int32_t* aux) {
   switch (cls) {
     case LC_GEMM_F32: return cdiv(d.rows, 64) * cdiv(d.cols, 64);
     case LC_GEMM_BF16_NT: return cdiv(d.rows, GB_M) * cdiv(d.cols, GB_N);
-    case LC_GEMM_BF16_NT256: return cdiv(d.rows, 256) * cdiv(d.cols, 256);
+    case LC_GEMM_BF16_NT256: return cdiv(d.rows, 256) * cdiv(d.cols, d.p.mode == 2 ? 128 : 256);
     case LC_RMS_STAT: return cdiv(d.rows, 4);
     case LC_RMS_APPLY: return cdiv((int64_t)d.rows * cdiv(d.cols, 8), 256);
     case LC_ROPE:

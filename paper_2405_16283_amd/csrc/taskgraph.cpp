@@ -42,7 +42,13 @@ tn_status validate_op(const TaskGraph& g, int32_t kind, const tn_op_params& p, c
     return fail(TN_ERR_SHAPE, "output tensor must be non-empty fp32 or bf16");
   switch (kind) {
     case TN_OP_GEMM: {
-      if (p.nk < 1 || n_in != 2 * p.nk) return fail(TN_ERR_SHAPE, "gemm: needs 2*nk operands");
+      if (p.mode < 0 || p.mode > 2) return fail(TN_ERR_SHAPE, "gemm: mode must be 0, 1 or 2");
+      const int32_t want = p.mode == 1 ? 2 * p.nk + 1 : p.mode == 2 ? 3 * p.nk : 2 * p.nk;
+      if (p.nk < 1 || n_in != want) return fail(TN_ERR_SHAPE, "gemm: needs %d operands for nk %d, mode %d", want, p.nk, p.mode);
+      if (p.mode != 0 && (p.trans_a || p.trans_c)) return fail(TN_ERR_SHAPE, "gemm: modes 1 and 2 go with neither trans_a nor trans_c");
+      if (p.mode == 1 && !same(D(2 * p.nk), out)) return fail(TN_ERR_SHAPE, "gemm: the residual operand must have the output's shape and type");
+      for (int k = 0; p.mode == 2 && k < p.nk; ++k)
+        if (!same(D(p.nk + k), D(2 * p.nk + k))) return fail(TN_ERR_SHAPE, "gemm: up tile %d is not shaped like its gate tile", k);
       tn_tensor_desc lo = out;  // logical [rows, cols] of the product
       if (p.trans_c) std::swap(lo.rows, lo.cols);
       for (int k = 0; k < p.nk; ++k) {
@@ -300,9 +306,21 @@ struct Tiler {
 
   // one output tile of X(row tile) * W: full K inside one vertex, or (k_split) partial products
   // over runs of K tiles joined by a sum vertex
+  // residual >= 0: that tile is added inside the vertex (mode 1); up != nullptr: the gated pair of products (mode 2)
   tn_vid gemm(const std::vector<tn_vid>& xrow, const Grid& w, size_t j, int32_t m, int32_t n,
-              bool trans_c = false) {
+              bool trans_c = false, tn_vid residual = -1, const Grid* up = nullptr) {
     const size_t nk = xrow.size();
+    if (residual >= 0 || up) {
+      tn_op_params p{};
+      p.nk = (int32_t)nk;
+      p.trans_b = c.weights_transposed ? 1 : 0;
+      p.mode = up ? 2 : 1;
+      std::vector<tn_vid> in(xrow);
+      for (size_t k = 0; k < nk; ++k) in.push_back(w[k][j]);
+      if (up) for (size_t k = 0; k < nk; ++k) in.push_back((*up)[k][j]);
+      else in.push_back(residual);
+      return op(TN_OP_GEMM, p, std::move(in), {c.dtype, m, n});
+    }
     const size_t per = c.k_split > 1 ? (nk + c.k_split - 1) / c.k_split : nk;
     const tn_tensor_desc d = trans_c ? tn_tensor_desc{c.dtype, n, m} : tn_tensor_desc{c.dtype, m, n};
     std::vector<tn_vid> parts;
@@ -627,6 +645,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.decode_steps > 0 && (c.train || c.materialize_scores || c.batch != 1 || c.lora_rank > 0))
     return fail(TN_ERR_INVALID, "decode_steps needs one sequence, and none of train, lora_rank, materialize_scores");
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
+  if (c.fuse_epilogues < 0 || c.fuse_epilogues > 3 || (c.fuse_epilogues && (c.train || c.k_split > 1)))
+    return fail(TN_ERR_INVALID, "fuse_epilogues takes bits 1 and 2 and goes with neither train nor k_split");
   if (c.checkpoint_layers < 0 || (c.checkpoint_layers > 0 && !c.checkpoint))
     return fail(TN_ERR_INVALID, "checkpoint_layers needs checkpoint and must not be negative");
   // layers whose forward tensors the reverse pass forms again instead of reading saved ones
@@ -803,13 +823,18 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         std::vector<tn_vid> h(nd);
         for (size_t j = 0; j < nd; ++j) {
           const int32_t n = t.dcols[j].len();
-          h[j] = t.op(TN_OP_ADD, tn_op_params{}, {xb[i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
+          h[j] = (c.fuse_epilogues & 1) ? t.gemm(o[i], wo, j, m, n, false, xb[i][j])
+                                        : t.op(TN_OP_ADD, tn_op_params{}, {xb[i][j], t.gemm(o[i], wo, j, m, n)}, {c.dtype, m, n});
         }
         tn_vid st2 = -1;
         auto bn = t.rmsnorm(h, g2, m, &st2);
         std::vector<tn_vid> act(nf), gates(nf), ups(nf);
         for (size_t j = 0; j < nf; ++j) {
           const int32_t n = t.fcols[j].len();
+          if (c.fuse_epilogues & 2) {  // never with train: nothing is saved
+            if (tail) act[j] = t.gemm(bn, w1, j, m, n, false, -1, &w3);
+            continue;
+          }
           tn_vid gate = t.gemm(bn, w1, j, m, n), up = t.gemm(bn, w3, j, m, n);
           gates[j] = gate;
           ups[j] = up;
@@ -820,7 +845,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
         }
         for (size_t j = 0; tail && j < nd; ++j) {
           const int32_t n = t.dcols[j].len();
-          xb[i][j] = t.op(TN_OP_ADD, tn_op_params{}, {h[j], t.gemm(act, w2, j, m, n)}, {c.dtype, m, n});
+          xb[i][j] = (c.fuse_epilogues & 1) ? t.gemm(act, w2, j, m, n, false, h[j])
+                                            : t.op(TN_OP_ADD, tn_op_params{}, {h[j], t.gemm(act, w2, j, m, n)}, {c.dtype, m, n});
         }
       }
     }
@@ -947,14 +973,20 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           }
         }
         std::vector<tn_vid> h(nd);
-        for (size_t j = 0; j < nd; ++j) h[j] = t.add(xr[j], t.gemm(o, w.wo, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
+        for (size_t j = 0; j < nd; ++j)
+          h[j] = (c.fuse_epilogues & 1) ? t.gemm(o, w.wo, j, 1, t.dcols[j].len(), false, xr[j])
+                                        : t.add(xr[j], t.gemm(o, w.wo, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
         auto bn = t.rmsnorm(h, w.g2, 1);
         std::vector<tn_vid> act(nf);
         for (size_t j = 0; j < nf; ++j) {
           const int32_t n = t.fcols[j].len();
-          act[j] = t.op(TN_OP_SILU_MUL, tn_op_params{}, {t.gemm(bn, w.w1, j, 1, n), t.gemm(bn, w.w3, j, 1, n)}, {c.dtype, 1, n});
+          act[j] = (c.fuse_epilogues & 2)
+                       ? t.gemm(bn, w.w1, j, 1, n, false, -1, &w.w3)
+                       : t.op(TN_OP_SILU_MUL, tn_op_params{}, {t.gemm(bn, w.w1, j, 1, n), t.gemm(bn, w.w3, j, 1, n)}, {c.dtype, 1, n});
         }
-        for (size_t j = 0; j < nd; ++j) xr[j] = t.add(h[j], t.gemm(act, w.w2, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
+        for (size_t j = 0; j < nd; ++j)
+          xr[j] = (c.fuse_epilogues & 1) ? t.gemm(act, w.w2, j, 1, t.dcols[j].len(), false, h[j])
+                                         : t.add(h[j], t.gemm(act, w.w2, j, 1, t.dcols[j].len()), 1, t.dcols[j].len());
         if (c.hidden_outputs && layer_is_output(l) && l + 1 < c.layers)
           for (size_t j = 0; j < nd; ++j) t.mark_output(xr[j], TN_T_H, l, rr, t.dcols[j]);
       }

@@ -31,7 +31,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
                         k_split: int = 0, materialize_scores: bool = False,
                         checkpoint: bool = False, hidden_outputs: bool = False,
                         output_layer_stride: int = 0, attn_whole_rows: bool = False,
-                        checkpoint_layers: int = 0) -> B.tn_llama_config:
+                        checkpoint_layers: int = 0, fuse_epilogues: int = 0) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -44,7 +44,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         materialize_scores=int(materialize_scores), checkpoint=int(checkpoint),
         hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride),
         decode_steps=int(getattr(cfg, "decode_steps", 0)), attn_whole_rows=int(attn_whole_rows),
-        checkpoint_layers=int(checkpoint_layers))
+        checkpoint_layers=int(checkpoint_layers), fuse_epilogues=int(fuse_epilogues))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -196,6 +196,13 @@ BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered", "c2_capped25": "cl
 BENCH_WHOLE_ROWS = {}
 
 
+# Workloads the benchmark tiles with fused epilogues (tiler option fuse_epilogues, bits 1 | 2).  The one-layer
+# workload gains 3-4 % in HBM and 6 % streamed under 40 % of its peak; c3 and c4 measure the same either way
+# (the residual form of the product is 2-3 % slower than the plain one, which eats what the additions cost),
+# and under 25 % of the peak the gated vertex, which wants its W1 and W3 tiles resident together, loses.
+BENCH_FUSE = {"c2": 3, "c2_capped40": 3}
+
+
 def cap_for(cfg, tg) -> int:
     """The workload's GPU-memory cap in bytes."""
     if cfg.cap_bytes:
@@ -214,7 +221,7 @@ class GpuSession:
                  lora_rank: int = 0, train: bool = False, progress=None, k_split: int = 0,
                  materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
                  device_inputs: bool = False, hidden_outputs: bool = False, output_layer_stride: int = 0,
-                 attn_whole_rows: bool = False, checkpoint_layers: int = 0):
+                 attn_whole_rows: bool = False, checkpoint_layers: int = 0, fuse_epilogues: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -223,7 +230,7 @@ class GpuSession:
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
                                                        lora_rank, train, k_split, materialize_scores,
                                                        checkpoint, hidden_outputs, output_layer_stride,
-                                                       attn_whole_rows, checkpoint_layers))
+                                                       attn_whole_rows, checkpoint_layers, fuse_epilogues))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

@@ -53,6 +53,55 @@ def test_library_taskgraph_evaluated_by_the_oracle_equals_the_untiled_model(name
     assert kinds(otg) == kinds(own)
 
 
+@pytest.mark.parametrize("name,fuse", [("ragged_f32", 3), ("ragged_bf16", 1), ("ragged_bf16", 2), ("decode_f32", 3)])
+def test_library_taskgraph_with_fused_epilogues_equals_the_oracles(name, fuse):
+    """fuse_epilogues: the library's graph, interpreted by the oracle, gives the bits of the oracle's own fused
+    graph and stays at the untiled model; the fused kinds replace exactly the vertices they stand for."""
+    cfg = config(name)
+    tg = B.tn_build_llama(H.llama_config_struct(cfg, fuse_epilogues=fuse))
+    try:
+        otg = oracle_taskgraph(tg)
+    finally:
+        B.tn_taskgraph_destroy(tg)
+    w = R.widen(cfg, make_llama_inputs(cfg, 0))
+    y_lib = T.assemble_outputs(otg, T.evaluate(otg, T.cut_inputs(otg, w)), cfg.tokens, cfg.d_model)
+    own = T.build_llama_taskgraph(cfg, fuse_epilogues=fuse)
+    y_own = T.assemble_outputs(own, T.evaluate(own, T.cut_inputs(own, w)), cfg.tokens, cfg.d_model)
+    np.testing.assert_array_equal(y_lib, y_own)
+    assert R.rel_err(y_lib, R.forward(cfg, w)) < (2e-6 if cfg.dtype == "f32" else 5e-2)
+    kinds = lambda g: sorted((k, g.kind.count(k)) for k in set(g.kind))
+    assert kinds(otg) == kinds(own)
+    modes = lambda g: sorted(p.get("mode", 0) for k, p in zip(g.kind, g.params) if k == "gemm")
+    assert modes(otg) == modes(own) and set(modes(otg)) == {0} | ({1} if fuse & 1 else set()) | ({2} if fuse & 2 else set())
+    assert ("add" in otg.kind) == (not fuse & 1) and ("silu_mul" in otg.kind) == (not fuse & 2)
+
+
+def test_fused_epilogues_are_checked():
+    for kw in (dict(train=True, lora_rank=4), dict(k_split=2)):
+        with pytest.raises(B.TurnipError) as e:
+            B.tn_build_llama(H.llama_config_struct(config("c1"), fuse_epilogues=1, **kw))
+        assert e.value.status == B.TN_ERR_INVALID
+    c = H.llama_config_struct(config("c1"))
+    c.fuse_epilogues = 4
+    with pytest.raises(B.TurnipError):
+        B.tn_build_llama(c)
+    # a hand-built vertex: operand counts and shapes of the two modes
+    tg = B.tn_taskgraph_create()
+    try:
+        inp = lambda r, c_: B.tn_taskgraph_add_input(tg, B.TN_F32, r, c_, B.TN_DEVICE)
+        a, b, u, r, bad = inp(4, 8), inp(8, 6), inp(8, 6), inp(4, 6), inp(4, 5)
+        B.tn_taskgraph_add_op(tg, B.TN_OP_GEMM, B.tn_op_params(nk=1, mode=1), [a, b, r], B.TN_F32, 4, 6)
+        B.tn_taskgraph_add_op(tg, B.TN_OP_GEMM, B.tn_op_params(nk=1, mode=2), [a, b, u], B.TN_F32, 4, 6)
+        for params, ins in ((B.tn_op_params(nk=1, mode=1), [a, b]), (B.tn_op_params(nk=1, mode=1), [a, b, bad]),
+                            (B.tn_op_params(nk=1, mode=2), [a, b, r]), (B.tn_op_params(nk=1, mode=1, trans_c=1), [a, b, r]),
+                            (B.tn_op_params(nk=1, mode=3), [a, b])):
+            with pytest.raises(B.TurnipError) as e:
+                B.tn_taskgraph_add_op(tg, B.TN_OP_GEMM, params, ins, B.TN_F32, 4, 6)
+            assert e.value.status == B.TN_ERR_SHAPE
+    finally:
+        B.tn_taskgraph_destroy(tg)
+
+
 def test_kv_outputs_are_marked():
     cfg = config("c1")
     tg = B.tn_build_llama(H.llama_config_struct(cfg, kv_outputs=True))

@@ -13,11 +13,14 @@ from workloads import bf16_bits_to_f32, config, make_llama_inputs
 pytestmark = pytest.mark.gpu
 
 
-def _case(seed):
+FUSE = H.BENCH_FUSE.get("c2", 0)  # the benchmark tiles this workload with fused epilogues
+
+
+def _case(seed, fuse=FUSE):
     cfg = config("c2")
     full = make_llama_inputs(cfg, seed)
     w = R.widen(cfg, full)
-    tg = T.build_llama_taskgraph(cfg)
+    tg = T.build_llama_taskgraph(cfg, fuse_epilogues=fuse)
     y = T.assemble_outputs(tg, T.evaluate(tg, T.cut_inputs(tg, w)), cfg.tokens, cfg.d_model)
     return cfg, full, y
 
@@ -27,6 +30,11 @@ def c2():
     return _case(0)
 
 
+@pytest.fixture(scope="module")
+def c2_plain():
+    return _case(0, 0) if FUSE else None
+
+
 def bench_opts(**kw):
     return B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3, **kw)
 
@@ -34,7 +42,7 @@ def bench_opts(**kw):
 def test_c2_bench_configuration_matches_the_oracle_everywhere(c2):
     cfg, full, y_oracle = c2
     print("[case] c2 full size, bench configuration", flush=True)
-    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS, device_outputs=True)  # as bench.py runs it
+    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS, device_outputs=True, fuse_epilogues=FUSE)  # as bench.py runs it
     try:
         out, rep = s.run(bench_opts())
         y = bf16_bits_to_f32(out["y"]).astype(np.float64)
@@ -57,7 +65,7 @@ def test_c2_other_seeds_match_the_oracle_everywhere(seed):
     """The bar is 2e-2 over all 16.7 M outputs; the margin is printed for every seed."""
     cfg, full, y_oracle = _case(seed)
     print(f"[case] c2 full size, seed {seed}", flush=True)
-    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS, device_outputs=True)
+    s = H.GpuSession(cfg, full, n_compute=H.BENCH_COMPUTE_STREAMS, device_outputs=True, fuse_epilogues=FUSE)
     try:
         out, rep = s.run(bench_opts())
         y = bf16_bits_to_f32(out["y"]).astype(np.float64)
@@ -69,19 +77,20 @@ def test_c2_other_seeds_match_the_oracle_everywhere(seed):
 
 
 @pytest.mark.parametrize("percent,order", [(40, "clustered"), (25, "clustered"), (40, "level")])
-def test_c2_streamed_under_a_fraction_of_its_peak_gives_the_same_bits(c2, percent, order):
+def test_c2_streamed_under_a_fraction_of_its_peak_gives_the_same_bits(c2, c2_plain, percent, order):
     """The benchmark's capped runs of the one-layer workload (everything streamed from the host; cap 40 % and
-    25 % of the uncapped peak, clustered serial order) and the level order at 40 %, which offloads: the
-    oracle's result at the one-layer bar, and the bits of the uncapped run."""
-    cfg, full, y_oracle = c2
+    25 % of the uncapped peak, clustered serial order, epilogues fused as the benchmark has them) and the level
+    order at 40 %, which offloads: the oracle's result at the one-layer bar, and the same bits in another order."""
+    fuse = H.BENCH_FUSE.get(f"c2_capped{percent}", 0) if order == "clustered" else 0
+    cfg, full, y_oracle = c2 if fuse == FUSE else c2_plain
     capped = cfg.with_(cap_bytes=0, cap_frac=percent / 100.0, weights_resident=False, x_resident=False)
-    print(f"[case] c2 streamed, cap = {percent} % of the uncapped peak, serial order {order}", flush=True)
-    tg = B.tn_build_llama(H.llama_config_struct(capped))
+    print(f"[case] c2 streamed, cap = {percent} % of the uncapped peak, serial order {order}, fuse_epilogues {fuse}", flush=True)
+    tg = B.tn_build_llama(H.llama_config_struct(capped, fuse_epilogues=fuse))
     cap = H.cap_for(capped, tg)
     B.tn_taskgraph_destroy(tg)
     # the serial order, compile options and stream count of the benchmark's capped runs
     s = H.GpuSession(capped, full, cap=cap, compile_opts=H.bench_compile_opts(cap, False, pressed=True),
-                     n_compute=H.BENCH_COMPUTE_STREAMS, order=order)
+                     n_compute=H.BENCH_COMPUTE_STREAMS, order=order, fuse_epilogues=fuse)
     try:
         print(f"  {s.stats.n_offload} offloads, {s.stats.n_load} loads", flush=True)
         assert s.stats.n_load > 0 and s.stats.high_water <= cap
