@@ -44,8 +44,10 @@ HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 # against 51 with the defaults; 10 to 16 workgroups measure within 2 % of one another, 24 cost 5 %); on
 # the compute-bound c3 the same setting costs 20 %.  On c5 the small groups of tile products appear while
 # the link is the bottleneck (the reverse pass waits for reloads), and spread over all compute units they
-# slow the copy kernel more than they gain (1.34 against 1.30 s per step).
-TRANSFERS = {"c4": (128, 14)}
+# slow the copy kernel more than they gain (1.34 against 1.30 s per step).  The one-layer workload streamed
+# under a fraction of its peak is bound by the link as well: 16 copy workgroups move 52 GB/s beside the tile
+# products where 8 move 45 (11.0 -> 9.9 ms per step under 40 %; larger groups do not help it further).
+TRANSFERS = {"c4": (128, 14), "c2_capped40": (32, 16), "c2_capped25": (32, 16)}
 SMALL_GEMM_TILES = {"c5": -1}
 # c5's sub-record is also timed with this many of its first layers checkpointed (--checkpoint --checkpoint-layers)
 MIXED_CHECKPOINT_LAYERS = 12
