@@ -82,7 +82,7 @@ def decoder_layer(x, w, layer: int, n_heads: int, head_dim: int, eps: float, bas
 
 
 def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim: int, eps: float, base: float,
-                       k_ctx=None, v_ctx=None, store=None, own_follow_ctx=False):
+                       k_ctx=None, v_ctx=None, store=None, own_follow_ctx=False, fuse_epilogues=0):
     """One decoder layer for a sample of the rows of one sequence.
 
     Every step of the layer works row by row except attention, in which the row at position p reads
@@ -94,8 +94,10 @@ def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim:
     taskgraph tensor is rounded to its storage type; attention partials and statistics are not);
     None: exact.  own_follow_ctx: the context holds positions 0..n_ctx-1 and the rows given are the
     positions n_ctx..n_ctx+n-1 that follow it, so each row attends to the context and to the given rows
-    up to itself (a decode step: the cache, then the new row).  Returns (output rows, key rows after the
-    rotation, value rows).
+    up to itself (a decode step: the cache, then the new row).  fuse_epilogues: which tensors the tiled
+    execution never stores, and so never rounds -- bit 0: the Wo and W2 products (the residual is added inside
+    their vertices), bit 1: the gate and up products (silu * up happens inside theirs).  Returns (output rows,
+    key rows after the rotation, value rows).
     """
     st = store if store is not None else (lambda z: z)
     h = np.asarray(h_rows, dtype=np.float64)
@@ -125,11 +127,13 @@ def decoder_layer_rows(h_rows, positions, w, layer: int, n_heads: int, head_dim:
             e = np.exp(s - np.max(s))
             o[r, sl] = (e / np.sum(e)) @ vc[:p + 1, sl]
     o = st(o)
-    h1 = st(h + st(o @ w[f"wo.{layer}"]))
+    st_res = (lambda z: z) if fuse_epilogues & 1 else st  # the products that a residual is added to
+    st_gate = (lambda z: z) if fuse_epilogues & 2 else st  # the gate and up products
+    h1 = st(h + st_res(o @ w[f"wo.{layer}"]))
     b = st(rmsnorm(h1, w[f"g2.{layer}"], eps))
-    gate, up = st(b @ w[f"w1.{layer}"]), st(b @ w[f"w3.{layer}"])
+    gate, up = st_gate(b @ w[f"w1.{layer}"]), st_gate(b @ w[f"w3.{layer}"])
     act = st(silu(gate) * up)
-    y = st(h1 + st(act @ w[f"w2.{layer}"]))
+    y = st(h1 + st_res(act @ w[f"w2.{layer}"]))
     return y, k, v
 
 

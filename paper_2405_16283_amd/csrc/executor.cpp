@@ -890,7 +890,10 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
   int xring[2] = {0, 0};
   const int xdepth = std::max(1, std::min<int>(opt.transfer_depth > 0 ? opt.transfer_depth : 3, kMaxQueueDepth));
   std::vector<int64_t> same, xverts, sort_b, stage_verts;
-  std::vector<uint64_t> stage_sizes, stage_run;
+  std::vector<uint64_t> stage_sizes, stage_run, stage_tmp_s;
+  std::vector<size_t> stage_ord;
+  std::vector<int64_t> stage_tmp_v;
+  std::vector<const void*> stage_tmp_src;
   std::vector<std::array<int64_t, 4>> sort_keys;
   std::vector<hipEvent_t> waited;
 
@@ -1049,6 +1052,33 @@ static tn_status run_memgraph(tn_executor* ex, const void* const* host_inputs, v
         if (!stage_run.empty() && !arena_alloc_run(*ex, stage_run.data(), (int)stage_run.size(), &at)) {
           status = fail(TN_ERR_ARENA, "pinned host arena: no run of adjacent slots for %zu offloads", stage_run.size());
           break;
+        }
+        // Stores first sorted by where they go in host memory, so that tiles the caller keeps next to each other
+        // leave as one copy: a copy engine moves 512 KiB in 12 us and 4 MiB in 75, and between two copies it rests.
+        if (stage_verts.size() > 1) {
+          const size_t n = stage_verts.size();
+          std::vector<size_t>& ord = stage_ord;
+          ord.resize(n);
+          for (size_t k = 0; k < n; ++k) ord[k] = k;
+          auto key = [&](size_t k) -> uintptr_t {
+            const MVertex& x = mg.v[stage_verts[k]];
+            return x.kind == TN_MG_OFFLOAD ? 0 : (uintptr_t)host_outputs[x.output_index];
+          };
+          std::stable_sort(ord.begin(), ord.end(), [&](size_t a, size_t b) { return key(a) < key(b); });
+          stage_tmp_v.assign(stage_verts.begin(), stage_verts.end());
+          stage_tmp_s.assign(stage_sizes.begin(), stage_sizes.end());
+          stage_tmp_src.resize(n);
+          for (size_t k = 0; k < n; ++k) stage_tmp_src[k] = copies.it[k].src;
+          uint64_t pos = 0;
+          int32_t blocks = 0;
+          for (size_t k = 0; k < n; ++k) {
+            const size_t o = ord[k];
+            stage_verts[k] = stage_tmp_v[o];
+            stage_sizes[k] = stage_tmp_s[o];
+            copies.it[k] = {stage_tmp_src[o], slot + pos, (uint32_t)stage_sizes[k], (uint32_t)blocks};
+            blocks += (int32_t)((stage_sizes[k] + kCopyBlockBytes - 1) / kCopyBlockBytes);
+            pos += (stage_sizes[k] + 255) / 256 * 256;
+          }
         }
         e = launch_copies(copies, kStageGatherWorkgroups, sl.stream);
         // A run may cross the padding behind a tensor (sizes are rounded up to 256 bytes in the slot) only where

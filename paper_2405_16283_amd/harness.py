@@ -193,14 +193,14 @@ BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered", "c2_capped25": "cl
 
 # Workloads whose attention the benchmark tiles as one vertex per query block over all earlier keys
 # (tiler option attn_whole_rows) instead of one per pair of blocks.
-BENCH_WHOLE_ROWS = {}
+BENCH_WHOLE_ROWS = {"c3": True}
 
 
 # Workloads the benchmark tiles with fused epilogues (tiler option fuse_epilogues, bits 1 | 2).  The one-layer
 # workload gains 3-4 % in HBM and 6 % streamed under 40 % of its peak; c3 and c4 measure the same either way
 # (the residual form of the product is 2-3 % slower than the plain one, which eats what the additions cost),
 # and under 25 % of the peak the gated vertex, which wants its W1 and W3 tiles resident together, loses.
-BENCH_FUSE = {"c2": 3, "c2_capped40": 3}
+BENCH_FUSE = {"c2": 3, "c2_capped40": 3, "c3": 3}
 
 
 def cap_for(cfg, tg) -> int:
@@ -278,9 +278,15 @@ class GpuSession:
         self.in_ptrs = B.ptr_array(self.in_ptrs)  # marshalled once, not on every execute
         # outputs: one pinned slab
         self.out_vids, self.out_shapes, self.out_bind = output_vertices(self.tg)
-        self.out_offs, total = [], 0
-        for (r, c) in self.out_shapes:
-            self.out_offs.append(total)
+        # laid out in the order in which the serial order produces them, which is the order their stores are
+        # compiled in: outputs that lie next to each other here and are stored by one group of transfers leave
+        # the GPU as one copy
+        pos = {v: k for k, v in enumerate(order)} if order is not None else {}
+        place = lambda i: pos.get(self.out_vids[i], self.out_vids[i])
+        self.out_offs, total = [0] * len(self.out_shapes), 0
+        for i in sorted(range(len(self.out_shapes)), key=place):
+            r, c = self.out_shapes[i]
+            self.out_offs[i] = total
             total += (r * c * es + 255) // 256 * 256
         # results in pinned host memory, or (device_outputs) in GPU memory outside the capped buffer
         self.out_slab = (torch.empty(max(total, 256), dtype=torch.uint8, device="cuda:0") if device_outputs

@@ -48,8 +48,10 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
     full = make_llama_inputs(cfg, 0, distinct_layers=distinct, workers=16)
     print(f"[{name}] inputs generated {time.time() - t0:.1f}s", flush=True)
     # K/V and the hidden state of pairs of neighbouring layers through the depth of the stack are outputs
+    # the serial order, attention tiling and fused epilogues the benchmark compiles this workload with
+    whole_rows, fuse = H.BENCH_WHOLE_ROWS.get(name, False), H.BENCH_FUSE.get(name, 0)
     s = H.GpuSession(cfg, full, kv_outputs=kv, hidden_outputs=True, output_layer_stride=stride,
-                     order=H.BENCH_ORDER.get(name))  # the serial order the benchmark compiles this workload for
+                     order=H.BENCH_ORDER.get(name), attn_whole_rows=whole_rows, fuse_epilogues=fuse)
     probe = [0] + [l for l in range(stride, cfg.layers - 1, stride)] + [last]  # layers checked one by one
     print(f"[{name}] compiled and placed {time.time() - t0:.1f}s: {s.stats.n_vertices} vertices, "
           f"{s.stats.n_load} loads, {s.stats.n_offload} offloads, {s.stats.n_store} stores", flush=True)
@@ -94,7 +96,7 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
         rng = np.random.default_rng(11)
         rows = np.unique(np.concatenate([np.arange(8), rng.integers(8, cfg.seq - 8, size=8), np.arange(cfg.seq - 8, cfg.seq)]))
         for l in probe:
-            check_layer_rows(cfg, full, out, l, 0, rows, 2e-2, True, f"[{name}]", wide)
+            check_layer_rows(cfg, full, out, l, 0, rows, 2e-2, True, f"[{name}]", wide, fuse_epilogues=fuse)
         print(f"[{name}] layers {probe} checked one by one {time.time() - t0:.1f}s", flush=True)
 
         # the whole stack on the prefix: exact (float64, untiled), and tiled with the GPU path's
@@ -104,7 +106,7 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
             y_exact = R.decoder_layer(y_exact, layer_weights(l), l, cfg.n_heads, cfg.head_dim, cfg.eps, cfg.rope_base)
         print(f"[{name}] exact prefix forward done {time.time() - t0:.1f}s", flush=True)
         pcfg = cfg.with_(seq=PREFIX)
-        tgp = T.build_llama_taskgraph(pcfg)
+        tgp = T.build_llama_taskgraph(pcfg, attn_whole_rows=whole_rows, fuse_epilogues=fuse)
         pfull = dict(full)
         pfull["x"] = full["x"][:PREFIX]
         vals = T.evaluate(tgp, T.LazyInputs(tgp, pfull, R.widen_array, cache_bytes=16 << 30))

@@ -208,6 +208,16 @@ def test_layer_on_sampled_rows_is_the_layer():
     # blocked and unblocked softmax differ in the last bits of float64, which moves a rounding now and then
     assert np.mean(y_rows != y_tiled) < 2e-3 and R.rel_err(y_rows, y_tiled) < 2.0 ** -7
     assert R.rel_err(y_rows, R.decoder_layer(x, w, 0, *args)) > 1e-4  # the rounding is really applied
+    # the same with fused epilogues: the tensors the fused graph never stores are not rounded
+    for fuse in (1, 2, 3):
+        tgf = T.build_llama_taskgraph(one, fuse_epilogues=fuse)
+        y_tf = T.assemble_outputs(tgf, T.evaluate(tgf, T.cut_inputs(tgf, w1)), one.tokens, one.d_model)
+        y_rf, _, _ = R.decoder_layer_rows(x, np.arange(cfg.seq), w, 0, *args, store=lambda z: T.round_store(z, "bf16"),
+                                          fuse_epilogues=fuse)
+        assert np.mean(y_rf != y_tf) < 2e-3 and R.rel_err(y_rf, y_tf) < 2.0 ** -7
+        assert np.mean(y_rf != y_rows) > 0.01  # ... and that moves roundings: the unfused rows are another result
+    exact, _, _ = R.decoder_layer_rows(x, np.arange(cfg.seq), w, 0, *args, fuse_epilogues=3)
+    np.testing.assert_array_equal(exact, R.decoder_layer_rows(x, np.arange(cfg.seq), w, 0, *args)[0])
 
 
 def test_decode_steps_give_the_rows_of_the_whole_sequence():

@@ -74,11 +74,13 @@ def check_all(preds, mg: M.MemGraph, n_random=20, seed=0, exhaustive=False):
     return count, ref
 
 
-def check_layer_rows(cfg, full, out, layer, seq_index, rows, tol, use_context, label="", wide_cache=None):
+def check_layer_rows(cfg, full, out, layer, seq_index, rows, tol, use_context, label="", wide_cache=None,
+                     fuse_epilogues=0):
     """One layer of a deep stack held to the one-layer tolerance: the GPU run's own input rows of
     `layer` (x, or its hidden state after layer - 1) go through one oracle layer with the tiled
     execution's storage rounding, and the GPU's output rows of that layer (hidden state after it,
-    or y) must agree within `tol`.  use_context: late rows attend to the GPU's stored keys and values
+    or y) must agree within `tol`.  fuse_epilogues: the tiler option the run was compiled with (which
+    tensors are never stored).  use_context: late rows attend to the GPU's stored keys and values
     of that layer, which are themselves held to `tol` on the sampled rows; otherwise `rows` must be
     a prefix 0..n-1.  `out` maps "h.l", "k.l", "v.l", "y" to the GPU's full tensors (storage type)."""
     from oracle import llama_ref as R
@@ -104,7 +106,7 @@ def check_layer_rows(cfg, full, out, layer, seq_index, rows, tol, use_context, l
         kc = f64(out[f"k.{layer}"][base:base + cfg.seq])
         vc = f64(out[f"v.{layer}"][base:base + cfg.seq])
     y, k, v = R.decoder_layer_rows(f64(src[base + rows]), rows, w, layer, cfg.n_heads, cfg.head_dim, cfg.eps,
-                                   cfg.rope_base, k_ctx=kc, v_ctx=vc, store=store)
+                                   cfg.rope_base, k_ctx=kc, v_ctx=vc, store=store, fuse_epilogues=fuse_epilogues)
     errs = {"h": R.rel_err(f64(dst[base + rows]), y)}
     if use_context:
         errs["k"] = R.rel_err(kc[rows], k)
