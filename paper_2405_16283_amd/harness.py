@@ -192,14 +192,15 @@ BENCH_ORDER = {"c3": "clustered", "c2_capped40": "clustered", "c2_capped25": "cl
 
 
 # Workloads whose attention the benchmark tiles as one vertex per query block over all earlier keys
-# (tiler option attn_whole_rows) instead of one per pair of blocks.
+# (tiler option attn_whole_rows) instead of one per pair of blocks: c3, 383 -> 363 ms (a twelfth of the partial
+# traffic; c4 measures the same either way).
 BENCH_WHOLE_ROWS = {"c3": True}
 
 
 # Workloads the benchmark tiles with fused epilogues (tiler option fuse_epilogues, bits 1 | 2).  The one-layer
-# workload gains 3-4 % in HBM and 6 % streamed under 40 % of its peak; c3 and c4 measure the same either way
-# (the residual form of the product is 2-3 % slower than the plain one, which eats what the additions cost),
-# and under 25 % of the peak the gated vertex, which wants its W1 and W3 tiles resident together, loses.
+# workload gains 3-4 % in HBM and 6 % streamed under 40 % of its peak, c3 2.5 % (363 -> 354 ms); the link-bound
+# c4 measures the same either way, and under 25 % of the peak the gated vertex, which wants its W1 and W3 tiles
+# resident together, loses.
 BENCH_FUSE = {"c2": 3, "c2_capped40": 3, "c3": 3}
 
 
