@@ -256,8 +256,10 @@ tn_status build_tables(tn_executor& ex) {
           if (kk % 32) k32 = false;
         }
         const bool big = k32 && d.rows >= 256 && d.cols >= 256;
-        // the fused forms (mode 1: + residual, mode 2: gated pair) exist in the 256-tile kernel and in the generic one
-        vi.cls = !mfma ? LC_GEMM_F32 : big ? LC_GEMM_BF16_NT256 : x.p.mode != 0 ? LC_GEMM_F32 : LC_GEMM_BF16_NT;
+        // the fused forms (mode 1: + residual, mode 2: gated pair) exist in the 256-tile kernel, which clamps its
+        // loads and guards its stores for any shape, and in the generic one, which the thinnest products take
+        const bool fused_mfma = x.p.mode != 0 && k32 && d.rows >= 64;
+        vi.cls = !mfma ? LC_GEMM_F32 : (big || fused_mfma) ? LC_GEMM_BF16_NT256 : x.p.mode != 0 ? LC_GEMM_F32 : LC_GEMM_BF16_NT;
         vi.flops = (x.p.mode == 2 ? 4.0 : 2.0) * d.rows * d.cols * K;
         break;
       }

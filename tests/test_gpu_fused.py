@@ -54,11 +54,13 @@ def test_fused_forward_matches_the_oracle_under_the_cap(name, fuse):
 
 
 @pytest.mark.parametrize("mode", [1, 2])
-@pytest.mark.parametrize("shape", [(256, 256, 64), (384, 640, 96), (300, 264, 32), (512, 1024, 128), (128, 136, 40)])
+@pytest.mark.parametrize("shape", [(256, 256, 64), (384, 640, 96), (300, 264, 32), (512, 1024, 128), (128, 136, 40),
+                                   (128, 136, 64), (72, 40, 32), (40, 72, 32)])
 def test_fused_product_vertex_alone(mode, shape):
     """One vertex of each fused mode on hand-built graphs, two k tiles, weights stored [out, in]: shapes the
-    256-tile kernel takes whole, ragged in rows and columns (its clamped loads and guarded stores), and one
-    below its size (the generic kernel), against the oracle's vertex in float64."""
+    256-tile kernel takes whole, ragged in rows and columns and smaller than one tile (its clamped loads and
+    guarded stores), and shapes that go to the generic kernel (K not a multiple of 32, fewer than 64 rows),
+    against the oracle's vertex in float64."""
     m, n, k = shape
     rng = np.random.default_rng(m + n + mode)
     g = Graph("bf16")
