@@ -1762,9 +1762,15 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(DeviceTables t, Batch
 // lane.  What keeps the host link busy is the number of waves with a load outstanding, not the
 // loads per wave (measured: 8 such workgroups reach 56 GB/s, the rate of the copy engines).
 // The large GEMM kernel needs a whole compute unit for one workgroup, so every compute unit
-// that holds a copy wave is lost to it: hence few, wide workgroups.
+// that holds a copy workgroup is lost to it (see `held` below): hence few, wide workgroups.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kCopyThreads) copy_kernel(CopyBatch b) {
+  // What a lane has loaded waits in LDS, each lane in a place of its own (no barrier): 32 KiB per workgroup, which is
+  // what keeps a copy workgroup off a compute unit that holds a workgroup of the 256x256 tile product (128 KiB
+  // of the 160) or two of the attention kernel.  Sharing a unit with those costs them far more than the unit is
+  // worth to the copy (measured with the data held in registers instead: tile products 970 -> 610 TFLOP/s on the
+  // 80-layer workload); reserving 96 KiB instead costs the compute-bound workloads 5-13 %.
+  __shared__ uint4 held[kCopyLoads][kCopyThreads];
   int item = 0;
   for (uint32_t g = blockIdx.x; g < (uint32_t)b.total_blocks; g += gridDim.x) {
     while (item + 1 < b.n && g >= b.it[item + 1].first_block) ++item;
@@ -1774,16 +1780,15 @@ __global__ void __launch_bounds__(kCopyThreads) copy_kernel(CopyBatch b) {
     const char* src = (const char*)it.src + off;
     char* dst = (char*)it.dst + off;
     const uint32_t vec = len / 16;  // whole 16-byte pieces (tensor locations are 256-byte aligned)
-    uint4 v[kCopyLoads];
 #pragma unroll
     for (int k = 0; k < kCopyLoads; ++k) {
       const uint32_t i = threadIdx.x + kCopyThreads * k;
-      if (i < vec) v[k] = ((const uint4*)src)[i];
+      if (i < vec) held[k][threadIdx.x] = ((const uint4*)src)[i];
     }
 #pragma unroll
     for (int k = 0; k < kCopyLoads; ++k) {
       const uint32_t i = threadIdx.x + kCopyThreads * k;
-      if (i < vec) ((uint4*)dst)[i] = v[k];
+      if (i < vec) ((uint4*)dst)[i] = held[k][threadIdx.x];
     }
     const uint32_t tail = vec * 16 + threadIdx.x;
     if (tail < len) dst[tail] = src[tail];
