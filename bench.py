@@ -137,6 +137,9 @@ def main():
     ap.add_argument("--fuse-epilogues", type=int, default=-1,
                     help="tiler option fuse_epilogues (bit 0: residual additions inside the products before them, bit 1: "
                          "W1, W3 and silu * up as one vertex); default: harness.BENCH_FUSE for the workload")
+    ap.add_argument("--recompute-normed", type=int, default=-1,
+                    help="fine-tuning step: 1 = the reverse pass forms the normalised layer input again instead of keeping "
+                         "it from the forward pass (tiler option recompute_normed); default: harness.BENCH_RECOMPUTE_NORMED")
     ap.add_argument("--checkpoint-layers", type=int, default=0,
                     help="with --checkpoint: only the first this many layers are recomputed, the rest keep saved activations")
     ap.add_argument("--materialize-scores", action="store_true",
@@ -253,6 +256,8 @@ def main():
         fuse = (args.fuse_epilogues if (headline and args.fuse_epilogues >= 0) else H.BENCH_FUSE.get(name, 0))
         if train or k_split > 1:
             fuse = 0
+        lean = train and bool(args.recompute_normed if (headline and args.recompute_normed >= 0)
+                              else H.BENCH_RECOMPUTE_NORMED.get(name, False))
         t0 = time.perf_counter()
         distinct = args.distinct_layers if (headline and args.distinct_layers >= 0) else (0 if cfg.layers <= 8 else 4)
         kv_outputs = (bool(args.kv_outputs) if (headline and args.kv_outputs >= 0)
@@ -272,7 +277,7 @@ def main():
             struct = lambda cc: H.llama_config_struct(cc, kv_outputs, lora_rank=16 if train else 0, train=train,
                                                       k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint,
                                                       attn_whole_rows=whole_rows, checkpoint_layers=ck_layers,
-                                                      fuse_epilogues=fuse)
+                                                      fuse_epilogues=fuse, recompute_normed=lean)
             if pressed:  # the cap is a fraction of the uncapped peak: the compile options need it in bytes
                 tg = B.tn_build_llama(struct(c))
                 c = c.with_(cap_bytes=H.cap_for(c, tg), cap_frac=0.0)
@@ -290,7 +295,8 @@ def main():
             return H.GpuSession(c, full, n_compute=args.streams, kv_outputs=kv_outputs, order=order, compile_opts=copts,
                                 lora_rank=16 if train else 0, train=train, progress=lambda m: note(f"{name}: {m}"),
                                 k_split=k_split, materialize_scores=materialize, checkpoint=checkpoint, attn_whole_rows=whole_rows,
-                                checkpoint_layers=ck_layers, device_outputs=device_outputs, fuse_epilogues=fuse)
+                                checkpoint_layers=ck_layers, device_outputs=device_outputs, fuse_epilogues=fuse,
+                                recompute_normed=lean)
 
         t0 = time.perf_counter()
         s = session(cfg, device_outputs)
@@ -357,7 +363,7 @@ def main():
             "gpu_cap_bytes": s.cap, "distinct_layers": distinct or cfg.layers, "kv_outputs": kv_outputs,
             "outputs": "GPU memory outside the capped buffer" if device_outputs else "pinned host memory",
             "serial_order": level or "tiler", "attention_vertices": "whole rows" if whole_rows else "per pair of blocks",
-            "fuse_epilogues": fuse,
+            "fuse_epilogues": fuse, "recompute_normed": lean,
             "memgraph": {"vertices": int(st.n_vertices), "offloads": int(st.n_offload), "reloads": int(st.n_reload),
                          "loads": int(st.n_load), "drops": int(st.n_drop), "stores": int(st.n_store),
                          "mem_edges": int(st.n_mem_edges), "offload_GB": st.offload_bytes / 1e9,

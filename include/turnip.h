@@ -309,6 +309,11 @@ typedef struct {
    * products and silu(gate) * up become one vertex (GEMM, mode 2), so the two [rows, ffn] intermediates
    * never exist.  A fused vertex rounds to the storage type once. */
   int32_t fuse_epilogues;
+  /* != 0 (needs train != 0): the normalised layer input, which the adapter gradients read, is not kept from
+   * the forward pass; the reverse pass forms it again from the layer input and its statistic, which it keeps
+   * anyway (one elementwise vertex per tile, the same bits).  One [tokens, d_model] tensor per layer less to
+   * hold, or to offload under a cap. */
+  int32_t recompute_normed;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

@@ -647,6 +647,7 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
   if (c.fuse_epilogues < 0 || c.fuse_epilogues > 3 || (c.fuse_epilogues && (c.train || c.k_split > 1)))
     return fail(TN_ERR_INVALID, "fuse_epilogues takes bits 1 and 2 and goes with neither train nor k_split");
+  if (c.recompute_normed && !c.train) return fail(TN_ERR_INVALID, "recompute_normed needs train");
   if (c.checkpoint_layers < 0 || (c.checkpoint_layers > 0 && !c.checkpoint))
     return fail(TN_ERR_INVALID, "checkpoint_layers needs checkpoint and must not be negative");
   // layers whose forward tensors the reverse pass forms again instead of reading saved ones
@@ -1160,7 +1161,10 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           all_dtv.push_back(tr(dtv, m, rk));
           for (size_t j = 0; j < nd; ++j) {
             const int32_t n = t.dcols[j].len();
-            a_cols[j].push_back(tr(sv.a[i][j], m, n));
+            const tn_vid an = c.recompute_normed
+                                  ? t.op(TN_OP_RMS_APPLY, tn_op_params{}, {sv.xin[i][j], sv.rstd1[i], w.g1[j]}, {c.dtype, m, n})
+                                  : sv.a[i][j];
+            a_cols[j].push_back(tr(an, m, n));
             dq_cols[j].push_back(tr(dq[i][j], m, n));
             dv_cols[j].push_back(tr(dv[i][j], m, n));
           }

@@ -15,9 +15,9 @@ from util import check_all, oracle_memgraph, task_preds
 RANK = 8
 
 
-def _graph(cfg, checkpoint, checkpoint_layers=0):
+def _graph(cfg, checkpoint, checkpoint_layers=0, recompute_normed=False):
     tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint,
-                                                checkpoint_layers=checkpoint_layers))
+                                                checkpoint_layers=checkpoint_layers, recompute_normed=recompute_normed))
     try:
         return H.export_taskgraph(tg)
     finally:
@@ -71,6 +71,29 @@ def test_checkpointing_the_first_layers_only(name):
         B.tn_taskgraph_destroy(tg)
     with pytest.raises(B.TurnipError):  # a count without the option
         B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint_layers=1))
+
+
+@pytest.mark.parametrize("name", ["c1", "batch2_f32", "ragged_bf16"])
+def test_the_recomputed_normalised_input_is_the_same_expression(name):
+    """recompute_normed: the adapter gradients read a normalised layer input formed again in the reverse pass
+    from the layer input and its statistic.  Every output stays the same expression of the inputs (so the
+    deterministic kernels give the same bits); the graph has one more normalisation per tile, layer and
+    sequence; the first normalisation's outputs have no reader left in the reverse pass."""
+    cfg = config(name)
+    plain, lean = _graph(cfg, False), _graph(cfg, False, recompute_normed=True)
+    assert _expressions(lean) == _expressions(plain)
+    n_tiles = -(-cfg.seq // cfg.tile) * -(-cfg.d_model // cfg.tile) * cfg.batch * cfg.layers
+    assert lean["kind"].count("rms_apply") == plain["kind"].count("rms_apply") + n_tiles
+    assert len(lean["kind"]) == len(plain["kind"]) + n_tiles
+
+    def transposed_normed(e):  # rms_apply vertices that a transpose (the adapter gradients' operand) reads
+        return {u for v, k in enumerate(e["kind"]) if k == "transpose" for u in e["inputs"][v] if e["kind"][u] == "rms_apply"}
+
+    first = min(v for v, k in enumerate(plain["kind"]) if k.endswith("_bwd") or k == "attn_bwd")  # the reverse pass starts here
+    assert all(u < first for u in transposed_normed(plain)) and all(u > first for u in transposed_normed(lean))
+    with pytest.raises(B.TurnipError) as err:
+        B.tn_build_llama(H.llama_config_struct(cfg, recompute_normed=True))
+    assert err.value.status == B.TN_ERR_INVALID
 
 
 def test_a_changed_operand_changes_the_expression():

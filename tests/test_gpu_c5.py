@@ -86,6 +86,7 @@ def test_full_step_in_the_benchmark_configuration():
     probe = [0] + [l for l in range(stride, cfg.layers - 1, stride)] + [last]
     s = H.GpuSession(cfg, full, lora_rank=RANK, train=True, compile_opts=H.bench_compile_opts(cfg.cap_bytes, True), n_compute=H.BENCH_COMPUTE_STREAMS,
                      hidden_outputs=True, output_layer_stride=stride,
+                     recompute_normed=H.BENCH_RECOMPUTE_NORMED.get("c5", False),  # as the benchmark compiles it
                      progress=lambda m: print(f"[c5] {m} {time.time() - t0:.1f}s", flush=True))
     st = s.stats
     print(f"[c5] compiled and placed {time.time() - t0:.1f}s: {st.n_vertices} vertices, {st.n_load} loads "

@@ -83,6 +83,29 @@ def test_twenty_dispatch_orders_of_the_fine_tuning_step_give_identical_bits(name
         s.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "ragged_bf16", "mid_bf16"])
+def test_recomputed_normalised_input_gives_the_same_bits(name):
+    """Tiler option recompute_normed (the reverse pass forms the normalised layer input again instead of
+    keeping it): every output carries the bits of the step that kept it, in other dispatch orders too."""
+    cfg, s, _, _ = _case(name, 0.02)
+    try:
+        want, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
+        kept = s.stats.n_vertices
+    finally:
+        s.close()
+    cfg, s, _, _ = _case(name, 0.02, recompute_normed=True)
+    try:
+        print(f"[case] {name} recompute_normed: {s.stats.n_vertices} vertices ({kept} without), {s.stats.n_offload} offloads", flush=True)
+        for seed in range(3):
+            out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, max_delay_us=(0, 50)[seed % 2],
+                                            max_batch=(1, 0, 7)[seed]))
+            assert out.keys() == want.keys()
+            for k in want:
+                np.testing.assert_array_equal(out[k], want[k])
+    finally:
+        s.close()
+
+
 @pytest.mark.parametrize("name,tol,first", [("c1", 1e-4, 0), ("batch2_f32", 1e-4, 0), ("ragged_bf16", 4e-2, 0),
                                             ("c1", 1e-4, 1), ("ragged_bf16", 4e-2, 1)])
 def test_checkpointed_step_gives_the_same_bits_as_the_saved_activation_step(name, tol, first):
