@@ -314,6 +314,13 @@ typedef struct {
    * anyway (one elementwise vertex per tile, the same bits).  One [tokens, d_model] tensor per layer less to
    * hold, or to offload under a cap. */
   int32_t recompute_normed;
+  /* != 0 (needs train != 0): the gate and up products of the feed-forward block, which the reverse pass of
+   * SiLU*mul reads, are not kept from the forward pass; the reverse pass forms them again from h1 (normalised
+   * again from h1 and its statistic, then the two products: the same kernels on the same operands, the same
+   * bits).  These are the two largest saved tensors of a layer ([tokens, ffn] each): forming them again costs
+   * two products per layer and the W1 and W3 tiles a second time, keeping them under a cap costs their way to
+   * the host and back.  Layers that are checkpointed as a whole are not affected. */
+  int32_t recompute_gate_up;
 } tn_llama_config;
 
 /* Which vertex is which piece of which tensor of the decoder. */

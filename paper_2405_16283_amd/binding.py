@@ -63,7 +63,7 @@ class tn_llama_config(C.Structure):
                 ("v_transposed", C.c_int32), ("lora_rank", C.c_int32), ("train", C.c_int32), ("k_split", C.c_int32), ("materialize_scores", C.c_int32),
                 ("checkpoint", C.c_int32), ("hidden_outputs", C.c_int32),
                 ("output_layer_stride", C.c_int32), ("decode_steps", C.c_int32),
-                ("attn_whole_rows", C.c_int32), ("checkpoint_layers", C.c_int32), ("fuse_epilogues", C.c_int32), ("recompute_normed", C.c_int32)]
+                ("attn_whole_rows", C.c_int32), ("checkpoint_layers", C.c_int32), ("fuse_epilogues", C.c_int32), ("recompute_normed", C.c_int32), ("recompute_gate_up", C.c_int32)]
 
 
 class tn_llama_binding(C.Structure):

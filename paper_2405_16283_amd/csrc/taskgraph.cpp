@@ -647,7 +647,8 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
   if (c.checkpoint && !c.train) return fail(TN_ERR_INVALID, "checkpoint applies to train only");
   if (c.fuse_epilogues < 0 || c.fuse_epilogues > 3 || (c.fuse_epilogues && (c.train || c.k_split > 1)))
     return fail(TN_ERR_INVALID, "fuse_epilogues takes bits 1 and 2 and goes with neither train nor k_split");
-  if (c.recompute_normed && !c.train) return fail(TN_ERR_INVALID, "recompute_normed needs train");
+  if ((c.recompute_normed || c.recompute_gate_up) && !c.train)
+    return fail(TN_ERR_INVALID, "recompute_normed and recompute_gate_up need train");
   if (c.checkpoint_layers < 0 || (c.checkpoint_layers > 0 && !c.checkpoint))
     return fail(TN_ERR_INVALID, "checkpoint_layers needs checkpoint and must not be negative");
   // layers whose forward tensors the reverse pass forms again instead of reading saved ones
@@ -1030,13 +1031,23 @@ tn_status tn_build_llama(const tn_llama_config* cfg, tn_taskgraph** out) {
           const int32_t m = t.rows[i].len();
           // feed-forward block: y = h1 + (silu(gate) * up) W2, gate = bn W1, up = bn W3, bn = RMSNorm(h1; g2)
           std::vector<tn_vid> dgate(nf), dup(nf);
+          // recompute_gate_up: the gate and up products of this row tile are formed again, from the normalised h1
+          // (itself formed again from h1 and its statistic), instead of read from the forward pass
+          const bool again = c.recompute_gate_up && !recomputed(l);
+          std::vector<tn_vid> bn2;
+          if (again)
+            for (size_t j = 0; j < nd; ++j)
+              bn2.push_back(t.op(TN_OP_RMS_APPLY, tn_op_params{}, {sv.h1[i][j], sv.rstd2[i], w.g2[j]},
+                                 {c.dtype, m, t.dcols[j].len()}));
           for (size_t f = 0; f < nf; ++f) {
             const int32_t n = t.fcols[f].len();
             tn_vid dact = t.gemm_list(dy[b][i], w2n[f], m, n, false, true);
+            const tn_vid gate = again ? t.gemm(bn2, w.w1, f, m, n) : sv.gate[i][f];
+            const tn_vid up = again ? t.gemm(bn2, w.w3, f, m, n) : sv.up[i][f];
             tn_op_params p{};
-            dgate[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, sv.gate[i][f], sv.up[i][f]}, {c.dtype, m, n});
+            dgate[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, gate, up}, {c.dtype, m, n});
             p.mode = 1;
-            dup[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, sv.gate[i][f], sv.up[i][f]}, {c.dtype, m, n});
+            dup[f] = t.op(TN_OP_SILU_MUL_BWD, p, {dact, gate, up}, {c.dtype, m, n});
           }
           std::vector<tn_vid> dbn(nd);
           for (size_t j = 0; j < nd; ++j) {

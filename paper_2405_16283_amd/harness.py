@@ -32,7 +32,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
                         checkpoint: bool = False, hidden_outputs: bool = False,
                         output_layer_stride: int = 0, attn_whole_rows: bool = False,
                         checkpoint_layers: int = 0, fuse_epilogues: int = 0,
-                        recompute_normed: bool = False) -> B.tn_llama_config:
+                        recompute_normed: bool = False, recompute_gate_up: bool = False) -> B.tn_llama_config:
     """workloads.LlamaConfig -> tn_llama_config."""
     return B.tn_llama_config(
         layers=cfg.layers, d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, ffn=cfg.ffn,
@@ -46,7 +46,7 @@ def llama_config_struct(cfg, kv_outputs: bool = False, weights_transposed: bool 
         hidden_outputs=int(hidden_outputs), output_layer_stride=int(output_layer_stride),
         decode_steps=int(getattr(cfg, "decode_steps", 0)), attn_whole_rows=int(attn_whole_rows),
         checkpoint_layers=int(checkpoint_layers), fuse_epilogues=int(fuse_epilogues),
-        recompute_normed=int(recompute_normed))
+        recompute_normed=int(recompute_normed), recompute_gate_up=int(recompute_gate_up))
 
 
 def bindings(tg) -> List[Tuple[int, str, int, int, int, int, int]]:
@@ -210,6 +210,10 @@ BENCH_FUSE = {"c2": 3, "c2_capped40": 3, "c3": 3}
 BENCH_RECOMPUTE_NORMED = {"c5": True}  # 17.9 -> 14.9 GB of offloads, 1.19 -> 1.15 s per step
 
 
+# ... and the gate and up products of the feed-forward block (tiler option recompute_gate_up).
+BENCH_RECOMPUTE_GATE_UP = {"c5": True}  # nothing left to offload under the 32 GB cap: 1.15 -> 1.01 s per step
+
+
 def cap_for(cfg, tg) -> int:
     """The workload's GPU-memory cap in bytes."""
     if cfg.cap_bytes:
@@ -229,7 +233,7 @@ class GpuSession:
                  materialize_scores: bool = False, checkpoint: bool = False, device_outputs: bool = False,
                  device_inputs: bool = False, hidden_outputs: bool = False, output_layer_stride: int = 0,
                  attn_whole_rows: bool = False, checkpoint_layers: int = 0, fuse_epilogues: int = 0,
-                 recompute_normed: bool = False):
+                 recompute_normed: bool = False, recompute_gate_up: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("GpuSession needs a GPU; there is no CPU fallback")
@@ -238,7 +242,8 @@ class GpuSession:
         self.tg = B.tn_build_llama(llama_config_struct(cfg, kv_outputs, weights_transposed, v_transposed,
                                                        lora_rank, train, k_split, materialize_scores,
                                                        checkpoint, hidden_outputs, output_layer_stride,
-                                                       attn_whole_rows, checkpoint_layers, fuse_epilogues, recompute_normed))
+                                                       attn_whole_rows, checkpoint_layers, fuse_epilogues, recompute_normed,
+                                                       recompute_gate_up))
         self.cap = int(cap) if cap is not None else cap_for(cfg, self.tg)
         say = progress or (lambda msg: None)
         say("taskgraph built")

@@ -15,9 +15,10 @@ from util import check_all, oracle_memgraph, task_preds
 RANK = 8
 
 
-def _graph(cfg, checkpoint, checkpoint_layers=0, recompute_normed=False):
+def _graph(cfg, checkpoint, checkpoint_layers=0, recompute_normed=False, recompute_gate_up=False):
     tg = B.tn_build_llama(H.llama_config_struct(cfg, lora_rank=RANK, train=True, checkpoint=checkpoint,
-                                                checkpoint_layers=checkpoint_layers, recompute_normed=recompute_normed))
+                                                checkpoint_layers=checkpoint_layers, recompute_normed=recompute_normed,
+                                                recompute_gate_up=recompute_gate_up))
     try:
         return H.export_taskgraph(tg)
     finally:
@@ -94,6 +95,33 @@ def test_the_recomputed_normalised_input_is_the_same_expression(name):
     with pytest.raises(B.TurnipError) as err:
         B.tn_build_llama(H.llama_config_struct(cfg, recompute_normed=True))
     assert err.value.status == B.TN_ERR_INVALID
+
+
+@pytest.mark.parametrize("name", ["c1", "batch2_f32", "ragged_bf16"])
+def test_the_recomputed_gate_and_up_products_are_the_same_expressions(name):
+    """recompute_gate_up: the reverse pass of SiLU*mul reads gate and up products formed again from h1.  Every
+    output stays the same expression of the inputs; the graph has per layer, sequence and row tile one more
+    normalisation per column tile and two more products per feed-forward column tile; no product of the forward
+    pass is read by a silu_mul_bwd any more.  With one layer checkpointed as a whole, that layer is left alone."""
+    cfg = config(name)
+    plain, again = _graph(cfg, False), _graph(cfg, False, recompute_gate_up=True)
+    assert _expressions(again) == _expressions(plain)
+    rows, dcols, fcols = -(-cfg.seq // cfg.tile), -(-cfg.d_model // cfg.tile), -(-cfg.ffn // cfg.tile)
+    per = cfg.batch * cfg.layers * rows
+    assert again["kind"].count("rms_apply") == plain["kind"].count("rms_apply") + per * dcols
+    assert again["kind"].count("gemm") == plain["kind"].count("gemm") + per * 2 * fcols
+    first = min(v for v, k in enumerate(plain["kind"]) if k.endswith("_bwd"))  # the reverse pass starts here
+    read = lambda e: {u for v, k in enumerate(e["kind"]) if k == "silu_mul_bwd" for u in e["inputs"][v][1:]}
+    assert all(u < first for u in read(plain)) and all(u > first for u in read(again))
+    both = _graph(cfg, False, recompute_normed=True, recompute_gate_up=True)
+    assert _expressions(both) == _expressions(plain)
+    if cfg.layers == 2:
+        mixed = _graph(cfg, True, 1, recompute_gate_up=True)
+        assert _expressions(mixed) == _expressions(plain)
+        only_ck = _graph(cfg, True, 1)
+        assert mixed["kind"].count("gemm") == only_ck["kind"].count("gemm") + cfg.batch * rows * 2 * fcols  # layer 1 only
+    with pytest.raises(B.TurnipError):
+        B.tn_build_llama(H.llama_config_struct(cfg, recompute_gate_up=True))
 
 
 def test_a_changed_operand_changes_the_expression():

@@ -83,19 +83,23 @@ def test_twenty_dispatch_orders_of_the_fine_tuning_step_give_identical_bits(name
         s.close()
 
 
-@pytest.mark.parametrize("name", ["c1", "ragged_bf16", "mid_bf16"])
-def test_recomputed_normalised_input_gives_the_same_bits(name):
-    """Tiler option recompute_normed (the reverse pass forms the normalised layer input again instead of
-    keeping it): every output carries the bits of the step that kept it, in other dispatch orders too."""
+@pytest.mark.parametrize("name,options", [("c1", dict(recompute_normed=True)), ("ragged_bf16", dict(recompute_normed=True)),
+                                          ("c1", dict(recompute_gate_up=True)), ("ragged_bf16", dict(recompute_gate_up=True)),
+                                          ("mid_bf16", dict(recompute_normed=True, recompute_gate_up=True)),
+                                          ("ragged_bf16", dict(recompute_gate_up=True, checkpoint=True, checkpoint_layers=1))])
+def test_recomputed_tensors_give_the_same_bits(name, options):
+    """Tiler options recompute_normed and recompute_gate_up (the reverse pass forms the normalised layer input,
+    or the gate and up products, again instead of keeping them): every output carries the bits of the step that
+    kept them, in other dispatch orders too."""
     cfg, s, _, _ = _case(name, 0.02)
     try:
         want, _ = s.run(B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, queue_depth=3))
         kept = s.stats.n_vertices
     finally:
         s.close()
-    cfg, s, _, _ = _case(name, 0.02, recompute_normed=True)
+    cfg, s, _, _ = _case(name, 0.02, **options)
     try:
-        print(f"[case] {name} recompute_normed: {s.stats.n_vertices} vertices ({kept} without), {s.stats.n_offload} offloads", flush=True)
+        print(f"[case] {name} {options}: {s.stats.n_vertices} vertices ({kept} without), {s.stats.n_offload} offloads", flush=True)
         for seed in range(3):
             out, rep = s.run(B.tn_exec_opts(policy=B.TN_POLICY_RANDOM, order_seed=seed, max_delay_us=(0, 50)[seed % 2],
                                             max_batch=(1, 0, 7)[seed]))
