@@ -291,11 +291,13 @@ class GpuSession:
         self.in_ptrs = B.ptr_array(self.in_ptrs)  # marshalled once, not on every execute
         # outputs: one pinned slab
         self.out_vids, self.out_shapes, self.out_bind = output_vertices(self.tg)
-        # laid out in the order in which the serial order produces them, which is the order their stores are
-        # compiled in: outputs that lie next to each other here and are stored by one group of transfers leave
-        # the GPU as one copy
+        # laid out tensor by tensor and, inside a tensor, in the order in which the serial order produces the tiles
+        # (the tiles of one tensor come out of the same launches, so their stores are ready together and in that
+        # order): outputs that lie next to each other here and are stored by one group of transfers leave the GPU
+        # as one copy
         pos = {v: k for k, v in enumerate(order)} if order is not None else {}
-        place = lambda i: pos.get(self.out_vids[i], self.out_vids[i])
+        place = lambda i: (self.out_bind[self.out_vids[i]][1] if self.out_vids[i] in self.out_bind else "",
+                           pos.get(self.out_vids[i], self.out_vids[i]))
         self.out_offs, total = [0] * len(self.out_shapes), 0
         for i in sorted(range(len(self.out_shapes)), key=place):
             r, c = self.out_shapes[i]
