@@ -51,7 +51,7 @@ TRANSFERS = {"c4": (128, 14), "c2_capped40": (32, 16), "c2_capped25": (32, 16)}
 SMALL_GEMM_TILES = {"c5": -1}
 # Groups of tile products in flight at once (default 1: the next group waits and gathers more ready tiles).  The
 # fine-tuning step, whose launches stay small in the tiler's order, gains 5 % from a second group in flight
-# (1008 -> 954 ms; no limit at all measures the same).
+# (889 -> 841 ms; no limit at all measures the same).
 GEMM_INFLIGHT = {"c5": 2}
 
 # steps / warm-up steps of the sub-records (the headline takes --steps / --warmup)

@@ -38,7 +38,8 @@ struct VInfo {
   int8_t cls = -1;  // LaunchClass, or -1 for non-kernel vertices
   int8_t dtype = 0;
   int16_t head_dim = 0;
-  int16_t group = -1;  // index of its (cls, dtype, head_dim) combination: vertices of one group can share a launch
+  int8_t depth = 0;    // tile products: class of the summed depth K (see the GEMM case of tn_executor_create)
+  int16_t group = -1;  // index of its (cls, dtype, head_dim, depth) combination: vertices of one group can share a launch
   int32_t desc = -1;
   int32_t nblocks = 0;
   int64_t lock = -1;  // increments: the vertex whose output they add to; one of them runs at a time
@@ -261,6 +262,11 @@ tn_status build_tables(tn_executor& ex) {
         const bool fused_mfma = x.p.mode != 0 && k32 && d.rows >= 64;
         vi.cls = !mfma ? LC_GEMM_F32 : (big || fused_mfma) ? LC_GEMM_BF16_NT256 : x.p.mode != 0 ? LC_GEMM_F32 : LC_GEMM_BF16_NT;
         vi.flops = (x.p.mode == 2 ? 4.0 : 2.0) * d.rows * d.cols * K;
+        // Products of very different depth do not share a launch.  The workgroups of a launch that run at the same
+        // time read the same operand panels at the same moment only as long as they walk along K in step, and that
+        // sharing in the L2s is what feeds them: 22016-deep products started one by one between 4096-deep ones
+        // run at 390 TFLOP/s, in a launch of their own at 1000.
+        vi.depth = K <= 6144 ? 0 : K <= 12288 ? 1 : 2;
         break;
       }
       case TN_OP_RMS_STAT:
@@ -665,7 +671,7 @@ tn_status tn_executor_create(const tn_memgraph* mg, void* device_base, uint64_t 
       if (vi.cls < 0) continue;
       size_t g = 0;
       while (g < ex->groups.size() && !(ex->groups[g].cls == vi.cls && ex->groups[g].dtype == vi.dtype &&
-                                        ex->groups[g].head_dim == vi.head_dim)) ++g;
+                                        ex->groups[g].head_dim == vi.head_dim && ex->groups[g].depth == vi.depth)) ++g;
       if (g == ex->groups.size()) ex->groups.push_back(vi);
       vi.group = (int16_t)g;
     }
