@@ -44,11 +44,13 @@ HOST_LINK_GBS = 64.0  # PCIe Gen5 x16, per direction
 # against 51 with the defaults; 10 to 16 workgroups measure within 2 % of one another, 24 cost 5 %); on
 # the compute-bound c3 the same setting costs 20 %.  On c5 the small groups of tile products appear while
 # the link is the bottleneck (the reverse pass waits for reloads), and spread over all compute units they
-# slow the copy kernel more than they gain (1.34 against 1.30 s per step).  The one-layer workload streamed
+# slow the copy kernel more than they gain (1.34 against 1.30 s per step); on c4 the 128x128 workgroups share
+# compute units with the copy workgroups, which the 256x256 ones do not, and run at 133 TFLOP/s (62 launches, 63 ms
+# of a step: tile products 960 -> 1010 TFLOP/s in situ without them; the step is bound by the link either way).  The one-layer workload streamed
 # under a fraction of its peak is bound by the link as well: 16 copy workgroups move 52 GB/s beside the tile
 # products where 8 move 45 (11.0 -> 9.9 ms per step under 40 %; larger groups do not help it further).
 TRANSFERS = {"c4": (128, 14), "c2_capped40": (32, 16), "c2_capped25": (32, 16)}
-SMALL_GEMM_TILES = {"c5": -1}
+SMALL_GEMM_TILES = {"c5": -1, "c4": -1, "c2_capped40": -1}
 # Groups of tile products in flight at once (default 1: the next group waits and gathers more ready tiles).  The
 # fine-tuning step, whose launches stay small in the tiler's order, gains 5 % from a second group in flight
 # (889 -> 841 ms; no limit at all measures the same).

@@ -60,7 +60,7 @@ def test_prefix_matches_the_oracle_and_orders_agree(name, PREFIX, distinct, stri
             + [f"h.{l - 1}" for l in probe if l > 0]
         opts = B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, max_gemm_inflight=1, queue_depth=3)
         if name == "c4":  # the launch configuration the benchmark times this workload in
-            opts.max_transfers, opts.copy_workgroups = 128, 14
+            opts.max_transfers, opts.copy_workgroups, opts.small_gemm_tiles = 128, 14, -1
         out, rep = s.run(opts, only=names)
         print(f"[{name}] executed in {rep.wall_ms:.1f} ms ({cfg.tokens / rep.wall_ms * 1e3:.0f} tokens/s), "
               f"h2d {rep.h2d_bytes / 1e9:.2f} GB, d2h {rep.d2h_bytes / 1e9:.2f} GB {time.time() - t0:.1f}s", flush=True)
