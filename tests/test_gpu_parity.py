@@ -331,3 +331,53 @@ def test_whole_row_attention_vertices_match_the_oracle(name):
         np.testing.assert_array_equal(o2["y"], out["y"])
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("k_second,launches", [(1024, 1), (8192, 2), (16384, 2)])
+def test_tile_products_of_different_depth_do_not_share_a_launch(k_second, launches):
+    """Two independent 512x512 products that are ready together: of the same depth class they go out as one
+    launch of two vertices, of different classes (up to 6144, up to 12288, deeper) as two launches -- workgroups
+    that do not walk along K in step lose the sharing in the L2s.  Both results against the oracle's vertex."""
+    import torch
+    from workloads import to_bf16_bits
+    rng = np.random.default_rng(k_second)
+    tg = B.tn_taskgraph_create()
+    host, wide, outs = {}, {}, []
+    for k in (1024, k_second):
+        ins = []
+        for _ in range(2):
+            a = to_bf16_bits(np.ascontiguousarray(rng.standard_normal((512, k)) / np.sqrt(np.sqrt(k)), dtype=np.float32)).reshape(512, k)
+            v = B.tn_taskgraph_add_input(tg, B.TN_BF16, 512, k, B.TN_HOST)
+            host[v] = torch.from_numpy(a.view(np.int16)).pin_memory()
+            wide[v] = bf16_bits_to_f32(a).astype(np.float64)
+            ins.append(v)
+        o = B.tn_taskgraph_add_op(tg, B.TN_OP_GEMM, B.tn_op_params(nk=1, trans_b=1), ins, B.TN_BF16, 512, 512)
+        B.tn_taskgraph_mark_output(tg, o)
+        outs.append((o, ins))
+    cap = 256 << 20
+    mg = B.tn_compile(tg, None, cap, None)
+    dev = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    bufs = [torch.zeros(512 * 512, dtype=torch.int16).pin_memory() for _ in outs]
+    ex = B.tn_executor_create(mg, dev.data_ptr(), cap, 0, 0, [streams[0].cuda_stream], streams[1].cuda_stream, streams[2].cuda_stream)
+    try:
+        n = B.tn_taskgraph_num_vertices(tg)
+        print(f"[case] two products, depths 1024 and {k_second}", flush=True)
+        # small copy groups, so that nothing but the products' readiness decides; the products wait for all loads
+        B.tn_execute(ex, [host[v].data_ptr() if v in host else 0 for v in range(n)], [b.data_ptr() for b in bufs],
+                     B.tn_exec_opts(policy=B.TN_POLICY_BY_ORDER, max_batch=1920, profile=1, max_gemm_inflight=1, max_delay_us=2000,
+                                    delay_seed=1))
+        rec = B.tn_executor_last_launches(ex)
+        gemm = rec[rec["family"] == 0]
+        print("  tile-product launches:", [(int(x["n_vertices"]), int(x["work"])) for x in gemm], flush=True)
+        assert int(gemm["n_vertices"].sum()) == 2
+        if launches == 2:
+            assert len(gemm) == 2  # never together, whatever the timing
+        for (o, ins), b in zip(outs, bufs):
+            ref = T._eval_vertex("gemm", dict(nk=1, trans_b=1), [wide[v] for v in ins])
+            got = bf16_bits_to_f32(b.numpy().view(np.uint16)).astype(np.float64).reshape(512, 512)
+            assert R.rel_err(got, T.round_bf16(ref)) < 2.0 ** -7
+    finally:
+        B.tn_executor_destroy(ex)
+        B.tn_memgraph_destroy(mg)
+        B.tn_taskgraph_destroy(tg)
